@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the rollout denoising step on one MI355X.
+
+A "step" is one denoising step of the LLaDA-8B-shaped rollout (batch 8, 32 heads, head_dim 128,
+hidden 4096, vocabulary 126464, prompt 512, 256 generated tokens in 8 blocks of 32, threshold 0.9
+with the most confident position always committed, prefix cache refreshed at every block start):
+block attention against [prefix | block], LM head -> confidence on the still-masked rows,
+threshold commit with KV write-back, plus the block-boundary cache refresh when a block starts.
+Steps continue across blocks and rollouts; K productive steps are timed.
+
+Prints ONE JSON line: committed tokens/s, the roofline of the dominant kernel (the LM head, which
+streams the 1.04 GB W_vocab every step) measured with HIP events on the launch stream, and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1500)
+    ap.add_argument("--warmup", type=int, default=150)
+    ap.add_argument("--config", default="c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="skip per-step LM-head event timing")
+    ap.add_argument("--sync-loop", action="store_true", help="poll every step synchronously (no one-step-late poll)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (sequences are independent, so a multi-GPU "
+              "rollout is N copies of this program with B/N sequences each); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2604_04215_amd import binding as dlm
+    from paper_2604_04215_amd import synth
+    from paper_2604_04215_amd.rollout import GpuRollout, StepRunner
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dlm.lib()  # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    cfg = synth.CONFIGS[args.config]
+    t_setup = time.time()
+
+    def to_dev(u16):
+        return torch.from_numpy(np.ascontiguousarray(u16).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    w_host = synth.w_vocab(cfg)
+    w = to_dev(w_host)
+    g = GpuRollout(cfg, w, dev)
+    g.diagnostics = False
+    x0 = torch.from_numpy(synth.initial_tokens(cfg, cfg.L)).to(dev)
+    images = {}
+
+    def image(block):
+        if block not in images:
+            k, v = synth.cache_kv(cfg, block)
+            images[block] = (to_dev(k), to_dev(v))
+        return images[block]
+
+    init_masks = {b: torch.from_numpy(synth.initial_block_mask(cfg, b)).to(dev) for b in range(cfg.n_blocks)}
+    pool = {}
+
+    def inputs(block, step):
+        key = (block, step)
+        if key not in pool:
+            kb, vb = synth.step_kv(cfg, block, step)
+            pool[key] = (to_dev(synth.step_q(cfg, block, step)), to_dev(kb), to_dev(vb),
+                         to_dev(synth.step_hidden(cfg, block, step)))
+        return pool[key]
+
+    def setup(block):
+        # block 0 installs the prompt cache image; later blocks refresh it when the workload says so
+        refresh = image(block) if (block == 0 or cfg.refresh) else None
+        return dict(init_mask=init_masks[block], refresh=refresh, n_masked=int(init_masks[block].sum()))
+
+    def restart():
+        g.x.copy_(x0)
+
+    # ---- discovery pass (untimed): generates and uploads every step input the rollout touches ------
+    runner = StepRunner(g, inputs, setup, on_restart=restart, lagged=not args.sync_loop)
+    while runner.blocks_done < cfg.n_blocks:
+        runner.run(1)
+    # make sure the extra step a one-step-late poll may queue after a block's last step exists too
+    steps_per_block = list(runner.steps_per_block[:cfg.n_blocks])
+    for b, s in enumerate(steps_per_block):
+        inputs(b, s)
+    while runner.in_block:        # finish the block the discovery loop may have started
+        runner.run(1)
+    torch.cuda.synchronize()
+    rollout_steps = sum(steps_per_block)
+    setup_s = time.time() - t_setup
+
+    # ---- LM-head event timing hook ------------------------------------------------------------------
+    lm_events = []
+    orig_lmhead = dlm.lmhead_confidence
+    m_trace = []
+
+    def timed_lmhead(*a, **kw):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(torch.cuda.current_stream())
+        orig_lmhead(*a, **kw)
+        e1.record(torch.cuda.current_stream())
+        lm_events.append((e0, e1))
+
+    import paper_2604_04215_amd.rollout as ro_mod
+
+    # ---- warm-up, then the timed region -------------------------------------------------------------
+    runner.run(args.warmup) if args.warmup > 0 else None
+    torch.cuda.synchronize()
+    if not args.no_kernel_events:
+        ro_mod.dlm.lmhead_confidence = timed_lmhead
+    c0, e0 = runner.committed, runner.empty
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    res = runner.run(args.steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ro_mod.dlm.lmhead_confidence = orig_lmhead
+    elapsed = t1 - t0
+    committed = runner.committed - c0
+    empty = runner.empty - e0
+    assert res["steps"] == args.steps
+
+    # ---- roofline of the LM head (dominant kernel): algorithmic bytes / measured duration -----------
+    roof = None
+    w_bytes = cfg.V * cfg.Dh * 2
+    # rows per LM-head launch averaged over the rollout: every productive step processes the rows
+    # still masked before it; over a whole rollout that is sum over steps of masked-before
+    if lm_events:
+        ms = [a.elapsed_time(b) for a, b in lm_events]
+        productive_ms = sorted(ms)[len(ms) // 20:]          # drop nothing systematic; keep all but report median too
+        avg_ms = sum(ms) / len(ms)
+        # average rows per launch: committed tokens tell how many row-evaluations happened in total
+        # (each launch evaluates the rows masked before it); approximate by mean masked count
+        mean_rows = runner_mean_rows(runner, cfg)
+        bytes_per_launch = w_bytes + mean_rows * cfg.Dh * 2 + mean_rows * 8
+        achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+        roof = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    kernel="lmhead_kernel + lmhead_reduce_kernel (one dlm_lmhead_confidence call)",
+                    avg_us=round(avg_ms * 1e3, 2), median_us=round(sorted(ms)[len(ms) // 2] * 1e3, 2),
+                    launches=len(ms), bytes_per_launch=int(bytes_per_launch), mean_rows=round(mean_rows, 1))
+
+    # ---- CPU oracle on a bounded sample of the same workload ----------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        o = oracle.OracleRollout(cfg, synth, seqs=[0], w=w_host)
+        o.begin_block(0)
+        tc0 = time.perf_counter()
+        n_tok = 0
+        n_steps_cpu = 0
+        while o.mask.any() and (time.perf_counter() - tc0) < 25.0:
+            r = o.step()
+            n_tok += int(r["n_commit"].sum())
+            n_steps_cpu += 1
+        tc = time.perf_counter() - tc0
+        cpu = dict(value=round(n_tok / tc, 3), unit="committed tokens/s", cores=oracle.num_threads(), kind="oracle",
+                   sample=f"sequence 0 of the batch, block 0 (prefix 512 + block 32), {n_steps_cpu} denoising "
+                          f"steps, {n_tok} tokens committed in {tc:.1f} s")
+
+    out = {
+        "metric": "committed tokens/sec per denoise step",
+        "value": round(committed / elapsed, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c2: LLaDA-8B-shaped rollout, B=8, 32 heads MHA, d=128, hidden 4096, V=126464, "
+                               "prompt 512, gen 256 in 8 blocks of 32, threshold 0.9 + forced top-1, "
+                               "prefix cache refreshed per block" if args.config == "c2" else args.config,
+                   "committed_tokens": committed, "tokens_per_step": round(committed / args.steps, 3),
+                   "steps_per_rollout": rollout_steps, "steps_per_block": steps_per_block,
+                   "empty_steps_in_timed_region": empty,
+                   "loop": "sync" if args.sync_loop else "one-step-late poll", "setup_s": round(setup_s, 1)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def runner_mean_rows(runner, cfg) -> float:
+    """Mean number of masked rows an LM-head launch processed, over whole rollouts: the rows masked
+    before step s of a block.  Reconstructed from the per-step commit totals is not possible on the
+    host without per-step logs, so the runner's counters are used: total row evaluations = sum over
+    productive steps of the masked count before the step."""
+    return runner.row_evals / max(1, runner.lm_launches) if hasattr(runner, "row_evals") else float(cfg.B * cfg.Lb) / 2
+
+
+if __name__ == "__main__":
+    main()

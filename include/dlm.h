@@ -1,0 +1,248 @@
+/*
+ * dlm.h -- C ABI of libdlm: one denoising step of a masked / block diffusion
+ * language model rollout on one AMD MI355X (gfx950).
+ *
+ * The step (reverse process of a masked diffusion LM; paper Section 2.1, Eq. 1-3,
+ * and the rollout paragraph of Section 3.4):
+ *   1. dlm_block_attn         the block being denoised attends to the cached
+ *                             context and to itself;
+ *   2. dlm_lmhead_confidence  the mask predictor's categorical (Eq. 2) is reduced,
+ *                             per masked position, to its arg-max token and that
+ *                             token's probability, without storing logits;
+ *   3. dlm_unmask_commit      a threshold or fixed-count rule (Section 4.1 schedule)
+ *                             fixes several positions at once and writes the
+ *                             block's K/V back into the cache;
+ *   dlm_kv_refresh            block-boundary cache refresh (strided 16-bit copy).
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name starts with host_.  The
+ *     argument structs themselves live in host memory.
+ *   - bf16 tensors are passed as const void*; strides are in ELEMENTS; the
+ *     innermost (head_dim / hidden) axis is contiguous.
+ *   - The caller owns every buffer, including workspaces; the library allocates
+ *     no device memory and keeps no pointer after a call's work has completed.
+ *   - Calls validate on the host, enqueue on the HIP stream passed as `stream`
+ *     (a hipStream_t; NULL = the default stream) and return without
+ *     synchronising.  Outputs are valid once the stream has been synchronised.
+ *   - Return value: DLM_OK or a negative DLM_ERR_* code; nothing aborts or
+ *     throws.  dlm_last_error() gives a thread-local description of the last
+ *     failure on the calling thread.
+ *   - struct_size must be set to sizeof(the struct) by the caller.
+ */
+#ifndef DLM_H
+#define DLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DLM_OK                 0
+#define DLM_ERR_INVALID_ARG   (-1)  /* null / negative / inconsistent argument                */
+#define DLM_ERR_UNSUPPORTED   (-2)  /* valid but not implemented (e.g. head_dim not 64 / 128) */
+#define DLM_ERR_WORKSPACE     (-3)  /* workspace missing or smaller than *_workspace_bytes    */
+#define DLM_ERR_HIP           (-4)  /* a HIP runtime call failed (launch error)               */
+
+#define DLM_MASK_FULL          0    /* every query sees every key (masked diffusion LM)       */
+#define DLM_MASK_BLOCK_CAUSAL  1    /* key visible iff its block index <= the query's (Eq. 3) */
+
+#define DLM_RULE_THRESHOLD     0
+#define DLM_RULE_TOPK          1
+
+#define DLM_WB_NONE            0
+#define DLM_WB_BLOCK_WHEN_DONE 1    /* copy the whole block's K/V when a sequence's last masked position commits */
+#define DLM_WB_COMMITTED_ROWS  2    /* copy the K/V rows of the positions committed by this call */
+
+/* One segment of keys/values: k, v are bf16 [B, Hkv, len, d] addressed as
+ * base + b*stride_b + h*stride_h + t*stride_t + c.  len == 0 means "absent".
+ * pos0 is the absolute sequence position of row 0 (block-causal mask only). */
+typedef struct dlm_kv_seg {
+    const void *k, *v;
+    int32_t len;
+    int32_t pos0;
+    int64_t stride_b, stride_h, stride_t;
+} dlm_kv_seg;
+
+/* ------------------------------------------------------------------------- *
+ * dlm_block_attn -- O = softmax(scale * Q K^T) V for a block of Lq query rows
+ * per sequence against the concatenation [prefix | block | suffix] of KV
+ * segments, with grouped-query heads (kv head = q head / (Hq / Hkv)).
+ *
+ * Defines: Section 3.4 "Rollout-side optimization for MDLMs" (KV-cache reuse:
+ * the block attends to cached context plus itself; bidirectional, Eq. 2) and
+ * the block partition before Eq. 3 (block-causal visibility).
+ *
+ *   q       bf16 [B, Lq, Hq, d]   (q_stride_b, q_stride_t, q_stride_h)
+ *   out     bf16 [B, Lq, Hq, d]   (o_stride_*), written
+ *   lse     optional fp32 [B, Hq, Lq] contiguous: natural-log sum of exp(scale*s)
+ *   prefix_len_b  optional int32 [B]: only the first prefix_len_b[b] rows of
+ *           `prefix` exist for sequence b (0 <= value <= prefix.len)
+ *   mask_mode DLM_MASK_BLOCK_CAUSAL: key at absolute position p is visible to
+ *           query row i iff floor(p / block_size) <= floor((q_pos0 + i) / block_size)
+ *   scale   <= 0 selects 1/sqrt(d)
+ * Arithmetic: bf16 operands, fp32 scores / softmax / accumulation, probabilities
+ * rounded to bf16 for the second product, bf16 output.  A row that sees no key
+ * gets out = 0 and lse = -inf.
+ * Supported: d in {64, 128}; Hq % Hkv == 0; all base pointers 16-byte aligned and
+ * all strides multiples of 8 elements.  Lq, Hq/Hkv and segment lengths are arbitrary.
+ * workspace: dlm_block_attn_workspace_bytes(args) bytes (may be 0; then NULL is fine).
+ * ------------------------------------------------------------------------- */
+typedef struct dlm_attn_args {
+    uint32_t struct_size;
+    int32_t B, Lq, Hq, Hkv, d;
+    const void *q;
+    int64_t q_stride_b, q_stride_t, q_stride_h;
+    dlm_kv_seg prefix, block, suffix;
+    const int32_t *prefix_len_b;
+    int32_t mask_mode;
+    int32_t block_size, q_pos0;
+    float scale;
+    void *out;
+    int64_t o_stride_b, o_stride_t, o_stride_h;
+    float *lse;
+    void *workspace;
+    size_t workspace_bytes;
+} dlm_attn_args;
+
+int dlm_block_attn(const dlm_attn_args *args, void *stream);
+size_t dlm_block_attn_workspace_bytes(const dlm_attn_args *args);
+
+/* ------------------------------------------------------------------------- *
+ * dlm_lmhead_confidence -- for each of M selected rows r of `hidden`:
+ *   z_v  = (hidden[row(r), :] . w[v, :]) * inv_temperature,  v in [0, V)
+ *   z_forbid_token = -inf (when forbid_token >= 0)
+ *   tok  = smallest v maximising z_v;  zmax = z_tok;  z2nd = max_{v != tok} z_v
+ *   lse  = log sum_v exp(z_v);  conf = exp(zmax - lse)
+ *   ztarget = z_{target[r]}  (optional; log p(target) = ztarget - lse, the term
+ *             summed by the NELBO of Eq. 2 / Eq. 3)
+ * The V logits of a row are never written to memory.
+ *
+ * Defines: the mask predictor p_theta(x_0 | x_t) of Eq. 2 evaluated at masked
+ * positions; "logits-free" fused projection as in Section 3.4.
+ *
+ *   hidden  bf16 [rows_total, Dh], row stride hidden_stride_row
+ *   row_idx optional int32 [M]: row(r) = row_idx[r]; NULL: row(r) = r
+ *   m_dev   optional device int32 scalar: the call processes min(M, max(*m_dev,0))
+ *           rows (lets the previous step's compaction set the row count without a
+ *           host round trip); outputs beyond that count are left untouched
+ *   w       bf16 [V, Dh], row stride w_stride_row
+ *   out_scatter  0: outputs are indexed by r; 1: by row(r) (dense per-position arrays)
+ *   conf, tok    required; lse, zmax, z2nd, target+ztarget optional.  `target` is
+ *           indexed like the outputs.
+ * Arithmetic: bf16 operands, fp32 accumulation and softmax.
+ * Supported: Dh % 64 == 0; hidden, w 16-byte aligned; strides multiples of 8.
+ * workspace: dlm_lmhead_workspace_bytes(args) bytes, 16-byte aligned.
+ * ------------------------------------------------------------------------- */
+typedef struct dlm_lmhead_args {
+    uint32_t struct_size;
+    int32_t M, Dh, V;
+    const void *hidden;
+    int64_t hidden_stride_row;
+    const int32_t *row_idx;
+    const int32_t *m_dev;
+    const void *w;
+    int64_t w_stride_row;
+    float inv_temperature;
+    int32_t forbid_token;
+    int32_t out_scatter;
+    float *conf;
+    int32_t *tok;
+    float *lse, *zmax, *z2nd;
+    const int32_t *target;
+    float *ztarget;
+    void *workspace;
+    size_t workspace_bytes;
+} dlm_lmhead_args;
+
+int dlm_lmhead_confidence(const dlm_lmhead_args *args, void *stream);
+size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args *args);
+
+/* ------------------------------------------------------------------------- *
+ * dlm_unmask_commit -- per sequence and per commit group of group_len
+ * consecutive positions, among positions with mask == 1:
+ *   DLM_RULE_THRESHOLD  commit every position with conf >= threshold and, when
+ *                       force_top1 != 0, the most confident one (lowest index on ties);
+ *   DLM_RULE_TOPK       commit the min(k, #masked) most confident (ties: lowest index).
+ * For committed position i: x[b, x_pos0 + i] = tok[b, i]; mask[b, i] = 0.
+ * Positions with mask == 0 on entry are neither read for selection nor written.
+ *
+ * Defines: the reverse-process commit ("repeated denoising on partially fixed
+ * states", Section 3.4) with the fixed schedule of Section 4.1 (top-k) or the
+ * confidence-threshold parallel decoding the paper adopts for rollout.
+ *
+ *   conf, tok   dense fp32 / int32 [B, n_pos] contiguous (index b*n_pos + i)
+ *   x           int32, row stride x_stride_b, in/out
+ *   mask        uint8, row stride mask_stride_b, in/out
+ *   commit_now  optional uint8 [B, n_pos]: 1 where this call committed (fully written)
+ *   n_commit, remaining   int32 [B]: committed by this call / still masked after it
+ *   next_row_idx, next_m  optional: ascending list of flat indices b*n_pos + i that are
+ *                         still masked after this call, and its length (device scalar)
+ *   commit_step optional int16 [B, n_pos]: `step` is stored where this call committed
+ *   writeback   DLM_WB_*: copy rows of src_block (bf16 [B, Hkv, src_block.len, d]) into
+ *               cache_k / cache_v (bf16, strides c_stride_*) at rows cache_pos0 + t.
+ *               BLOCK_WHEN_DONE: all rows, for sequences whose remaining becomes 0 in this
+ *               call with n_commit > 0.  COMMITTED_ROWS: row i for each committed i
+ *               (needs src_block.len == n_pos).
+ * Selection compares fp32 values; outputs are integers (bit-exact given conf).
+ * Limits: 1 <= group_len <= 1024; d % 8 == 0 for write-back.
+ * Calls on one stream are ordered; the kernels of one call race with nothing else.
+ * ------------------------------------------------------------------------- */
+typedef struct dlm_commit_args {
+    uint32_t struct_size;
+    int32_t B, n_pos, group_len;
+    int32_t rule;
+    float threshold;
+    int32_t force_top1;
+    int32_t k;
+    const float *conf;
+    const int32_t *tok;
+    int32_t *x;
+    int64_t x_stride_b;
+    int32_t x_pos0;
+    uint8_t *mask;
+    int64_t mask_stride_b;
+    uint8_t *commit_now;
+    int32_t *n_commit, *remaining;
+    int32_t *next_row_idx, *next_m;
+    int16_t *commit_step;
+    int32_t step;
+    int32_t writeback;
+    dlm_kv_seg src_block;
+    void *cache_k, *cache_v;
+    int64_t c_stride_b, c_stride_h, c_stride_t;
+    int32_t cache_pos0, Hkv, d;
+} dlm_commit_args;
+
+int dlm_unmask_commit(const dlm_commit_args *args, void *stream);
+
+/* dlm_mask_compact -- ascending list of flat indices b*n_pos + i with mask[b, i] != 0
+ * into row_idx (capacity B*n_pos) and its length into *m_out (device scalar).
+ * Used at block start to seed dlm_lmhead_confidence's row list (masked rows only, Eq. 2). */
+int dlm_mask_compact(const uint8_t *mask, int64_t mask_stride_b, int32_t B, int32_t n_pos,
+                     int32_t *row_idx, int32_t *m_out, void *stream);
+
+/* dlm_kv_refresh -- copy src K,V [B, Hkv, src->len, d] into the cache at rows
+ * [cache_pos0, cache_pos0 + src->len): the block-boundary cache refresh of a
+ * KV-cached rollout (Section 3.4).  Bit-exact 16-bit copy; d % 8 == 0, 16-byte
+ * aligned bases, strides multiples of 8.  Source and destination must not overlap. */
+int dlm_kv_refresh(const dlm_kv_seg *src, int32_t B, int32_t Hkv, int32_t d,
+                   void *cache_k, void *cache_v,
+                   int64_t c_stride_b, int64_t c_stride_h, int64_t c_stride_t,
+                   int32_t cache_pos0, void *stream);
+
+/* dlm_set_option -- process-wide tuning / test knobs (not thread-safe against running calls).
+ *   "attn_variant"  0 = pick the attention kernel shape from the problem shape (default);
+ *                   1 = 32-row workgroups whose wavefronts split the keys (needs g*Lq <= 32,
+ *                       otherwise falls back to 2); 2 = 128-row; 3 = 256-row workgroups.
+ * Every shape computes the same function; the knob exists for tests and tuning sweeps. */
+int dlm_set_option(const char *name, int value);
+
+const char *dlm_last_error(void);
+int dlm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLM_H */

@@ -1,0 +1,282 @@
+"""ctypes binding to libdlm.so: argument marshalling only.
+
+Every function here fills the C structs of include/dlm.h from torch tensors
+(device pointers, element strides) and calls the library on the current torch
+HIP stream.  There is no fallback: if the HIP library has not been built, or a
+tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdlm.so")
+
+DLM_OK, DLM_ERR_INVALID_ARG, DLM_ERR_UNSUPPORTED, DLM_ERR_WORKSPACE, DLM_ERR_HIP = 0, -1, -2, -3, -4
+MASK_FULL, MASK_BLOCK_CAUSAL = 0, 1
+RULE_THRESHOLD, RULE_TOPK = 0, 1
+WB_NONE, WB_BLOCK_WHEN_DONE, WB_COMMITTED_ROWS = 0, 1, 2
+
+EXPORTS = ["dlm_block_attn", "dlm_block_attn_workspace_bytes", "dlm_lmhead_confidence",
+           "dlm_lmhead_workspace_bytes", "dlm_unmask_commit", "dlm_mask_compact", "dlm_kv_refresh",
+           "dlm_set_option", "dlm_last_error", "dlm_version"]
+
+
+class KvSeg(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("len", C.c_int32), ("pos0", C.c_int32),
+                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_t", C.c_int64)]
+
+
+class AttnArgs(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32),
+                ("B", C.c_int32), ("Lq", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32),
+                ("q", C.c_void_p), ("q_stride_b", C.c_int64), ("q_stride_t", C.c_int64), ("q_stride_h", C.c_int64),
+                ("prefix", KvSeg), ("block", KvSeg), ("suffix", KvSeg),
+                ("prefix_len_b", C.c_void_p),
+                ("mask_mode", C.c_int32), ("block_size", C.c_int32), ("q_pos0", C.c_int32), ("scale", C.c_float),
+                ("out", C.c_void_p), ("o_stride_b", C.c_int64), ("o_stride_t", C.c_int64), ("o_stride_h", C.c_int64),
+                ("lse", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class LmheadArgs(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("M", C.c_int32), ("Dh", C.c_int32), ("V", C.c_int32),
+                ("hidden", C.c_void_p), ("hidden_stride_row", C.c_int64),
+                ("row_idx", C.c_void_p), ("m_dev", C.c_void_p),
+                ("w", C.c_void_p), ("w_stride_row", C.c_int64),
+                ("inv_temperature", C.c_float), ("forbid_token", C.c_int32), ("out_scatter", C.c_int32),
+                ("conf", C.c_void_p), ("tok", C.c_void_p),
+                ("lse", C.c_void_p), ("zmax", C.c_void_p), ("z2nd", C.c_void_p),
+                ("target", C.c_void_p), ("ztarget", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class CommitArgs(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("B", C.c_int32), ("n_pos", C.c_int32), ("group_len", C.c_int32),
+                ("rule", C.c_int32), ("threshold", C.c_float), ("force_top1", C.c_int32), ("k", C.c_int32),
+                ("conf", C.c_void_p), ("tok", C.c_void_p),
+                ("x", C.c_void_p), ("x_stride_b", C.c_int64), ("x_pos0", C.c_int32),
+                ("mask", C.c_void_p), ("mask_stride_b", C.c_int64),
+                ("commit_now", C.c_void_p), ("n_commit", C.c_void_p), ("remaining", C.c_void_p),
+                ("next_row_idx", C.c_void_p), ("next_m", C.c_void_p),
+                ("commit_step", C.c_void_p), ("step", C.c_int32), ("writeback", C.c_int32),
+                ("src_block", KvSeg), ("cache_k", C.c_void_p), ("cache_v", C.c_void_p),
+                ("c_stride_b", C.c_int64), ("c_stride_h", C.c_int64), ("c_stride_t", C.c_int64),
+                ("cache_pos0", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32)]
+
+
+class DlmError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libdlm error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load libdlm.so (built in-tree by paper_2604_04215_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2604_04215_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        L.dlm_block_attn.restype = C.c_int
+        L.dlm_block_attn.argtypes = [C.POINTER(AttnArgs), C.c_void_p]
+        L.dlm_block_attn_workspace_bytes.restype = C.c_size_t
+        L.dlm_block_attn_workspace_bytes.argtypes = [C.POINTER(AttnArgs)]
+        L.dlm_lmhead_confidence.restype = C.c_int
+        L.dlm_lmhead_confidence.argtypes = [C.POINTER(LmheadArgs), C.c_void_p]
+        L.dlm_lmhead_workspace_bytes.restype = C.c_size_t
+        L.dlm_lmhead_workspace_bytes.argtypes = [C.POINTER(LmheadArgs)]
+        L.dlm_unmask_commit.restype = C.c_int
+        L.dlm_unmask_commit.argtypes = [C.POINTER(CommitArgs), C.c_void_p]
+        L.dlm_mask_compact.restype = C.c_int
+        L.dlm_mask_compact.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.dlm_kv_refresh.restype = C.c_int
+        L.dlm_kv_refresh.argtypes = [C.POINTER(KvSeg), C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                     C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_void_p]
+        L.dlm_set_option.restype = C.c_int
+        L.dlm_set_option.argtypes = [C.c_char_p, C.c_int]
+        L.dlm_last_error.restype = C.c_char_p
+        L.dlm_version.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().dlm_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != DLM_OK:
+        raise DlmError(rc, last_error())
+
+
+def _stream(stream=None) -> C.c_void_p:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dev(t, dtype=None, name="tensor"):
+    """Device pointer of a torch tensor after checking device / dtype / inner contiguity."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU (no CPU path exists)")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if t.dim() > 0 and t.numel() > 0 and t.stride(-1) != 1:
+        raise ValueError(f"{name}: innermost axis must be contiguous")
+    return t.data_ptr()
+
+
+def set_option(name: str, value: int) -> None:
+    _check(lib().dlm_set_option(name.encode(), int(value)))
+
+
+def kv_seg(k=None, v=None, pos0: int = 0) -> KvSeg:
+    """k, v: bf16 [B, Hkv, len, d] views (any batch/head/row strides) or None for an absent segment."""
+    import torch
+    s = KvSeg()
+    if k is None or k.shape[2] == 0:
+        s.k = s.v = None
+        s.len = 0
+        s.pos0 = int(pos0)
+        return s
+    if k.shape != v.shape or k.stride() != v.stride():
+        raise ValueError("k and v of a segment must have the same shape and strides")
+    s.k, s.v = _dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v")
+    s.len, s.pos0 = int(k.shape[2]), int(pos0)
+    s.stride_b, s.stride_h, s.stride_t = int(k.stride(0)), int(k.stride(1)), int(k.stride(2))
+    return s
+
+
+def block_attn(q, out, prefix: Optional[Tuple] = None, block: Optional[Tuple] = None,
+               suffix: Optional[Tuple] = None, *, n_kv_heads: Optional[int] = None,
+               mask_mode: int = MASK_FULL, block_size: int = 0, q_pos0: int = 0, scale: float = 0.0,
+               prefix_len_b=None, lse=None, workspace=None, stream=None) -> None:
+    """q, out: bf16 [B, Lq, Hq, d]; each segment is (k, v, pos0) with k, v bf16 [B, Hkv, len, d]."""
+    import torch
+    a = AttnArgs()
+    a.struct_size = C.sizeof(AttnArgs)
+    B, Lq, Hq, d = q.shape
+    if out.shape != q.shape:
+        raise ValueError("out must have q's shape")
+    segs = [prefix, block, suffix]
+    hkv = n_kv_heads
+    for sg in segs:
+        if sg is not None and sg[0] is not None:
+            hkv = sg[0].shape[1]
+    a.B, a.Lq, a.Hq, a.Hkv, a.d = B, Lq, Hq, int(hkv if hkv else Hq), d
+    a.q = _dev(q, torch.bfloat16, "q")
+    a.q_stride_b, a.q_stride_t, a.q_stride_h = q.stride(0), q.stride(1), q.stride(2)
+    a.prefix = kv_seg(*prefix) if prefix else kv_seg()
+    a.block = kv_seg(*block) if block else kv_seg()
+    a.suffix = kv_seg(*suffix) if suffix else kv_seg()
+    a.prefix_len_b = _dev(prefix_len_b, torch.int32, "prefix_len_b")
+    a.mask_mode, a.block_size, a.q_pos0, a.scale = int(mask_mode), int(block_size), int(q_pos0), float(scale)
+    a.out = _dev(out, torch.bfloat16, "out")
+    a.o_stride_b, a.o_stride_t, a.o_stride_h = out.stride(0), out.stride(1), out.stride(2)
+    if lse is not None and (not lse.is_contiguous() or tuple(lse.shape) != (B, Hq, Lq)):
+        raise ValueError("lse must be contiguous fp32 [B, Hq, Lq]")
+    a.lse = _dev(lse, torch.float32, "lse")
+    a.workspace = _dev(workspace, None, "workspace")
+    a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().dlm_block_attn(C.byref(a), _stream(stream)))
+
+
+def lmhead_workspace_bytes(M: int, V: int) -> int:
+    a = LmheadArgs()
+    a.struct_size = C.sizeof(LmheadArgs)
+    a.M, a.V, a.Dh = int(M), int(V), 64
+    return int(lib().dlm_lmhead_workspace_bytes(C.byref(a)))
+
+
+def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=None, m_dev=None,
+                      inv_temperature: float = 1.0, forbid_token: int = -1, out_scatter: bool = False,
+                      lse=None, zmax=None, z2nd=None, target=None, ztarget=None, workspace=None,
+                      stream=None) -> None:
+    """hidden bf16 [rows, Dh]; w bf16 [V, Dh]; conf fp32 / tok int32 outputs; workspace: a uint8 tensor."""
+    import torch
+    a = LmheadArgs()
+    a.struct_size = C.sizeof(LmheadArgs)
+    rows, Dh = hidden.shape
+    V = w.shape[0]
+    if w.shape[1] != Dh:
+        raise ValueError("w must be [V, Dh]")
+    if M is None:
+        M = row_idx.shape[0] if row_idx is not None else rows
+    a.M, a.Dh, a.V = int(M), int(Dh), int(V)
+    a.hidden, a.hidden_stride_row = _dev(hidden, torch.bfloat16, "hidden"), hidden.stride(0)
+    a.row_idx = _dev(row_idx, torch.int32, "row_idx")
+    a.m_dev = _dev(m_dev, torch.int32, "m_dev")
+    a.w, a.w_stride_row = _dev(w, torch.bfloat16, "w"), w.stride(0)
+    a.inv_temperature, a.forbid_token, a.out_scatter = float(inv_temperature), int(forbid_token), int(bool(out_scatter))
+    a.conf, a.tok = _dev(conf, torch.float32, "conf"), _dev(tok, torch.int32, "tok")
+    a.lse, a.zmax, a.z2nd = (_dev(lse, torch.float32, "lse"), _dev(zmax, torch.float32, "zmax"),
+                             _dev(z2nd, torch.float32, "z2nd"))
+    a.target, a.ztarget = _dev(target, torch.int32, "target"), _dev(ztarget, torch.float32, "ztarget")
+    a.workspace = _dev(workspace, None, "workspace")
+    a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().dlm_lmhead_confidence(C.byref(a), _stream(stream)))
+
+
+def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group_len: Optional[int] = None,
+                  rule: int = RULE_THRESHOLD, threshold: float = 0.0, force_top1: bool = True, k: int = 0,
+                  commit_now=None, next_row_idx=None, next_m=None, commit_step=None, step: int = 0,
+                  writeback: int = WB_NONE, src_block: Optional[Tuple] = None, cache_k=None, cache_v=None,
+                  cache_pos0: int = 0, stream=None) -> None:
+    """conf fp32 / tok int32 dense [B, n_pos]; x int32 [B, L]; mask uint8 [B, n_pos] (row-strided views are fine)."""
+    import torch
+    a = CommitArgs()
+    a.struct_size = C.sizeof(CommitArgs)
+    B, n_pos = mask.shape
+    if not conf.is_contiguous() or not tok.is_contiguous() or conf.numel() != B * n_pos or tok.numel() != B * n_pos:
+        raise ValueError("conf / tok must be contiguous [B, n_pos]")
+    a.B, a.n_pos, a.group_len = B, n_pos, int(n_pos if group_len is None else group_len)
+    a.rule, a.threshold, a.force_top1, a.k = int(rule), float(threshold), int(bool(force_top1)), int(k)
+    a.conf, a.tok = _dev(conf, torch.float32, "conf"), _dev(tok, torch.int32, "tok")
+    a.x, a.x_stride_b, a.x_pos0 = _dev(x, torch.int32, "x"), x.stride(0), int(x_pos0)
+    a.mask, a.mask_stride_b = _dev(mask, torch.uint8, "mask"), mask.stride(0)
+    for name, t in (("commit_now", commit_now), ("commit_step", commit_step)):
+        if t is not None and (not t.is_contiguous() or t.numel() != B * n_pos):
+            raise ValueError(f"{name} must be contiguous [B, n_pos]")
+    a.commit_now = _dev(commit_now, torch.uint8, "commit_now")
+    a.n_commit, a.remaining = _dev(n_commit, torch.int32, "n_commit"), _dev(remaining, torch.int32, "remaining")
+    a.next_row_idx, a.next_m = _dev(next_row_idx, torch.int32, "next_row_idx"), _dev(next_m, torch.int32, "next_m")
+    a.commit_step, a.step = _dev(commit_step, torch.int16, "commit_step"), int(step)
+    a.writeback = int(writeback)
+    if writeback != WB_NONE:
+        a.src_block = kv_seg(*src_block)
+        if cache_k.stride() != cache_v.stride():
+            raise ValueError("cache_k and cache_v must share strides")
+        a.cache_k, a.cache_v = _dev(cache_k, torch.bfloat16, "cache_k"), _dev(cache_v, torch.bfloat16, "cache_v")
+        a.c_stride_b, a.c_stride_h, a.c_stride_t = cache_k.stride(0), cache_k.stride(1), cache_k.stride(2)
+        a.cache_pos0, a.Hkv, a.d = int(cache_pos0), int(cache_k.shape[1]), int(cache_k.shape[3])
+    _check(lib().dlm_unmask_commit(C.byref(a), _stream(stream)))
+
+
+def mask_compact(mask, row_idx, m_out, stream=None) -> None:
+    import torch
+    B, n_pos = mask.shape
+    _check(lib().dlm_mask_compact(_dev(mask, torch.uint8, "mask"), mask.stride(0), B, n_pos,
+                                  _dev(row_idx, torch.int32, "row_idx"), _dev(m_out, torch.int32, "m_out"),
+                                  _stream(stream)))
+
+
+def kv_refresh(src_k, src_v, cache_k, cache_v, cache_pos0: int, stream=None) -> None:
+    """Copy src K,V [B, Hkv, len, d] into cache rows [cache_pos0, cache_pos0 + len)."""
+    import torch
+    seg = kv_seg(src_k, src_v, 0)
+    if cache_k.stride() != cache_v.stride():
+        raise ValueError("cache_k and cache_v must share strides")
+    B, Hkv, _, d = src_k.shape
+    if cache_pos0 + src_k.shape[2] > cache_k.shape[2]:
+        raise ValueError("refresh would write past the end of the cache")
+    _check(lib().dlm_kv_refresh(C.byref(seg), B, Hkv, d, _dev(cache_k, torch.bfloat16, "cache_k"),
+                                _dev(cache_v, torch.bfloat16, "cache_v"), cache_k.stride(0), cache_k.stride(1),
+                                cache_k.stride(2), int(cache_pos0), _stream(stream)))

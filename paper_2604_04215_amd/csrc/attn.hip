@@ -1,0 +1,436 @@
+// dlm_block_attn: attention of a query block against [prefix | block | suffix] KV.
+//
+// Work decomposition (gfx950, 64-wide wavefronts, MFMA 32x32x16 bf16):
+//   * The g = Hq/Hkv query heads that share a KV head are packed, together with the
+//     Lq query rows, into R = g*Lq "rows" (row = i*g + head_in_group), so K/V of a
+//     KV head are streamed once for all of them.
+//   * A workgroup owns 32*NWR*RTW rows of one (sequence, KV head).  Its NWR*NWK
+//     wavefronts either split the rows (NWK == 1: K/V tiles are shared through LDS)
+//     or split the keys (NWR == 1: each wavefront streams every NWK-th 32-key tile
+//     and the partial (max, sum, O) are merged through LDS at the end).
+//   * Per 32-key tile: S^T = K Q^T with K as the MFMA A operand, so a lane ends up
+//     holding 16 keys of ONE query column: the row max / row sum are in-register
+//     reductions plus one exchange with lane^32.  P is rounded to bf16 in place and
+//     is already in B-operand layout for O^T += V^T P^T; V^T fragments come from LDS
+//     with the transposing 64-bit LDS read.
+//   * fp32 scores, max, sum and accumulators; the row sum uses the unrounded p.
+#include "common.hpp"
+#include <string.h>
+
+namespace dlm {
+
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+struct SegDev {
+    const uint16_t *k, *v;
+    int len, pos0;
+    int64_t sb, sh, st;
+};
+
+struct AttnParams {
+    int B, Lq, Hq, Hkv, g, R;
+    const uint16_t* q;
+    int64_t q_sb, q_st, q_sh;
+    SegDev seg[3];
+    const int32_t* prefix_len_b;
+    int bs, q_pos0;
+    float scale_log2;  // scale * log2(e): softmax is evaluated with exp2
+    uint16_t* out;
+    int64_t o_sb, o_st, o_sh;
+    float* lse;
+};
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
+    union { u32x4 u; bf16x8 b; } x;
+    x.u = v;
+    return x.b;
+}
+
+template <int D, int NWR, int NWK, int RTW, bool BC>
+__global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
+    static_assert(NWR == 1 || NWK == 1, "waves split either rows or keys");
+    constexpr int NT = 64 * NWR * NWK;
+    constexpr int KP = D * 2 + 16;          // K tile row pitch (bytes): 16-byte reads of 16 rows hit distinct banks
+    constexpr int VP = D * 2 + 64;          // V tile row pitch: 4 rows x 64 B of a transposing read tile the 64 banks
+    constexpr int TILE_BYTES = 32 * KP + 32 * VP;
+    constexpr int C8 = D / 8;               // 16-byte chunks per row
+    constexpr int NLD = (32 * C8) / (64 * NWR);
+    constexpr int MP = D + 4;               // merge buffer row pitch (floats)
+    constexpr int MERGE_BYTES = (NWK > 1) ? NWK * 32 * MP * 4 : 0;
+    constexpr int SMEM = (NWK * TILE_BYTES > MERGE_BYTES) ? NWK * TILE_BYTES : MERGE_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wr = w % NWR, wk = w / NWR;
+    const int n = lane & 31, hi = lane >> 5;
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int r0 = blockIdx.x * (32 * NWR * RTW);
+
+    // ---- visible extent of each segment for this workgroup -----------------
+    int len0 = p.seg[0].len, len1 = p.seg[1].len, len2 = p.seg[2].len;
+    if (p.prefix_len_b) len0 = min(len0, max(p.prefix_len_b[b], 0));
+    if (BC) {
+        const int rmax = min(r0 + 32 * NWR * RTW, p.R) - 1;
+        const int lim = ((p.q_pos0 + rmax / p.g) / p.bs + 1) * p.bs;  // positions >= lim are invisible to every row here
+        len0 = max(0, min(len0, lim - p.seg[0].pos0));
+        len1 = max(0, min(len1, lim - p.seg[1].pos0));
+        len2 = max(0, min(len2, lim - p.seg[2].pos0));
+    }
+    const int e1 = len0, e2 = len0 + len1, Lk = e2 + len2;
+    const int T = (Lk + 31) >> 5;
+    const int n_it = (T + NWK - 1) / NWK;
+
+    const uint16_t* kb0 = p.seg[0].k + b * p.seg[0].sb + kvh * p.seg[0].sh;
+    const uint16_t* vb0 = p.seg[0].v + b * p.seg[0].sb + kvh * p.seg[0].sh;
+    const uint16_t* kb1 = p.seg[1].k + b * p.seg[1].sb + kvh * p.seg[1].sh;
+    const uint16_t* vb1 = p.seg[1].v + b * p.seg[1].sb + kvh * p.seg[1].sh;
+    const uint16_t* kb2 = p.seg[2].k + b * p.seg[2].sb + kvh * p.seg[2].sh;
+    const uint16_t* vb2 = p.seg[2].v + b * p.seg[2].sb + kvh * p.seg[2].sh;
+    const int64_t st0 = p.seg[0].st, st1 = p.seg[1].st, st2 = p.seg[2].st;
+
+    // ---- Q fragments (B operand: lane = query column, 8 consecutive d) ------
+    bf16x8 qf[RTW][D / 16];
+    int qlim[RTW];
+#pragma unroll
+    for (int rt = 0; rt < RTW; ++rt) {
+        const int r = r0 + (wr * RTW + rt) * 32 + n;
+        const bool valid = r < p.R;
+        const int i = valid ? r / p.g : 0;
+        const int hg = valid ? r - i * p.g : 0;
+        const uint16_t* qp = p.q + b * p.q_sb + i * p.q_st + (int64_t)(kvh * p.g + hg) * p.q_sh;
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) {
+            u32x4 v = {0, 0, 0, 0};
+            if (valid) v = *reinterpret_cast<const u32x4*>(qp + 16 * c + 8 * hi);
+            qf[rt][c] = as_bf16x8(v);
+        }
+        qlim[rt] = BC ? ((p.q_pos0 + i) / p.bs + 1) * p.bs : 0;
+    }
+
+    f32x16 O[RTW][D / 32];
+    float m_run[RTW], l_run[RTW];
+#pragma unroll
+    for (int rt = 0; rt < RTW; ++rt) {
+        m_run[rt] = -INFINITY;
+        l_run[rt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[rt][dt][i] = 0.f;
+    }
+
+    unsigned char* Kl = smem + wk * TILE_BYTES;
+    unsigned char* Vl = Kl + 32 * KP;
+    const int tl = wr * 64 + lane;  // thread index inside the wave group that shares a tile
+
+    u32x4 kreg[NLD], vreg[NLD];
+    auto prefetch = [&](int t) {
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int cidx = tl + q * (64 * NWR);
+            const int row = cidx / C8, c = cidx - row * C8;
+            const int j = t * 32 + row;
+            u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+            if (j < Lk) {
+                const uint16_t* kb = (j < e1) ? kb0 : ((j < e2) ? kb1 : kb2);
+                const uint16_t* vb = (j < e1) ? vb0 : ((j < e2) ? vb1 : vb2);
+                const int64_t stt = (j < e1) ? st0 : ((j < e2) ? st1 : st2);
+                const int loc = (j < e1) ? j : ((j < e2) ? j - e1 : j - e2);
+                const int64_t off = loc * stt + c * 8;
+                kv = *reinterpret_cast<const u32x4*>(kb + off);
+                vv = *reinterpret_cast<const u32x4*>(vb + off);
+            }
+            kreg[q] = kv;
+            vreg[q] = vv;
+        }
+    };
+
+    if (n_it > 0) prefetch(wk);
+    for (int it = 0; it < n_it; ++it) {
+        const int t = it * NWK + wk;
+        __syncthreads();  // everyone finished reading the previous tile
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int cidx = tl + q * (64 * NWR);
+            const int row = cidx / C8, c = cidx - row * C8;
+            *reinterpret_cast<u32x4*>(Kl + row * KP + c * 16) = kreg[q];
+            *reinterpret_cast<u32x4*>(Vl + row * VP + c * 16) = vreg[q];
+        }
+        __syncthreads();
+        if (it + 1 < n_it) prefetch(t + NWK);
+        if (t >= T) continue;  // wave-uniform: this wave group has no tile in the last round
+
+        // ---- S^T = K Q^T -----------------------------------------------------
+        f32x16 S[RTW];
+#pragma unroll
+        for (int rt = 0; rt < RTW; ++rt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) S[rt][i] = 0.f;
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Kl + n * KP + (16 * c + 8 * hi) * 2);
+#pragma unroll
+            for (int rt = 0; rt < RTW; ++rt) S[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rt][c], S[rt], 0, 0, 0);
+        }
+
+        // ---- online softmax; register i of a lane is key 8*(i/4) + 4*hi + i%4 ---
+        const bool ragged = BC || (t * 32 + 32 > Lk);
+        bf16x8 pf[RTW][2];
+#pragma unroll
+        for (int rt = 0; rt < RTW; ++rt) {
+            float sv[16];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float s = S[rt][i] * p.scale_log2;
+                if (ragged) {
+                    const int j = t * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
+                    bool ok = j < Lk;
+                    if (BC) {
+                        const int pos = (j < e1) ? p.seg[0].pos0 + j
+                                                 : ((j < e2) ? p.seg[1].pos0 + (j - e1) : p.seg[2].pos0 + (j - e2));
+                        ok = ok && (pos < qlim[rt]);
+                    }
+                    if (!ok) s = -INFINITY;
+                }
+                sv[i] = s;
+                mx = fmaxf(mx, s);
+            }
+            mx = fmaxf(mx, shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run[rt], mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2(m_run[rt] - m_use);
+            float rs = 0.f;
+            uint32_t pk[8];
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float p0 = fast_exp2(sv[i] - m_use), p1 = fast_exp2(sv[i + 1] - m_use);
+                rs += p0 + p1;
+                pk[i >> 1] = pack_bf16x2(p0, p1);
+            }
+            l_run[rt] = l_run[rt] * alpha + rs;
+            m_run[rt] = m_new;
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) O[rt][dt][i] *= alpha;
+            u32x4 lo = {pk[0], pk[1], pk[2], pk[3]}, hi4 = {pk[4], pk[5], pk[6], pk[7]};
+            pf[rt][0] = as_bf16x8(lo);
+            pf[rt][1] = as_bf16x8(hi4);
+        }
+
+        // ---- O^T += V^T P^T ----------------------------------------------------
+        const int s16 = lane & 15, blk = (lane >> 4) & 1;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) {
+#pragma unroll
+            for (int j2 = 0; j2 < 2; ++j2) {
+                union { s16x4 h[2]; bf16x8 v; } vf;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int krow = 16 * j2 + 8 * q + 4 * hi + (s16 >> 2);
+                    const int dcol = 32 * dt + 16 * blk + 4 * (s16 & 3);
+                    vf.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Vl + krow * VP + dcol * 2));
+                }
+#pragma unroll
+                for (int rt = 0; rt < RTW; ++rt)
+                    O[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[rt][j2], O[rt][dt], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- finish -----------------------------------------------------------------
+    constexpr float LN2 = 0.6931471805599453f;
+    if (NWK == 1) {
+#pragma unroll
+        for (int rt = 0; rt < RTW; ++rt) {
+            const float l = l_run[rt] + shfl_xor(l_run[rt], 32);
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            const int r = r0 + (wr * RTW + rt) * 32 + n;
+            if (r < p.R) {
+                const int i = r / p.g, hg = r - i * p.g;
+                const int h = kvh * p.g + hg;
+                uint16_t* op = p.out + b * p.o_sb + i * p.o_st + (int64_t)h * p.o_sh;
+#pragma unroll
+                for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        u32x2 v;
+                        v[0] = pack_bf16x2(O[rt][dt][4 * q4] * inv, O[rt][dt][4 * q4 + 1] * inv);
+                        v[1] = pack_bf16x2(O[rt][dt][4 * q4 + 2] * inv, O[rt][dt][4 * q4 + 3] * inv);
+                        *reinterpret_cast<u32x2*>(op + 32 * dt + 8 * q4 + 4 * hi) = v;
+                    }
+                if (p.lse && hi == 0)
+                    p.lse[((int64_t)b * p.Hq + h) * p.Lq + i] = l > 0.f ? (m_run[rt] + log2f(l)) * LN2 : -INFINITY;
+            }
+        }
+    } else {
+        float* mb = reinterpret_cast<float*>(smem);
+#pragma unroll
+        for (int rt = 0; rt < RTW; ++rt) {
+            __syncthreads();  // tiles (or the previous row tile's merge data) are no longer needed
+            const float l = l_run[rt] + shfl_xor(l_run[rt], 32);
+            float* row = mb + (wk * 32 + n) * MP;
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    f32x4 v = {O[rt][dt][4 * q4], O[rt][dt][4 * q4 + 1], O[rt][dt][4 * q4 + 2], O[rt][dt][4 * q4 + 3]};
+                    *reinterpret_cast<f32x4*>(row + 32 * dt + 8 * q4 + 4 * hi) = v;
+                }
+            if (hi == 0) {
+                row[D] = m_run[rt];
+                row[D + 1] = l;
+            }
+            __syncthreads();
+            for (int task = tid; task < 32 * C8; task += NT) {
+                const int rr = task / C8, c8 = task - rr * C8;
+                const int r = r0 + rt * 32 + rr;
+                if (r >= p.R) continue;
+                float M = -INFINITY;
+#pragma unroll
+                for (int k = 0; k < NWK; ++k) M = fmaxf(M, mb[(k * 32 + rr) * MP + D]);
+                float wgt[NWK], den = 0.f;
+#pragma unroll
+                for (int k = 0; k < NWK; ++k) {
+                    const float mk = mb[(k * 32 + rr) * MP + D];
+                    wgt[k] = (mk == -INFINITY) ? 0.f : fast_exp2(mk - M);
+                    den += wgt[k] * mb[(k * 32 + rr) * MP + D + 1];
+                }
+                const float inv = den > 0.f ? 1.f / den : 0.f;
+                float o[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+                for (int k = 0; k < NWK; ++k) {
+                    const f32x4 a = *reinterpret_cast<const f32x4*>(mb + (k * 32 + rr) * MP + 8 * c8);
+                    const f32x4 c = *reinterpret_cast<const f32x4*>(mb + (k * 32 + rr) * MP + 8 * c8 + 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        o[e] += wgt[k] * a[e];
+                        o[4 + e] += wgt[k] * c[e];
+                    }
+                }
+                const int i = r / p.g, hg = r - i * p.g;
+                const int h = kvh * p.g + hg;
+                u32x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = pack_bf16x2(o[2 * e] * inv, o[2 * e + 1] * inv);
+                *reinterpret_cast<u32x4*>(p.out + b * p.o_sb + i * p.o_st + (int64_t)h * p.o_sh + 8 * c8) = v;
+                if (p.lse && c8 == 0)
+                    p.lse[((int64_t)b * p.Hq + h) * p.Lq + i] = den > 0.f ? (M + log2f(den)) * LN2 : -INFINITY;
+            }
+        }
+    }
+}
+
+int g_attn_variant = 0;  // 0 = choose by shape; 1..3 force a kernel shape (dlm_set_option "attn_variant")
+
+template <int D, bool BC>
+static int launch_attn(const AttnParams& p, hipStream_t st) {
+    const int64_t BH = (int64_t)p.B * p.Hkv;
+    int variant = g_attn_variant;
+    if (variant == 0) {
+        if (p.R <= 32) variant = 1;                                  // waves split the keys, merge on chip
+        else if (BH * ((p.R + 255) / 256) < 1024) variant = 2;       // 128-row workgroups: more of them
+        else variant = 3;                                            // 256-row workgroups
+    }
+    if (variant == 1 && p.R > 32) variant = 2;
+    if (variant == 1) {
+        hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
+    } else if (variant == 2) {
+        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC>), dim3((p.R + 127) / 128, p.Hkv, p.B), dim3(256), 0, st, p);
+    } else {
+        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 2, BC>), dim3((p.R + 255) / 256, p.Hkv, p.B), dim3(256), 0, st, p);
+    }
+    return check_hip(hipGetLastError(), "attn_kernel launch");
+}
+
+static int validate_seg(const dlm_kv_seg& s, const char* name, int d) {
+    if (s.len < 0) return fail(DLM_ERR_INVALID_ARG, "block_attn: %s.len < 0", name);
+    if (s.len == 0) return DLM_OK;
+    if (!s.k || !s.v) return fail(DLM_ERR_INVALID_ARG, "block_attn: %s has null k/v", name);
+    if (!aligned16(s.k) || !aligned16(s.v)) return fail(DLM_ERR_UNSUPPORTED, "block_attn: %s k/v not 16-byte aligned", name);
+    if ((s.stride_b | s.stride_h | s.stride_t) % 8) return fail(DLM_ERR_UNSUPPORTED, "block_attn: %s strides must be multiples of 8", name);
+    if (s.stride_t < d) return fail(DLM_ERR_INVALID_ARG, "block_attn: %s.stride_t < d", name);
+    if (s.pos0 < 0 || (int64_t)s.pos0 + s.len > (1 << 30)) return fail(DLM_ERR_INVALID_ARG, "block_attn: %s positions outside [0, 2^30]", name);
+    return DLM_OK;
+}
+
+static int validate_attn(const dlm_attn_args* a) {
+    if (!a) return fail(DLM_ERR_INVALID_ARG, "block_attn: null args");
+    if (a->struct_size != sizeof(dlm_attn_args))
+        return fail(DLM_ERR_INVALID_ARG, "block_attn: struct_size %u != %zu", a->struct_size, sizeof(dlm_attn_args));
+    if (a->B < 0 || a->Lq < 0 || a->Hq <= 0 || a->Hkv <= 0 || a->d <= 0)
+        return fail(DLM_ERR_INVALID_ARG, "block_attn: bad sizes B=%d Lq=%d Hq=%d Hkv=%d d=%d", a->B, a->Lq, a->Hq, a->Hkv, a->d);
+    if (a->Hq % a->Hkv) return fail(DLM_ERR_INVALID_ARG, "block_attn: Hq=%d is not a multiple of Hkv=%d", a->Hq, a->Hkv);
+    if (a->d != 64 && a->d != 128) return fail(DLM_ERR_UNSUPPORTED, "block_attn: head_dim %d (supported: 64, 128)", a->d);
+    if (a->mask_mode != DLM_MASK_FULL && a->mask_mode != DLM_MASK_BLOCK_CAUSAL)
+        return fail(DLM_ERR_INVALID_ARG, "block_attn: unknown mask_mode %d", a->mask_mode);
+    if (a->mask_mode == DLM_MASK_BLOCK_CAUSAL) {
+        if (a->block_size < 1) return fail(DLM_ERR_INVALID_ARG, "block_attn: block-causal needs block_size >= 1");
+        if (a->q_pos0 < 0 || (int64_t)a->q_pos0 + a->Lq + a->block_size > (1 << 30))
+            return fail(DLM_ERR_INVALID_ARG, "block_attn: query positions outside [0, 2^30]");
+    }
+    if (a->B > 65535 || a->Hkv > 65535) return fail(DLM_ERR_UNSUPPORTED, "block_attn: B or Hkv above 65535");
+    if ((int64_t)a->Lq * (a->Hq / a->Hkv) > (1 << 30)) return fail(DLM_ERR_UNSUPPORTED, "block_attn: too many rows per KV head");
+    int rc;
+    if ((rc = validate_seg(a->prefix, "prefix", a->d)) != DLM_OK) return rc;
+    if ((rc = validate_seg(a->block, "block", a->d)) != DLM_OK) return rc;
+    if ((rc = validate_seg(a->suffix, "suffix", a->d)) != DLM_OK) return rc;
+    if ((int64_t)a->prefix.len + a->block.len + a->suffix.len > (1 << 30))
+        return fail(DLM_ERR_UNSUPPORTED, "block_attn: more than 2^30 keys");
+    if (a->B == 0 || a->Lq == 0) return DLM_OK;
+    if (!a->q || !a->out) return fail(DLM_ERR_INVALID_ARG, "block_attn: null q/out");
+    if (!aligned16(a->q) || !aligned16(a->out)) return fail(DLM_ERR_UNSUPPORTED, "block_attn: q/out not 16-byte aligned");
+    if ((a->q_stride_b | a->q_stride_t | a->q_stride_h | a->o_stride_b | a->o_stride_t | a->o_stride_h) % 8)
+        return fail(DLM_ERR_UNSUPPORTED, "block_attn: q/out strides must be multiples of 8");
+    if (a->q_stride_h < a->d || a->o_stride_h < a->d) return fail(DLM_ERR_INVALID_ARG, "block_attn: head stride < d");
+    if (!(a->scale == a->scale)) return fail(DLM_ERR_INVALID_ARG, "block_attn: scale is NaN");
+    return DLM_OK;
+}
+
+}  // namespace dlm
+
+using namespace dlm;
+
+extern "C" int dlm_set_option(const char* name, int value) {
+    if (!name) return fail(DLM_ERR_INVALID_ARG, "set_option: null name");
+    if (!strcmp(name, "attn_variant")) {
+        if (value < 0 || value > 3) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..3");
+        g_attn_variant = value;
+        return DLM_OK;
+    }
+    return fail(DLM_ERR_INVALID_ARG, "set_option: unknown option '%s'", name);
+}
+
+extern "C" size_t dlm_block_attn_workspace_bytes(const dlm_attn_args* a) {
+    (void)a;
+    return 0;  // key-split partials are merged on chip
+}
+
+extern "C" int dlm_block_attn(const dlm_attn_args* a, void* stream) {
+    int rc = validate_attn(a);
+    if (rc != DLM_OK) return rc;
+    if (a->B == 0 || a->Lq == 0) return DLM_OK;
+    AttnParams p;
+    p.B = a->B; p.Lq = a->Lq; p.Hq = a->Hq; p.Hkv = a->Hkv; p.g = a->Hq / a->Hkv; p.R = p.g * a->Lq;
+    p.q = (const uint16_t*)a->q; p.q_sb = a->q_stride_b; p.q_st = a->q_stride_t; p.q_sh = a->q_stride_h;
+    const dlm_kv_seg* segs[3] = {&a->prefix, &a->block, &a->suffix};
+    for (int s = 0; s < 3; ++s) {
+        p.seg[s].k = (const uint16_t*)segs[s]->k; p.seg[s].v = (const uint16_t*)segs[s]->v;
+        p.seg[s].len = segs[s]->len; p.seg[s].pos0 = segs[s]->pos0;
+        p.seg[s].sb = segs[s]->stride_b; p.seg[s].sh = segs[s]->stride_h; p.seg[s].st = segs[s]->stride_t;
+    }
+    p.prefix_len_b = a->prefix_len_b;
+    p.bs = a->block_size; p.q_pos0 = a->q_pos0;
+    const float scale = a->scale > 0.f ? a->scale : 1.0f / sqrtf((float)a->d);
+    p.scale_log2 = scale * 1.4426950408889634f;
+    p.out = (uint16_t*)a->out; p.o_sb = a->o_stride_b; p.o_st = a->o_stride_t; p.o_sh = a->o_stride_h;
+    p.lse = a->lse;
+    hipStream_t st = (hipStream_t)stream;
+    const bool bc = a->mask_mode == DLM_MASK_BLOCK_CAUSAL;
+    if (a->d == 128) return bc ? launch_attn<128, true>(p, st) : launch_attn<128, false>(p, st);
+    return bc ? launch_attn<64, true>(p, st) : launch_attn<64, false>(p, st);
+}

@@ -1,0 +1,362 @@
+// dlm_unmask_commit, dlm_mask_compact, dlm_kv_refresh: selection of the positions
+// to fix in this denoising step, token / mask update, compaction of the rows that
+// stay masked, and the K/V copies into the cache.
+//
+// Selection is integer work decided by fp32 compares: one wavefront owns one
+// commit group (a block of the rollout, or one block of a block-diffusion
+// sequence), keeps the group's confidences in registers and finds arg-maxima
+// with xor-shuffles, so the result is independent of scheduling.
+#include "common.hpp"
+
+namespace dlm {
+
+struct Cand {
+    float v;
+    int i;
+};
+__device__ __forceinline__ bool better(float av, int ai, float bv, int bi) {
+    return av > bv || (av == bv && ai < bi);
+}
+__device__ __forceinline__ Cand wave_argmax(Cand c) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        float ov = shfl_xor(c.v, off);
+        int oi = shfl_xor(c.i, off);
+        if (better(ov, oi, c.v, c.i)) { c.v = ov; c.i = oi; }
+    }
+    return c;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += shfl_xor(v, off);
+    return v;
+}
+
+struct CommitParams {
+    int B, n_pos, group_len, n_groups;
+    int rule;
+    float threshold;
+    int force_top1, k;
+    const float* conf;
+    const int32_t* tok;
+    int32_t* x;
+    int64_t x_stride_b;
+    int x_pos0;
+    uint8_t* mask;
+    int64_t mask_stride_b;
+    uint8_t* commit_now;
+    int32_t *n_commit, *remaining;
+    int16_t* commit_step;
+    int step;
+};
+
+// CH = ceil(group_len / 64): positions per lane.
+template <int CH>
+__global__ __launch_bounds__(256) void commit_wave_kernel(CommitParams p) {
+    const int lane = lane_id();
+    const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (gw >= p.B * p.n_groups) return;
+    const int b = gw / p.n_groups, gi = gw - b * p.n_groups;
+    const int g0 = gi * p.group_len;
+    const int64_t base = (int64_t)b * p.n_pos + g0;
+    uint8_t* mrow = p.mask + b * p.mask_stride_b + g0;
+
+    float cf[CH];
+    bool masked[CH], chosen[CH];
+    int cnt = 0;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int i = lane + 64 * c;
+        masked[c] = (i < p.group_len) && (mrow[i] != 0);
+        chosen[c] = false;
+        float v = -INFINITY;
+        if (masked[c]) {
+            v = p.conf[base + i];
+            if (!(v == v)) v = -INFINITY;
+            ++cnt;
+        }
+        cf[c] = v;
+    }
+    cnt = wave_sum(cnt);
+    int ncom = 0;
+    if (cnt > 0) {
+        if (p.rule == DLM_RULE_THRESHOLD) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) chosen[c] = masked[c] && (cf[c] >= p.threshold);
+            if (p.force_top1) {
+                Cand best{-INFINITY, 0x7fffffff};
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    if (masked[c] && better(cf[c], lane + 64 * c, best.v, best.i)) best = Cand{cf[c], lane + 64 * c};
+                best = wave_argmax(best);
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    if (masked[c] && best.i == lane + 64 * c) chosen[c] = true;
+            }
+        } else {
+            const int kk = min(p.k, cnt);
+            for (int it = 0; it < kk; ++it) {
+                Cand best{-INFINITY, 0x7fffffff};
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    if (masked[c] && !chosen[c] && better(cf[c], lane + 64 * c, best.v, best.i))
+                        best = Cand{cf[c], lane + 64 * c};
+                best = wave_argmax(best);
+#pragma unroll
+                for (int c = 0; c < CH; ++c)
+                    if (masked[c] && best.i == lane + 64 * c) chosen[c] = true;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int i = lane + 64 * c;
+            if (chosen[c]) {
+                p.x[b * p.x_stride_b + p.x_pos0 + g0 + i] = p.tok[base + i];
+                mrow[i] = 0;
+                if (p.commit_step) p.commit_step[base + i] = (int16_t)p.step;
+                ++ncom;
+            }
+        }
+        ncom = wave_sum(ncom);
+    }
+    if (p.commit_now) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int i = lane + 64 * c;
+            if (i < p.group_len) p.commit_now[base + i] = chosen[c] ? 1 : 0;
+        }
+    }
+    if (lane == 0) {
+        if (p.n_groups == 1) {
+            p.n_commit[b] = ncom;
+            p.remaining[b] = cnt - ncom;
+        } else if (cnt > 0) {
+            atomicAdd(&p.n_commit[b], ncom);           // integer sums: order-independent
+            atomicAdd(&p.remaining[b], cnt - ncom);
+        }
+    }
+}
+
+__global__ void zero2_i32_kernel(int32_t* a, int32_t* b, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { a[i] = 0; b[i] = 0; }
+}
+
+// Ordered stream compaction of mask != 0 by a single 1024-thread workgroup.
+__global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* mask, int64_t mask_stride_b, int B, int n_pos,
+                                                        int32_t* row_idx, int32_t* m_out) {
+    __shared__ int wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t N = (int64_t)B * n_pos;
+    int running = 0;
+    for (int64_t start = 0; start < N; start += 1024) {
+        const int64_t idx = start + tid;
+        bool flag = false;
+        if (idx < N) {
+            const int b = (int)(idx / n_pos), i = (int)(idx - (int64_t)b * n_pos);
+            flag = mask[b * mask_stride_b + i] != 0;
+        }
+        const unsigned long long bal = __ballot(flag);
+        const int prefix = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_tot[w] = __popcll(bal);
+        __syncthreads();
+        int off = running, all = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int t = wave_tot[j];
+            if (j < w) off += t;
+            all += t;
+        }
+        if (flag) row_idx[off + prefix] = (int32_t)idx;
+        running += all;
+        __syncthreads();
+    }
+    if (tid == 0) *m_out = running;
+}
+
+struct CopyParams {
+    const uint16_t *sk, *sv;
+    int64_t s_sb, s_sh, s_st;
+    uint16_t *ck, *cv;
+    int64_t c_sb, c_sh, c_st;
+    int len, d8;  // rows, 16-byte chunks per row
+    int cache_pos0;
+    // conditional write-back
+    int mode;  // 0 unconditional, DLM_WB_BLOCK_WHEN_DONE, DLM_WB_COMMITTED_ROWS
+    const int32_t *n_commit, *remaining;
+    const uint8_t* commit_now;
+    int n_pos;
+};
+
+template <int U>
+__global__ __launch_bounds__(256) void kv_copy_kernel(CopyParams p) {
+    const int b = blockIdx.z, h = blockIdx.y;
+    if (p.mode == DLM_WB_BLOCK_WHEN_DONE) {
+        if (!(p.remaining[b] == 0 && p.n_commit[b] > 0)) return;
+    }
+    const int64_t total = (int64_t)p.len * p.d8;
+    const uint16_t* sk = p.sk + b * p.s_sb + h * p.s_sh;
+    const uint16_t* sv = p.sv + b * p.s_sb + h * p.s_sh;
+    uint16_t* ck = p.ck + b * p.c_sb + h * p.c_sh + (int64_t)p.cache_pos0 * p.c_st;
+    uint16_t* cv = p.cv + b * p.c_sb + h * p.c_sh + (int64_t)p.cache_pos0 * p.c_st;
+    u32x4 kreg[U], vreg[U];
+    int64_t so[U], co[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t e = ((int64_t)blockIdx.x * U + u) * 256 + threadIdx.x;
+        ok[u] = e < total;
+        const int t = ok[u] ? (int)(e / p.d8) : 0;
+        const int c = ok[u] ? (int)(e - (int64_t)t * p.d8) : 0;
+        if (p.mode == DLM_WB_COMMITTED_ROWS && ok[u]) ok[u] = p.commit_now[(int64_t)b * p.n_pos + t] != 0;
+        so[u] = t * p.s_st + c * 8;
+        co[u] = t * p.c_st + c * 8;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (ok[u]) {
+            kreg[u] = *reinterpret_cast<const u32x4*>(sk + so[u]);
+            vreg[u] = *reinterpret_cast<const u32x4*>(sv + so[u]);
+        }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (ok[u]) {
+            *reinterpret_cast<u32x4*>(ck + co[u]) = kreg[u];
+            *reinterpret_cast<u32x4*>(cv + co[u]) = vreg[u];
+        }
+}
+
+static int validate_seg_copy(const dlm_kv_seg* s, int B, int Hkv, int d, const void* ck, const void* cv,
+                             int64_t c_sb, int64_t c_sh, int64_t c_st, int cache_pos0) {
+    if (!s) return fail(DLM_ERR_INVALID_ARG, "kv copy: null source segment");
+    if (B < 0 || Hkv <= 0 || d <= 0 || s->len < 0 || cache_pos0 < 0)
+        return fail(DLM_ERR_INVALID_ARG, "kv copy: negative size (B=%d Hkv=%d d=%d len=%d pos0=%d)", B, Hkv, d, s->len, cache_pos0);
+    if (d % 8) return fail(DLM_ERR_UNSUPPORTED, "kv copy: d=%d is not a multiple of 8", d);
+    if (s->len == 0 || B == 0) return DLM_OK;
+    if (!s->k || !s->v || !ck || !cv) return fail(DLM_ERR_INVALID_ARG, "kv copy: null K/V pointer");
+    if (!aligned16(s->k) || !aligned16(s->v) || !aligned16(ck) || !aligned16(cv))
+        return fail(DLM_ERR_UNSUPPORTED, "kv copy: pointers must be 16-byte aligned");
+    if ((s->stride_b | s->stride_h | s->stride_t | c_sb | c_sh | c_st) % 8)
+        return fail(DLM_ERR_UNSUPPORTED, "kv copy: strides must be multiples of 8 elements");
+    if (s->stride_t < d || c_st < d) return fail(DLM_ERR_INVALID_ARG, "kv copy: row stride smaller than d");
+    return DLM_OK;
+}
+
+static int launch_kv_copy(const dlm_kv_seg* s, int B, int Hkv, int d, void* ck, void* cv, int64_t c_sb, int64_t c_sh,
+                          int64_t c_st, int cache_pos0, int mode, const int32_t* n_commit, const int32_t* remaining,
+                          const uint8_t* commit_now, int n_pos, hipStream_t st) {
+    if (s->len == 0 || B == 0) return DLM_OK;
+    CopyParams p;
+    p.sk = (const uint16_t*)s->k; p.sv = (const uint16_t*)s->v;
+    p.s_sb = s->stride_b; p.s_sh = s->stride_h; p.s_st = s->stride_t;
+    p.ck = (uint16_t*)ck; p.cv = (uint16_t*)cv;
+    p.c_sb = c_sb; p.c_sh = c_sh; p.c_st = c_st;
+    p.len = s->len; p.d8 = d / 8; p.cache_pos0 = cache_pos0;
+    p.mode = mode; p.n_commit = n_commit; p.remaining = remaining; p.commit_now = commit_now; p.n_pos = n_pos;
+    const int64_t total = (int64_t)s->len * p.d8;
+    if (Hkv > 65535 || B > 65535) return fail(DLM_ERR_UNSUPPORTED, "kv copy: B or Hkv above 65535");
+    constexpr int U = 4;
+    const int64_t gx = (total + 256 * U - 1) / (256 * U);
+    if (gx > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "kv copy: segment too long");
+    hipLaunchKernelGGL(kv_copy_kernel<U>, dim3((unsigned)gx, Hkv, B), dim3(256), 0, st, p);
+    return check_hip(hipGetLastError(), "kv_copy_kernel launch");
+}
+
+}  // namespace dlm
+
+using namespace dlm;
+
+extern "C" int dlm_kv_refresh(const dlm_kv_seg* src, int32_t B, int32_t Hkv, int32_t d, void* cache_k, void* cache_v,
+                              int64_t c_stride_b, int64_t c_stride_h, int64_t c_stride_t, int32_t cache_pos0,
+                              void* stream) {
+    int rc = validate_seg_copy(src, B, Hkv, d, cache_k, cache_v, c_stride_b, c_stride_h, c_stride_t, cache_pos0);
+    if (rc != DLM_OK) return rc;
+    return launch_kv_copy(src, B, Hkv, d, cache_k, cache_v, c_stride_b, c_stride_h, c_stride_t, cache_pos0, 0, nullptr,
+                          nullptr, nullptr, 0, (hipStream_t)stream);
+}
+
+extern "C" int dlm_mask_compact(const uint8_t* mask, int64_t mask_stride_b, int32_t B, int32_t n_pos, int32_t* row_idx,
+                                int32_t* m_out, void* stream) {
+    if (B < 0 || n_pos < 0) return fail(DLM_ERR_INVALID_ARG, "mask_compact: negative size");
+    if (!m_out) return fail(DLM_ERR_INVALID_ARG, "mask_compact: null m_out");
+    if ((int64_t)B * n_pos > 0 && (!mask || !row_idx)) return fail(DLM_ERR_INVALID_ARG, "mask_compact: null pointer");
+    if ((int64_t)B * n_pos > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "mask_compact: more than 2^31 positions");
+    if (B > 0 && n_pos > 0 && mask_stride_b < n_pos) return fail(DLM_ERR_INVALID_ARG, "mask_compact: stride < n_pos");
+    hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, mask, mask_stride_b, B, n_pos,
+                       row_idx, m_out);
+    return check_hip(hipGetLastError(), "compact_kernel launch");
+}
+
+extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
+    if (!a) return fail(DLM_ERR_INVALID_ARG, "unmask_commit: null args");
+    if (a->struct_size != sizeof(dlm_commit_args))
+        return fail(DLM_ERR_INVALID_ARG, "unmask_commit: struct_size %u != %zu", a->struct_size, sizeof(dlm_commit_args));
+    if (a->B < 0 || a->n_pos < 0) return fail(DLM_ERR_INVALID_ARG, "unmask_commit: negative B or n_pos");
+    if (a->group_len < 1 || a->group_len > 1024)
+        return fail(DLM_ERR_INVALID_ARG, "unmask_commit: group_len=%d outside [1, 1024]", a->group_len);
+    if (a->n_pos % a->group_len) return fail(DLM_ERR_INVALID_ARG, "unmask_commit: n_pos %% group_len != 0");
+    if (a->rule != DLM_RULE_THRESHOLD && a->rule != DLM_RULE_TOPK)
+        return fail(DLM_ERR_INVALID_ARG, "unmask_commit: unknown rule %d", a->rule);
+    if (a->rule == DLM_RULE_TOPK && a->k < 1) return fail(DLM_ERR_INVALID_ARG, "unmask_commit: top-k needs k >= 1");
+    if (a->rule == DLM_RULE_THRESHOLD && !(a->threshold == a->threshold))
+        return fail(DLM_ERR_INVALID_ARG, "unmask_commit: threshold is NaN");
+    if (a->writeback < DLM_WB_NONE || a->writeback > DLM_WB_COMMITTED_ROWS)
+        return fail(DLM_ERR_INVALID_ARG, "unmask_commit: unknown writeback mode %d", a->writeback);
+    const int64_t N = (int64_t)a->B * a->n_pos;
+    if (N > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "unmask_commit: more than 2^31 positions");
+    if (a->B > 0 && (!a->n_commit || !a->remaining)) return fail(DLM_ERR_INVALID_ARG, "unmask_commit: null n_commit/remaining");
+    if (N > 0) {
+        if (!a->conf || !a->tok || !a->x || !a->mask) return fail(DLM_ERR_INVALID_ARG, "unmask_commit: null conf/tok/x/mask");
+        if (a->mask_stride_b < a->n_pos || a->x_stride_b < (int64_t)a->x_pos0 + a->n_pos || a->x_pos0 < 0)
+            return fail(DLM_ERR_INVALID_ARG, "unmask_commit: x/mask stride too small for n_pos (+x_pos0)");
+    }
+    if ((a->next_row_idx == nullptr) != (a->next_m == nullptr))
+        return fail(DLM_ERR_INVALID_ARG, "unmask_commit: next_row_idx and next_m go together");
+    if (a->writeback != DLM_WB_NONE) {
+        if (a->src_block.len <= 0) return fail(DLM_ERR_INVALID_ARG, "unmask_commit: write-back needs a non-empty src_block");
+        int rc = validate_seg_copy(&a->src_block, a->B, a->Hkv, a->d, a->cache_k, a->cache_v, a->c_stride_b,
+                                   a->c_stride_h, a->c_stride_t, a->cache_pos0);
+        if (rc != DLM_OK) return rc;
+        if (a->writeback == DLM_WB_COMMITTED_ROWS) {
+            if (a->src_block.len != a->n_pos)
+                return fail(DLM_ERR_INVALID_ARG, "unmask_commit: COMMITTED_ROWS needs src_block.len == n_pos");
+            if (!a->commit_now && N > 0)
+                return fail(DLM_ERR_INVALID_ARG, "unmask_commit: COMMITTED_ROWS needs commit_now");
+        }
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (a->B == 0) return DLM_OK;
+    const int n_groups = a->n_pos / a->group_len;
+    if (N > 0) {
+        CommitParams p;
+        p.B = a->B; p.n_pos = a->n_pos; p.group_len = a->group_len; p.n_groups = n_groups;
+        p.rule = a->rule; p.threshold = a->threshold; p.force_top1 = a->force_top1; p.k = a->k;
+        p.conf = a->conf; p.tok = a->tok; p.x = a->x; p.x_stride_b = a->x_stride_b; p.x_pos0 = a->x_pos0;
+        p.mask = a->mask; p.mask_stride_b = a->mask_stride_b; p.commit_now = a->commit_now;
+        p.n_commit = a->n_commit; p.remaining = a->remaining; p.commit_step = a->commit_step; p.step = a->step;
+        if (n_groups != 1) {
+            hipLaunchKernelGGL(zero2_i32_kernel, dim3((a->B + 255) / 256), dim3(256), 0, st, a->n_commit, a->remaining, a->B);
+        }
+        const int64_t waves = (int64_t)a->B * n_groups;
+        const unsigned grid = (unsigned)((waves + 3) / 4);
+        if (a->group_len <= 64) hipLaunchKernelGGL(commit_wave_kernel<1>, dim3(grid), dim3(256), 0, st, p);
+        else if (a->group_len <= 256) hipLaunchKernelGGL(commit_wave_kernel<4>, dim3(grid), dim3(256), 0, st, p);
+        else hipLaunchKernelGGL(commit_wave_kernel<16>, dim3(grid), dim3(256), 0, st, p);
+        int rc = check_hip(hipGetLastError(), "commit_wave_kernel launch");
+        if (rc != DLM_OK) return rc;
+    } else {
+        hipLaunchKernelGGL(zero2_i32_kernel, dim3((a->B + 255) / 256), dim3(256), 0, st, a->n_commit, a->remaining, a->B);
+    }
+    if (a->next_row_idx) {
+        hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, a->mask, a->mask_stride_b, a->B, a->n_pos,
+                           a->next_row_idx, a->next_m);
+        int rc = check_hip(hipGetLastError(), "compact_kernel launch");
+        if (rc != DLM_OK) return rc;
+    }
+    if (a->writeback != DLM_WB_NONE && N > 0) {
+        return launch_kv_copy(&a->src_block, a->B, a->Hkv, a->d, a->cache_k, a->cache_v, a->c_stride_b, a->c_stride_h,
+                              a->c_stride_t, a->cache_pos0, a->writeback, a->n_commit, a->remaining, a->commit_now,
+                              a->n_pos, st);
+    }
+    return DLM_OK;
+}

@@ -1,0 +1,321 @@
+// dlm_lmhead_confidence: fused hidden x W_vocab^T with online max / arg-max /
+// runner-up / sum-of-exp per row, so the [M, V] logits never leave the chip.
+//
+// Work decomposition (gfx950, MFMA 32x32x16 bf16):
+//   * The product is computed transposed, Z^T = W H^T: vocabulary rows are the MFMA
+//     A operand (matrix rows), hidden rows the B operand (matrix columns).  A lane then
+//     holds 16 vocabulary entries of ONE hidden row per accumulator tile, so the
+//     per-row reductions over the vocabulary are in-register, plus one exchange with
+//     lane^32 and one small LDS merge across the wavefronts of the workgroup.
+//   * A workgroup owns TV vocabulary rows and up to MB hidden rows and streams its
+//     W panel exactly once from HBM over the Dh axis in 64-element chunks, LDS
+//     double-buffered with register prefetch; the (small) H panel is re-read from
+//     L2 by every workgroup.
+//   * Each workgroup writes one partial (max, sumexp, argmax, runner-up) per row;
+//     a second kernel merges the V/TV partials per row in a fixed order
+//     (deterministic; ties resolve to the lowest vocabulary index).
+#include "common.hpp"
+
+namespace dlm {
+
+struct LmParams {
+    int M, Dh, V;
+    const uint16_t* hidden;
+    int64_t h_stride;
+    const int32_t* row_idx;
+    const int32_t* m_dev;
+    const uint16_t* w;
+    int64_t w_stride;
+    float inv_t;
+    int forbid;
+    int out_scatter;
+    float* conf;
+    int32_t* tok;
+    float *lse, *zmax, *z2nd;
+    const int32_t* target;
+    float* ztarget;
+    f32x4* part;  // [n_vtiles][M] of (max, sumexp, runner-up, argmax bits)
+    int n_vt;
+};
+
+struct Red {
+    float m, s, m2;
+    int idx;
+};
+// merge two partial reductions; on equal maxima the lower index wins and the runner-up equals the maximum
+__device__ __forceinline__ Red red_merge(const Red a, const Red b) {
+    const bool takeb = (b.m > a.m) || (b.m == a.m && b.idx < a.idx);
+    const float mx = fmaxf(a.m, b.m), mn = fminf(a.m, b.m);
+    const float sa = (a.m == -INFINITY) ? 0.f : a.s * fast_exp2((a.m - mx) * 1.4426950408889634f);
+    const float sb = (b.m == -INFINITY) ? 0.f : b.s * fast_exp2((b.m - mx) * 1.4426950408889634f);
+    const int ai = a.idx, bi = b.idx;
+    Red r;
+    r.m = mx;
+    r.s = sa + sb;
+    r.m2 = fmaxf(fmaxf(a.m2, b.m2), mn);
+    r.idx = takeb ? bi : ai;
+    return r;
+}
+__device__ __forceinline__ Red red_shfl_xor(const Red a, int off) {
+    Red o;
+    o.m = shfl_xor(a.m, off);
+    o.s = shfl_xor(a.s, off);
+    o.m2 = shfl_xor(a.m2, off);
+    o.idx = shfl_xor(a.idx, off);
+    return o;
+}
+
+constexpr int KC = 64;             // Dh elements per pipeline stage (128 B per row)
+constexpr int LP = KC * 2 + 16;    // LDS row pitch in bytes
+
+// WV x WH wavefronts; each owns TVW x THW accumulator tiles of 32 (vocab) x 32 (hidden rows).
+template <int WV, int WH, int TVW, int THW>
+__global__ __launch_bounds__(64 * WV * WH) void lmhead_kernel(LmParams p) {
+    constexpr int NT = 64 * WV * WH;
+    constexpr int TV = 32 * TVW * WV;   // vocabulary rows per workgroup
+    constexpr int MB = 32 * THW * WH;   // hidden rows per workgroup
+    constexpr int WLD = (TV * 8) / NT;  // 16-byte loads per thread per stage (8 per row)
+    constexpr int HLD = (MB * 8) / NT;
+    static_assert((TV * 8) % NT == 0 && (MB * 8) % NT == 0, "tile / thread mismatch");
+    constexpr int STAGE = (TV + MB) * LP;
+    constexpr int RED_BYTES = WV * MB * 16;
+    static_assert(2 * STAGE >= RED_BYTES, "reduction buffer must fit in the staging area");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wv = w % WV, wh = w / WV;
+    const int n = lane & 31, hi = lane >> 5;
+    const int v0 = blockIdx.x * TV;
+    const int m0 = blockIdx.y * MB;
+    int M = p.M;
+    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (m0 >= M) return;
+
+    // ---- global -> register staging addresses --------------------------------
+    const int lrow = tid >> 3, lc = tid & 7;  // 8 threads cover one 128-byte row segment
+    const uint16_t* wsrc[WLD];
+#pragma unroll
+    for (int q = 0; q < WLD; ++q) {
+        const int v = min(v0 + lrow + q * (NT / 8), p.V - 1);  // rows past V are clamped, masked in the epilogue
+        wsrc[q] = p.w + (int64_t)v * p.w_stride + lc * 8;
+    }
+    const uint16_t* hsrc[HLD];
+#pragma unroll
+    for (int q = 0; q < HLD; ++q) {
+        const int r = min(m0 + lrow + q * (NT / 8), M - 1);    // rows past M are clamped, never stored
+        const int64_t src = p.row_idx ? p.row_idx[r] : r;
+        hsrc[q] = p.hidden + src * p.h_stride + lc * 8;
+    }
+    u32x4 wreg[WLD], hreg[HLD];
+    auto gload = [&](int kc) {
+#pragma unroll
+        for (int q = 0; q < WLD; ++q) wreg[q] = *reinterpret_cast<const u32x4*>(wsrc[q] + kc * KC);
+#pragma unroll
+        for (int q = 0; q < HLD; ++q) hreg[q] = *reinterpret_cast<const u32x4*>(hsrc[q] + kc * KC);
+    };
+    auto lstore = [&](int buf) {
+        unsigned char* Wl = smem + buf * STAGE;
+        unsigned char* Hl = Wl + TV * LP;
+#pragma unroll
+        for (int q = 0; q < WLD; ++q) *reinterpret_cast<u32x4*>(Wl + (lrow + q * (NT / 8)) * LP + lc * 16) = wreg[q];
+#pragma unroll
+        for (int q = 0; q < HLD; ++q) *reinterpret_cast<u32x4*>(Hl + (lrow + q * (NT / 8)) * LP + lc * 16) = hreg[q];
+    };
+
+    f32x16 acc[TVW][THW];
+#pragma unroll
+    for (int a = 0; a < TVW; ++a)
+#pragma unroll
+        for (int c = 0; c < THW; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][c][i] = 0.f;
+
+    const int nk = p.Dh / KC;
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    for (int kc = 0; kc < nk; ++kc) {
+        const int buf = kc & 1;
+        if (kc + 1 < nk) gload(kc + 1);
+        const unsigned char* Wl = smem + buf * STAGE + (wv * TVW * 32 + n) * LP + hi * 16;
+        const unsigned char* Hl = smem + buf * STAGE + TV * LP + (wh * THW * 32 + n) * LP + hi * 16;
+#pragma unroll
+        for (int ks = 0; ks < KC / 16; ++ks) {
+            bf16x8 af[TVW], bfr[THW];
+#pragma unroll
+            for (int a = 0; a < TVW; ++a) af[a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP + ks * 32);
+#pragma unroll
+            for (int c = 0; c < THW; ++c) bfr[c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + ks * 32);
+#pragma unroll
+            for (int a = 0; a < TVW; ++a)
+#pragma unroll
+                for (int c = 0; c < THW; ++c)
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0);
+        }
+        if (kc + 1 < nk) lstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: per hidden row (matrix column) reduce over this workgroup's vocabulary rows
+    constexpr float LOG2E = 1.4426950408889634f;
+    f32x4* redbuf = reinterpret_cast<f32x4*>(smem);  // [WV][MB] of (max, sumexp, runner-up, argmax bits)
+    // (the loop above ended with a barrier: the staging area is free)
+#pragma unroll
+    for (int c = 0; c < THW; ++c) {
+        const int col = (wh * THW + c) * 32 + n;       // hidden row inside the workgroup's MB
+        const int r = m0 + col;
+        int tgt = -1;
+        int64_t oidx = 0;
+        if (r < M) {
+            oidx = (p.out_scatter && p.row_idx) ? (int64_t)p.row_idx[r] : (int64_t)r;
+            if (p.target) tgt = p.target[oidx];
+        }
+        Red red{-INFINITY, 0.f, -INFINITY, 0x7fffffff};
+#pragma unroll
+        for (int a = 0; a < TVW; ++a) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int v = v0 + (wv * TVW + a) * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
+                float z = acc[a][c][i] * p.inv_t;
+                if (v >= p.V || v == p.forbid) z = -INFINITY;
+                if (v == tgt) p.ztarget[oidx] = z;
+                acc[a][c][i] = z;
+                if (z > red.m) {
+                    red.m2 = red.m;
+                    red.m = z;
+                    red.idx = v;
+                } else if (z > red.m2) {
+                    red.m2 = z;
+                }
+            }
+        }
+        if (red.m > -INFINITY) {
+            const float mb = red.m * LOG2E;
+            float s = 0.f;
+#pragma unroll
+            for (int a = 0; a < TVW; ++a)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s += fast_exp2(acc[a][c][i] * LOG2E - mb);
+            red.s = s;
+        }
+        red = red_merge(red, red_shfl_xor(red, 32));
+        if (hi == 0) {
+            f32x4 packed = {red.m, red.s, red.m2, __int_as_float(red.idx)};
+            redbuf[wv * MB + col] = packed;
+        }
+    }
+    __syncthreads();
+    for (int col = tid; col < MB; col += NT) {
+        const int r = m0 + col;
+        if (r >= M) continue;
+        const f32x4 f = redbuf[col];
+        Red red{f[0], f[1], f[2], __float_as_int(f[3])};
+#pragma unroll
+        for (int k = 1; k < WV; ++k) {
+            const f32x4 o = redbuf[k * MB + col];
+            red = red_merge(red, Red{o[0], o[1], o[2], __float_as_int(o[3])});
+        }
+        f32x4 out = {red.m, red.s, red.m2, __int_as_float(red.idx)};
+        p.part[(int64_t)blockIdx.x * p.M + r] = out;
+    }
+}
+
+// One wavefront per row: merge the per-vocabulary-tile partials in a fixed tree order.
+__global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    int M = p.M;
+    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (r >= M) return;
+    Red red{-INFINITY, 0.f, -INFINITY, 0x7fffffff};
+    for (int t = lane; t < p.n_vt; t += 64) {
+        const f32x4 v = p.part[(int64_t)t * p.M + r];
+        red = red_merge(red, Red{v[0], v[1], v[2], __float_as_int(v[3])});
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) red = red_merge(red, red_shfl_xor(red, off));
+    if (lane == 0) {
+        const int64_t oidx = (p.out_scatter && p.row_idx) ? (int64_t)p.row_idx[r] : (int64_t)r;
+        p.conf[oidx] = 1.0f / red.s;          // exp(zmax - lse) = 1 / sum_v exp(z_v - zmax)
+        p.tok[oidx] = red.idx;
+        if (p.lse) p.lse[oidx] = red.m + logf(red.s);
+        if (p.zmax) p.zmax[oidx] = red.m;
+        if (p.z2nd) p.z2nd[oidx] = red.m2;
+    }
+}
+
+struct LmPlan {
+    int variant;  // index into the launch table
+    int tv, mb;
+};
+
+static LmPlan plan_lmhead(int M) {
+    if (M <= 32) return {0, 128, 32};
+    if (M <= 64) return {1, 128, 64};
+    if (M <= 128) return {2, 128, 128};
+    return {3, 128, 256};
+}
+
+static int validate_lm(const dlm_lmhead_args* a) {
+    if (!a) return fail(DLM_ERR_INVALID_ARG, "lmhead: null args");
+    if (a->struct_size != sizeof(dlm_lmhead_args))
+        return fail(DLM_ERR_INVALID_ARG, "lmhead: struct_size %u != %zu", a->struct_size, sizeof(dlm_lmhead_args));
+    if (a->M < 0 || a->Dh <= 0 || a->V <= 0) return fail(DLM_ERR_INVALID_ARG, "lmhead: bad sizes M=%d Dh=%d V=%d", a->M, a->Dh, a->V);
+    if (a->Dh % KC) return fail(DLM_ERR_UNSUPPORTED, "lmhead: Dh=%d is not a multiple of %d", a->Dh, KC);
+    if (a->forbid_token >= a->V) return fail(DLM_ERR_INVALID_ARG, "lmhead: forbid_token %d >= V", a->forbid_token);
+    if (a->forbid_token >= 0 && a->V < 2) return fail(DLM_ERR_INVALID_ARG, "lmhead: forbid_token with V < 2 leaves no token");
+    if (!(a->inv_temperature > 0.f) || a->inv_temperature > 3.0e38f) return fail(DLM_ERR_INVALID_ARG, "lmhead: inv_temperature must be positive and finite");
+    if ((a->target == nullptr) != (a->ztarget == nullptr)) return fail(DLM_ERR_INVALID_ARG, "lmhead: target and ztarget go together");
+    if (a->M == 0) return DLM_OK;
+    if (!a->hidden || !a->w || !a->conf || !a->tok) return fail(DLM_ERR_INVALID_ARG, "lmhead: null hidden/w/conf/tok");
+    if (!aligned16(a->hidden) || !aligned16(a->w)) return fail(DLM_ERR_UNSUPPORTED, "lmhead: hidden/w not 16-byte aligned");
+    if ((a->hidden_stride_row | a->w_stride_row) % 8) return fail(DLM_ERR_UNSUPPORTED, "lmhead: strides must be multiples of 8");
+    if (a->hidden_stride_row < a->Dh || a->w_stride_row < a->Dh) return fail(DLM_ERR_INVALID_ARG, "lmhead: row stride < Dh");
+    return DLM_OK;
+}
+
+}  // namespace dlm
+
+using namespace dlm;
+
+extern "C" size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args* a) {
+    if (!a || a->M <= 0 || a->V <= 0) return 0;
+    const LmPlan pl = plan_lmhead(a->M);
+    const size_t n_vt = ((size_t)a->V + pl.tv - 1) / pl.tv;
+    return n_vt * (size_t)a->M * sizeof(f32x4);
+}
+
+extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
+    int rc = validate_lm(a);
+    if (rc != DLM_OK) return rc;
+    if (a->M == 0) return DLM_OK;
+    const size_t need = dlm_lmhead_workspace_bytes(a);
+    if (!a->workspace || a->workspace_bytes < need)
+        return fail(DLM_ERR_WORKSPACE, "lmhead: workspace of %zu bytes needed, %zu given", need, a->workspace ? a->workspace_bytes : (size_t)0);
+    if (!aligned16(a->workspace)) return fail(DLM_ERR_WORKSPACE, "lmhead: workspace not 16-byte aligned");
+    const LmPlan pl = plan_lmhead(a->M);
+    LmParams p;
+    p.M = a->M; p.Dh = a->Dh; p.V = a->V;
+    p.hidden = (const uint16_t*)a->hidden; p.h_stride = a->hidden_stride_row;
+    p.row_idx = a->row_idx; p.m_dev = a->m_dev;
+    p.w = (const uint16_t*)a->w; p.w_stride = a->w_stride_row;
+    p.inv_t = a->inv_temperature; p.forbid = a->forbid_token; p.out_scatter = a->out_scatter;
+    p.conf = a->conf; p.tok = a->tok; p.lse = a->lse; p.zmax = a->zmax; p.z2nd = a->z2nd;
+    p.target = a->target; p.ztarget = a->ztarget;
+    p.part = (f32x4*)a->workspace;
+    p.n_vt = (a->V + pl.tv - 1) / pl.tv;
+    const int n_mc = (a->M + pl.mb - 1) / pl.mb;
+    if (n_mc > 65535) return fail(DLM_ERR_UNSUPPORTED, "lmhead: M too large");
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid(p.n_vt, n_mc);
+    switch (pl.variant) {
+        case 0: hipLaunchKernelGGL((lmhead_kernel<4, 1, 1, 1>), grid, dim3(256), 0, st, p); break;
+        case 1: hipLaunchKernelGGL((lmhead_kernel<4, 1, 1, 2>), grid, dim3(256), 0, st, p); break;
+        case 2: hipLaunchKernelGGL((lmhead_kernel<2, 2, 2, 2>), grid, dim3(256), 0, st, p); break;
+        default: hipLaunchKernelGGL((lmhead_kernel<2, 2, 2, 4>), grid, dim3(256), 0, st, p); break;
+    }
+    rc = check_hip(hipGetLastError(), "lmhead_kernel launch");
+    if (rc != DLM_OK) return rc;
+    hipLaunchKernelGGL(lmhead_reduce_kernel, dim3((a->M + 3) / 4), dim3(256), 0, st, p);
+    return check_hip(hipGetLastError(), "lmhead_reduce_kernel launch");
+}

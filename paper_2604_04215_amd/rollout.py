@@ -1,0 +1,249 @@
+"""Block rollout driver on top of the libdlm binding.
+
+Owns the device-side state of a rollout (token buffer, block mask, KV cache,
+per-step outputs) and enqueues the three calls of one denoising step.  All
+arithmetic happens inside libdlm's kernels; this module only wires buffers.
+
+Loop control: the commit kernel leaves the compacted list of still-masked rows
+and its length on the device, and the next LM-head call reads that length from
+the device, so a step never needs a host round trip to size its work.  The
+host only has to learn when a block is finished; `run_block` polls `remaining`
+one step late (the copy of step s-1 is read after step s has been queued), so
+the GPU never idles waiting for the host, at the price of at most one empty
+step per block.
+"""
+from __future__ import annotations
+
+from typing import Callable, Optional
+
+import torch
+
+from . import binding as dlm
+
+_RULES = {"threshold": dlm.RULE_THRESHOLD, "topk": dlm.RULE_TOPK}
+_MASKS = {"full": dlm.MASK_FULL, "block_causal": dlm.MASK_BLOCK_CAUSAL}
+
+
+class GpuRollout:
+    def __init__(self, cfg, w: torch.Tensor, device: str = "cuda:0", record_steps: bool = False):
+        self.cfg, self.dev = cfg, torch.device(device)
+        B, Lb, L = cfg.B, cfg.Lb, cfg.L
+        dev = self.dev
+        self.w = w
+        self.x = torch.zeros((B, L), dtype=torch.int32, device=dev)
+        self.mask = torch.zeros((B, Lb), dtype=torch.uint8, device=dev)
+        self.cache_k = torch.zeros((B, cfg.Hkv, L, cfg.d), dtype=torch.bfloat16, device=dev)
+        self.cache_v = torch.zeros_like(self.cache_k)
+        self.O = torch.zeros((B, Lb, cfg.Hq, cfg.d), dtype=torch.bfloat16, device=dev)
+        self.lse_attn = torch.zeros((B, cfg.Hq, Lb), dtype=torch.float32, device=dev)
+        n = B * Lb
+        self.conf = torch.zeros((B, Lb), dtype=torch.float32, device=dev)
+        self.tok = torch.zeros((B, Lb), dtype=torch.int32, device=dev)
+        self.lse = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.zmax = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.z2nd = torch.zeros(n, dtype=torch.float32, device=dev)
+        self.commit_now = torch.zeros((B, Lb), dtype=torch.uint8, device=dev)
+        self.n_commit = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.remaining = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.row_idx = torch.zeros(n, dtype=torch.int32, device=dev)
+        self.m_dev = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.commit_step = torch.full((B, Lb), -1, dtype=torch.int16, device=dev) if record_steps else None
+        self.workspace = torch.empty(max(16, dlm.lmhead_workspace_bytes(n, cfg.V)), dtype=torch.uint8, device=dev)
+        self.total_committed = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.block = -1
+        self.step_idx = 0
+        self.m_host = n          # host-side upper bound of the masked-row count
+        self.diagnostics = True  # also write lse / zmax / z2nd (tests); the benchmark turns it off
+        # ring of pinned host buffers + events for polling `remaining` (allocated once: pinned allocation is slow)
+        self._ring = [(torch.cuda.Event(), torch.empty(B, dtype=torch.int32, pin_memory=True)) for _ in range(4)]
+        self._ring_pos = 0
+
+    def queue_poll(self):
+        """Start an asynchronous copy of `remaining` to pinned host memory; returns (event, host tensor).
+        At most 3 polls may be outstanding (the ring holds 4 slots)."""
+        ev, host = self._ring[self._ring_pos]
+        self._ring_pos = (self._ring_pos + 1) % len(self._ring)
+        host.copy_(self.remaining, non_blocking=True)
+        ev.record(torch.cuda.current_stream())
+        return ev, host
+
+    # geometry of the current block
+    @property
+    def P(self) -> int:
+        return self.cfg.prompt + self.block * self.cfg.Lb
+
+    @property
+    def S(self) -> int:
+        return self.cfg.L - self.P - self.cfg.Lb if self.cfg.dual_cache else 0
+
+    def begin_block(self, block: int, init_mask: Optional[torch.Tensor] = None,
+                    refresh_k: Optional[torch.Tensor] = None, refresh_v: Optional[torch.Tensor] = None) -> None:
+        """Start denoising `block`: optionally refresh the cache from a full-sequence K/V image
+        (prefix always, suffix too for the dual cache), reset the block mask, compact its rows."""
+        cfg = self.cfg
+        self.block, self.step_idx = block, 0
+        P, Lb = self.P, cfg.Lb
+        if refresh_k is not None:
+            if P > 0:
+                dlm.kv_refresh(refresh_k[:, :, :P], refresh_v[:, :, :P], self.cache_k, self.cache_v, 0)
+            if cfg.dual_cache and P + Lb < cfg.L:
+                dlm.kv_refresh(refresh_k[:, :, P + Lb:], refresh_v[:, :, P + Lb:], self.cache_k, self.cache_v, P + Lb)
+        if init_mask is None:
+            self.mask.fill_(1)
+        else:
+            self.mask.copy_(init_mask)
+        if self.commit_step is not None:
+            self.commit_step.fill_(-1)
+        dlm.mask_compact(self.mask, self.row_idx, self.m_dev)
+        self.m_host = cfg.B * Lb
+
+    def step(self, q: torch.Tensor, kblk: torch.Tensor, vblk: torch.Tensor, hidden: torch.Tensor) -> None:
+        """Enqueue one denoising step.  q [B, Lb, Hq, d]; kblk, vblk [B, Hkv, Lb, d]; hidden [B, Lb, Dh]."""
+        cfg = self.cfg
+        P, Lb, S = self.P, cfg.Lb, self.S
+        prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
+        suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
+        dlm.block_attn(q, self.O, prefix=prefix, block=(kblk, vblk, P), suffix=suffix,
+                       mask_mode=_MASKS[cfg.mask_mode], block_size=cfg.bs, q_pos0=P,
+                       lse=self.lse_attn if self.diagnostics else None)
+        diag = self.diagnostics
+        dlm.lmhead_confidence(hidden.view(cfg.B * Lb, cfg.Dh), self.w, self.conf, self.tok,
+                              M=self.m_host, row_idx=self.row_idx, m_dev=self.m_dev,
+                              forbid_token=cfg.forbid_token, out_scatter=True,
+                              lse=self.lse if diag else None, zmax=self.zmax if diag else None,
+                              z2nd=self.z2nd if diag else None, workspace=self.workspace)
+        dlm.unmask_commit(self.conf, self.tok, self.x, self.mask, self.n_commit, self.remaining,
+                          x_pos0=P, rule=_RULES[cfg.rule], threshold=cfg.tau, force_top1=True, k=cfg.k,
+                          commit_now=self.commit_now, next_row_idx=self.row_idx, next_m=self.m_dev,
+                          commit_step=self.commit_step, step=self.step_idx,
+                          writeback=dlm.WB_BLOCK_WHEN_DONE, src_block=(kblk, vblk, 0),
+                          cache_k=self.cache_k, cache_v=self.cache_v, cache_pos0=P)
+        self.step_idx += 1
+
+    def set_row_bound(self, m: int) -> None:
+        """Tell the driver an upper bound of the masked-row count (sizes the LM-head launch)."""
+        self.m_host = max(1, min(int(m), self.cfg.B * self.cfg.Lb))
+
+    def run_block(self, block: int, inputs: Callable[[int, int], tuple], init_mask=None,
+                  refresh=None, lagged: bool = True, max_steps: Optional[int] = None) -> dict:
+        """Denoise one block to completion.  inputs(block, step) -> (q, kblk, vblk, hidden) on the GPU.
+
+        Returns {"steps": queued steps, "empty": queued steps that found nothing masked}.
+        With lagged=False the host waits for every step's `remaining` before queuing the next.
+        """
+        cfg = self.cfg
+        rk, rv = refresh if refresh is not None else (None, None)
+        self.begin_block(block, init_mask, rk, rv)
+        max_steps = cfg.Lb + 1 if max_steps is None else max_steps
+        pending = []   # (event, pinned host copy of remaining) of steps already queued
+        steps = empty = 0
+        done = False
+        while not done and steps < max_steps:
+            self.step(*inputs(block, steps))
+            steps += 1
+            pending.append(self.queue_poll())
+            # look at the newest result that is allowed to be waited for
+            lag = 1 if lagged else 0
+            while len(pending) > lag:
+                ev0, h0 = pending.pop(0)
+                ev0.synchronize()
+                rem = int(h0.sum())
+                self.set_row_bound(rem if rem > 0 else 1)
+                if rem == 0:
+                    done = True
+                    empty = len(pending)   # steps queued after the finishing one found nothing to do
+                    pending.clear()
+                    break
+        if not done:
+            for ev0, h0 in pending:
+                ev0.synchronize()
+                if int(h0.sum()) == 0:
+                    done = True
+            if not done:
+                raise RuntimeError(f"block {block} not finished after {steps} steps")
+        return {"steps": steps - empty, "empty": empty}
+
+
+class StepRunner:
+    """Runs an exact number of productive denoising steps, continuing across blocks and restarting
+    the rollout after its last block.  Used by the benchmark and by long-running callers.
+
+    setup(block) -> dict(init_mask=None | tensor, refresh=None | (k, v), restart=bool) describes how a
+    block starts; inputs(block, step) -> (q, kblk, vblk, hidden).  A step is productive when it found
+    masked positions; with the one-step-late poll at most one queued step per block is not.
+    """
+
+    def __init__(self, g: GpuRollout, inputs: Callable[[int, int], tuple], setup: Callable[[int], dict],
+                 on_restart: Optional[Callable[[], None]] = None, lagged: bool = True, on_step=None):
+        self.g, self.inputs, self.setup, self.on_restart, self.lagged = g, inputs, setup, on_restart, lagged
+        self.on_step = on_step          # optional hook(g, fn) wrapping the enqueue of one step (timing)
+        self.block = -1
+        self.in_block = False
+        self.queued = 0                 # steps queued in the current block
+        self.known = 0                  # of those, how many are known to be productive
+        self.rem_prev = 0               # masked count before the oldest not-yet-polled step
+        self.pending = []               # (event, pinned remaining copy)
+        self.committed = 0
+        self.empty = 0
+        self.blocks_done = 0
+        self.steps_per_block = []
+
+    def _begin_next_block(self):
+        g = self.g
+        self.block = (self.block + 1) % g.cfg.n_blocks
+        if self.block == 0 and self.on_restart is not None:
+            self.on_restart()
+        st = self.setup(self.block)
+        rk, rv = st.get("refresh") or (None, None)
+        g.begin_block(self.block, st.get("init_mask"), rk, rv)
+        self.in_block, self.queued, self.known = True, 0, 0
+        self.rem_prev = int(st.get("n_masked", g.cfg.B * g.cfg.Lb))
+        self.pending = []
+
+    def _poll_one(self) -> bool:
+        """Wait for the oldest queued step's result; returns True when it finished the block."""
+        ev, host = self.pending.pop(0)
+        ev.synchronize()
+        rem = int(host.sum())
+        if self.rem_prev > 0:
+            self.known += 1
+            self.committed += self.rem_prev - rem
+        else:
+            self.empty += 1
+        self.rem_prev = rem
+        self.g.set_row_bound(rem if rem > 0 else 1)
+        return rem == 0
+
+    def run(self, n_steps: int) -> dict:
+        g = self.g
+        done_steps = 0                  # productive steps completed and polled in this call
+        start_committed, start_empty = self.committed, self.empty
+        while done_steps < n_steps:
+            if not self.in_block:
+                self._begin_next_block()
+            unpolled = len(self.pending)
+            # queue one more step unless every step we still need might already be in flight
+            if done_steps + unpolled < n_steps:
+                args = self.inputs(self.block, self.queued)
+                if self.on_step is not None:
+                    self.on_step(g, lambda: g.step(*args))
+                else:
+                    g.step(*args)
+                self.queued += 1
+                self.pending.append(g.queue_poll())
+            lag = 1 if (self.lagged and done_steps + len(self.pending) < n_steps) else 0
+            while len(self.pending) > lag:
+                was_productive = self.rem_prev > 0
+                finished = self._poll_one()
+                if was_productive:
+                    done_steps += 1
+                if finished:
+                    # whatever is still queued in this block found nothing masked
+                    while self.pending:
+                        self._poll_one()
+                    self.steps_per_block.append(self.known)
+                    self.blocks_done += 1
+                    self.in_block = False
+                    break
+        return dict(steps=done_steps, committed=self.committed - start_committed,
+                    empty=self.empty - start_empty)

@@ -1,0 +1,160 @@
+"""dlm_block_attn against the oracle, element by element (GPU)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import KV
+from paper_2604_04215_amd import binding as dlm
+from gpu_util import DEV, attn_rel_err, bf16_dev, bf16_host, dev, rnd
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2          # max relative error, bf16 operands with fp32 accumulation
+LSE_TOL = 2e-3
+
+
+def run_case(B, Lq, Hq, Hkv, d, P, Lb, S, mode="full", bs=0, q_pos0=None, plen=None, variant=0, seed=0,
+             block_is_q=True, pos=None):
+    q = rnd(seed * 10 + 1, (B, Lq, Hq, d))
+    Ltot = P + Lb + S
+    k = rnd(seed * 10 + 2, (B, Hkv, Ltot, d))
+    v = rnd(seed * 10 + 3, (B, Hkv, Ltot, d))
+    q_pos0 = P if q_pos0 is None else q_pos0
+    pos = (0, P, P + Lb) if pos is None else pos
+    segs = [KV(k[:, :, :P], v[:, :, :P], pos[0]), KV(k[:, :, P:P + Lb], v[:, :, P:P + Lb], pos[1]),
+            KV(k[:, :, P + Lb:], v[:, :, P + Lb:], pos[2])]
+    ref, ref_lse = oracle.attention(q, segs, mask_mode=mode, bs=bs, q_pos0=q_pos0, prefix_len_b=plen)
+    kd, vd, qd = bf16_dev(k), bf16_dev(v), bf16_dev(q)          # one cache tensor: segments are strided views
+    out = torch.full((B, Lq, Hq, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lse = torch.full((B, Hq, Lq), float("nan"), dtype=torch.float32, device=DEV)
+    dlm.set_option("attn_variant", variant)
+    try:
+        dlm.block_attn(qd, out,
+                       prefix=(kd[:, :, :P], vd[:, :, :P], pos[0]) if P else None,
+                       block=(kd[:, :, P:P + Lb], vd[:, :, P:P + Lb], pos[1]) if Lb else None,
+                       suffix=(kd[:, :, P + Lb:], vd[:, :, P + Lb:], pos[2]) if S else None,
+                       n_kv_heads=Hkv,
+                       mask_mode=dlm.MASK_BLOCK_CAUSAL if mode == "block_causal" else dlm.MASK_FULL,
+                       block_size=bs, q_pos0=q_pos0, lse=lse,
+                       prefix_len_b=None if plen is None else dev(np.asarray(plen, np.int32)))
+        torch.cuda.synchronize()
+    finally:
+        dlm.set_option("attn_variant", 0)
+    err = attn_rel_err(bf16_host(out), ref)
+    assert err <= TOL, f"attention rel err {err}"
+    got_lse = lse.cpu().numpy().astype(np.float64)
+    fin = np.isfinite(ref_lse)
+    assert np.array_equal(np.isfinite(got_lse), fin)
+    assert np.all(got_lse[~fin] == ref_lse[~fin])
+    if fin.any():
+        assert np.abs(got_lse[fin] - ref_lse[fin]).max() <= LSE_TOL
+    return err
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+def test_rollout_shape_mha(variant):
+    # block of 32 against a ragged prefix (several 32-key tiles and a tail), d = 128
+    run_case(B=2, Lq=32, Hq=4, Hkv=4, d=128, P=200, Lb=32, S=0, variant=variant, seed=1)
+
+
+@pytest.mark.parametrize("variant", [0, 2, 3])
+def test_dual_cache_and_gqa7(variant):
+    # 7 query heads per KV head (224 packed rows), prefix | block | suffix, ragged suffix
+    run_case(B=2, Lq=32, Hq=14, Hkv=2, d=128, P=96, Lb=32, S=45, variant=variant, seed=2)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Lq,Hq,Hkv", [(1, 2, 2), (5, 4, 2), (32, 4, 4), (40, 6, 2), (70, 4, 1)])
+def test_shapes(d, Lq, Hq, Hkv):
+    run_case(B=2, Lq=Lq, Hq=Hq, Hkv=Hkv, d=d, P=77, Lb=Lq, S=9, seed=3 + Lq)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("bs", [1, 4, 32])
+def test_block_causal_rollout(variant, bs):
+    # last block(s) of a block-diffusion sequence against the cache; positions are absolute
+    run_case(B=2, Lq=8, Hq=8, Hkv=2, d=128, P=188, Lb=8, S=0, mode="block_causal", bs=bs, variant=variant, seed=5)
+
+
+@pytest.mark.parametrize("variant", [2, 3])
+def test_block_causal_full_sequence(variant):
+    # training-style pass: Lq = Lk, bidirectional inside blocks of 4, causal across blocks
+    B, L, Hq, Hkv, d = 2, 204, 4, 2, 128
+    run_case(B=B, Lq=L, Hq=Hq, Hkv=Hkv, d=d, P=0, Lb=L, S=0, mode="block_causal", bs=4, q_pos0=0,
+             variant=variant, seed=6)
+
+
+def test_block_causal_hides_suffix_and_uses_positions():
+    # suffix keys lie in later blocks: invisible; shifting every position by a block multiple changes nothing
+    run_case(B=1, Lq=8, Hq=4, Hkv=2, d=64, P=40, Lb=8, S=16, mode="block_causal", bs=8, seed=7)
+    run_case(B=1, Lq=8, Hq=4, Hkv=2, d=64, P=40, Lb=8, S=16, mode="block_causal", bs=8, q_pos0=1040,
+             pos=(1000, 1040, 1048), seed=7)
+
+
+def test_ragged_prefix_per_sequence():
+    run_case(B=3, Lq=32, Hq=4, Hkv=2, d=128, P=100, Lb=32, S=20, plen=[100, 37, 0], seed=8)
+
+
+def test_degenerate_contexts():
+    # no prefix and no suffix; a single key; no key at all (output 0, lse -inf)
+    run_case(B=1, Lq=32, Hq=2, Hkv=2, d=128, P=0, Lb=32, S=0, seed=9)
+    run_case(B=1, Lq=3, Hq=2, Hkv=1, d=64, P=1, Lb=0, S=0, seed=10)
+    run_case(B=2, Lq=4, Hq=2, Hkv=2, d=128, P=5, Lb=0, S=0, plen=[0, 5], seed=11)
+
+
+def test_noncontiguous_q_and_out_views():
+    B, Lq, Hq, Hkv, d, P = 2, 32, 4, 4, 128, 64
+    q = rnd(121, (B, Lq, Hq, d))
+    k, v = rnd(122, (B, Hkv, P, d)), rnd(123, (B, Hkv, P, d))
+    ref, _ = oracle.attention(q, [KV(k, v, 0)])
+    big_q = torch.zeros((B, Lq, Hq + 2, d + 64), dtype=torch.bfloat16, device=DEV)
+    big_o = torch.zeros_like(big_q)
+    qv, ov = big_q[:, :, 1:1 + Hq, :d], big_o[:, :, 1:1 + Hq, :d]
+    qv.copy_(bf16_dev(q))
+    dlm.block_attn(qv, ov, prefix=(bf16_dev(k), bf16_dev(v), 0))
+    torch.cuda.synchronize()
+    assert attn_rel_err(bf16_host(ov), ref) <= TOL
+    assert float(big_o[:, :, 0].abs().max()) == 0 and float(big_o[..., d:].abs().max()) == 0
+
+
+def test_rerun_is_bitwise_identical():
+    B, Lq, Hq, Hkv, d, P = 2, 32, 8, 2, 128, 300
+    q, k, v = bf16_dev(rnd(131, (B, Lq, Hq, d))), bf16_dev(rnd(132, (B, Hkv, P, d))), bf16_dev(rnd(133, (B, Hkv, P, d)))
+    o1, o2 = torch.empty_like(q), torch.empty_like(q)
+    dlm.block_attn(q, o1, prefix=(k, v, 0))
+    dlm.block_attn(q, o2, prefix=(k, v, 0))
+    torch.cuda.synchronize()
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_planted_one_hot_values_expose_every_key(variant):
+    """V[j] = e_(j mod d): output channel c is the total probability of keys j = c (mod d), so a
+    dropped, duplicated or misplaced key shifts some channel by a large relative amount; with Q = 0
+    every probability is exactly 1/Lk."""
+    B, Lq, Hq, Hkv, d, P, Lb, S = 1, 32, 2, 2, 64, 150, 32, 21
+    Lk = P + Lb + S
+    v = np.zeros((B, Hkv, Lk, d), np.float32)
+    v[:, :, np.arange(Lk), np.arange(Lk) % d] = 1.0
+    from paper_2604_04215_amd import synth
+    vb = synth.f32_to_bf16_bits(v)
+    k = rnd(201, (B, Hkv, Lk, d))
+    for qbits in (np.zeros((B, Lq, Hq, d), np.uint16), rnd(202, (B, Lq, Hq, d), 0.3)):
+        segs = [KV(k[:, :, :P], vb[:, :, :P], 0), KV(k[:, :, P:P + Lb], vb[:, :, P:P + Lb], P),
+                KV(k[:, :, P + Lb:], vb[:, :, P + Lb:], P + Lb)]
+        ref, _ = oracle.attention(qbits, segs)
+        kd, vd = bf16_dev(k), bf16_dev(vb)
+        out = torch.empty((B, Lq, Hq, d), dtype=torch.bfloat16, device=DEV)
+        dlm.set_option("attn_variant", variant)
+        try:
+            dlm.block_attn(bf16_dev(qbits), out, prefix=(kd[:, :, :P], vd[:, :, :P], 0),
+                           block=(kd[:, :, P:P + Lb], vd[:, :, P:P + Lb], P),
+                           suffix=(kd[:, :, P + Lb:], vd[:, :, P + Lb:], P + Lb))
+            torch.cuda.synchronize()
+        finally:
+            dlm.set_option("attn_variant", 0)
+        from paper_2604_04215_amd.synth import bf16_bits_to_f64
+        got = bf16_bits_to_f64(bf16_host(out))
+        # every channel is a sum of 3-4 probabilities: a per-element relative check is meaningful here
+        assert np.abs(got - ref).max() <= 2e-2 * ref.min()

@@ -1,0 +1,150 @@
+"""dlm_lmhead_confidence against the oracle (GPU)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_04215_amd import binding as dlm
+from paper_2604_04215_amd import synth
+from gpu_util import DEV, bf16_dev, dev, rnd
+
+pytestmark = pytest.mark.gpu
+
+CONF_TOL = 1e-3     # absolute, confidences
+MARGIN = 1e-3       # rows whose top-2 logit margin is below this may legitimately pick the other token
+Z_TOL = 2e-3        # logits-scale outputs (lse, zmax, z2nd): fp32 accumulation over Dh terms
+
+
+def run_lm(hidden, w, *, row_idx=None, M=None, m_dev=None, forbid=-1, inv_t=1.0, scatter=False, target=None):
+    R, Dh = hidden.shape
+    V = w.shape[0]
+    hd, wd = bf16_dev(hidden), bf16_dev(w)
+    ridx = None if row_idx is None else dev(np.asarray(row_idx, np.int32))
+    Mh = M if M is not None else (len(row_idx) if row_idx is not None else R)
+    n_out = R if scatter else Mh
+    f = lambda: torch.full((n_out,), float("nan"), dtype=torch.float32, device=DEV)
+    conf, lse, zmax, z2nd = f(), f(), f(), f()
+    tok = torch.full((n_out,), -7, dtype=torch.int32, device=DEV)
+    tgt = zt = None
+    if target is not None:
+        tgt, zt = dev(np.asarray(target, np.int32)), f()
+    ws = torch.empty(max(16, dlm.lmhead_workspace_bytes(Mh, V)), dtype=torch.uint8, device=DEV)
+    dlm.lmhead_confidence(hd, wd, conf, tok, M=Mh, row_idx=ridx,
+                          m_dev=None if m_dev is None else dev(np.asarray([m_dev], np.int32)),
+                          forbid_token=forbid, inv_temperature=inv_t, out_scatter=scatter,
+                          lse=lse, zmax=zmax, z2nd=z2nd, target=tgt, ztarget=zt, workspace=ws)
+    torch.cuda.synchronize()
+    out = dict(conf=conf.cpu().numpy(), tok=tok.cpu().numpy(), lse=lse.cpu().numpy(), zmax=zmax.cpu().numpy(),
+               z2nd=z2nd.cpu().numpy())
+    if zt is not None:
+        out["zt"] = zt.cpu().numpy()
+    return out
+
+
+def compare(got, ref, sel=None):
+    """got arrays indexed by output slot; ref from the oracle in the same order (sel picks got's slots)."""
+    g = {k: (v if sel is None else v[sel]) for k, v in got.items()}
+    assert np.abs(g["conf"].astype(np.float64) - ref["conf"]).max() <= CONF_TOL
+    margin = ref["zmax"] - ref["z2nd"]
+    clear = margin >= MARGIN
+    assert np.array_equal(g["tok"][clear], ref["tok"][clear])
+    assert clear.mean() > 0.9
+    assert np.abs(g["lse"] - ref["lse"]).max() <= Z_TOL
+    assert np.abs(g["zmax"] - ref["zmax"]).max() <= Z_TOL
+    both = np.isfinite(ref["z2nd"])
+    assert np.abs(g["z2nd"][both] - ref["z2nd"][both]).max() <= Z_TOL
+    if "zt" in ref:
+        fin = np.isfinite(ref["zt"])
+        assert np.abs(g["zt"][fin] - ref["zt"][fin]).max() <= Z_TOL
+        assert np.array_equal(np.isfinite(g["zt"]), fin)
+
+
+@pytest.mark.parametrize("M,Dh,V", [(1, 64, 300), (16, 256, 2048), (33, 128, 777), (64, 192, 1000),
+                                    (100, 320, 1500), (200, 256, 900), (256, 128, 2048), (300, 64, 515),
+                                    (700, 64, 400)])
+def test_shapes_vs_oracle(M, Dh, V):
+    # covers every row-tile variant (<=32, <=64, <=128, <=256 rows), several row chunks, ragged V tails
+    h, w = rnd(M + Dh, (M, Dh)), rnd(V + Dh, (V, Dh), Dh ** -0.25)
+    ref = oracle.lmhead(h, w, forbid_token=V - 1)
+    got = run_lm(h, w, forbid=V - 1)
+    compare(got, ref)
+    assert np.all(got["tok"] != V - 1)
+
+
+def test_gather_scatter_mdev_temperature_target():
+    R, Dh, V = 96, 128, 1000
+    h, w = rnd(1, (R, Dh)), rnd(2, (V, Dh), Dh ** -0.25)
+    idx = np.array(sorted(np.random.default_rng(0).permutation(R)[:41]), np.int32)
+    tgt_dense = np.random.default_rng(1).integers(0, V, size=R).astype(np.int32)
+    ref = oracle.lmhead(h, w, row_idx=idx, inv_temperature=0.7, forbid_token=5, target=tgt_dense[idx])
+    # compact outputs
+    got = run_lm(h, w, row_idx=idx, inv_t=0.7, forbid=5, target=tgt_dense[idx])
+    compare(got, ref)
+    # dense outputs: slot row_idx[r]; untouched slots keep their fill
+    got = run_lm(h, w, row_idx=idx, inv_t=0.7, forbid=5, scatter=True, target=tgt_dense)
+    compare(got, ref, sel=idx)
+    rest = np.setdiff1d(np.arange(R), idx)
+    assert np.all(np.isnan(got["conf"][rest])) and np.all(got["tok"][rest] == -7)
+    # device-side row count smaller than the host bound: only the first m rows are produced
+    got = run_lm(h, w, row_idx=idx, M=41, m_dev=17, inv_t=0.7, forbid=5)
+    compare({k: v[:17] for k, v in got.items()}, {k: v[:17] for k, v in ref.items() if k != "zt"})
+    assert np.all(np.isnan(got["conf"][17:])) and np.all(got["tok"][17:] == -7)
+    got = run_lm(h, w, row_idx=idx, M=41, m_dev=0)
+    assert np.all(np.isnan(got["conf"])) and np.all(got["tok"] == -7)
+
+
+def test_ties_pick_lowest_index():
+    Dh, V = 64, 700
+    h = synth.f32_to_bf16_bits(np.ones((40, Dh), np.float32))
+    w = synth.f32_to_bf16_bits(np.full((V, Dh), 0.25, np.float32))
+    got = run_lm(h, w)
+    assert np.all(got["tok"] == 0)
+    assert np.allclose(got["conf"], 1.0 / V, atol=1e-6)
+    assert np.allclose(got["z2nd"], got["zmax"])
+    got = run_lm(h, w, forbid=0)
+    assert np.all(got["tok"] == 1) and np.allclose(got["conf"], 1.0 / (V - 1), atol=1e-6)
+    # two equal maxima in different vocabulary tiles: the lower one wins
+    wf = np.zeros((V, Dh), np.float32)
+    wf[650, 0] = 2.0
+    wf[131, 0] = 2.0
+    got = run_lm(synth.f32_to_bf16_bits(np.eye(3, Dh, dtype=np.float32)), synth.f32_to_bf16_bits(wf))
+    assert got["tok"][0] == 131 and got["z2nd"][0] == got["zmax"][0] == 2.0
+
+
+def test_closed_form_threshold_boundary():
+    # z = (a, 0, ..., 0): conf = e^a / (e^a + V - 1)
+    Dh, V = 64, 2048
+    for a in (2.0, 7.5, 9.8125):
+        wf = np.zeros((V, Dh), np.float32)
+        wf[1234, 0] = a
+        got = run_lm(synth.f32_to_bf16_bits(np.eye(1, Dh, dtype=np.float32)), synth.f32_to_bf16_bits(wf))
+        want = np.exp(a) / (np.exp(a) + V - 1)
+        assert got["tok"][0] == 1234 and abs(got["conf"][0] - want) < 1e-5
+
+
+def test_rerun_is_bitwise_identical():
+    h, w = rnd(5, (200, 256)), rnd(6, (3000, 256), 0.25)
+    a, b = run_lm(h, w), run_lm(h, w)
+    for k in a:
+        assert np.array_equal(a[k], b[k])
+
+
+def test_full_vocabulary_sampled_rows():
+    """LLaDA-8B-sized head (V = 126464, Dh = 4096), 256 rows as in the benchmark's first step;
+    the oracle checks a sample of rows one by one."""
+    cfg = synth.CONFIGS["c2"]
+    w = synth.w_vocab(cfg)
+    hid = synth.step_hidden(cfg, 0, 0).reshape(cfg.B * cfg.Lb, cfg.Dh)
+    got = run_lm(hid, w, forbid=cfg.forbid_token)
+    sample = np.array([0, 31, 77, 128, 200, 255], np.int32)
+    ref = oracle.lmhead(hid, w, row_idx=sample, forbid_token=cfg.forbid_token)
+    g = {k: v[sample] for k, v in got.items()}
+    assert np.abs(g["conf"] - ref["conf"]).max() <= CONF_TOL
+    clear = (ref["zmax"] - ref["z2nd"]) >= MARGIN
+    assert np.array_equal(g["tok"][clear], ref["tok"][clear])
+    assert np.abs(g["lse"] - ref["lse"]).max() <= 5e-3 and np.abs(g["zmax"] - ref["zmax"]).max() <= 5e-3
+    # properties that hold at any size
+    assert np.all(got["conf"] > 0) and np.all(got["conf"] <= 1.0 + 1e-6)
+    assert np.all((got["tok"] >= 0) & (got["tok"] < cfg.V - 1))
+    assert np.all(got["z2nd"] <= got["zmax"]) and np.all(got["lse"] >= got["zmax"])
+    assert np.allclose(got["conf"], np.exp(got["zmax"] - got["lse"]), atol=1e-5)

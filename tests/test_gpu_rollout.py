@@ -1,0 +1,218 @@
+"""Whole denoising steps and block rollouts: HIP path in lock-step with the oracle (GPU)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import KV
+from paper_2604_04215_amd import binding as dlm
+from paper_2604_04215_amd import synth
+from paper_2604_04215_amd.rollout import GpuRollout
+from gpu_util import DEV, attn_rel_err, bf16_dev, bf16_host, dev
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL, CONF_TOL, NEAR = 2e-2, 1e-3, 1e-3
+
+
+def step_inputs_dev(cfg, block, step):
+    q = bf16_dev(synth.step_q(cfg, block, step))
+    kb, vb = synth.step_kv(cfg, block, step)
+    hid = bf16_dev(synth.step_hidden(cfg, block, step))
+    return q, bf16_dev(kb), bf16_dev(vb), hid
+
+
+def load_state(g: GpuRollout, o: oracle.OracleRollout):
+    g.x.copy_(dev(o.x))
+    g.cache_k.copy_(bf16_dev(o.cache_k))
+    g.cache_v.copy_(bf16_dev(o.cache_v))
+
+
+def lockstep(cfg, blocks=None):
+    """Run oracle and GPU side by side; both start every step from the same state.  A step may differ
+    only where the oracle says the decision is numerically ambiguous (confidence within NEAR of the
+    threshold, top-2 logit margin below NEAR, or a rank gap below NEAR between the last selected and
+    the first unselected confidence); then the oracle is re-synchronised to the GPU's state."""
+    w = synth.w_vocab(cfg)
+    o = oracle.OracleRollout(cfg, synth, w=w)
+    g = GpuRollout(cfg, bf16_dev(w), DEV, record_steps=True)
+    load_state(g, o)
+    stats = dict(steps=0, seq_steps=0, excluded=0, committed=0)
+    for b in (range(cfg.n_blocks) if blocks is None else blocks):
+        o.begin_block(b)
+        rk = rv = None
+        if cfg.refresh and b > 0:
+            k, v = synth.cache_kv(cfg, b)
+            rk, rv = bf16_dev(k), bf16_dev(v)
+        g.begin_block(b, init_mask=dev(o.mask), refresh_k=rk, refresh_v=rv)
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_host(g.cache_k), o.cache_k), "cache refresh is a bitwise copy"
+        while o.mask.any():
+            mask_before = o.mask.copy()
+            r = o.step()
+            g.step(*step_inputs_dev(cfg, b, r["step"]))
+            torch.cuda.synchronize()
+            stats["steps"] += 1
+            # attention
+            err = attn_rel_err(bf16_host(g.O), r["O"])
+            assert err <= ATTN_TOL, f"block {b} step {r['step']}: attention rel err {err}"
+            # LM head on the masked rows
+            rows = r["row_idx"]
+            conf_g = g.conf.cpu().numpy().ravel()[rows].astype(np.float64)
+            tok_g = g.tok.cpu().numpy().ravel()[rows]
+            lm = r["lm"]
+            assert np.abs(conf_g - lm["conf"]).max() <= CONF_TOL
+            clear_tok = (lm["zmax"] - lm["z2nd"]) >= NEAR
+            assert np.array_equal(tok_g[clear_tok], lm["tok"][clear_tok])
+            # selection: per sequence, exact unless flagged ambiguous
+            commit_g = g.commit_now.cpu().numpy()
+            x_g, mask_g = g.x.cpu().numpy(), g.mask.cpu().numpy()
+            conf_o = r["conf"]
+            for s in range(cfg.B):
+                if not mask_before[s].any():
+                    assert not commit_g[s].any()
+                    continue
+                stats["seq_steps"] += 1
+                m = mask_before[s].astype(bool)
+                amb = False
+                if cfg.rule == "threshold":
+                    amb |= bool((np.abs(conf_o[s][m] - cfg.tau) < NEAR).any())
+                    top = np.sort(conf_o[s][m])[::-1]
+                    amb |= bool(len(top) > 1 and top[0] - top[1] < NEAR and top[0] < cfg.tau + NEAR)
+                else:
+                    top = np.sort(conf_o[s][m])[::-1]
+                    kk = min(cfg.k, len(top))
+                    amb |= bool(len(top) > kk and top[kk - 1] - top[kk] < NEAR)
+                sel = r["commit"][s].astype(bool)
+                amb_tok = bool((~clear_tok[(rows // cfg.Lb) == s]).any())
+                if np.array_equal(commit_g[s], r["commit"][s]):
+                    same_tok = np.array_equal(x_g[s, o.P:o.P + cfg.Lb][sel], r["tok"][s][sel])
+                    assert same_tok or amb_tok, f"token mismatch in block {b} step {r['step']} seq {s}"
+                    if not same_tok:
+                        stats["excluded"] += 1
+                else:
+                    assert amb, f"commit mask mismatch in block {b} step {r['step']} seq {s}"
+                    stats["excluded"] += 1
+            # invariants on the GPU side
+            n_commit_g, remaining_g = g.n_commit.cpu().numpy(), g.remaining.cpu().numpy()
+            had = mask_before.sum(axis=1) > 0
+            assert np.all(n_commit_g[had] >= 1) and np.all(n_commit_g[~had] == 0)
+            assert np.array_equal(remaining_g, mask_g.sum(axis=1)) and np.all(mask_g <= mask_before)
+            assert np.array_equal(commit_g, mask_before - mask_g)
+            stats["committed"] += int(n_commit_g.sum())
+            # re-synchronise the oracle to the GPU state (a no-op unless an ambiguous step differed)
+            o.x[:] = x_g
+            o.mask[:] = mask_g
+            o.cache_k[:] = bf16_host(g.cache_k)
+            o.cache_v[:] = bf16_host(g.cache_v)
+        # block done: nothing masked, the final step's block K/V sits in the cache
+        assert not g.mask.any().item()
+    assert stats["excluded"] <= 0.05 * max(1, stats["seq_steps"]), stats
+    return o, g, stats
+
+
+@pytest.mark.parametrize("name", ["mini1", "mini2", "mini3", "mini4", "mini5a", "c1"])
+def test_lockstep_rollout(name):
+    cfg = synth.CONFIGS[name]
+    o, g, stats = lockstep(cfg)
+    n_init = cfg.init_masked if cfg.init_masked is not None else cfg.Lb
+    assert stats["committed"] == cfg.B * (n_init + (cfg.n_blocks - 1) * cfg.Lb)
+    if cfg.rule == "topk":
+        assert stats["steps"] == cfg.n_blocks * cfg.Lb // cfg.k
+
+
+def test_c1_single_step():
+    """Config 1 as stated: one step on a block with 16 of 32 positions masked."""
+    cfg = synth.CONFIGS["c1"]
+    w = synth.w_vocab(cfg)
+    o = oracle.OracleRollout(cfg, synth, w=w)
+    g = GpuRollout(cfg, bf16_dev(w), DEV)
+    load_state(g, o)
+    o.begin_block(0)
+    g.begin_block(0, init_mask=dev(o.mask))
+    assert int(g.mask.sum().item()) == 16
+    r = o.step()
+    g.step(*step_inputs_dev(cfg, 0, 0))
+    torch.cuda.synchronize()
+    assert attn_rel_err(bf16_host(g.O), r["O"]) <= ATTN_TOL
+    rows = r["row_idx"]
+    assert np.abs(g.conf.cpu().numpy().ravel()[rows] - r["lm"]["conf"]).max() <= CONF_TOL
+    near = (np.abs(r["lm"]["conf"] - cfg.tau) < NEAR).any() or ((r["lm"]["zmax"] - r["lm"]["z2nd"]) < NEAR).any()
+    if not near:
+        assert np.array_equal(g.commit_now.cpu().numpy(), r["commit"])
+        assert np.array_equal(g.x.cpu().numpy(), o.x)
+    assert int(g.n_commit.sum().item()) >= 1
+
+
+@pytest.mark.parametrize("name", ["mini2", "mini4"])
+def test_lagged_loop_matches_synchronous(name):
+    """run_block with the one-step-late host poll ends in the same state as the synchronous loop."""
+    cfg = synth.CONFIGS[name]
+    w = bf16_dev(synth.w_vocab(cfg))
+    x0 = dev(synth.initial_tokens(cfg, cfg.L))
+    k0, v0 = synth.cache_kv(cfg, 0)
+    finals = []
+    for lagged in (False, True):
+        g = GpuRollout(cfg, w, DEV)
+        g.x.copy_(x0)
+        g.cache_k.copy_(bf16_dev(k0))
+        g.cache_v.copy_(bf16_dev(v0))
+        tot_steps = tot_empty = 0
+        for b in range(cfg.n_blocks):
+            refresh = None
+            if cfg.refresh and b > 0:
+                k, v = synth.cache_kv(cfg, b)
+                refresh = (bf16_dev(k), bf16_dev(v))
+            res = g.run_block(b, lambda blk, s: step_inputs_dev(cfg, blk, s), refresh=refresh, lagged=lagged)
+            tot_steps += res["steps"]
+            tot_empty += res["empty"]
+        torch.cuda.synchronize()
+        assert tot_empty <= cfg.n_blocks
+        finals.append((g.x.cpu().numpy(), bf16_host(g.cache_k), tot_steps))
+    assert np.array_equal(finals[0][0], finals[1][0]) and np.array_equal(finals[0][1], finals[1][1])
+    assert finals[0][2] == finals[1][2]
+
+
+def test_full_pass_mini():
+    """Block-causal full-sequence pass with Bernoulli masking, one threshold commit per block of 4."""
+    cfg = synth.FULLPASS["mini5b"]
+    ref = oracle.full_pass(cfg, synth)
+    q, k, v = synth.fullpass_qkv(cfg)
+    hid = synth.fullpass_hidden(cfg)
+    w = synth.w_vocab(cfg)
+    B, L = cfg.B, cfg.L
+    out = torch.empty((B, L, cfg.Hq, cfg.d), dtype=torch.bfloat16, device=DEV)
+    dlm.block_attn(bf16_dev(q), out, block=(bf16_dev(k), bf16_dev(v), 0), mask_mode=dlm.MASK_BLOCK_CAUSAL,
+                   block_size=cfg.bs, q_pos0=0)
+    mask = dev(ref["mask_before"])
+    row_idx = torch.zeros(B * L, dtype=torch.int32, device=DEV)
+    m_dev = torch.zeros(1, dtype=torch.int32, device=DEV)
+    dlm.mask_compact(mask, row_idx, m_dev)
+    conf = torch.zeros((B, L), dtype=torch.float32, device=DEV)
+    tok = torch.zeros((B, L), dtype=torch.int32, device=DEV)
+    ws = torch.empty(dlm.lmhead_workspace_bytes(B * L, cfg.V), dtype=torch.uint8, device=DEV)
+    dlm.lmhead_confidence(bf16_dev(hid).view(B * L, cfg.Dh), bf16_dev(w), conf, tok, M=B * L, row_idx=row_idx,
+                          m_dev=m_dev, forbid_token=cfg.forbid_token, out_scatter=True, workspace=ws)
+    x = dev(ref["x_before"])
+    n_commit = torch.zeros(B, dtype=torch.int32, device=DEV)
+    remaining = torch.zeros(B, dtype=torch.int32, device=DEV)
+    commit_now = torch.zeros((B, L), dtype=torch.uint8, device=DEV)
+    dlm.unmask_commit(conf, tok, x, mask, n_commit, remaining, x_pos0=0, group_len=cfg.bs,
+                      rule=dlm.RULE_THRESHOLD, threshold=cfg.tau, commit_now=commit_now)
+    torch.cuda.synchronize()
+    assert attn_rel_err(bf16_host(out), ref["O"]) <= ATTN_TOL
+    rows = ref["row_idx"]
+    assert np.abs(conf.cpu().numpy().ravel()[rows] - ref["lm"]["conf"]).max() <= CONF_TOL
+    # groups without a numerically ambiguous member must agree exactly
+    conf_o = ref["conf"].reshape(B, L // cfg.bs, cfg.bs)
+    m0 = ref["mask_before"].reshape(B, L // cfg.bs, cfg.bs).astype(bool)
+    margin = np.full(B * L, np.inf)
+    margin[rows] = ref["lm"]["zmax"] - ref["lm"]["z2nd"]
+    amb = ((np.abs(conf_o - cfg.tau) < NEAR) & m0).any(-1) | ((margin.reshape(conf_o.shape) < NEAR) & m0).any(-1)
+    srt = np.sort(np.where(m0, conf_o, -1.0), axis=-1)
+    amb |= (m0.sum(-1) > 1) & (srt[..., -1] - srt[..., -2] < NEAR)
+    cg = commit_now.cpu().numpy().reshape(conf_o.shape)
+    cr = ref["commit"].reshape(conf_o.shape)
+    assert np.array_equal(cg[~amb], cr[~amb]) and amb.mean() < 0.05
+    xg, xr = x.cpu().numpy().reshape(conf_o.shape), ref["x"].reshape(conf_o.shape)
+    assert np.array_equal(xg[~amb], xr[~amb])
