@@ -110,7 +110,6 @@ def main():
     # ---- LM-head event timing hook ------------------------------------------------------------------
     lm_events = []
     orig_lmhead = dlm.lmhead_confidence
-    m_trace = []
 
     def timed_lmhead(*a, **kw):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -126,7 +125,7 @@ def main():
     torch.cuda.synchronize()
     if not args.no_kernel_events:
         ro_mod.dlm.lmhead_confidence = timed_lmhead
-    c0, e0 = runner.committed, runner.empty
+    c0, e0, log0 = runner.committed, runner.empty, len(runner.log)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     res = runner.run(args.steps)
@@ -139,24 +138,29 @@ def main():
     assert res["steps"] == args.steps
 
     # ---- roofline of the LM head (dominant kernel): algorithmic bytes / measured duration -----------
+    # One dlm_lmhead_confidence call streams W_vocab once (V*Dh*2 bytes), gathers M hidden rows
+    # (M*Dh*2 bytes) and writes a handful of bytes per row; M is the number of rows masked before the step.
     roof = None
     w_bytes = cfg.V * cfg.Dh * 2
-    # rows per LM-head launch averaged over the rollout: every productive step processes the rows
-    # still masked before it; over a whole rollout that is sum over steps of masked-before
     if lm_events:
-        ms = [a.elapsed_time(b) for a, b in lm_events]
-        productive_ms = sorted(ms)[len(ms) // 20:]          # drop nothing systematic; keep all but report median too
+        log = runner.log[log0:]
+        assert len(log) == len(lm_events)
+        ms, rows = [], []
+        for (a, b), (_, before, _after) in zip(lm_events, log):
+            if before > 0:                      # launches that found nothing masked move no data
+                ms.append(a.elapsed_time(b))
+                rows.append(before)
         avg_ms = sum(ms) / len(ms)
-        # average rows per launch: committed tokens tell how many row-evaluations happened in total
-        # (each launch evaluates the rows masked before it); approximate by mean masked count
-        mean_rows = runner_mean_rows(runner, cfg)
+        mean_rows = sum(rows) / len(rows)
         bytes_per_launch = w_bytes + mean_rows * cfg.Dh * 2 + mean_rows * 8
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         roof = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
                     kernel="lmhead_kernel + lmhead_reduce_kernel (one dlm_lmhead_confidence call)",
                     avg_us=round(avg_ms * 1e3, 2), median_us=round(sorted(ms)[len(ms) // 2] * 1e3, 2),
-                    launches=len(ms), bytes_per_launch=int(bytes_per_launch), mean_rows=round(mean_rows, 1))
+                    launches=len(ms), bytes_per_launch=int(bytes_per_launch), mean_rows=round(mean_rows, 1),
+                    flops_per_launch=int(2 * mean_rows * cfg.Dh * cfg.V),
+                    mfma_tflops=round(2 * mean_rows * cfg.Dh * cfg.V / (avg_ms * 1e-3) / 1e12, 1))
 
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------------
     cpu = None
@@ -200,14 +204,6 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
-
-
-def runner_mean_rows(runner, cfg) -> float:
-    """Mean number of masked rows an LM-head launch processed, over whole rollouts: the rows masked
-    before step s of a block.  Reconstructed from the per-step commit totals is not possible on the
-    host without per-step logs, so the runner's counters are used: total row evaluations = sum over
-    productive steps of the masked count before the step."""
-    return runner.row_evals / max(1, runner.lm_launches) if hasattr(runner, "row_evals") else float(cfg.B * cfg.Lb) / 2
 
 
 if __name__ == "__main__":

@@ -187,6 +187,7 @@ class StepRunner:
         self.empty = 0
         self.blocks_done = 0
         self.steps_per_block = []
+        self.log = []                   # per polled step, in queue order: (block, masked before, masked after)
 
     def _begin_next_block(self):
         g = self.g
@@ -205,6 +206,7 @@ class StepRunner:
         ev, host = self.pending.pop(0)
         ev.synchronize()
         rem = int(host.sum())
+        self.log.append((self.block, self.rem_prev, rem))
         if self.rem_prev > 0:
             self.known += 1
             self.committed += self.rem_prev - rem
