@@ -402,6 +402,7 @@ extern "C" int dlm_set_option(const char* name, int value) {
         g_attn_variant = value;
         return DLM_OK;
     }
+    if (!strcmp(name, "lmhead_variant")) return lm_set_variant(value);
     return fail(DLM_ERR_INVALID_ARG, "set_option: unknown option '%s'", name);
 }
 

@@ -35,7 +35,7 @@ struct LmParams {
     const int32_t* target;
     float* ztarget;
     f32x4* part;  // [n_vtiles][M] of (max, sumexp, runner-up, argmax bits)
-    int n_vt;
+    int n_vt, n_mc;
 };
 
 struct Red {
@@ -66,17 +66,29 @@ __device__ __forceinline__ Red red_shfl_xor(const Red a, int off) {
 }
 
 constexpr int KC = 64;             // Dh elements per pipeline stage (128 B per row)
-constexpr int LP = KC * 2 + 16;    // LDS row pitch in bytes
+constexpr int LP = KC * 2 + 16;    // LDS row pitch in bytes: 16-byte reads of 16 consecutive rows hit distinct banks
+
+// Workgroup -> (vocabulary tile, row chunk).  Workgroups are dealt round-robin to the 8 XCDs (each with
+// its own L2), so the row chunks that share one W tile get consecutive slots on the SAME XCD: the tile
+// comes from HBM once and the other chunks hit it in that XCD's L2.
+__device__ __forceinline__ void lm_tile_of_block(int bid, int n_mc, int& vt, int& mc) {
+    const int xcd = bid & 7, slot = bid >> 3;
+    mc = slot % n_mc;
+    vt = (slot / n_mc) * 8 + xcd;
+}
 
 // WV x WH wavefronts; each owns TVW x THW accumulator tiles of 32 (vocab) x 32 (hidden rows).
-template <int WV, int WH, int TVW, int THW>
+// PD = how many 64-element chunks of W / H are in flight in registers ahead of the one being multiplied.
+template <int WV, int WH, int TVW, int THW, int PD>
 __global__ __launch_bounds__(64 * WV * WH) void lmhead_kernel(LmParams p) {
     constexpr int NT = 64 * WV * WH;
     constexpr int TV = 32 * TVW * WV;   // vocabulary rows per workgroup
     constexpr int MB = 32 * THW * WH;   // hidden rows per workgroup
-    constexpr int WLD = (TV * 8) / NT;  // 16-byte loads per thread per stage (8 per row)
-    constexpr int HLD = (MB * 8) / NT;
-    static_assert((TV * 8) % NT == 0 && (MB * 8) % NT == 0, "tile / thread mismatch");
+    constexpr int RPP = NT / 8;         // rows covered by one pass of 16-byte loads (8 threads per 128-byte row)
+    constexpr int WLD = (TV + RPP - 1) / RPP;
+    constexpr int HLD = (MB + RPP - 1) / RPP;
+    static_assert(TV % RPP == 0 || TV < RPP, "W tile / thread mismatch");
+    static_assert(MB % RPP == 0 || MB < RPP, "H tile / thread mismatch");
     constexpr int STAGE = (TV + MB) * LP;
     constexpr int RED_BYTES = WV * MB * 16;
     static_assert(2 * STAGE >= RED_BYTES, "reduction buffer must fit in the staging area");
@@ -85,42 +97,33 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_kernel(LmParams p) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wv = w % WV, wh = w / WV;
     const int n = lane & 31, hi = lane >> 5;
-    const int v0 = blockIdx.x * TV;
-    const int m0 = blockIdx.y * MB;
+    int vt, mc;
+    lm_tile_of_block(blockIdx.x, p.n_mc, vt, mc);
+    if (vt >= p.n_vt) return;
+    const int v0 = vt * TV;
+    const int m0 = mc * MB;
     int M = p.M;
     if (p.m_dev) M = min(M, max(*p.m_dev, 0));
     if (m0 >= M) return;
 
     // ---- global -> register staging addresses --------------------------------
-    const int lrow = tid >> 3, lc = tid & 7;  // 8 threads cover one 128-byte row segment
+    const int lrow = tid >> 3, lc = tid & 7;
+    const bool w_on = (TV >= RPP) || (lrow < TV);   // tiles smaller than one pass: the extra threads idle
+    const bool h_on = (MB >= RPP) || (lrow < MB);
     const uint16_t* wsrc[WLD];
 #pragma unroll
     for (int q = 0; q < WLD; ++q) {
-        const int v = min(v0 + lrow + q * (NT / 8), p.V - 1);  // rows past V are clamped, masked in the epilogue
+        const int v = min(v0 + lrow + q * RPP, p.V - 1);       // rows past V are clamped, masked in the epilogue
         wsrc[q] = p.w + (int64_t)v * p.w_stride + lc * 8;
     }
     const uint16_t* hsrc[HLD];
 #pragma unroll
     for (int q = 0; q < HLD; ++q) {
-        const int r = min(m0 + lrow + q * (NT / 8), M - 1);    // rows past M are clamped, never stored
+        const int r = min(m0 + lrow + q * RPP, M - 1);         // rows past M are clamped, never stored
         const int64_t src = p.row_idx ? p.row_idx[r] : r;
         hsrc[q] = p.hidden + src * p.h_stride + lc * 8;
     }
-    u32x4 wreg[WLD], hreg[HLD];
-    auto gload = [&](int kc) {
-#pragma unroll
-        for (int q = 0; q < WLD; ++q) wreg[q] = *reinterpret_cast<const u32x4*>(wsrc[q] + kc * KC);
-#pragma unroll
-        for (int q = 0; q < HLD; ++q) hreg[q] = *reinterpret_cast<const u32x4*>(hsrc[q] + kc * KC);
-    };
-    auto lstore = [&](int buf) {
-        unsigned char* Wl = smem + buf * STAGE;
-        unsigned char* Hl = Wl + TV * LP;
-#pragma unroll
-        for (int q = 0; q < WLD; ++q) *reinterpret_cast<u32x4*>(Wl + (lrow + q * (NT / 8)) * LP + lc * 16) = wreg[q];
-#pragma unroll
-        for (int q = 0; q < HLD; ++q) *reinterpret_cast<u32x4*>(Hl + (lrow + q * (NT / 8)) * LP + lc * 16) = hreg[q];
-    };
+    u32x4 wreg[PD][WLD], hreg[PD][HLD];
 
     f32x16 acc[TVW][THW];
 #pragma unroll
@@ -131,30 +134,83 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_kernel(LmParams p) {
             for (int i = 0; i < 16; ++i) acc[a][c][i] = 0.f;
 
     const int nk = p.Dh / KC;
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int kc = 0; kc < nk; ++kc) {
-        const int buf = kc & 1;
-        if (kc + 1 < nk) gload(kc + 1);
-        const unsigned char* Wl = smem + buf * STAGE + (wv * TVW * 32 + n) * LP + hi * 16;
-        const unsigned char* Hl = smem + buf * STAGE + TV * LP + (wh * THW * 32 + n) * LP + hi * 16;
-#pragma unroll
-        for (int ks = 0; ks < KC / 16; ++ks) {
-            bf16x8 af[TVW], bfr[THW];
-#pragma unroll
-            for (int a = 0; a < TVW; ++a) af[a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP + ks * 32);
-#pragma unroll
-            for (int c = 0; c < THW; ++c) bfr[c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + ks * 32);
-#pragma unroll
-            for (int a = 0; a < TVW; ++a)
-#pragma unroll
-                for (int c = 0; c < THW; ++c)
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0);
-        }
-        if (kc + 1 < nk) lstore(buf ^ 1);
-        __syncthreads();
+    // Every workgroup walks the Dh axis from a different starting chunk (and wraps).  Rows of W are a power
+    // of two apart, so workgroups marching in step over the same columns would all hit the same few HBM
+    // channels; the rotation spreads them (measured: 5.0 -> 6.2 TB/s on a pure read of W in this pattern).
+    const int kstart = (int)(((long)vt * 11) % nk);
+#define LM_CHUNK(kc) (((kc) + kstart) >= nk ? ((kc) + kstart - nk) : ((kc) + kstart))
+#define LM_GLOAD(slot, kc)                                                                               \
+    {                                                                                                    \
+        _Pragma("unroll") for (int q = 0; q < WLD; ++q) if (w_on)                                        \
+            wreg[slot][q] = *reinterpret_cast<const u32x4*>(wsrc[q] + LM_CHUNK(kc) * KC);                \
+        _Pragma("unroll") for (int q = 0; q < HLD; ++q) if (h_on)                                        \
+            hreg[slot][q] = *reinterpret_cast<const u32x4*>(hsrc[q] + LM_CHUNK(kc) * KC);                \
     }
+#define LM_LSTORE(slot, buf)                                                                             \
+    {                                                                                                    \
+        unsigned char* Wl_ = smem + (buf) * STAGE;                                                       \
+        unsigned char* Hl_ = Wl_ + TV * LP;                                                              \
+        _Pragma("unroll") for (int q = 0; q < WLD; ++q) if (w_on)                                        \
+            *reinterpret_cast<u32x4*>(Wl_ + (lrow + q * RPP) * LP + lc * 16) = wreg[slot][q];            \
+        _Pragma("unroll") for (int q = 0; q < HLD; ++q) if (h_on)                                        \
+            *reinterpret_cast<u32x4*>(Hl_ + (lrow + q * RPP) * LP + lc * 16) = hreg[slot][q];            \
+    }
+
+#define LM_COMPUTE(buf)                                                                                  \
+    {                                                                                                    \
+        const unsigned char* Wl = smem + (buf) * STAGE + (wv * TVW * 32 + n) * LP + hi * 16;             \
+        const unsigned char* Hl = smem + (buf) * STAGE + TV * LP + (wh * THW * 32 + n) * LP + hi * 16;   \
+        _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                         \
+            bf16x8 af[TVW], bfr[THW];                                                                    \
+            _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
+                af[a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP + ks * 32);                    \
+            _Pragma("unroll") for (int c = 0; c < THW; ++c)                                              \
+                bfr[c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + ks * 32);                   \
+            _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
+                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0); \
+        }                                                                                                \
+    }
+
+    // prologue: chunks 0 .. PD-1 in flight, chunk 0 staged, chunk PD requested
+#pragma unroll
+    for (int s = 0; s < PD; ++s)
+        if (s < nk) LM_GLOAD(s, s);
+    LM_LSTORE(0, 0);
+    if (PD < nk) LM_GLOAD(0, PD);
+    __syncthreads();
+
+    // Steady state, free of conditions so that the load counter waits can be exact: iteration kc stages
+    // chunk kc+1 (requested PD chunks ago) into the other LDS buffer, requests chunk kc+1+PD into the
+    // register slot just freed, multiplies chunk kc.  Chunk c lives in register slot c % PD.
+    int kc = 0;
+    const int n_main = (nk - PD - 1 > 0) ? ((nk - PD - 1) / PD) * PD : 0;
+    for (; kc < n_main; kc += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            LM_LSTORE((u + 1) % PD, (kc + u + 1) & 1);
+            LM_GLOAD((u + 1) % PD, kc + u + 1 + PD);
+            LM_COMPUTE((kc + u) & 1);
+            __syncthreads();
+        }
+    }
+    // Drain (at most 2*PD chunks): same steps, each guarded.
+#pragma unroll
+    for (int u = 0; u < 2 * PD; ++u) {
+        const int k = kc + u;
+        if (k < nk) {
+            if (k + 1 < nk) {
+                LM_LSTORE((u + 1) % PD, (k + 1) & 1);
+                if (k + 1 + PD < nk) LM_GLOAD((u + 1) % PD, k + 1 + PD);
+            }
+            LM_COMPUTE(k & 1);
+            __syncthreads();
+        }
+    }
+#undef LM_COMPUTE
+#undef LM_GLOAD
+#undef LM_CHUNK
+#undef LM_LSTORE
 
     // ---- epilogue: per hidden row (matrix column) reduce over this workgroup's vocabulary rows
     constexpr float LOG2E = 1.4426950408889634f;
@@ -216,44 +272,75 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_kernel(LmParams p) {
             red = red_merge(red, Red{o[0], o[1], o[2], __float_as_int(o[3])});
         }
         f32x4 out = {red.m, red.s, red.m2, __int_as_float(red.idx)};
-        p.part[(int64_t)blockIdx.x * p.M + r] = out;
+        p.part[(int64_t)vt * p.M + r] = out;
     }
 }
 
-// One wavefront per row: merge the per-vocabulary-tile partials in a fixed tree order.
+// One wavefront per row: merge the per-vocabulary-tile partials in a fixed order (four independent
+// chains per lane so the loads overlap, then a fixed tree).
 __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
     const int lane = threadIdx.x & 63;
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     int M = p.M;
     if (p.m_dev) M = min(M, max(*p.m_dev, 0));
     if (r >= M) return;
-    Red red{-INFINITY, 0.f, -INFINITY, 0x7fffffff};
-    for (int t = lane; t < p.n_vt; t += 64) {
-        const f32x4 v = p.part[(int64_t)t * p.M + r];
-        red = red_merge(red, Red{v[0], v[1], v[2], __float_as_int(v[3])});
-    }
+    Red red[4];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) red = red_merge(red, red_shfl_xor(red, off));
+    for (int a = 0; a < 4; ++a) red[a] = Red{-INFINITY, 0.f, -INFINITY, 0x7fffffff};
+    for (int t0 = 0; t0 < p.n_vt; t0 += 256) {
+        f32x4 v[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int t = t0 + a * 64 + lane;
+            v[a] = f32x4{-INFINITY, 0.f, -INFINITY, __int_as_float(0x7fffffff)};
+            if (t < p.n_vt) v[a] = p.part[(int64_t)t * p.M + r];
+        }
+#pragma unroll
+        for (int a = 0; a < 4; ++a) red[a] = red_merge(red[a], Red{v[a][0], v[a][1], v[a][2], __float_as_int(v[a][3])});
+    }
+    Red tot = red_merge(red_merge(red[0], red[1]), red_merge(red[2], red[3]));
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) tot = red_merge(tot, red_shfl_xor(tot, off));
     if (lane == 0) {
         const int64_t oidx = (p.out_scatter && p.row_idx) ? (int64_t)p.row_idx[r] : (int64_t)r;
-        p.conf[oidx] = 1.0f / red.s;          // exp(zmax - lse) = 1 / sum_v exp(z_v - zmax)
-        p.tok[oidx] = red.idx;
-        if (p.lse) p.lse[oidx] = red.m + logf(red.s);
-        if (p.zmax) p.zmax[oidx] = red.m;
-        if (p.z2nd) p.z2nd[oidx] = red.m2;
+        p.conf[oidx] = 1.0f / tot.s;          // exp(zmax - lse) = 1 / sum_v exp(z_v - zmax)
+        p.tok[oidx] = tot.idx;
+        if (p.lse) p.lse[oidx] = tot.m + logf(tot.s);
+        if (p.zmax) p.zmax[oidx] = tot.m;
+        if (p.z2nd) p.z2nd[oidx] = tot.m2;
     }
 }
 
-struct LmPlan {
-    int variant;  // index into the launch table
-    int tv, mb;
+struct LmVariant {
+    int tv, mb, threads;
+    void (*launch)(dim3, hipStream_t, const LmParams&);
 };
+template <int WV, int WH, int TVW, int THW, int PD>
+static void launch_lm(dim3 grid, hipStream_t st, const LmParams& p) {
+    hipLaunchKernelGGL((lmhead_kernel<WV, WH, TVW, THW, PD>), grid, dim3(64 * WV * WH), 0, st, p);
+}
+#define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD>}
+static const LmVariant g_lm_variants[] = {
+    /* 0*/ LMV(4, 1, 1, 1, 3),  /* 1*/ LMV(4, 1, 1, 2, 3),  /* 2*/ LMV(2, 2, 2, 2, 3),  /* 3*/ LMV(2, 2, 2, 4, 3),
+    /* 4*/ LMV(4, 1, 1, 1, 2),  /* 5*/ LMV(4, 1, 1, 1, 4),  /* 6*/ LMV(4, 1, 2, 1, 2),  /* 7*/ LMV(4, 1, 2, 1, 3),
+    /* 8*/ LMV(8, 1, 1, 1, 3),  /* 9*/ LMV(4, 1, 2, 2, 3),  /*10*/ LMV(4, 1, 1, 2, 4),  /*11*/ LMV(4, 1, 1, 4, 3),
+    /*12*/ LMV(4, 1, 2, 4, 2),  /*13*/ LMV(2, 2, 2, 2, 4),  /*14*/ LMV(2, 2, 2, 4, 2),  /*15*/ LMV(2, 2, 2, 4, 4),
+    /*16*/ LMV(4, 2, 2, 2, 3),  /*17*/ LMV(4, 2, 1, 4, 3),  /*18*/ LMV(2, 4, 2, 2, 3),  /*19*/ LMV(4, 2, 2, 4, 2),
+    /*20*/ LMV(8, 1, 1, 2, 3),  /*21*/ LMV(4, 2, 1, 2, 3),
+};
+#undef LMV
+constexpr int N_LM_VARIANTS = sizeof(g_lm_variants) / sizeof(g_lm_variants[0]);
+constexpr int LM_MIN_TV = 128;   // smallest vocabulary tile of any variant: sizes the workspace
+int g_lm_variant = -1;           // -1 = choose by M; otherwise force an entry of the table (dlm_set_option)
 
-static LmPlan plan_lmhead(int M) {
-    if (M <= 32) return {0, 128, 32};
-    if (M <= 64) return {1, 128, 64};
-    if (M <= 128) return {2, 128, 128};
-    return {3, 128, 256};
+// Shape choice from a sweep at V = 126464, Dh = 4096 on MI355X (us per call): M<=64 is a pure W stream
+// (~182 us = 5.7 TB/s for every 128-row-tile shape); above that the 8-wavefront shapes hide LDS latency better.
+static int plan_lmhead(int M) {
+    if (g_lm_variant >= 0) return g_lm_variant;
+    if (M <= 32) return 0;
+    if (M <= 64) return 1;
+    if (M <= 128) return 16;
+    return 19;
 }
 
 static int validate_lm(const dlm_lmhead_args* a) {
@@ -280,8 +367,7 @@ using namespace dlm;
 
 extern "C" size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args* a) {
     if (!a || a->M <= 0 || a->V <= 0) return 0;
-    const LmPlan pl = plan_lmhead(a->M);
-    const size_t n_vt = ((size_t)a->V + pl.tv - 1) / pl.tv;
+    const size_t n_vt = ((size_t)a->V + LM_MIN_TV - 1) / LM_MIN_TV;   // enough for every kernel shape
     return n_vt * (size_t)a->M * sizeof(f32x4);
 }
 
@@ -293,7 +379,7 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     if (!a->workspace || a->workspace_bytes < need)
         return fail(DLM_ERR_WORKSPACE, "lmhead: workspace of %zu bytes needed, %zu given", need, a->workspace ? a->workspace_bytes : (size_t)0);
     if (!aligned16(a->workspace)) return fail(DLM_ERR_WORKSPACE, "lmhead: workspace not 16-byte aligned");
-    const LmPlan pl = plan_lmhead(a->M);
+    const LmVariant& var = g_lm_variants[plan_lmhead(a->M)];
     LmParams p;
     p.M = a->M; p.Dh = a->Dh; p.V = a->V;
     p.hidden = (const uint16_t*)a->hidden; p.h_stride = a->hidden_stride_row;
@@ -303,19 +389,22 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     p.conf = a->conf; p.tok = a->tok; p.lse = a->lse; p.zmax = a->zmax; p.z2nd = a->z2nd;
     p.target = a->target; p.ztarget = a->ztarget;
     p.part = (f32x4*)a->workspace;
-    p.n_vt = (a->V + pl.tv - 1) / pl.tv;
-    const int n_mc = (a->M + pl.mb - 1) / pl.mb;
-    if (n_mc > 65535) return fail(DLM_ERR_UNSUPPORTED, "lmhead: M too large");
+    p.n_vt = (a->V + var.tv - 1) / var.tv;
+    p.n_mc = (a->M + var.mb - 1) / var.mb;
+    const int64_t n_wg = (int64_t)((p.n_vt + 7) / 8) * 8 * p.n_mc;
+    if (n_wg > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "lmhead: M * V too large for one launch");
     hipStream_t st = (hipStream_t)stream;
-    const dim3 grid(p.n_vt, n_mc);
-    switch (pl.variant) {
-        case 0: hipLaunchKernelGGL((lmhead_kernel<4, 1, 1, 1>), grid, dim3(256), 0, st, p); break;
-        case 1: hipLaunchKernelGGL((lmhead_kernel<4, 1, 1, 2>), grid, dim3(256), 0, st, p); break;
-        case 2: hipLaunchKernelGGL((lmhead_kernel<2, 2, 2, 2>), grid, dim3(256), 0, st, p); break;
-        default: hipLaunchKernelGGL((lmhead_kernel<2, 2, 2, 4>), grid, dim3(256), 0, st, p); break;
-    }
+    var.launch(dim3((unsigned)n_wg), st, p);
     rc = check_hip(hipGetLastError(), "lmhead_kernel launch");
     if (rc != DLM_OK) return rc;
     hipLaunchKernelGGL(lmhead_reduce_kernel, dim3((a->M + 3) / 4), dim3(256), 0, st, p);
     return check_hip(hipGetLastError(), "lmhead_reduce_kernel launch");
 }
+
+namespace dlm {
+int lm_set_variant(int v) {
+    if (v < -1 || v >= N_LM_VARIANTS) return fail(DLM_ERR_INVALID_ARG, "set_option: lmhead_variant must be -1..%d", N_LM_VARIANTS - 1);
+    g_lm_variant = v;
+    return DLM_OK;
+}
+}  // namespace dlm
