@@ -65,7 +65,7 @@ __device__ __forceinline__ Red red_shfl_xor(const Red a, int off) {
     return o;
 }
 
-constexpr int KC = 64;             // Dh elements per pipeline stage (128 B per row)
+constexpr int KC = 64;             // Dh elements per pipeline stage (128 B per row); Dh must be a multiple of it
 constexpr int LP = KC * 2 + 16;    // LDS row pitch in bytes: 16-byte reads of 16 consecutive rows hit distinct banks
 
 // Workgroup -> (vocabulary tile, row chunk).  Workgroups are dealt round-robin to the 8 XCDs (each with
@@ -77,142 +77,13 @@ __device__ __forceinline__ void lm_tile_of_block(int bid, int n_mc, int& vt, int
     vt = (slot / n_mc) * 8 + xcd;
 }
 
-// WV x WH wavefronts; each owns TVW x THW accumulator tiles of 32 (vocab) x 32 (hidden rows).
-// PD = how many 64-element chunks of W / H are in flight in registers ahead of the one being multiplied.
-template <int WV, int WH, int TVW, int THW, int PD>
-__global__ __launch_bounds__(64 * WV * WH) void lmhead_kernel(LmParams p) {
+// Per hidden row (matrix column): reduce over this workgroup's vocabulary rows and write one partial.
+// Called after the main loop's final barrier, so the staging area can be reused.
+template <int WV, int WH, int TVW, int THW>
+__device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW][THW], unsigned char* smem, int v0, int m0,
+                                            int M, int vt, int wv, int wh, int n, int hi, int tid) {
     constexpr int NT = 64 * WV * WH;
-    constexpr int TV = 32 * TVW * WV;   // vocabulary rows per workgroup
-    constexpr int MB = 32 * THW * WH;   // hidden rows per workgroup
-    constexpr int RPP = NT / 8;         // rows covered by one pass of 16-byte loads (8 threads per 128-byte row)
-    constexpr int WLD = (TV + RPP - 1) / RPP;
-    constexpr int HLD = (MB + RPP - 1) / RPP;
-    static_assert(TV % RPP == 0 || TV < RPP, "W tile / thread mismatch");
-    static_assert(MB % RPP == 0 || MB < RPP, "H tile / thread mismatch");
-    constexpr int STAGE = (TV + MB) * LP;
-    constexpr int RED_BYTES = WV * MB * 16;
-    static_assert(2 * STAGE >= RED_BYTES, "reduction buffer must fit in the staging area");
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
-
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int wv = w % WV, wh = w / WV;
-    const int n = lane & 31, hi = lane >> 5;
-    int vt, mc;
-    lm_tile_of_block(blockIdx.x, p.n_mc, vt, mc);
-    if (vt >= p.n_vt) return;
-    const int v0 = vt * TV;
-    const int m0 = mc * MB;
-    int M = p.M;
-    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
-    if (m0 >= M) return;
-
-    // ---- global -> register staging addresses --------------------------------
-    const int lrow = tid >> 3, lc = tid & 7;
-    const bool w_on = (TV >= RPP) || (lrow < TV);   // tiles smaller than one pass: the extra threads idle
-    const bool h_on = (MB >= RPP) || (lrow < MB);
-    const uint16_t* wsrc[WLD];
-#pragma unroll
-    for (int q = 0; q < WLD; ++q) {
-        const int v = min(v0 + lrow + q * RPP, p.V - 1);       // rows past V are clamped, masked in the epilogue
-        wsrc[q] = p.w + (int64_t)v * p.w_stride + lc * 8;
-    }
-    const uint16_t* hsrc[HLD];
-#pragma unroll
-    for (int q = 0; q < HLD; ++q) {
-        const int r = min(m0 + lrow + q * RPP, M - 1);         // rows past M are clamped, never stored
-        const int64_t src = p.row_idx ? p.row_idx[r] : r;
-        hsrc[q] = p.hidden + src * p.h_stride + lc * 8;
-    }
-    u32x4 wreg[PD][WLD], hreg[PD][HLD];
-
-    f32x16 acc[TVW][THW];
-#pragma unroll
-    for (int a = 0; a < TVW; ++a)
-#pragma unroll
-        for (int c = 0; c < THW; ++c)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][c][i] = 0.f;
-
-    const int nk = p.Dh / KC;
-    // Every workgroup walks the Dh axis from a different starting chunk (and wraps).  Rows of W are a power
-    // of two apart, so workgroups marching in step over the same columns would all hit the same few HBM
-    // channels; the rotation spreads them (measured: 5.0 -> 6.2 TB/s on a pure read of W in this pattern).
-    const int kstart = (int)(((long)vt * 11) % nk);
-#define LM_CHUNK(kc) (((kc) + kstart) >= nk ? ((kc) + kstart - nk) : ((kc) + kstart))
-#define LM_GLOAD(slot, kc)                                                                               \
-    {                                                                                                    \
-        _Pragma("unroll") for (int q = 0; q < WLD; ++q) if (w_on)                                        \
-            wreg[slot][q] = *reinterpret_cast<const u32x4*>(wsrc[q] + LM_CHUNK(kc) * KC);                \
-        _Pragma("unroll") for (int q = 0; q < HLD; ++q) if (h_on)                                        \
-            hreg[slot][q] = *reinterpret_cast<const u32x4*>(hsrc[q] + LM_CHUNK(kc) * KC);                \
-    }
-#define LM_LSTORE(slot, buf)                                                                             \
-    {                                                                                                    \
-        unsigned char* Wl_ = smem + (buf) * STAGE;                                                       \
-        unsigned char* Hl_ = Wl_ + TV * LP;                                                              \
-        _Pragma("unroll") for (int q = 0; q < WLD; ++q) if (w_on)                                        \
-            *reinterpret_cast<u32x4*>(Wl_ + (lrow + q * RPP) * LP + lc * 16) = wreg[slot][q];            \
-        _Pragma("unroll") for (int q = 0; q < HLD; ++q) if (h_on)                                        \
-            *reinterpret_cast<u32x4*>(Hl_ + (lrow + q * RPP) * LP + lc * 16) = hreg[slot][q];            \
-    }
-
-#define LM_COMPUTE(buf)                                                                                  \
-    {                                                                                                    \
-        const unsigned char* Wl = smem + (buf) * STAGE + (wv * TVW * 32 + n) * LP + hi * 16;             \
-        const unsigned char* Hl = smem + (buf) * STAGE + TV * LP + (wh * THW * 32 + n) * LP + hi * 16;   \
-        _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                         \
-            bf16x8 af[TVW], bfr[THW];                                                                    \
-            _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
-                af[a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP + ks * 32);                    \
-            _Pragma("unroll") for (int c = 0; c < THW; ++c)                                              \
-                bfr[c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + ks * 32);                   \
-            _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
-                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0); \
-        }                                                                                                \
-    }
-
-    // prologue: chunks 0 .. PD-1 in flight, chunk 0 staged, chunk PD requested
-#pragma unroll
-    for (int s = 0; s < PD; ++s)
-        if (s < nk) LM_GLOAD(s, s);
-    LM_LSTORE(0, 0);
-    if (PD < nk) LM_GLOAD(0, PD);
-    __syncthreads();
-
-    // Steady state, free of conditions so that the load counter waits can be exact: iteration kc stages
-    // chunk kc+1 (requested PD chunks ago) into the other LDS buffer, requests chunk kc+1+PD into the
-    // register slot just freed, multiplies chunk kc.  Chunk c lives in register slot c % PD.
-    int kc = 0;
-    const int n_main = (nk - PD - 1 > 0) ? ((nk - PD - 1) / PD) * PD : 0;
-    for (; kc < n_main; kc += PD) {
-#pragma unroll
-        for (int u = 0; u < PD; ++u) {
-            LM_LSTORE((u + 1) % PD, (kc + u + 1) & 1);
-            LM_GLOAD((u + 1) % PD, kc + u + 1 + PD);
-            LM_COMPUTE((kc + u) & 1);
-            __syncthreads();
-        }
-    }
-    // Drain (at most 2*PD chunks): same steps, each guarded.
-#pragma unroll
-    for (int u = 0; u < 2 * PD; ++u) {
-        const int k = kc + u;
-        if (k < nk) {
-            if (k + 1 < nk) {
-                LM_LSTORE((u + 1) % PD, (k + 1) & 1);
-                if (k + 1 + PD < nk) LM_GLOAD((u + 1) % PD, k + 1 + PD);
-            }
-            LM_COMPUTE(k & 1);
-            __syncthreads();
-        }
-    }
-#undef LM_COMPUTE
-#undef LM_GLOAD
-#undef LM_CHUNK
-#undef LM_LSTORE
-
-    // ---- epilogue: per hidden row (matrix column) reduce over this workgroup's vocabulary rows
+    constexpr int MB = 32 * THW * WH;
     constexpr float LOG2E = 1.4426950408889634f;
     f32x4* redbuf = reinterpret_cast<f32x4*>(smem);  // [WV][MB] of (max, sumexp, runner-up, argmax bits)
     // (the loop above ended with a barrier: the staging area is free)
@@ -276,6 +147,333 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_kernel(LmParams p) {
     }
 }
 
+// WV x WH wavefronts; each owns TVW x THW accumulator tiles of 32 (vocab) x 32 (hidden rows).
+// PD = how many 64-element chunks of W / H are in flight in registers ahead of the one being multiplied.
+template <int WV, int WH, int TVW, int THW, int PD, int KCH = 64, int OCC = 1, bool PIPE = false>
+__global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
+    constexpr int NT = 64 * WV * WH;
+    constexpr int TV = 32 * TVW * WV;   // vocabulary rows per workgroup
+    constexpr int MB = 32 * THW * WH;   // hidden rows per workgroup
+    constexpr int KC = KCH;             // shadows the namespace constant: elements per stage of THIS shape
+    constexpr int LP = KC * 2 + 16;
+    constexpr int TPR = KC / 8;         // threads covering one row segment with 16-byte loads
+    constexpr int RPP = NT / TPR;       // rows covered by one pass
+    constexpr int WLD = (TV + RPP - 1) / RPP;
+    constexpr int HLD = (MB + RPP - 1) / RPP;
+    constexpr int STAGE = (TV + MB) * LP;
+    constexpr int RED_BYTES = WV * MB * 16;
+    static_assert(2 * STAGE >= RED_BYTES, "reduction buffer must fit in the staging area");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wv = w % WV, wh = w / WV;
+    const int n = lane & 31, hi = lane >> 5;
+    int vt, mc;
+    lm_tile_of_block(blockIdx.x, p.n_mc, vt, mc);
+    if (vt >= p.n_vt) return;
+    const int v0 = vt * TV;
+    const int m0 = mc * MB;
+    int M = p.M;
+    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (m0 >= M) return;
+
+    // ---- global -> register staging addresses --------------------------------
+    const int lrow = tid / TPR, lc = tid % TPR;
+#define W_ON(q) ((TV % RPP == 0) || (lrow + (q) * RPP < TV))   // a ragged last pass leaves some threads idle
+#define H_ON(q) ((MB % RPP == 0) || (lrow + (q) * RPP < MB))
+    const uint16_t* wsrc[WLD];
+#pragma unroll
+    for (int q = 0; q < WLD; ++q) {
+        const int v = min(v0 + lrow + q * RPP, p.V - 1);       // rows past V are clamped, masked in the epilogue
+        wsrc[q] = p.w + (int64_t)v * p.w_stride + lc * 8;
+    }
+    const uint16_t* hsrc[HLD];
+#pragma unroll
+    for (int q = 0; q < HLD; ++q) {
+        const int r = min(m0 + lrow + q * RPP, M - 1);         // rows past M are clamped, never stored
+        const int64_t src = p.row_idx ? p.row_idx[r] : r;
+        hsrc[q] = p.hidden + src * p.h_stride + lc * 8;
+    }
+    u32x4 wreg[PD][WLD], hreg[PD][HLD];
+
+    f32x16 acc[TVW][THW];
+#pragma unroll
+    for (int a = 0; a < TVW; ++a)
+#pragma unroll
+        for (int c = 0; c < THW; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][c][i] = 0.f;
+
+    const int nk = p.Dh / KC;
+    // Every workgroup walks the Dh axis from a different starting chunk (and wraps).  Rows of W are a power
+    // of two apart, so workgroups marching in step over the same columns would all hit the same few HBM
+    // channels; the rotation spreads them (measured: 5.0 -> 6.2 TB/s on a pure read of W in this pattern).
+    const int kstart = (int)(((long)vt * 11) % nk);
+#define LM_CHUNK(kc) (((kc) + kstart) >= nk ? ((kc) + kstart - nk) : ((kc) + kstart))
+#define LM_GLOAD(slot, kc)                                                                               \
+    {                                                                                                    \
+        _Pragma("unroll") for (int q = 0; q < WLD; ++q) if (W_ON(q))                                     \
+            wreg[slot][q] = *reinterpret_cast<const u32x4*>(wsrc[q] + LM_CHUNK(kc) * KC);                \
+        _Pragma("unroll") for (int q = 0; q < HLD; ++q) if (H_ON(q))                                     \
+            hreg[slot][q] = *reinterpret_cast<const u32x4*>(hsrc[q] + LM_CHUNK(kc) * KC);                \
+    }
+#define LM_LSTORE(slot, buf)                                                                             \
+    {                                                                                                    \
+        unsigned char* Wl_ = smem + (buf) * STAGE;                                                       \
+        unsigned char* Hl_ = Wl_ + TV * LP;                                                              \
+        _Pragma("unroll") for (int q = 0; q < WLD; ++q) if (W_ON(q))                                     \
+            *reinterpret_cast<u32x4*>(Wl_ + (lrow + q * RPP) * LP + lc * 16) = wreg[slot][q];            \
+        _Pragma("unroll") for (int q = 0; q < HLD; ++q) if (H_ON(q))                                     \
+            *reinterpret_cast<u32x4*>(Hl_ + (lrow + q * RPP) * LP + lc * 16) = hreg[slot][q];            \
+    }
+
+#define LM_COMPUTE(buf)                                                                                  \
+    {                                                                                                    \
+        const unsigned char* Wl = smem + (buf) * STAGE + (wv * TVW * 32 + n) * LP + hi * 16;             \
+        const unsigned char* Hl = smem + (buf) * STAGE + TV * LP + (wh * THW * 32 + n) * LP + hi * 16;   \
+        _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                         \
+            bf16x8 af[TVW], bfr[THW];                                                                    \
+            _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
+                af[a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP + ks * 32);                    \
+            _Pragma("unroll") for (int c = 0; c < THW; ++c)                                              \
+                bfr[c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + ks * 32);                   \
+            _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
+                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0); \
+        }                                                                                                \
+    }
+
+    // Software-pipelined iteration: fragments of step ks+1 are requested before the MFMAs of step ks, and
+    // the LDS stores of the next chunk are spread between the MFMA groups instead of preceding them, so the
+    // LDS port and the load-counter waits overlap with matrix work inside each wavefront.
+    constexpr int KSTEPS = KC / 16;
+    constexpr int NST = WLD + HLD;
+#define LM_STORE_ONE(slot, buf, i)                                                                       \
+    {                                                                                                    \
+        unsigned char* Wl_ = smem + (buf) * STAGE;                                                       \
+        unsigned char* Hl_ = Wl_ + TV * LP;                                                              \
+        if ((i) < WLD) { if (W_ON(i)) *reinterpret_cast<u32x4*>(Wl_ + (lrow + (i) * RPP) * LP + lc * 16) = wreg[slot][(i) < WLD ? (i) : 0]; } \
+        else { if (H_ON((i) - WLD)) *reinterpret_cast<u32x4*>(Hl_ + (lrow + ((i) - WLD) * RPP) * LP + lc * 16) = hreg[slot][(i) >= WLD ? (i) - WLD : 0]; } \
+    }
+#define LM_ITER_PIPE(buf, do_store, slot, nbuf)                                                          \
+    {                                                                                                    \
+        const unsigned char* Wl = smem + (buf) * STAGE + (wv * TVW * 32 + n) * LP + hi * 16;             \
+        const unsigned char* Hl = smem + (buf) * STAGE + TV * LP + (wh * THW * 32 + n) * LP + hi * 16;   \
+        bf16x8 af[2][TVW], bfr[2][THW];                                                                  \
+        _Pragma("unroll") for (int a = 0; a < TVW; ++a) af[0][a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP); \
+        _Pragma("unroll") for (int c = 0; c < THW; ++c) bfr[0][c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP); \
+        _Pragma("unroll") for (int ks = 0; ks < KSTEPS; ++ks) {                                          \
+            if (ks + 1 < KSTEPS) {                                                                       \
+                _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                          \
+                    af[(ks + 1) & 1][a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP + (ks + 1) * 32); \
+                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
+                    bfr[(ks + 1) & 1][c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + (ks + 1) * 32); \
+            }                                                                                            \
+            _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
+                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][a], bfr[ks & 1][c], acc[a][c], 0, 0, 0); \
+            if (do_store) {                                                                              \
+                _Pragma("unroll") for (int i = 0; i < NST; ++i)                                          \
+                    if (i * KSTEPS / NST == ks) LM_STORE_ONE(slot, nbuf, i);                             \
+            }                                                                                            \
+            __builtin_amdgcn_sched_barrier(0);                                                           \
+        }                                                                                                \
+    }
+
+    // prologue: chunks 0 .. PD-1 in flight, chunk 0 staged, chunk PD requested
+#pragma unroll
+    for (int s = 0; s < PD; ++s)
+        if (s < nk) LM_GLOAD(s, s);
+    LM_LSTORE(0, 0);
+    if (PD < nk) LM_GLOAD(0, PD);
+    __syncthreads();
+
+    // Steady state, free of conditions so that the load counter waits can be exact: iteration kc stages
+    // chunk kc+1 (requested PD chunks ago) into the other LDS buffer, requests chunk kc+1+PD into the
+    // register slot just freed, multiplies chunk kc.  Chunk c lives in register slot c % PD.
+    int kc = 0;
+    const int n_main = (nk - PD - 1 > 0) ? ((nk - PD - 1) / PD) * PD : 0;
+    for (; kc < n_main; kc += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            if (PIPE) {
+                LM_ITER_PIPE((kc + u) & 1, true, (u + 1) % PD, (kc + u + 1) & 1);
+                LM_GLOAD((u + 1) % PD, kc + u + 1 + PD);
+            } else {
+                LM_LSTORE((u + 1) % PD, (kc + u + 1) & 1);
+                LM_GLOAD((u + 1) % PD, kc + u + 1 + PD);
+                LM_COMPUTE((kc + u) & 1);
+            }
+            __syncthreads();
+        }
+    }
+    // Drain (at most 2*PD chunks): same steps, each guarded.
+#pragma unroll
+    for (int u = 0; u < 2 * PD; ++u) {
+        const int k = kc + u;
+        if (k < nk) {
+            if (k + 1 < nk) {
+                LM_LSTORE((u + 1) % PD, (k + 1) & 1);
+                if (k + 1 + PD < nk) LM_GLOAD((u + 1) % PD, k + 1 + PD);
+            }
+            LM_COMPUTE(k & 1);
+            __syncthreads();
+        }
+    }
+#undef W_ON
+#undef H_ON
+#undef LM_COMPUTE
+#undef LM_ITER_PIPE
+#undef LM_STORE_ONE
+#undef LM_GLOAD
+#undef LM_CHUNK
+#undef LM_LSTORE
+
+    lm_epilogue<WV, WH, TVW, THW>(p, acc, smem, v0, m0, M, vt, wv, wh, n, hi, tid);
+}
+
+// Second kernel family: W fragments go straight from global memory into MFMA A-operand registers.
+// The wavefronts of a workgroup split only the vocabulary, so no W element is shared between them and
+// staging W in LDS would only add LDS traffic (the LDS port, not the MFMA pipe, limits the shared-W shapes
+// once M > 128).  Only the H panel, which every wavefront needs, is staged in LDS.
+// Within a 64-element chunk a lane half `hi` owns elements [32*hi, 32*hi + 32): it reads 64 contiguous
+// bytes of its W row with four 16-byte loads, and MFMA step ks contracts elements 32*hi + 8*ks + e.  H is
+// read from LDS with the same element order, so the contraction still covers every k exactly once.
+template <int WV, int TVW, int THW, int PDW>
+__global__ __launch_bounds__(64 * WV) void lmhead_wdirect_kernel(LmParams p) {
+    constexpr int NT = 64 * WV;
+    constexpr int TV = 32 * TVW * WV;
+    constexpr int MB = 32 * THW;
+    constexpr int PDH = (PDW > 1) ? PDW - 1 : 1;   // H chunks in flight (H comes from L2: shorter latency)
+    constexpr int UNR = PDW * PDH;                 // iterations per unrolled group: both register rings return to slot 0
+    constexpr int RPP = NT / 8;
+    constexpr int HLD = (MB + RPP - 1) / RPP;
+    constexpr int HSTAGE = MB * LP;
+    static_assert(2 * HSTAGE >= WV * MB * 16, "reduction buffer must fit in the staging area");
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * HSTAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int n = lane & 31, hi = lane >> 5;
+    int vt, mc;
+    lm_tile_of_block(blockIdx.x, p.n_mc, vt, mc);
+    if (vt >= p.n_vt) return;
+    const int v0 = vt * TV;
+    const int m0 = mc * MB;
+    int M = p.M;
+    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (m0 >= M) return;
+
+    const uint16_t* wsrc[TVW];
+#pragma unroll
+    for (int a = 0; a < TVW; ++a) {
+        const int v = min(v0 + (wv * TVW + a) * 32 + n, p.V - 1);
+        wsrc[a] = p.w + (int64_t)v * p.w_stride + hi * 32;
+    }
+    const int lrow = tid >> 3, lc = tid & 7;
+#define H_ON(q) ((MB % RPP == 0) || (lrow + (q) * RPP < MB))
+    const uint16_t* hsrc[HLD];
+#pragma unroll
+    for (int q = 0; q < HLD; ++q) {
+        const int r = min(m0 + lrow + q * RPP, M - 1);
+        const int64_t src = p.row_idx ? p.row_idx[r] : r;
+        hsrc[q] = p.hidden + src * p.h_stride + lc * 8;
+    }
+    u32x4 wreg[PDW][TVW][4], hreg[PDH][HLD];
+    f32x16 acc[TVW][THW];
+#pragma unroll
+    for (int a = 0; a < TVW; ++a)
+#pragma unroll
+        for (int c = 0; c < THW; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][c][i] = 0.f;
+
+    const int nk = p.Dh / KC;
+    const int kstart = (int)(((long)vt * 11) % nk);
+#define LM_CHUNK(kc) (((kc) + kstart) >= nk ? ((kc) + kstart - nk) : ((kc) + kstart))
+#define WD_GLOAD_W(slot, kc)                                                                             \
+    {                                                                                                    \
+        const int ch_ = LM_CHUNK(kc) * KC;                                                               \
+        _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                                  \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                \
+                wreg[slot][a][j] = *reinterpret_cast<const u32x4*>(wsrc[a] + ch_ + j * 8);               \
+    }
+#define WD_GLOAD_H(slot, kc)                                                                             \
+    {                                                                                                    \
+        const int ch_ = LM_CHUNK(kc) * KC;                                                               \
+        _Pragma("unroll") for (int q = 0; q < HLD; ++q) if (H_ON(q))                                     \
+            hreg[slot][q] = *reinterpret_cast<const u32x4*>(hsrc[q] + ch_);                              \
+    }
+#define WD_LSTORE_H(slot, buf)                                                                           \
+    {                                                                                                    \
+        unsigned char* Hl_ = smem + (buf) * HSTAGE;                                                      \
+        _Pragma("unroll") for (int q = 0; q < HLD; ++q) if (H_ON(q))                                     \
+            *reinterpret_cast<u32x4*>(Hl_ + (lrow + q * RPP) * LP + lc * 16) = hreg[slot][q];            \
+    }
+#define WD_COMPUTE(wslot, buf)                                                                           \
+    {                                                                                                    \
+        const unsigned char* Hl = smem + (buf) * HSTAGE + n * LP + hi * 64;                              \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                               \
+            bf16x8 bfr[THW];                                                                             \
+            _Pragma("unroll") for (int c = 0; c < THW; ++c)                                              \
+                bfr[c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + ks * 16);                   \
+            _Pragma("unroll") for (int a = 0; a < TVW; ++a) {                                            \
+                union { u32x4 u; bf16x8 b; } af_;                                                        \
+                af_.u = wreg[wslot][a][ks];                                                              \
+                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af_.b, bfr[c], acc[a][c], 0, 0, 0); \
+            }                                                                                            \
+        }                                                                                                \
+    }
+
+    // prologue: H(0) staged in LDS buffer 0; registers hold H(1..PDH) and W(0..PDW-1); chunk c sits in
+    // slot c % PDH (H) / c % PDW (W)
+    WD_GLOAD_H(0, 0);
+#pragma unroll
+    for (int c = 0; c < PDW; ++c) {
+        if (c < nk) WD_GLOAD_W(c, c);
+        if (c + 1 < PDH && c + 1 < nk) WD_GLOAD_H((c + 1) % PDH, c + 1);
+    }
+    WD_LSTORE_H(0, 0);
+    if (PDH < nk) WD_GLOAD_H(0, PDH);
+    __syncthreads();
+
+    // steady state (no conditions): stage H(kc+1), request H(kc+1+PDH), multiply chunk kc, request W(kc+PDW)
+    int kc = 0;
+    const int n_main = (nk - PDW > 0) ? ((nk - PDW) / UNR) * UNR : 0;
+    for (; kc < n_main; kc += UNR) {
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            WD_LSTORE_H((u + 1) % PDH, (kc + u + 1) & 1);
+            WD_GLOAD_H((u + 1) % PDH, kc + u + 1 + PDH);
+            WD_COMPUTE(u % PDW, (kc + u) & 1);
+            WD_GLOAD_W(u % PDW, kc + u + PDW);
+            __syncthreads();
+        }
+    }
+    // drain: same steps, each guarded
+#pragma unroll
+    for (int u = 0; u < UNR + PDW; ++u) {
+        const int k = kc + u;
+        if (k < nk) {
+            if (k + 1 < nk) {
+                WD_LSTORE_H((u + 1) % PDH, (k + 1) & 1);
+                if (k + 1 + PDH < nk) WD_GLOAD_H((u + 1) % PDH, k + 1 + PDH);
+            }
+            WD_COMPUTE(u % PDW, k & 1);
+            if (k + PDW < nk) WD_GLOAD_W(u % PDW, k + PDW);
+            __syncthreads();
+        }
+    }
+#undef H_ON
+#undef WD_GLOAD_W
+#undef WD_GLOAD_H
+#undef WD_LSTORE_H
+#undef WD_COMPUTE
+#undef LM_CHUNK
+
+    lm_epilogue<WV, 1, TVW, THW>(p, acc, smem, v0, m0, M, vt, wv, 0, n, hi, tid);
+}
+
 // One wavefront per row: merge the per-vocabulary-tile partials in a fixed order (four independent
 // chains per lane so the loads overlap, then a fixed tree).
 __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
@@ -315,32 +513,46 @@ struct LmVariant {
     int tv, mb, threads;
     void (*launch)(dim3, hipStream_t, const LmParams&);
 };
-template <int WV, int WH, int TVW, int THW, int PD>
+template <int WV, int WH, int TVW, int THW, int PD, int KCH = 64, int OCC = 1, bool PIPE = false>
 static void launch_lm(dim3 grid, hipStream_t st, const LmParams& p) {
-    hipLaunchKernelGGL((lmhead_kernel<WV, WH, TVW, THW, PD>), grid, dim3(64 * WV * WH), 0, st, p);
+    hipLaunchKernelGGL((lmhead_kernel<WV, WH, TVW, THW, PD, KCH, OCC, PIPE>), grid, dim3(64 * WV * WH), 0, st, p);
 }
+#define LMP(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD, 64, 1, true>}
+template <int WV, int TVW, int THW, int PDW>
+static void launch_lmd(dim3 grid, hipStream_t st, const LmParams& p) {
+    hipLaunchKernelGGL((lmhead_wdirect_kernel<WV, TVW, THW, PDW>), grid, dim3(64 * WV), 0, st, p);
+}
+#define LMD(WV, TVW, THW, PDW) {32 * TVW * WV, 32 * THW, 64 * WV, launch_lmd<WV, TVW, THW, PDW>}
 #define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD>}
 static const LmVariant g_lm_variants[] = {
-    /* 0*/ LMV(4, 1, 1, 1, 3),  /* 1*/ LMV(4, 1, 1, 2, 3),  /* 2*/ LMV(2, 2, 2, 2, 3),  /* 3*/ LMV(2, 2, 2, 4, 3),
-    /* 4*/ LMV(4, 1, 1, 1, 2),  /* 5*/ LMV(4, 1, 1, 1, 4),  /* 6*/ LMV(4, 1, 2, 1, 2),  /* 7*/ LMV(4, 1, 2, 1, 3),
-    /* 8*/ LMV(8, 1, 1, 1, 3),  /* 9*/ LMV(4, 1, 2, 2, 3),  /*10*/ LMV(4, 1, 1, 2, 4),  /*11*/ LMV(4, 1, 1, 4, 3),
-    /*12*/ LMV(4, 1, 2, 4, 2),  /*13*/ LMV(2, 2, 2, 2, 4),  /*14*/ LMV(2, 2, 2, 4, 2),  /*15*/ LMV(2, 2, 2, 4, 4),
-    /*16*/ LMV(4, 2, 2, 2, 3),  /*17*/ LMV(4, 2, 1, 4, 3),  /*18*/ LMV(2, 4, 2, 2, 3),  /*19*/ LMV(4, 2, 2, 4, 2),
-    /*20*/ LMV(8, 1, 1, 2, 3),  /*21*/ LMV(4, 2, 1, 2, 3),
+    // shapes the planner uses, by row count M (sweep at V = 126464, Dh = 4096 on MI355X, us per call):
+    /*0*/ LMV(4, 1, 1, 1, 3),   // M <= 32   128 x 32 tile,  4 waves            ~181
+    /*1*/ LMP(4, 1, 1, 2, 3),   // M <= 64   128 x 64,       4 waves            ~181
+    /*2*/ LMP(8, 1, 1, 3, 3),   // M <= 96   256 x 96,       8 waves            ~191
+    /*3*/ LMP(4, 2, 2, 2, 3),   // M <= 128  256 x 128,      8 waves            ~200
+    /*4*/ LMP(4, 2, 2, 3, 2),   // M <= 192  256 x 192,      8 waves            ~235
+    /*5*/ LMP(4, 2, 2, 4, 2),   // M <= 256  256 x 256,      8 waves            ~283 (and row chunks beyond)
+    // alternatives kept for tests and tuning sweeps
+    /*6*/ LMV(2, 2, 2, 4, 3),   // 128 x 256, 4 waves, stores before the MFMA block
+    /*7*/ LMD(4, 1, 1, 3),      // W fragments straight from global memory, 128 x 32
+    /*8*/ LMD(4, 2, 4, 3),      // same, 256 x 128
+    /*9*/ LMD(4, 2, 8, 2),      // same, 256 x 256
 };
 #undef LMV
+#undef LMP
+#undef LMD
 constexpr int N_LM_VARIANTS = sizeof(g_lm_variants) / sizeof(g_lm_variants[0]);
 constexpr int LM_MIN_TV = 128;   // smallest vocabulary tile of any variant: sizes the workspace
 int g_lm_variant = -1;           // -1 = choose by M; otherwise force an entry of the table (dlm_set_option)
 
-// Shape choice from a sweep at V = 126464, Dh = 4096 on MI355X (us per call): M<=64 is a pure W stream
-// (~182 us = 5.7 TB/s for every 128-row-tile shape); above that the 8-wavefront shapes hide LDS latency better.
 static int plan_lmhead(int M) {
     if (g_lm_variant >= 0) return g_lm_variant;
     if (M <= 32) return 0;
     if (M <= 64) return 1;
-    if (M <= 128) return 16;
-    return 19;
+    if (M <= 96) return 2;
+    if (M <= 128) return 3;
+    if (M <= 192) return 4;
+    return 5;
 }
 
 static int validate_lm(const dlm_lmhead_args* a) {

@@ -59,9 +59,9 @@ def compare(got, ref, sel=None):
         assert np.array_equal(np.isfinite(g["zt"]), fin)
 
 
-@pytest.mark.parametrize("M,Dh,V", [(1, 64, 300), (16, 256, 2048), (33, 128, 777), (64, 192, 1000),
-                                    (100, 320, 1500), (200, 256, 900), (256, 128, 2048), (300, 64, 515),
-                                    (700, 64, 400)])
+@pytest.mark.parametrize("M,Dh,V", [(1, 64, 300), (16, 256, 2048), (33, 128, 777), (64, 192, 1000), (90, 128, 600),
+                                    (100, 320, 1500), (150, 128, 700), (200, 256, 900), (256, 128, 2048),
+                                    (300, 64, 515), (700, 64, 400)])
 def test_shapes_vs_oracle(M, Dh, V):
     # covers every row-tile variant (<=32, <=64, <=128, <=256 rows), several row chunks, ragged V tails
     h, w = rnd(M + Dh, (M, Dh)), rnd(V + Dh, (V, Dh), Dh ** -0.25)
@@ -69,6 +69,21 @@ def test_shapes_vs_oracle(M, Dh, V):
     got = run_lm(h, w, forbid=V - 1)
     compare(got, ref)
     assert np.all(got["tok"] != V - 1)
+
+
+@pytest.mark.parametrize("variant", range(10))
+def test_every_kernel_shape(variant):
+    # each entry of the library's shape table on a problem with several row chunks and ragged tails
+    M, Dh, V = 300, 192, 1100
+    h, w = rnd(900, (M, Dh)), rnd(901, (V, Dh), Dh ** -0.25)
+    tgt = np.random.default_rng(2).integers(0, V, size=M).astype(np.int32)
+    ref = oracle.lmhead(h, w, forbid_token=V - 1, target=tgt)
+    dlm.set_option("lmhead_variant", variant)
+    try:
+        got = run_lm(h, w, forbid=V - 1, target=tgt)
+    finally:
+        dlm.set_option("lmhead_variant", -1)
+    compare(got, ref)
 
 
 def test_gather_scatter_mdev_temperature_target():
