@@ -185,6 +185,11 @@ size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args *args);
  *               BLOCK_WHEN_DONE: all rows, for sequences whose remaining becomes 0 in this
  *               call with n_commit > 0.  COMMITTED_ROWS: row i for each committed i
  *               (needs src_block.len == n_pos).
+ *   host_remaining_total  optional pointer to ONE int32 in pinned host memory that the device can
+ *               address (hipHostMalloc): receives sum_b remaining[b] with a system-scope store, so a
+ *               caller that records an event after the call can learn "block finished" without
+ *               queueing a device-to-host copy.  Only the single-workgroup path (one commit group per
+ *               sequence and B * n_pos <= 16384) supports it; otherwise DLM_ERR_UNSUPPORTED.
  * Selection compares fp32 values; outputs are integers (bit-exact given conf).
  * Limits: 1 <= group_len <= 1024; d % 8 == 0 for write-back.
  * Calls on one stream are ordered; the kernels of one call race with nothing else.
@@ -213,6 +218,7 @@ typedef struct dlm_commit_args {
     void *cache_k, *cache_v;
     int64_t c_stride_b, c_stride_h, c_stride_t;
     int32_t cache_pos0, Hkv, d;
+    int32_t *host_remaining_total;
 } dlm_commit_args;
 
 int dlm_unmask_commit(const dlm_commit_args *args, void *stream);

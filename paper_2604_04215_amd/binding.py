@@ -63,7 +63,8 @@ class CommitArgs(C.Structure):
                 ("commit_step", C.c_void_p), ("step", C.c_int32), ("writeback", C.c_int32),
                 ("src_block", KvSeg), ("cache_k", C.c_void_p), ("cache_v", C.c_void_p),
                 ("c_stride_b", C.c_int64), ("c_stride_h", C.c_int64), ("c_stride_t", C.c_int64),
-                ("cache_pos0", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32)]
+                ("cache_pos0", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32),
+                ("host_remaining_total", C.c_void_p)]
 
 
 class DlmError(RuntimeError):
@@ -229,8 +230,9 @@ def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group
                   rule: int = RULE_THRESHOLD, threshold: float = 0.0, force_top1: bool = True, k: int = 0,
                   commit_now=None, next_row_idx=None, next_m=None, commit_step=None, step: int = 0,
                   writeback: int = WB_NONE, src_block: Optional[Tuple] = None, cache_k=None, cache_v=None,
-                  cache_pos0: int = 0, stream=None) -> None:
-    """conf fp32 / tok int32 dense [B, n_pos]; x int32 [B, L]; mask uint8 [B, n_pos] (row-strided views are fine)."""
+                  cache_pos0: int = 0, host_remaining_total=None, stream=None) -> None:
+    """conf fp32 / tok int32 dense [B, n_pos]; x int32 [B, L]; mask uint8 [B, n_pos] (row-strided views are fine).
+    host_remaining_total: optional pinned CPU int32 tensor (1 element) the kernel writes through."""
     import torch
     a = CommitArgs()
     a.struct_size = C.sizeof(CommitArgs)
@@ -257,6 +259,10 @@ def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group
         a.cache_k, a.cache_v = _dev(cache_k, torch.bfloat16, "cache_k"), _dev(cache_v, torch.bfloat16, "cache_v")
         a.c_stride_b, a.c_stride_h, a.c_stride_t = cache_k.stride(0), cache_k.stride(1), cache_k.stride(2)
         a.cache_pos0, a.Hkv, a.d = int(cache_pos0), int(cache_k.shape[1]), int(cache_k.shape[3])
+    if host_remaining_total is not None:
+        if host_remaining_total.is_cuda or not host_remaining_total.is_pinned() or host_remaining_total.dtype != torch.int32:
+            raise ValueError("host_remaining_total must be a pinned CPU int32 tensor")
+        a.host_remaining_total = host_remaining_total.data_ptr()
     _check(lib().dlm_unmask_commit(C.byref(a), _stream(stream)))
 
 

@@ -137,6 +137,116 @@ __global__ __launch_bounds__(256) void commit_wave_kernel(CommitParams p) {
     }
 }
 
+// Rollout-sized problems (one commit group per sequence, at most 16384 positions in all): ONE workgroup
+// selects for every sequence (a wavefront per sequence, 16 at a time), then compacts the still-masked rows
+// in order and publishes the total, so a denoising step needs a single small launch here.
+constexpr int FUSED_MAX_POS = 16384;
+template <int CH>
+__global__ __launch_bounds__(1024) void commit_fused_kernel(CommitParams p, int32_t* row_idx, int32_t* next_m,
+                                                            int32_t* host_total) {
+    __shared__ uint8_t newmask[FUSED_MAX_POS];
+    __shared__ int wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    for (int b = w; b < p.B; b += 16) {
+        const int64_t base = (int64_t)b * p.n_pos;
+        uint8_t* mrow = p.mask + b * p.mask_stride_b;
+        float cf[CH];
+        bool masked[CH], chosen[CH];
+        int cnt = 0;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int i = lane + 64 * c;
+            masked[c] = (i < p.group_len) && (mrow[i] != 0);
+            chosen[c] = false;
+            float v = -INFINITY;
+            if (masked[c]) {
+                v = p.conf[base + i];
+                if (!(v == v)) v = -INFINITY;
+                ++cnt;
+            }
+            cf[c] = v;
+        }
+        cnt = wave_sum(cnt);
+        int ncom = 0;
+        if (cnt > 0) {
+            if (p.rule == DLM_RULE_THRESHOLD) {
+#pragma unroll
+                for (int c = 0; c < CH; ++c) chosen[c] = masked[c] && (cf[c] >= p.threshold);
+                if (p.force_top1) {
+                    Cand best{-INFINITY, 0x7fffffff};
+#pragma unroll
+                    for (int c = 0; c < CH; ++c)
+                        if (masked[c] && better(cf[c], lane + 64 * c, best.v, best.i)) best = Cand{cf[c], lane + 64 * c};
+                    best = wave_argmax(best);
+#pragma unroll
+                    for (int c = 0; c < CH; ++c)
+                        if (masked[c] && best.i == lane + 64 * c) chosen[c] = true;
+                }
+            } else {
+                const int kk = min(p.k, cnt);
+                for (int it = 0; it < kk; ++it) {
+                    Cand best{-INFINITY, 0x7fffffff};
+#pragma unroll
+                    for (int c = 0; c < CH; ++c)
+                        if (masked[c] && !chosen[c] && better(cf[c], lane + 64 * c, best.v, best.i))
+                            best = Cand{cf[c], lane + 64 * c};
+                    best = wave_argmax(best);
+#pragma unroll
+                    for (int c = 0; c < CH; ++c)
+                        if (masked[c] && best.i == lane + 64 * c) chosen[c] = true;
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int i = lane + 64 * c;
+            if (i < p.group_len) {
+                if (chosen[c]) {
+                    p.x[b * p.x_stride_b + p.x_pos0 + i] = p.tok[base + i];
+                    mrow[i] = 0;
+                    if (p.commit_step) p.commit_step[base + i] = (int16_t)p.step;
+                    ++ncom;
+                }
+                if (p.commit_now) p.commit_now[base + i] = chosen[c] ? 1 : 0;
+                newmask[base + i] = (masked[c] && !chosen[c]) ? 1 : 0;
+            }
+        }
+        ncom = wave_sum(ncom);
+        if (lane == 0) {
+            p.n_commit[b] = ncom;
+            p.remaining[b] = cnt - ncom;
+        }
+    }
+    __syncthreads();
+    // ordered compaction of the still-masked positions (from LDS)
+    const int N = p.B * p.n_pos;
+    int running = 0;
+    for (int start = 0; start < N; start += 1024) {
+        const int idx = start + tid;
+        const bool flag = (idx < N) && newmask[idx] != 0;
+        const unsigned long long bal = __ballot(flag);
+        const int prefix = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_tot[w] = __popcll(bal);
+        __syncthreads();
+        int off = running, all = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int t = wave_tot[j];
+            if (j < w) off += t;
+            all += t;
+        }
+        if (flag && row_idx) row_idx[off + prefix] = idx;
+        running += all;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (next_m) *next_m = running;
+        if (host_total) {
+            __hip_atomic_store(host_total, running, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
+}
+
 __global__ void zero2_i32_kernel(int32_t* a, int32_t* b, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) { a[i] = 0; b[i] = 0; }
@@ -326,32 +436,43 @@ extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
     }
     hipStream_t st = (hipStream_t)stream;
     if (a->B == 0) return DLM_OK;
-    const int n_groups = a->n_pos / a->group_len;
-    if (N > 0) {
-        CommitParams p;
-        p.B = a->B; p.n_pos = a->n_pos; p.group_len = a->group_len; p.n_groups = n_groups;
-        p.rule = a->rule; p.threshold = a->threshold; p.force_top1 = a->force_top1; p.k = a->k;
-        p.conf = a->conf; p.tok = a->tok; p.x = a->x; p.x_stride_b = a->x_stride_b; p.x_pos0 = a->x_pos0;
-        p.mask = a->mask; p.mask_stride_b = a->mask_stride_b; p.commit_now = a->commit_now;
-        p.n_commit = a->n_commit; p.remaining = a->remaining; p.commit_step = a->commit_step; p.step = a->step;
-        if (n_groups != 1) {
-            hipLaunchKernelGGL(zero2_i32_kernel, dim3((a->B + 255) / 256), dim3(256), 0, st, a->n_commit, a->remaining, a->B);
-        }
-        const int64_t waves = (int64_t)a->B * n_groups;
-        const unsigned grid = (unsigned)((waves + 3) / 4);
-        if (a->group_len <= 64) hipLaunchKernelGGL(commit_wave_kernel<1>, dim3(grid), dim3(256), 0, st, p);
-        else if (a->group_len <= 256) hipLaunchKernelGGL(commit_wave_kernel<4>, dim3(grid), dim3(256), 0, st, p);
-        else hipLaunchKernelGGL(commit_wave_kernel<16>, dim3(grid), dim3(256), 0, st, p);
-        int rc = check_hip(hipGetLastError(), "commit_wave_kernel launch");
+    const int n_groups = a->group_len > 0 ? a->n_pos / a->group_len : 0;
+    const bool fused = N > 0 && n_groups == 1 && N <= FUSED_MAX_POS;
+    if (a->host_remaining_total && !fused)
+        return fail(DLM_ERR_UNSUPPORTED, "unmask_commit: host_remaining_total needs one group per sequence and B*n_pos <= %d", FUSED_MAX_POS);
+    CommitParams p;
+    p.B = a->B; p.n_pos = a->n_pos; p.group_len = a->group_len; p.n_groups = n_groups;
+    p.rule = a->rule; p.threshold = a->threshold; p.force_top1 = a->force_top1; p.k = a->k;
+    p.conf = a->conf; p.tok = a->tok; p.x = a->x; p.x_stride_b = a->x_stride_b; p.x_pos0 = a->x_pos0;
+    p.mask = a->mask; p.mask_stride_b = a->mask_stride_b; p.commit_now = a->commit_now;
+    p.n_commit = a->n_commit; p.remaining = a->remaining; p.commit_step = a->commit_step; p.step = a->step;
+    if (fused) {
+        if (a->group_len <= 64) hipLaunchKernelGGL(commit_fused_kernel<1>, dim3(1), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total);
+        else if (a->group_len <= 256) hipLaunchKernelGGL(commit_fused_kernel<4>, dim3(1), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total);
+        else hipLaunchKernelGGL(commit_fused_kernel<16>, dim3(1), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total);
+        int rc = check_hip(hipGetLastError(), "commit_fused_kernel launch");
         if (rc != DLM_OK) return rc;
     } else {
-        hipLaunchKernelGGL(zero2_i32_kernel, dim3((a->B + 255) / 256), dim3(256), 0, st, a->n_commit, a->remaining, a->B);
-    }
-    if (a->next_row_idx) {
-        hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, a->mask, a->mask_stride_b, a->B, a->n_pos,
-                           a->next_row_idx, a->next_m);
-        int rc = check_hip(hipGetLastError(), "compact_kernel launch");
-        if (rc != DLM_OK) return rc;
+        if (N > 0) {
+            if (n_groups != 1) {
+                hipLaunchKernelGGL(zero2_i32_kernel, dim3((a->B + 255) / 256), dim3(256), 0, st, a->n_commit, a->remaining, a->B);
+            }
+            const int64_t waves = (int64_t)a->B * n_groups;
+            const unsigned grid = (unsigned)((waves + 3) / 4);
+            if (a->group_len <= 64) hipLaunchKernelGGL(commit_wave_kernel<1>, dim3(grid), dim3(256), 0, st, p);
+            else if (a->group_len <= 256) hipLaunchKernelGGL(commit_wave_kernel<4>, dim3(grid), dim3(256), 0, st, p);
+            else hipLaunchKernelGGL(commit_wave_kernel<16>, dim3(grid), dim3(256), 0, st, p);
+            int rc = check_hip(hipGetLastError(), "commit_wave_kernel launch");
+            if (rc != DLM_OK) return rc;
+        } else {
+            hipLaunchKernelGGL(zero2_i32_kernel, dim3((a->B + 255) / 256), dim3(256), 0, st, a->n_commit, a->remaining, a->B);
+        }
+        if (a->next_row_idx) {
+            hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(1024), 0, st, a->mask, a->mask_stride_b, a->B, a->n_pos,
+                               a->next_row_idx, a->next_m);
+            int rc = check_hip(hipGetLastError(), "compact_kernel launch");
+            if (rc != DLM_OK) return rc;
+        }
     }
     if (a->writeback != DLM_WB_NONE && N > 0) {
         return launch_kv_copy(&a->src_block, a->B, a->Hkv, a->d, a->cache_k, a->cache_v, a->c_stride_b, a->c_stride_h,

@@ -54,18 +54,16 @@ class GpuRollout:
         self.step_idx = 0
         self.m_host = n          # host-side upper bound of the masked-row count
         self.diagnostics = True  # also write lse / zmax / z2nd (tests); the benchmark turns it off
-        # ring of pinned host buffers + events for polling `remaining` (allocated once: pinned allocation is slow)
-        self._ring = [(torch.cuda.Event(), torch.empty(B, dtype=torch.int32, pin_memory=True)) for _ in range(4)]
+        # ring of pinned host words + events: the commit kernel stores the total still-masked count straight
+        # into pinned host memory, and an event recorded behind it tells the host when it may read it
+        self._ring = [(torch.cuda.Event(), torch.zeros(1, dtype=torch.int32).pin_memory()) for _ in range(4)]
         self._ring_pos = 0
+        self._last_poll = None
 
     def queue_poll(self):
-        """Start an asynchronous copy of `remaining` to pinned host memory; returns (event, host tensor).
-        At most 3 polls may be outstanding (the ring holds 4 slots)."""
-        ev, host = self._ring[self._ring_pos]
-        self._ring_pos = (self._ring_pos + 1) % len(self._ring)
-        host.copy_(self.remaining, non_blocking=True)
-        ev.record(torch.cuda.current_stream())
-        return ev, host
+        """(event, pinned host word) of the step queued last: after event.synchronize() the word holds the
+        number of positions still masked after that step.  At most 3 polls may be outstanding."""
+        return self._last_poll
 
     # geometry of the current block
     @property
@@ -101,6 +99,8 @@ class GpuRollout:
         """Enqueue one denoising step.  q [B, Lb, Hq, d]; kblk, vblk [B, Hkv, Lb, d]; hidden [B, Lb, Dh]."""
         cfg = self.cfg
         P, Lb, S = self.P, cfg.Lb, self.S
+        ev, host = self._ring[self._ring_pos]
+        self._ring_pos = (self._ring_pos + 1) % len(self._ring)
         prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
         suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
         dlm.block_attn(q, self.O, prefix=prefix, block=(kblk, vblk, P), suffix=suffix,
@@ -117,7 +117,10 @@ class GpuRollout:
                           commit_now=self.commit_now, next_row_idx=self.row_idx, next_m=self.m_dev,
                           commit_step=self.commit_step, step=self.step_idx,
                           writeback=dlm.WB_BLOCK_WHEN_DONE, src_block=(kblk, vblk, 0),
-                          cache_k=self.cache_k, cache_v=self.cache_v, cache_pos0=P)
+                          cache_k=self.cache_k, cache_v=self.cache_v, cache_pos0=P,
+                          host_remaining_total=host)
+        ev.record(torch.cuda.current_stream())
+        self._last_poll = (ev, host)
         self.step_idx += 1
 
     def set_row_bound(self, m: int) -> None:
@@ -147,7 +150,7 @@ class GpuRollout:
             while len(pending) > lag:
                 ev0, h0 = pending.pop(0)
                 ev0.synchronize()
-                rem = int(h0.sum())
+                rem = int(h0[0])
                 self.set_row_bound(rem if rem > 0 else 1)
                 if rem == 0:
                     done = True
@@ -157,7 +160,7 @@ class GpuRollout:
         if not done:
             for ev0, h0 in pending:
                 ev0.synchronize()
-                if int(h0.sum()) == 0:
+                if int(h0[0]) == 0:
                     done = True
             if not done:
                 raise RuntimeError(f"block {block} not finished after {steps} steps")
@@ -205,7 +208,7 @@ class StepRunner:
         """Wait for the oldest queued step's result; returns True when it finished the block."""
         ev, host = self.pending.pop(0)
         ev.synchronize()
-        rem = int(host.sum())
+        rem = int(host[0])
         self.log.append((self.block, self.rem_prev, rem))
         if self.rem_prev > 0:
             self.known += 1

@@ -56,7 +56,7 @@ def check_against_oracle(conf, tok, mask, x, x_pos0, got, *, rule, tau=0.0, k=0,
 @pytest.mark.parametrize("rule,tau,k", [("threshold", 0.9, 0), ("threshold", 0.5, 0), ("threshold", 1.5, 0),
                                         ("threshold", 0.0, 0), ("topk", 0, 1), ("topk", 0, 4), ("topk", 0, 40)])
 @pytest.mark.parametrize("B,n,group_len", [(8, 32, None), (3, 32, 4), (2, 200, 100), (2, 600, 300), (1, 1024, None),
-                                           (5, 64, 1)])
+                                           (5, 64, 1), (20, 200, None), (40, 512, None)])
 def test_selection_bit_exact(rule, tau, k, B, n, group_len):
     import zlib
     rng = np.random.default_rng(zlib.crc32(repr((rule, tau, k, B, n, group_len)).encode()))
@@ -68,6 +68,26 @@ def test_selection_bit_exact(rule, tau, k, B, n, group_len):
     x = rng.integers(0, 50000, size=(B, n + 20)).astype(np.int32)
     got = run_commit(conf, tok, mask, x, 11, rule=rule, tau=tau, k=k, group_len=group_len)
     check_against_oracle(conf, tok, mask, x, 11, got, rule=rule, tau=tau, k=k, group_len=group_len)
+
+
+def test_host_visible_total():
+    """The single-workgroup path can publish the still-masked total straight into pinned host memory."""
+    rng = np.random.default_rng(12)
+    B, n = 8, 32
+    conf, tok = rng.random((B, n)).astype(np.float32), rng.integers(0, 100, size=(B, n)).astype(np.int32)
+    mask = (rng.random((B, n)) < 0.7).astype(np.uint8)
+    d_mask, d_x = dev(mask), torch.zeros((B, n), dtype=torch.int32, device=DEV)
+    n_commit = torch.zeros(B, dtype=torch.int32, device=DEV)
+    remaining = torch.zeros(B, dtype=torch.int32, device=DEV)
+    host = torch.full((1,), -5, dtype=torch.int32).pin_memory()
+    dlm.unmask_commit(dev(conf), dev(tok), d_x, d_mask, n_commit, remaining, x_pos0=0, rule=dlm.RULE_TOPK, k=3,
+                      host_remaining_total=host)
+    torch.cuda.synchronize()
+    assert int(host[0]) == int(remaining.sum().item()) == int(d_mask.sum().item())
+    # not available when the multi-kernel path is needed
+    with pytest.raises(dlm.DlmError):
+        dlm.unmask_commit(dev(conf), dev(tok), d_x, d_mask, n_commit, remaining, x_pos0=0, group_len=4,
+                          rule=dlm.RULE_TOPK, k=1, host_remaining_total=host)
 
 
 def test_no_forced_pick():
