@@ -19,6 +19,8 @@ as ``uint16`` bit patterns on the host.
 from __future__ import annotations
 
 import dataclasses
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 from typing import Dict, Tuple
 
@@ -30,6 +32,15 @@ MASK64 = (1 << 64) - 1
 TAG_Q, TAG_KBLK, TAG_VBLK, TAG_HIDDEN, TAG_W, TAG_KCACHE, TAG_VCACHE, TAG_MASK, TAG_X = range(1, 10)
 
 W_CHUNK_ROWS = 1024  # W_vocab is drawn in fixed chunks of rows so any caller gets the same bits
+_WORKERS = max(1, min(16, os.cpu_count() or 1))   # independent streams are drawn in parallel threads
+
+
+def _pmap(fn, items):
+    items = list(items)
+    if len(items) <= 1 or _WORKERS == 1:
+        return [fn(i) for i in items]
+    with ThreadPoolExecutor(max_workers=_WORKERS) as ex:
+        return list(ex.map(fn, items))
 
 
 # --------------------------------------------------------------------------- #
@@ -215,17 +226,26 @@ def w_vocab(cfg, rows: slice | None = None) -> np.ndarray:
     lo, hi = (0, cfg.V) if rows is None else (rows.start or 0, cfg.V if rows.stop is None else rows.stop)
     out = np.empty((hi - lo, cfg.Dh), dtype=np.uint16)
     c0, c1 = lo // W_CHUNK_ROWS, (hi + W_CHUNK_ROWS - 1) // W_CHUNK_ROWS
-    for c in range(c0, c1):
+
+    def one(c):
         r0, r1 = c * W_CHUNK_ROWS, min((c + 1) * W_CHUNK_ROWS, cfg.V)
         blk = normal_bf16(cfg.seed, TAG_W, (c,), (r1 - r0, cfg.Dh), cfg.w_std)
         a, b = max(r0, lo), min(r1, hi)
         out[a - lo:b - lo] = blk[a - r0:b - r0]
+
+    _pmap(one, range(c0, c1))
     return out
 
 
 def _per_seq(cfg, tag: int, idx: Tuple[int, ...], shape_one, std: float = 1.0, seqs=None) -> np.ndarray:
-    seqs = range(cfg.B) if seqs is None else seqs
-    return np.stack([normal_bf16(cfg.seed, tag, idx + (b,), shape_one, std) for b in seqs])
+    seqs = list(range(cfg.B) if seqs is None else seqs)
+    out = np.empty((len(seqs),) + tuple(shape_one), dtype=np.uint16)
+
+    def one(n):
+        out[n] = normal_bf16(cfg.seed, tag, idx + (seqs[n],), shape_one, std)
+
+    _pmap(one, range(len(seqs)))
+    return out
 
 
 def step_q(cfg: Config, block: int, step: int, seqs=None) -> np.ndarray:
