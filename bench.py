@@ -24,6 +24,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per LM-head launch on the default workload, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
+# WRITE_SIZE x 1.0, factors calibrated with a 1 GiB copy); summary and commands in
+# profiles/lmhead_c2_rollout_hbm_traffic.md.  Only valid for --config c2.
+LMHEAD_C2_TRAFFIC_BYTES = 1123.8e6
 
 
 def parse():
@@ -155,7 +159,8 @@ def main():
         bytes_per_launch = w_bytes + mean_rows * cfg.Dh * 2 + mean_rows * 8
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         roof = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    frac=round(achieved / HBM_PEAK_GBS, 4),
+                    traffic=int(LMHEAD_C2_TRAFFIC_BYTES) if args.config == "c2" else None,
                     kernel="lmhead_kernel + lmhead_reduce_kernel (one dlm_lmhead_confidence call)",
                     avg_us=round(avg_ms * 1e3, 2), median_us=round(sorted(ms)[len(ms) // 2] * 1e3, 2),
                     launches=len(ms), bytes_per_launch=int(bytes_per_launch), mean_rows=round(mean_rows, 1),
