@@ -47,7 +47,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
     return x.b;
 }
 
-template <int D, int NWR, int NWK, int RTW, bool BC>
+template <int D, int NWR, int NWK, int RTW, bool BC, int PF = 1>
 __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
     static_assert(NWR == 1 || NWK == 1, "waves split either rows or keys");
     constexpr int NT = 64 * NWR * NWK;
@@ -124,42 +124,40 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
     unsigned char* Vl = Kl + 32 * KP;
     const int tl = wr * 64 + lane;  // thread index inside the wave group that shares a tile
 
-    u32x4 kreg[NLD], vreg[NLD];
-    auto prefetch = [&](int t) {
-#pragma unroll
-        for (int q = 0; q < NLD; ++q) {
-            const int cidx = tl + q * (64 * NWR);
-            const int row = cidx / C8, c = cidx - row * C8;
-            const int j = t * 32 + row;
-            u32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-            if (j < Lk) {
-                const uint16_t* kb = (j < e1) ? kb0 : ((j < e2) ? kb1 : kb2);
-                const uint16_t* vb = (j < e1) ? vb0 : ((j < e2) ? vb1 : vb2);
-                const int64_t stt = (j < e1) ? st0 : ((j < e2) ? st1 : st2);
-                const int loc = (j < e1) ? j : ((j < e2) ? j - e1 : j - e2);
-                const int64_t off = loc * stt + c * 8;
-                kv = *reinterpret_cast<const u32x4*>(kb + off);
-                vv = *reinterpret_cast<const u32x4*>(vb + off);
-            }
-            kreg[q] = kv;
-            vreg[q] = vv;
-        }
-    };
+    // PF tiles of K/V are in flight in registers per wave group; addresses are clamped so that the loads
+    // are unconditional (the load-counter waits stay exact) and rows past the end are zeroed when staged.
+    u32x4 kreg[PF][NLD], vreg[PF][NLD];
+#define ATTN_PREFETCH(slot, t)                                                                           \
+    {                                                                                                    \
+        _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
+            const int cidx = tl + q * (64 * NWR);                                                        \
+            const int row = cidx / C8, c = cidx - row * C8;                                              \
+            const int j = min((t) * 32 + row, Lk - 1);                                                   \
+            const uint16_t* kb = (j < e1) ? kb0 : ((j < e2) ? kb1 : kb2);                                \
+            const uint16_t* vb = (j < e1) ? vb0 : ((j < e2) ? vb1 : vb2);                                \
+            const int64_t stt = (j < e1) ? st0 : ((j < e2) ? st1 : st2);                                 \
+            const int loc = (j < e1) ? j : ((j < e2) ? j - e1 : j - e2);                                 \
+            const int64_t off = loc * stt + c * 8;                                                       \
+            kreg[slot][q] = *reinterpret_cast<const u32x4*>(kb + off);                                   \
+            vreg[slot][q] = *reinterpret_cast<const u32x4*>(vb + off);                                   \
+        }                                                                                                \
+    }
+#define ATTN_STAGE(slot, t)                                                                              \
+    {                                                                                                    \
+        __syncthreads(); /* everyone finished reading the previous tile */                               \
+        _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
+            const int cidx = tl + q * (64 * NWR);                                                        \
+            const int row = cidx / C8, c = cidx - row * C8;                                              \
+            const bool live = (t) * 32 + row < Lk;                                                       \
+            const u32x4 z = {0, 0, 0, 0};                                                                \
+            *reinterpret_cast<u32x4*>(Kl + row * KP + c * 16) = live ? kreg[slot][q] : z;                \
+            *reinterpret_cast<u32x4*>(Vl + row * VP + c * 16) = live ? vreg[slot][q] : z;                \
+        }                                                                                                \
+        __syncthreads();                                                                                 \
+    }
 
-    if (n_it > 0) prefetch(wk);
-    for (int it = 0; it < n_it; ++it) {
-        const int t = it * NWK + wk;
-        __syncthreads();  // everyone finished reading the previous tile
-#pragma unroll
-        for (int q = 0; q < NLD; ++q) {
-            const int cidx = tl + q * (64 * NWR);
-            const int row = cidx / C8, c = cidx - row * C8;
-            *reinterpret_cast<u32x4*>(Kl + row * KP + c * 16) = kreg[q];
-            *reinterpret_cast<u32x4*>(Vl + row * VP + c * 16) = vreg[q];
-        }
-        __syncthreads();
-        if (it + 1 < n_it) prefetch(t + NWK);
-        if (t >= T) continue;  // wave-uniform: this wave group has no tile in the last round
+    auto compute = [&](int t) {
+        if (t >= T) return;  // wave-uniform: this wave group has no tile in the last round
 
         // ---- S^T = K Q^T -----------------------------------------------------
         f32x16 S[RTW];
@@ -238,7 +236,37 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
                     O[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[rt][j2], O[rt][dt], 0, 0, 0);
             }
         }
+    };
+
+    // tile of iteration `it` for this wave group: it * NWK + wk; it sits in register slot it % PF
+    if (n_it > 0) {
+#pragma unroll
+        for (int s = 0; s < PF; ++s)
+            if (s < n_it) ATTN_PREFETCH(s, s * NWK + wk);
     }
+    int it = 0;
+    const int n_steady = (n_it - PF > 0) ? ((n_it - PF) / PF) * PF : 0;
+    for (; it < n_steady; it += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int t = (it + u) * NWK + wk;
+            ATTN_STAGE(u, t);
+            ATTN_PREFETCH(u, t + PF * NWK);
+            compute(t);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 2 * PF; ++u) {
+        const int i = it + u;
+        if (i < n_it) {
+            const int t = i * NWK + wk;
+            ATTN_STAGE(u % PF, t);
+            if (i + PF < n_it) ATTN_PREFETCH(u % PF, t + PF * NWK);
+            compute(t);
+        }
+    }
+#undef ATTN_PREFETCH
+#undef ATTN_STAGE
 
     // ---- finish -----------------------------------------------------------------
     constexpr float LN2 = 0.6931471805599453f;
@@ -338,7 +366,7 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
     }
     if (variant == 1 && p.R > 32) variant = 2;
     if (variant == 1) {
-        hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
     } else if (variant == 2) {
         hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC>), dim3((p.R + 127) / 128, p.Hkv, p.B), dim3(256), 0, st, p);
     } else {
