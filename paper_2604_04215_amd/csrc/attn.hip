@@ -107,6 +107,13 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
         }
         qlim[rt] = BC ? ((p.q_pos0 + i) / p.bs + 1) * p.bs : 0;
     }
+    int qlim_min = 0x7fffffff;   // first position that some row of this wavefront cannot see
+    if (BC) {
+#pragma unroll
+        for (int rt = 0; rt < RTW; ++rt) qlim_min = min(qlim_min, qlim[rt]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) qlim_min = min(qlim_min, shfl_xor(qlim_min, off));
+    }
 
     f32x16 O[RTW][D / 32];
     float m_run[RTW], l_run[RTW];
@@ -173,16 +180,22 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
         }
 
         // ---- online softmax; register i of a lane is key 8*(i/4) + 4*hi + i%4 ---
-        const bool ragged = BC || (t * 32 + 32 > Lk);
+        // Masking is needed only on the ragged last tile and, for the block-causal rule, on tiles that
+        // reach the first position some row of this wavefront cannot see (or that straddle two segments).
+        bool ragged = (t * 32 + 32 > Lk);
+        if (BC && !ragged) {
+            const int j0 = t * 32, j1 = t * 32 + 31;
+            const bool one_seg = (j1 < e1) || (j0 >= e1 && j1 < e2) || (j0 >= e2);
+            const int pos1 = (j1 < e1) ? p.seg[0].pos0 + j1 : ((j1 < e2) ? p.seg[1].pos0 + (j1 - e1) : p.seg[2].pos0 + (j1 - e2));
+            ragged = !one_seg || (pos1 >= qlim_min);
+        }
         bf16x8 pf[RTW][2];
 #pragma unroll
         for (int rt = 0; rt < RTW; ++rt) {
-            float sv[16];
             float mx = -INFINITY;
+            if (ragged) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float s = S[rt][i] * p.scale_log2;
-                if (ragged) {
+                for (int i = 0; i < 16; ++i) {
                     const int j = t * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
                     bool ok = j < Lk;
                     if (BC) {
@@ -190,12 +203,12 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
                                                  : ((j < e2) ? p.seg[1].pos0 + (j - e1) : p.seg[2].pos0 + (j - e2));
                         ok = ok && (pos < qlim[rt]);
                     }
-                    if (!ok) s = -INFINITY;
+                    if (!ok) S[rt][i] = -INFINITY;
                 }
-                sv[i] = s;
-                mx = fmaxf(mx, s);
             }
-            mx = fmaxf(mx, shfl_xor(mx, 32));
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[rt][i]);
+            mx = fmaxf(mx, shfl_xor(mx, 32)) * p.scale_log2;          // scale > 0: max commutes with scaling
             const float m_new = fmaxf(m_run[rt], mx);
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
             const float alpha = fast_exp2(m_run[rt] - m_use);
@@ -203,16 +216,19 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
             uint32_t pk[8];
 #pragma unroll
             for (int i = 0; i < 16; i += 2) {
-                const float p0 = fast_exp2(sv[i] - m_use), p1 = fast_exp2(sv[i + 1] - m_use);
+                const float p0 = fast_exp2(fmaf(S[rt][i], p.scale_log2, -m_use));
+                const float p1 = fast_exp2(fmaf(S[rt][i + 1], p.scale_log2, -m_use));
                 rs += p0 + p1;
                 pk[i >> 1] = pack_bf16x2(p0, p1);
             }
             l_run[rt] = l_run[rt] * alpha + rs;
             m_run[rt] = m_new;
+            if (__any(alpha != 1.0f)) {       // the running maximum of some row moved: rescale the accumulators
 #pragma unroll
-            for (int dt = 0; dt < D / 32; ++dt)
+                for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) O[rt][dt][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) O[rt][dt][i] *= alpha;
+            }
             u32x4 lo = {pk[0], pk[1], pk[2], pk[3]}, hi4 = {pk[4], pk[5], pk[6], pk[7]};
             pf[rt][0] = as_bf16x8(lo);
             pf[rt][1] = as_bf16x8(hi4);

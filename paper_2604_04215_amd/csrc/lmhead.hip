@@ -474,6 +474,131 @@ __global__ __launch_bounds__(64 * WV) void lmhead_wdirect_kernel(LmParams p) {
     lm_epilogue<WV, 1, TVW, THW>(p, acc, smem, v0, m0, M, vt, wv, 0, n, hi, tid);
 }
 
+// Third kernel family, for the MFMA-bound regime (M >= 256): both operand panels go from global memory
+// straight into LDS (global_load_lds, 16 bytes per lane, no staging registers), through a ring of NS stages
+// of 32 Dh elements each, so NS-1 stages are in flight while one is being multiplied and the register file is
+// left to a 128 x 128 accumulator tile per wavefront (4 x 4 MFMA tiles: half the LDS bytes per MFMA of the
+// 64 x 128 shapes).  A wave's load instruction fills 1 KB of LDS = 16 rows x 64 B in lane order, so the
+// bank-conflict-free layout is obtained by choosing WHICH 16-byte piece of its row each lane fetches:
+// piece c of row r is stored at position c ^ ((r >> 2) & 3).
+template <int WV, int WH, int TVW, int THW, int NS>
+__global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
+    constexpr int KCD = 32, ROWB = 64;
+    constexpr int NW = WV * WH, NT = 64 * NW;
+    constexpr int TV = 32 * TVW * WV, MB = 32 * THW * WH;
+    constexpr int STAGE = (TV + MB) * ROWB;
+    constexpr int IPW = (TV + MB) / 16 / NW;          // load instructions per wavefront per stage
+    static_assert((TV + MB) / 16 % NW == 0, "rows must split evenly over the wavefronts");
+    static_assert(NS >= 2 && NS <= 4, "ring of 2..4 stages");
+    static_assert(NS * STAGE >= WV * MB * 16, "reduction buffer must fit in the ring");
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wv = w % WV, wh = w / WV;
+    const int n = lane & 31, hi = lane >> 5;
+    int vt, mc;
+    lm_tile_of_block(blockIdx.x, p.n_mc, vt, mc);
+    if (vt >= p.n_vt) return;
+    const int v0 = vt * TV, m0 = mc * MB;
+    int M = p.M;
+    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (m0 >= M) return;
+
+    // per-lane source of each of this wavefront's load instructions (row of the combined [W rows | H rows] panel)
+    const uint16_t* src[IPW];
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+        const int row = (w * IPW + j) * 16 + (lane >> 2);
+        const int piece = (lane & 3) ^ ((row >> 2) & 3);
+        if (row < TV) {
+            const int v = min(v0 + row, p.V - 1);
+            src[j] = p.w + (int64_t)v * p.w_stride + piece * 8;
+        } else {
+            const int r = min(m0 + row - TV, M - 1);
+            const int64_t sr = p.row_idx ? p.row_idx[r] : r;
+            src[j] = p.hidden + sr * p.h_stride + piece * 8;
+        }
+    }
+    const int nk = p.Dh / KCD;
+    const int kstart = (int)(((long)vt * 11) % nk);
+#define DMA_CHUNK(kc) (((kc) + kstart) >= nk ? ((kc) + kstart - nk) : ((kc) + kstart))
+#define DMA_ISSUE(stage, kc)                                                                             \
+    {                                                                                                    \
+        const int ch_ = DMA_CHUNK(kc) * KCD;                                                             \
+        _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                  \
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + ch_), \
+                (__attribute__((address_space(3))) void*)(ring + (stage) * STAGE + (w * IPW + j) * 1024), 16, 0, 0); \
+    }
+    // wait until at most `cnt` of this wavefront's loads are outstanding, then meet the other wavefronts
+#define DMA_SYNC(cnt)                                                                                    \
+    {                                                                                                    \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(cnt) : "memory");                                       \
+        __builtin_amdgcn_s_barrier();                                                                    \
+        asm volatile("" ::: "memory");                                                                   \
+    }
+
+    f32x16 acc[TVW][THW];
+#pragma unroll
+    for (int a = 0; a < TVW; ++a)
+#pragma unroll
+        for (int c = 0; c < THW; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][c][i] = 0.f;
+
+    const int sw = (n >> 2) & 3;
+    const int off0 = n * ROWB + ((hi ^ sw) << 4);          // MFMA step 0: piece hi
+    const int off1 = n * ROWB + (((2 + hi) ^ sw) << 4);    // MFMA step 1: piece 2 + hi
+#define DMA_COMPUTE(stage)                                                                               \
+    {                                                                                                    \
+        const unsigned char* Wl = ring + (stage) * STAGE + wv * TVW * 32 * ROWB;                         \
+        const unsigned char* Hl = ring + (stage) * STAGE + TV * ROWB + wh * THW * 32 * ROWB;             \
+        bf16x8 af[2][TVW], bfr[2][THW];                                                                  \
+        _Pragma("unroll") for (int a = 0; a < TVW; ++a) af[0][a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * ROWB + off0); \
+        _Pragma("unroll") for (int c = 0; c < THW; ++c) bfr[0][c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * ROWB + off0); \
+        _Pragma("unroll") for (int a = 0; a < TVW; ++a) af[1][a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * ROWB + off1); \
+        _Pragma("unroll") for (int c = 0; c < THW; ++c) bfr[1][c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * ROWB + off1); \
+        _Pragma("unroll") for (int ks = 0; ks < 2; ++ks)                                                 \
+            _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
+                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][a], bfr[ks][c], acc[a][c], 0, 0, 0); \
+    }
+
+    // prologue: stages 0 .. NS-2 requested; stage 0 complete
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nk) DMA_ISSUE(s, s);
+    if (nk >= NS - 1) { DMA_SYNC(IPW * (NS - 2)); } else { DMA_SYNC(0); }
+
+    // steady state: request chunk kc+NS-1 into the stage freed by the previous iteration, multiply chunk kc,
+    // wait for this wavefront's share of chunk kc+1, barrier (which also frees stage kc % NS for the next request)
+    int kc = 0;
+    const int n_main = (nk - (NS - 1) > 0) ? ((nk - (NS - 1)) / NS) * NS : 0;
+    for (; kc < n_main; kc += NS) {
+#pragma unroll
+        for (int u = 0; u < NS; ++u) {
+            DMA_ISSUE((u + NS - 1) % NS, kc + u + NS - 1);
+            DMA_COMPUTE(u);
+            DMA_SYNC(IPW * (NS - 2));
+        }
+    }
+    // drain: the remaining requests (if any) are guarded; waits are total
+#pragma unroll
+    for (int u = 0; u < 2 * NS; ++u) {
+        const int k = kc + u;
+        if (k < nk) {
+            if (k + NS - 1 < nk) DMA_ISSUE((u + NS - 1) % NS, k + NS - 1);
+            DMA_COMPUTE(u % NS);
+            DMA_SYNC(0);
+        }
+    }
+#undef DMA_CHUNK
+#undef DMA_ISSUE
+#undef DMA_SYNC
+#undef DMA_COMPUTE
+    __syncthreads();
+    lm_epilogue<WV, WH, TVW, THW>(p, acc, ring, v0, m0, M, vt, wv, wh, n, hi, tid);
+}
+
 // One wavefront per row: merge the per-vocabulary-tile partials in a fixed order (four independent
 // chains per lane so the loads overlap, then a fixed tree).
 __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
@@ -523,6 +648,11 @@ static void launch_lmd(dim3 grid, hipStream_t st, const LmParams& p) {
     hipLaunchKernelGGL((lmhead_wdirect_kernel<WV, TVW, THW, PDW>), grid, dim3(64 * WV), 0, st, p);
 }
 #define LMD(WV, TVW, THW, PDW) {32 * TVW * WV, 32 * THW, 64 * WV, launch_lmd<WV, TVW, THW, PDW>}
+template <int WV, int WH, int TVW, int THW, int NS>
+static void launch_lma(dim3 grid, hipStream_t st, const LmParams& p) {
+    hipLaunchKernelGGL((lmhead_dma_kernel<WV, WH, TVW, THW, NS>), grid, dim3(64 * WV * WH), 0, st, p);
+}
+#define LMA(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lma<WV, WH, TVW, THW, NS>}
 #define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD>}
 static const LmVariant g_lm_variants[] = {
     // shapes the planner uses, by row count M (sweep at V = 126464, Dh = 4096 on MI355X, us per call):
@@ -537,8 +667,15 @@ static const LmVariant g_lm_variants[] = {
     /*7*/ LMD(4, 1, 1, 3),      // W fragments straight from global memory, 128 x 32
     /*8*/ LMD(4, 2, 4, 3),      // same, 256 x 128
     /*9*/ LMD(4, 2, 8, 2),      // same, 256 x 256
+    /*10*/ LMA(2, 2, 4, 4, 4),  // direct-to-LDS ring, 256 x 256, 4 waves x (128 x 128), 4 stages
+    /*11*/ LMA(2, 2, 4, 4, 3),  // same, 3 stages
+    /*12*/ LMA(2, 4, 4, 2, 4),  // 8 waves x (128 x 64)
+    /*13*/ LMA(4, 2, 2, 4, 4),  // 8 waves x (64 x 128)
+    /*14*/ LMA(2, 2, 2, 4, 4),  // 128 x 256, 4 waves x (64 x 128)
+    /*15*/ LMA(2, 2, 4, 2, 4),  // 256 x 128, 4 waves x (128 x 64)
 };
 #undef LMV
+#undef LMA
 #undef LMP
 #undef LMD
 constexpr int N_LM_VARIANTS = sizeof(g_lm_variants) / sizeof(g_lm_variants[0]);
