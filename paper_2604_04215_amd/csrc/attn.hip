@@ -58,7 +58,9 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
     constexpr int NLD = (32 * C8) / (64 * NWR);
     constexpr int MP = D + 4;               // merge buffer row pitch (floats)
     constexpr int MERGE_BYTES = (NWK > 1) ? NWK * 32 * MP * 4 : 0;
-    constexpr int SMEM = (NWK * TILE_BYTES > MERGE_BYTES) ? NWK * TILE_BYTES : MERGE_BYTES;
+    constexpr bool DB = (NWK == 1);        // row-split shapes double-buffer the shared K/V tile: one barrier per tile
+    constexpr int NBUF = DB ? 2 : 1;
+    constexpr int SMEM = (NBUF * NWK * TILE_BYTES > MERGE_BYTES) ? NBUF * NWK * TILE_BYTES : MERGE_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -127,7 +129,7 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
             for (int i = 0; i < 16; ++i) O[rt][dt][i] = 0.f;
     }
 
-    unsigned char* Kl = smem + wk * TILE_BYTES;
+    unsigned char* Kl = smem + wk * TILE_BYTES;   // re-pointed per tile when double-buffering
     unsigned char* Vl = Kl + 32 * KP;
     const int tl = wr * 64 + lane;  // thread index inside the wave group that shares a tile
 
@@ -161,6 +163,20 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
             *reinterpret_cast<u32x4*>(Vl + row * VP + c * 16) = live ? vreg[slot][q] : z;                \
         }                                                                                                \
         __syncthreads();                                                                                 \
+    }
+
+#define ATTN_STORE(slot, t, buf)                                                                         \
+    {                                                                                                    \
+        unsigned char* Kd = smem + (buf) * TILE_BYTES;                                                   \
+        unsigned char* Vd = Kd + 32 * KP;                                                                \
+        _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
+            const int cidx = tl + q * (64 * NWR);                                                        \
+            const int row = cidx / C8, c = cidx - row * C8;                                              \
+            const bool live = (t) * 32 + row < Lk;                                                       \
+            const u32x4 z = {0, 0, 0, 0};                                                                \
+            *reinterpret_cast<u32x4*>(Kd + row * KP + c * 16) = live ? kreg[slot][q] : z;                \
+            *reinterpret_cast<u32x4*>(Vd + row * VP + c * 16) = live ? vreg[slot][q] : z;                \
+        }                                                                                                \
     }
 
     auto compute = [&](int t) {
@@ -209,9 +225,14 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[rt][i]);
             mx = fmaxf(mx, shfl_xor(mx, 32)) * p.scale_log2;          // scale > 0: max commutes with scaling
-            const float m_new = fmaxf(m_run[rt], mx);
+            // m_run is the REFERENCE exponent of the row, not necessarily its maximum: it only moves when the
+            // tile maximum exceeds it by more than 2^LAZY (then p <= 2^LAZY, harmless in fp32 / bf16), so the
+            // accumulators are rescaled a handful of times per row instead of once per tile.
+            constexpr float LAZY = 8.0f;
+            const bool grow = mx > m_run[rt] + LAZY;                  // also true for the first visible key
+            const float m_new = grow ? mx : m_run[rt];
             const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = fast_exp2(m_run[rt] - m_use);
+            const float alpha = grow ? fast_exp2(m_run[rt] - m_use) : 1.0f;
             float rs = 0.f;
             uint32_t pk[8];
 #pragma unroll
@@ -222,13 +243,13 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
                 pk[i >> 1] = pack_bf16x2(p0, p1);
             }
             l_run[rt] = l_run[rt] * alpha + rs;
-            m_run[rt] = m_new;
-            if (__any(alpha != 1.0f)) {       // the running maximum of some row moved: rescale the accumulators
+            if (__any(grow && m_run[rt] != -INFINITY)) {   // some row with history moved its reference
 #pragma unroll
                 for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) O[rt][dt][i] *= alpha;
             }
+            m_run[rt] = m_new;
             u32x4 lo = {pk[0], pk[1], pk[2], pk[3]}, hi4 = {pk[4], pk[5], pk[6], pk[7]};
             pf[rt][0] = as_bf16x8(lo);
             pf[rt][1] = as_bf16x8(hi4);
@@ -260,27 +281,66 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
         for (int s = 0; s < PF; ++s)
             if (s < n_it) ATTN_PREFETCH(s, s * NWK + wk);
     }
-    int it = 0;
-    const int n_steady = (n_it - PF > 0) ? ((n_it - PF) / PF) * PF : 0;
-    for (; it < n_steady; it += PF) {
+    if (DB) {
+        // tile `it` is multiplied from LDS buffer it & 1 while tile it+1 is stored into the other buffer and
+        // tile it+1+PF is requested into the register slot that store frees
+        if (n_it > 0) {
+            ATTN_STORE(0, 0, 0);
+            if (PF < n_it) ATTN_PREFETCH(0, PF);
+        }
+        __syncthreads();
+        int it = 0;
+        const int n_steady = (n_it - PF - 1 > 0) ? ((n_it - PF - 1) / PF) * PF : 0;
+        for (; it < n_steady; it += PF) {
 #pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int t = (it + u) * NWK + wk;
-            ATTN_STAGE(u, t);
-            ATTN_PREFETCH(u, t + PF * NWK);
-            compute(t);
+            for (int u = 0; u < PF; ++u) {
+                const int t = it + u;
+                ATTN_STORE((u + 1) % PF, t + 1, (t + 1) & 1);
+                ATTN_PREFETCH((u + 1) % PF, t + 1 + PF);
+                Kl = smem + (t & 1) * TILE_BYTES;
+                Vl = Kl + 32 * KP;
+                compute(t);
+                __syncthreads();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2 * PF + 1; ++u) {
+            const int t = it + u;
+            if (t < n_it) {
+                if (t + 1 < n_it) {
+                    ATTN_STORE((u + 1) % PF, t + 1, (t + 1) & 1);
+                    if (t + 1 + PF < n_it) ATTN_PREFETCH((u + 1) % PF, t + 1 + PF);
+                }
+                Kl = smem + (t & 1) * TILE_BYTES;
+                Vl = Kl + 32 * KP;
+                compute(t);
+                __syncthreads();
+            }
+        }
+    } else {
+        int it = 0;
+        const int n_steady = (n_it - PF > 0) ? ((n_it - PF) / PF) * PF : 0;
+        for (; it < n_steady; it += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int t = (it + u) * NWK + wk;
+                ATTN_STAGE(u, t);
+                ATTN_PREFETCH(u, t + PF * NWK);
+                compute(t);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 2 * PF; ++u) {
+            const int i = it + u;
+            if (i < n_it) {
+                const int t = i * NWK + wk;
+                ATTN_STAGE(u % PF, t);
+                if (i + PF < n_it) ATTN_PREFETCH(u % PF, t + PF * NWK);
+                compute(t);
+            }
         }
     }
-#pragma unroll
-    for (int u = 0; u < 2 * PF; ++u) {
-        const int i = it + u;
-        if (i < n_it) {
-            const int t = i * NWK + wk;
-            ATTN_STAGE(u % PF, t);
-            if (i + PF < n_it) ATTN_PREFETCH(u % PF, t + PF * NWK);
-            compute(t);
-        }
-    }
+#undef ATTN_STORE
 #undef ATTN_PREFETCH
 #undef ATTN_STAGE
 
@@ -384,9 +444,9 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
     if (variant == 1) {
         hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
     } else if (variant == 2) {
-        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC>), dim3((p.R + 127) / 128, p.Hkv, p.B), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 3>), dim3((p.R + 127) / 128, p.Hkv, p.B), dim3(256), 0, st, p);
     } else {
-        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 2, BC>), dim3((p.R + 255) / 256, p.Hkv, p.B), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 2, BC, 3>), dim3((p.R + 255) / 256, p.Hkv, p.B), dim3(256), 0, st, p);
     }
     return check_hip(hipGetLastError(), "attn_kernel launch");
 }
