@@ -79,8 +79,10 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
         len1 = max(0, min(len1, lim - p.seg[1].pos0));
         len2 = max(0, min(len2, lim - p.seg[2].pos0));
     }
-    const int e1 = len0, e2 = len0 + len1, Lk = e2 + len2;
-    const int T = (Lk + 31) >> 5;
+    // Key tiles never straddle two segments: each segment is cut into its own 32-key tiles (its last one may
+    // be ragged), so a tile's rows share one base pointer, stride and position origin (all wave-uniform).
+    const int T0 = (len0 + 31) >> 5, T1 = (len1 + 31) >> 5, T2 = (len2 + 31) >> 5;
+    const int T = T0 + T1 + T2;
     const int n_it = (T + NWK - 1) / NWK;
 
     const uint16_t* kb0 = p.seg[0].k + b * p.seg[0].sb + kvh * p.seg[0].sh;
@@ -90,6 +92,9 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
     const uint16_t* kb2 = p.seg[2].k + b * p.seg[2].sb + kvh * p.seg[2].sh;
     const uint16_t* vb2 = p.seg[2].v + b * p.seg[2].sb + kvh * p.seg[2].sh;
     const int64_t st0 = p.seg[0].st, st1 = p.seg[1].st, st2 = p.seg[2].st;
+    // plain locals, so that selecting among them stays a register select (never an indexed reload of `p`)
+    const int sp0 = __builtin_amdgcn_readfirstlane(p.seg[0].pos0), sp1 = __builtin_amdgcn_readfirstlane(p.seg[1].pos0),
+              sp2 = __builtin_amdgcn_readfirstlane(p.seg[2].pos0);
 
     // ---- Q fragments (B operand: lane = query column, 8 consecutive d) ------
     bf16x8 qf[RTW][D / 16];
@@ -136,16 +141,22 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
     // PF tiles of K/V are in flight in registers per wave group; addresses are clamped so that the loads
     // are unconditional (the load-counter waits stay exact) and rows past the end are zeroed when staged.
     u32x4 kreg[PF][NLD], vreg[PF][NLD];
+    // segment of tile t (t < T), its index inside the segment, and the segment's extent
+#define ATTN_TILE(t, sg, lt, slen)                                                                       \
+    const int sg = ((t) < T0) ? 0 : (((t) < T0 + T1) ? 1 : 2);                                           \
+    const int lt = ((t) < T0) ? (t) : (((t) < T0 + T1) ? (t) - T0 : (t) - T0 - T1);                     \
+    const int slen = (sg == 0) ? len0 : ((sg == 1) ? len1 : len2);
 #define ATTN_PREFETCH(slot, t)                                                                           \
     {                                                                                                    \
+        const int tc_ = min((t), T - 1);                                                                 \
+        ATTN_TILE(tc_, sg_, lt_, slen_)                                                                  \
+        const uint16_t* kb = (sg_ == 0) ? kb0 : ((sg_ == 1) ? kb1 : kb2);                                \
+        const uint16_t* vb = (sg_ == 0) ? vb0 : ((sg_ == 1) ? vb1 : vb2);                                \
+        const int64_t stt = (sg_ == 0) ? st0 : ((sg_ == 1) ? st1 : st2);                                 \
         _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
             const int cidx = tl + q * (64 * NWR);                                                        \
             const int row = cidx / C8, c = cidx - row * C8;                                              \
-            const int j = min((t) * 32 + row, Lk - 1);                                                   \
-            const uint16_t* kb = (j < e1) ? kb0 : ((j < e2) ? kb1 : kb2);                                \
-            const uint16_t* vb = (j < e1) ? vb0 : ((j < e2) ? vb1 : vb2);                                \
-            const int64_t stt = (j < e1) ? st0 : ((j < e2) ? st1 : st2);                                 \
-            const int loc = (j < e1) ? j : ((j < e2) ? j - e1 : j - e2);                                 \
+            const int loc = min(lt_ * 32 + row, slen_ - 1);                                              \
             const int64_t off = loc * stt + c * 8;                                                       \
             kreg[slot][q] = *reinterpret_cast<const u32x4*>(kb + off);                                   \
             vreg[slot][q] = *reinterpret_cast<const u32x4*>(vb + off);                                   \
@@ -153,11 +164,13 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
     }
 #define ATTN_STAGE(slot, t)                                                                              \
     {                                                                                                    \
+        ATTN_TILE(min((t), T - 1), sg_, lt_, slen_)                                                      \
+        (void)sg_;                                                                                       \
         __syncthreads(); /* everyone finished reading the previous tile */                               \
         _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
             const int cidx = tl + q * (64 * NWR);                                                        \
             const int row = cidx / C8, c = cidx - row * C8;                                              \
-            const bool live = (t) * 32 + row < Lk;                                                       \
+            const bool live = ((t) < T) && (lt_ * 32 + row < slen_);                                     \
             const u32x4 z = {0, 0, 0, 0};                                                                \
             *reinterpret_cast<u32x4*>(Kl + row * KP + c * 16) = live ? kreg[slot][q] : z;                \
             *reinterpret_cast<u32x4*>(Vl + row * VP + c * 16) = live ? vreg[slot][q] : z;                \
@@ -167,113 +180,98 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
 
 #define ATTN_STORE(slot, t, buf)                                                                         \
     {                                                                                                    \
+        ATTN_TILE(min((t), T - 1), sg_, lt_, slen_)                                                      \
+        (void)sg_;                                                                                       \
         unsigned char* Kd = smem + (buf) * TILE_BYTES;                                                   \
         unsigned char* Vd = Kd + 32 * KP;                                                                \
         _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
             const int cidx = tl + q * (64 * NWR);                                                        \
             const int row = cidx / C8, c = cidx - row * C8;                                              \
-            const bool live = (t) * 32 + row < Lk;                                                       \
+            const bool live = ((t) < T) && (lt_ * 32 + row < slen_);                                     \
             const u32x4 z = {0, 0, 0, 0};                                                                \
             *reinterpret_cast<u32x4*>(Kd + row * KP + c * 16) = live ? kreg[slot][q] : z;                \
             *reinterpret_cast<u32x4*>(Vd + row * VP + c * 16) = live ? vreg[slot][q] : z;                \
         }                                                                                                \
     }
 
-    auto compute = [&](int t) {
-        if (t >= T) return;  // wave-uniform: this wave group has no tile in the last round
-
-        // ---- S^T = K Q^T -----------------------------------------------------
-        f32x16 S[RTW];
-#pragma unroll
-        for (int rt = 0; rt < RTW; ++rt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) S[rt][i] = 0.f;
-#pragma unroll
-        for (int c = 0; c < D / 16; ++c) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Kl + n * KP + (16 * c + 8 * hi) * 2);
-#pragma unroll
-            for (int rt = 0; rt < RTW; ++rt) S[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rt][c], S[rt], 0, 0, 0);
-        }
-
-        // ---- online softmax; register i of a lane is key 8*(i/4) + 4*hi + i%4 ---
-        // Masking is needed only on the ragged last tile and, for the block-causal rule, on tiles that
-        // reach the first position some row of this wavefront cannot see (or that straddle two segments).
-        bool ragged = (t * 32 + 32 > Lk);
-        if (BC && !ragged) {
-            const int j0 = t * 32, j1 = t * 32 + 31;
-            const bool one_seg = (j1 < e1) || (j0 >= e1 && j1 < e2) || (j0 >= e2);
-            const int pos1 = (j1 < e1) ? p.seg[0].pos0 + j1 : ((j1 < e2) ? p.seg[1].pos0 + (j1 - e1) : p.seg[2].pos0 + (j1 - e2));
-            ragged = !one_seg || (pos1 >= qlim_min);
-        }
-        bf16x8 pf[RTW][2];
-#pragma unroll
-        for (int rt = 0; rt < RTW; ++rt) {
-            float mx = -INFINITY;
-            if (ragged) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int j = t * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
-                    bool ok = j < Lk;
-                    if (BC) {
-                        const int pos = (j < e1) ? p.seg[0].pos0 + j
-                                                 : ((j < e2) ? p.seg[1].pos0 + (j - e1) : p.seg[2].pos0 + (j - e2));
-                        ok = ok && (pos < qlim[rt]);
-                    }
-                    if (!ok) S[rt][i] = -INFINITY;
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[rt][i]);
-            mx = fmaxf(mx, shfl_xor(mx, 32)) * p.scale_log2;          // scale > 0: max commutes with scaling
-            // m_run is the REFERENCE exponent of the row, not necessarily its maximum: it only moves when the
-            // tile maximum exceeds it by more than 2^LAZY (then p <= 2^LAZY, harmless in fp32 / bf16), so the
-            // accumulators are rescaled a handful of times per row instead of once per tile.
-            constexpr float LAZY = 8.0f;
-            const bool grow = mx > m_run[rt] + LAZY;                  // also true for the first visible key
-            const float m_new = grow ? mx : m_run[rt];
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = grow ? fast_exp2(m_run[rt] - m_use) : 1.0f;
-            float rs = 0.f;
-            uint32_t pk[8];
-#pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                const float p0 = fast_exp2(fmaf(S[rt][i], p.scale_log2, -m_use));
-                const float p1 = fast_exp2(fmaf(S[rt][i + 1], p.scale_log2, -m_use));
-                rs += p0 + p1;
-                pk[i >> 1] = pack_bf16x2(p0, p1);
-            }
-            l_run[rt] = l_run[rt] * alpha + rs;
-            if (__any(grow && m_run[rt] != -INFINITY)) {   // some row with history moved its reference
-#pragma unroll
-                for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) O[rt][dt][i] *= alpha;
-            }
-            m_run[rt] = m_new;
-            u32x4 lo = {pk[0], pk[1], pk[2], pk[3]}, hi4 = {pk[4], pk[5], pk[6], pk[7]};
-            pf[rt][0] = as_bf16x8(lo);
-            pf[rt][1] = as_bf16x8(hi4);
-        }
-
-        // ---- O^T += V^T P^T ----------------------------------------------------
-        const int s16 = lane & 15, blk = (lane >> 4) & 1;
-#pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) {
-#pragma unroll
-            for (int j2 = 0; j2 < 2; ++j2) {
-                union { s16x4 h[2]; bf16x8 v; } vf;
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const int krow = 16 * j2 + 8 * q + 4 * hi + (s16 >> 2);
-                    const int dcol = 32 * dt + 16 * blk + 4 * (s16 & 3);
-                    vf.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Vl + krow * VP + dcol * 2));
-                }
-#pragma unroll
-                for (int rt = 0; rt < RTW; ++rt)
-                    O[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[rt][j2], O[rt][dt], 0, 0, 0);
-            }
-        }
-    };
+    // One K/V tile: scores, (lazy) online softmax, P V.  A macro rather than a lambda: every array it
+    // touches must stay in registers.
+#define ATTN_COMPUTE() /* uses the tile index `t` of the enclosing scope */                              \
+    if (t < T) {                                                                                         \
+        f32x16 S[RTW]; \
+_Pragma("unroll") \
+        for (int rt = 0; rt < RTW; ++rt) \
+_Pragma("unroll") \
+            for (int i = 0; i < 16; ++i) S[rt][i] = 0.f; \
+_Pragma("unroll") \
+        for (int c = 0; c < D / 16; ++c) { \
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Kl + n * KP + (16 * c + 8 * hi) * 2); \
+_Pragma("unroll") \
+            for (int rt = 0; rt < RTW; ++rt) S[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rt][c], S[rt], 0, 0, 0); \
+        } \
+        ATTN_TILE(t, sg, lt, slen) \
+        const int spos0 = ((sg == 0) ? sp0 : ((sg == 1) ? sp1 : sp2)) + lt * 32; \
+        const bool ragged = (lt * 32 + 32 > slen) || (BC && spos0 + 31 >= qlim_min); \
+        bf16x8 pf[RTW][2]; \
+_Pragma("unroll") \
+        for (int rt = 0; rt < RTW; ++rt) { \
+            float mx = -INFINITY; \
+            if (ragged) { \
+_Pragma("unroll") \
+                for (int i = 0; i < 16; ++i) { \
+                    const int jl = 8 * (i >> 2) + 4 * hi + (i & 3); \
+                    bool ok = lt * 32 + jl < slen; \
+                    if (BC) ok = ok && (spos0 + jl < qlim[rt]); \
+                    if (!ok) S[rt][i] = -INFINITY; \
+                } \
+            } \
+_Pragma("unroll") \
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[rt][i]); \
+            mx = fmaxf(mx, shfl_xor(mx, 32)) * p.scale_log2; \
+            constexpr float LAZY = 8.0f; \
+            const bool grow = mx > m_run[rt] + LAZY; \
+            const float m_new = grow ? mx : m_run[rt]; \
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new; \
+            const float alpha = grow ? fast_exp2(m_run[rt] - m_use) : 1.0f; \
+            float rs = 0.f; \
+            uint32_t pk[8]; \
+_Pragma("unroll") \
+            for (int i = 0; i < 16; i += 2) { \
+                const float p0 = fast_exp2(fmaf(S[rt][i], p.scale_log2, -m_use)); \
+                const float p1 = fast_exp2(fmaf(S[rt][i + 1], p.scale_log2, -m_use)); \
+                rs += p0 + p1; \
+                pk[i >> 1] = pack_bf16x2(p0, p1); \
+            } \
+            l_run[rt] = l_run[rt] * alpha + rs; \
+            if (__any(grow && m_run[rt] != -INFINITY)) { \
+_Pragma("unroll") \
+                for (int dt = 0; dt < D / 32; ++dt) \
+_Pragma("unroll") \
+                    for (int i = 0; i < 16; ++i) O[rt][dt][i] *= alpha; \
+            } \
+            m_run[rt] = m_new; \
+            u32x4 lo = {pk[0], pk[1], pk[2], pk[3]}, hi4 = {pk[4], pk[5], pk[6], pk[7]}; \
+            pf[rt][0] = as_bf16x8(lo); \
+            pf[rt][1] = as_bf16x8(hi4); \
+        } \
+        const int s16 = lane & 15, blk = (lane >> 4) & 1; \
+_Pragma("unroll") \
+        for (int dt = 0; dt < D / 32; ++dt) { \
+_Pragma("unroll") \
+            for (int j2 = 0; j2 < 2; ++j2) { \
+                union { s16x4 h[2]; bf16x8 v; } vf; \
+_Pragma("unroll") \
+                for (int q = 0; q < 2; ++q) { \
+                    const int krow = 16 * j2 + 8 * q + 4 * hi + (s16 >> 2); \
+                    const int dcol = 32 * dt + 16 * blk + 4 * (s16 & 3); \
+                    vf.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Vl + krow * VP + dcol * 2)); \
+                } \
+_Pragma("unroll") \
+                for (int rt = 0; rt < RTW; ++rt) \
+                    O[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[rt][j2], O[rt][dt], 0, 0, 0); \
+            } \
+        } \
+    }
 
     // tile of iteration `it` for this wave group: it * NWK + wk; it sits in register slot it % PF
     if (n_it > 0) {
@@ -299,7 +297,7 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
                 ATTN_PREFETCH((u + 1) % PF, t + 1 + PF);
                 Kl = smem + (t & 1) * TILE_BYTES;
                 Vl = Kl + 32 * KP;
-                compute(t);
+                ATTN_COMPUTE();
                 __syncthreads();
             }
         }
@@ -313,7 +311,7 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
                 }
                 Kl = smem + (t & 1) * TILE_BYTES;
                 Vl = Kl + 32 * KP;
-                compute(t);
+                ATTN_COMPUTE();
                 __syncthreads();
             }
         }
@@ -326,7 +324,7 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
                 const int t = (it + u) * NWK + wk;
                 ATTN_STAGE(u, t);
                 ATTN_PREFETCH(u, t + PF * NWK);
-                compute(t);
+                ATTN_COMPUTE();
             }
         }
 #pragma unroll
@@ -336,12 +334,14 @@ __global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
                 const int t = i * NWK + wk;
                 ATTN_STAGE(u % PF, t);
                 if (i + PF < n_it) ATTN_PREFETCH(u % PF, t + PF * NWK);
-                compute(t);
+                ATTN_COMPUTE();
             }
         }
     }
 #undef ATTN_STORE
+#undef ATTN_COMPUTE
 #undef ATTN_PREFETCH
+#undef ATTN_TILE
 #undef ATTN_STAGE
 
     // ---- finish -----------------------------------------------------------------
