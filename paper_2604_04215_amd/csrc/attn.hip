@@ -47,8 +47,8 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
     return x.b;
 }
 
-template <int D, int NWR, int NWK, int RTW, bool BC, int PF = 1>
-__global__ __launch_bounds__(64 * NWR * NWK) void attn_kernel(AttnParams p) {
+template <int D, int NWR, int NWK, int RTW, bool BC, int PF = 1, int OCC = 1>
+__global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p) {
     static_assert(NWR == 1 || NWK == 1, "waves split either rows or keys");
     constexpr int NT = 64 * NWR * NWK;
     constexpr int KP = D * 2 + 16;          // K tile row pitch (bytes): 16-byte reads of 16 rows hit distinct banks
@@ -436,11 +436,20 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
     const int64_t BH = (int64_t)p.B * p.Hkv;
     int variant = g_attn_variant;
     if (variant == 0) {
-        if (p.R <= 32) variant = 1;                                  // waves split the keys, merge on chip
-        else if (BH * ((p.R + 255) / 256) < 1024) variant = 2;       // 128-row workgroups: more of them
-        else variant = 3;                                            // 256-row workgroups
+        const int64_t wgs128 = BH * ((p.R + 127) / 128);
+        if (p.R <= 32) variant = 1;           // waves split the keys, merge on chip
+        else if (wgs128 >= 768) variant = 6;  // 128-row workgroups, three resident per CU (softmax of one overlaps MFMA of another)
+        else variant = 4;                     // 128-row workgroups, two resident per CU, deeper prefetch
     }
     if (variant == 1 && p.R > 32) variant = 2;
+    if (variant >= 4) {   // 128-row workgroups, several resident per CU
+        const dim3 grid((p.R + 127) / 128, p.Hkv, p.B);
+        if (variant == 4) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 2, 2>), grid, dim3(256), 0, st, p);
+        else if (variant == 5) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 2, 3>), grid, dim3(256), 0, st, p);
+        else if (variant == 6) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 1, 3>), grid, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 1, 4>), grid, dim3(256), 0, st, p);
+        return check_hip(hipGetLastError(), "attn_kernel launch");
+    }
     if (variant == 1) {
         hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
     } else if (variant == 2) {
@@ -502,7 +511,7 @@ using namespace dlm;
 extern "C" int dlm_set_option(const char* name, int value) {
     if (!name) return fail(DLM_ERR_INVALID_ARG, "set_option: null name");
     if (!strcmp(name, "attn_variant")) {
-        if (value < 0 || value > 3) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..3");
+        if (value < 0 || value > 7) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..7");
         g_attn_variant = value;
         return DLM_OK;
     }

@@ -166,7 +166,7 @@ def test_refresh_compact_option_validation():
     assert L.dlm_mask_compact(None, 32, 2, 32, None, None, None) == dlm.DLM_ERR_INVALID_ARG
     assert L.dlm_mask_compact(0x1000, 16, 2, 32, 0x1000, 0x1000, None) == dlm.DLM_ERR_INVALID_ARG   # stride < n_pos
     assert L.dlm_set_option(b"nope", 1) == dlm.DLM_ERR_INVALID_ARG
-    assert L.dlm_set_option(b"attn_variant", 9) == dlm.DLM_ERR_INVALID_ARG
+    assert L.dlm_set_option(b"attn_variant", 99) == dlm.DLM_ERR_INVALID_ARG
     assert L.dlm_set_option(b"attn_variant", 0) == dlm.DLM_OK
 
 

@@ -58,7 +58,7 @@ def test_rollout_shape_mha(variant):
     run_case(B=2, Lq=32, Hq=4, Hkv=4, d=128, P=200, Lb=32, S=0, variant=variant, seed=1)
 
 
-@pytest.mark.parametrize("variant", [0, 2, 3])
+@pytest.mark.parametrize("variant", [0, 2, 3, 4, 5, 6, 7])
 def test_dual_cache_and_gqa7(variant):
     # 7 query heads per KV head (224 packed rows), prefix | block | suffix, ragged suffix
     run_case(B=2, Lq=32, Hq=14, Hkv=2, d=128, P=96, Lb=32, S=45, variant=variant, seed=2)
@@ -70,14 +70,14 @@ def test_shapes(d, Lq, Hq, Hkv):
     run_case(B=2, Lq=Lq, Hq=Hq, Hkv=Hkv, d=d, P=77, Lb=Lq, S=9, seed=3 + Lq)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 6])
 @pytest.mark.parametrize("bs", [1, 4, 32])
 def test_block_causal_rollout(variant, bs):
     # last block(s) of a block-diffusion sequence against the cache; positions are absolute
     run_case(B=2, Lq=8, Hq=8, Hkv=2, d=128, P=188, Lb=8, S=0, mode="block_causal", bs=bs, variant=variant, seed=5)
 
 
-@pytest.mark.parametrize("variant", [2, 3])
+@pytest.mark.parametrize("variant", [0, 2, 3, 4, 6])
 def test_block_causal_full_sequence(variant):
     # training-style pass: Lq = Lk, bidirectional inside blocks of 4, causal across blocks
     B, L, Hq, Hkv, d = 2, 204, 4, 2, 128
