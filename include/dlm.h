@@ -242,7 +242,8 @@ int dlm_kv_refresh(const dlm_kv_seg *src, int32_t B, int32_t Hkv, int32_t d,
  *   "attn_variant"  0 = pick the attention kernel shape from the problem shape (default);
  *                   1 = 32-row workgroups whose wavefronts split the keys (needs g*Lq <= 32,
  *                       otherwise falls back to 2); 2 = 128-row; 3 = 256-row workgroups (one per CU);
- *                   4..7 = 128-row workgroups sized for 2, 3, 3, 4 resident workgroups per CU.
+ *                   4..7 = 128-row workgroups sized for 2, 3, 3, 4 resident workgroups per CU;
+ *                   8..10 = key-split alternatives (deeper prefetch, 8 wavefronts) for g*Lq <= 32.
  *   "lmhead_variant" -1 = pick the LM-head kernel shape (workgroup tile, wavefront layout, prefetch
  *                   depth) from M (default); >= 0 forces one entry of the library's shape table.
  * Every shape computes the same function; the knobs exist for tests and tuning sweeps. */

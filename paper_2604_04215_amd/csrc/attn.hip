@@ -162,11 +162,18 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
             vreg[slot][q] = *reinterpret_cast<const u32x4*>(vb + off);                                   \
         }                                                                                                \
     }
+// Key-split wave groups are single wavefronts with private LDS tiles: LDS operations of one wavefront are
+    // processed in order, so only the compiler has to be kept from reordering them; no workgroup barrier.
+#define ATTN_TILE_SYNC()                                                                                 \
+    {                                                                                                    \
+        if (NWR == 1) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                 \
+        else __syncthreads();                                                                            \
+    }
 #define ATTN_STAGE(slot, t)                                                                              \
     {                                                                                                    \
         ATTN_TILE(min((t), T - 1), sg_, lt_, slen_)                                                      \
         (void)sg_;                                                                                       \
-        __syncthreads(); /* everyone finished reading the previous tile */                               \
+        ATTN_TILE_SYNC(); /* the previous tile has been read */                                          \
         _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
             const int cidx = tl + q * (64 * NWR);                                                        \
             const int row = cidx / C8, c = cidx - row * C8;                                              \
@@ -175,7 +182,7 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
             *reinterpret_cast<u32x4*>(Kl + row * KP + c * 16) = live ? kreg[slot][q] : z;                \
             *reinterpret_cast<u32x4*>(Vl + row * VP + c * 16) = live ? vreg[slot][q] : z;                \
         }                                                                                                \
-        __syncthreads();                                                                                 \
+        ATTN_TILE_SYNC();                                                                                \
     }
 
 #define ATTN_STORE(slot, t, buf)                                                                         \
@@ -275,9 +282,10 @@ _Pragma("unroll") \
 
     // tile of iteration `it` for this wave group: it * NWK + wk; it sits in register slot it % PF
     if (n_it > 0) {
+        const int rot0 = DB ? 0 : (int)((blockIdx.z * (unsigned)gridDim.y + blockIdx.y) * 5u % (unsigned)n_it);
 #pragma unroll
         for (int s = 0; s < PF; ++s)
-            if (s < n_it) ATTN_PREFETCH(s, s * NWK + wk);
+            if (s < n_it) ATTN_PREFETCH(s, ((s + rot0 >= n_it) ? s + rot0 - n_it : s + rot0) * NWK + wk);
     }
     if (DB) {
         // tile `it` is multiplied from LDS buffer it & 1 while tile it+1 is stored into the other buffer and
@@ -316,14 +324,19 @@ _Pragma("unroll") \
             }
         }
     } else {
+        // Each (sequence, KV head) starts its walk over the key tiles at a different tile and wraps: the K/V
+        // blocks of different heads are a large power-of-two-ish stride apart, so workgroups that all begin at
+        // tile 0 hit the same few HBM channels together.  Softmax is order-independent up to rounding.
+        const int rot = (n_it > 0) ? (int)((blockIdx.z * (unsigned)gridDim.y + blockIdx.y) * 5u % (unsigned)n_it) : 0;
+#define ATTN_KS_TILE(i) ((((i) + rot) >= n_it ? (i) + rot - n_it : (i) + rot) * NWK + wk)
         int it = 0;
         const int n_steady = (n_it - PF > 0) ? ((n_it - PF) / PF) * PF : 0;
         for (; it < n_steady; it += PF) {
 #pragma unroll
             for (int u = 0; u < PF; ++u) {
-                const int t = (it + u) * NWK + wk;
+                const int t = ATTN_KS_TILE(it + u);
                 ATTN_STAGE(u, t);
-                ATTN_PREFETCH(u, t + PF * NWK);
+                ATTN_PREFETCH(u, ATTN_KS_TILE(it + u + PF));
                 ATTN_COMPUTE();
             }
         }
@@ -331,14 +344,16 @@ _Pragma("unroll") \
         for (int u = 0; u < 2 * PF; ++u) {
             const int i = it + u;
             if (i < n_it) {
-                const int t = i * NWK + wk;
+                const int t = ATTN_KS_TILE(i);
                 ATTN_STAGE(u % PF, t);
-                if (i + PF < n_it) ATTN_PREFETCH(u % PF, t + PF * NWK);
+                if (i + PF < n_it) ATTN_PREFETCH(u % PF, ATTN_KS_TILE(i + PF));
                 ATTN_COMPUTE();
             }
         }
+#undef ATTN_KS_TILE
     }
 #undef ATTN_STORE
+#undef ATTN_TILE_SYNC
 #undef ATTN_COMPUTE
 #undef ATTN_PREFETCH
 #undef ATTN_TILE
@@ -442,6 +457,14 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
         else variant = 4;                     // 128-row workgroups, two resident per CU, deeper prefetch
     }
     if (variant == 1 && p.R > 32) variant = 2;
+    if (variant >= 8 && p.R <= 32) {   // key-split alternatives (tuning)
+        const dim3 grid(1, p.Hkv, p.B);
+        if (variant == 8) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2>), grid, dim3(256), 0, st, p);
+        else if (variant == 9) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 3>), grid, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((attn_kernel<D, 1, 8, 1, BC, 1>), grid, dim3(512), 0, st, p);
+        return check_hip(hipGetLastError(), "attn_kernel launch");
+    }
+    if (variant >= 8) variant = 0 + 4;
     if (variant >= 4) {   // 128-row workgroups, several resident per CU
         const dim3 grid((p.R + 127) / 128, p.Hkv, p.B);
         if (variant == 4) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 2, 2>), grid, dim3(256), 0, st, p);
@@ -451,7 +474,7 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
         return check_hip(hipGetLastError(), "attn_kernel launch");
     }
     if (variant == 1) {
-        hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
     } else if (variant == 2) {
         hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 3>), dim3((p.R + 127) / 128, p.Hkv, p.B), dim3(256), 0, st, p);
     } else {
@@ -511,7 +534,7 @@ using namespace dlm;
 extern "C" int dlm_set_option(const char* name, int value) {
     if (!name) return fail(DLM_ERR_INVALID_ARG, "set_option: null name");
     if (!strcmp(name, "attn_variant")) {
-        if (value < 0 || value > 7) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..7");
+        if (value < 0 || value > 10) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..10");
         g_attn_variant = value;
         return DLM_OK;
     }

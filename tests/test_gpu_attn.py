@@ -52,7 +52,7 @@ def run_case(B, Lq, Hq, Hkv, d, P, Lb, S, mode="full", bs=0, q_pos0=None, plen=N
     return err
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 8, 9, 10])
 def test_rollout_shape_mha(variant):
     # block of 32 against a ragged prefix (several 32-key tiles and a tail), d = 128
     run_case(B=2, Lq=32, Hq=4, Hkv=4, d=128, P=200, Lb=32, S=0, variant=variant, seed=1)
