@@ -247,6 +247,88 @@ __global__ __launch_bounds__(1024) void commit_fused_kernel(CommitParams p, int3
     }
 }
 
+// Many small commit groups (block-diffusion full-sequence pass: 65536 groups of 4): one LANE per group, the
+// group's confidences in registers, so the whole call is a single pass over ~15 bytes per position.
+template <int GL>
+__global__ __launch_bounds__(256) void commit_lane_kernel(CommitParams p) {
+    const int64_t total = (int64_t)p.B * p.n_groups;
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const bool active = gid < total;
+    const int b = active ? (int)(gid / p.n_groups) : -1;
+    const int gi = active ? (int)(gid - (int64_t)b * p.n_groups) : 0;
+    int ncom = 0, cnt = 0;
+    if (active) {
+        const int g0 = gi * GL;
+        const int64_t base = (int64_t)b * p.n_pos + g0;
+        uint8_t* mrow = p.mask + b * p.mask_stride_b + g0;
+        float cf[GL];
+        bool masked[GL], chosen[GL];
+#pragma unroll
+        for (int i = 0; i < GL; ++i) {
+            masked[i] = mrow[i] != 0;
+            chosen[i] = false;
+            float v = -INFINITY;
+            if (masked[i]) {
+                v = p.conf[base + i];
+                if (!(v == v)) v = -INFINITY;
+                ++cnt;
+            }
+            cf[i] = v;
+        }
+        if (cnt > 0) {
+            if (p.rule == DLM_RULE_THRESHOLD) {
+#pragma unroll
+                for (int i = 0; i < GL; ++i) chosen[i] = masked[i] && (cf[i] >= p.threshold);
+                if (p.force_top1) {
+                    float bv = -INFINITY;
+                    int bi = 0x7fffffff;
+#pragma unroll
+                    for (int i = 0; i < GL; ++i)
+                        if (masked[i] && better(cf[i], i, bv, bi)) { bv = cf[i]; bi = i; }
+#pragma unroll
+                    for (int i = 0; i < GL; ++i)
+                        if (i == bi) chosen[i] = true;
+                }
+            } else {
+                const int kk = min(p.k, cnt);
+                for (int it = 0; it < kk; ++it) {
+                    float bv = -INFINITY;
+                    int bi = 0x7fffffff;
+#pragma unroll
+                    for (int i = 0; i < GL; ++i)
+                        if (masked[i] && !chosen[i] && better(cf[i], i, bv, bi)) { bv = cf[i]; bi = i; }
+#pragma unroll
+                    for (int i = 0; i < GL; ++i)
+                        if (i == bi) chosen[i] = true;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < GL; ++i) {
+            if (chosen[i]) {
+                p.x[b * p.x_stride_b + p.x_pos0 + g0 + i] = p.tok[base + i];
+                mrow[i] = 0;
+                if (p.commit_step) p.commit_step[base + i] = (int16_t)p.step;
+                ++ncom;
+            }
+            if (p.commit_now) p.commit_now[base + i] = chosen[i] ? 1 : 0;
+        }
+    }
+    // per-sequence totals: one atomic per wavefront when all its lanes belong to one sequence
+    const int b0 = __builtin_amdgcn_readfirstlane(b);
+    const bool uniform = __all(b == b0 || !active) && b0 >= 0;
+    if (uniform) {
+        const int wn = wave_sum(ncom), wr = wave_sum(cnt - ncom);
+        if (lane_id() == 0 && (wn | wr)) {
+            atomicAdd(&p.n_commit[b0], wn);
+            atomicAdd(&p.remaining[b0], wr);
+        }
+    } else if (active && cnt > 0) {
+        atomicAdd(&p.n_commit[b], ncom);
+        atomicAdd(&p.remaining[b], cnt - ncom);
+    }
+}
+
 __global__ void zero2_i32_kernel(int32_t* a, int32_t* b, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) { a[i] = 0; b[i] = 0; }
@@ -459,7 +541,14 @@ extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
             }
             const int64_t waves = (int64_t)a->B * n_groups;
             const unsigned grid = (unsigned)((waves + 3) / 4);
-            if (a->group_len <= 64) hipLaunchKernelGGL(commit_wave_kernel<1>, dim3(grid), dim3(256), 0, st, p);
+            const unsigned lgrid = (unsigned)((waves + 255) / 256);
+            const int gl = a->group_len;
+            if (n_groups > 1 && (gl == 1 || gl == 2 || gl == 4 || gl == 8)) {
+                if (gl == 1) hipLaunchKernelGGL(commit_lane_kernel<1>, dim3(lgrid), dim3(256), 0, st, p);
+                else if (gl == 2) hipLaunchKernelGGL(commit_lane_kernel<2>, dim3(lgrid), dim3(256), 0, st, p);
+                else if (gl == 4) hipLaunchKernelGGL(commit_lane_kernel<4>, dim3(lgrid), dim3(256), 0, st, p);
+                else hipLaunchKernelGGL(commit_lane_kernel<8>, dim3(lgrid), dim3(256), 0, st, p);
+            } else if (a->group_len <= 64) hipLaunchKernelGGL(commit_wave_kernel<1>, dim3(grid), dim3(256), 0, st, p);
             else if (a->group_len <= 256) hipLaunchKernelGGL(commit_wave_kernel<4>, dim3(grid), dim3(256), 0, st, p);
             else hipLaunchKernelGGL(commit_wave_kernel<16>, dim3(grid), dim3(256), 0, st, p);
             int rc = check_hip(hipGetLastError(), "commit_wave_kernel launch");
