@@ -229,6 +229,17 @@ int dlm_unmask_commit(const dlm_commit_args *args, void *stream);
 int dlm_mask_compact(const uint8_t *mask, int64_t mask_stride_b, int32_t B, int32_t n_pos,
                      int32_t *row_idx, int32_t *m_out, void *stream);
 
+/* dlm_seq_logprob -- per-sequence masked log-likelihood from the LM head's logits-free outputs:
+ *   out[b] = weight_b * sum_{i : mask[b, i] != 0} (ztarget[b*n_pos + i] - lse[b*n_pos + i])
+ * i.e. the sum of log p_theta(x_0^i | x_t) over the masked positions that the NELBO of Eq. 2 (masked
+ * diffusion) and Eq. 3 (per block) weights by 1/t; `weight` (optional fp32 [B], e.g. -1/t) defaults to 1.
+ * Serves log-probability recomputation (old-policy / reference policy) without materialising logits:
+ * ztarget and lse are the dense (out_scatter = 1) outputs of dlm_lmhead_confidence with `target` set.
+ * n_terms (optional int32 [B]) receives the number of masked positions.  fp32 accumulation in a fixed
+ * order (deterministic).  mask rows are mask_stride_b apart; ztarget / lse are contiguous [B, n_pos]. */
+int dlm_seq_logprob(const float *ztarget, const float *lse, const uint8_t *mask, int64_t mask_stride_b,
+                    const float *weight, int32_t B, int32_t n_pos, float *out, int32_t *n_terms, void *stream);
+
 /* dlm_kv_refresh -- copy src K,V [B, Hkv, src->len, d] into the cache at rows
  * [cache_pos0, cache_pos0 + src->len): the block-boundary cache refresh of a
  * KV-cached rollout (Section 3.4).  Bit-exact 16-bit copy; d % 8 == 0, 16-byte

@@ -214,3 +214,25 @@ def full_pass(cfg, synth, seqs: Optional[Sequence[int]] = None, w: Optional[np.n
         out.update(conf=conf, tok=tok, commit=commit, n_commit=n_commit, remaining=remaining,
                    x_before=x_before, x=x, mask=mask)
     return out
+
+
+def seq_logprob(hidden, w, target, mask, *, weight=None, forbid_token: int = -1):
+    """Masked log-likelihood per sequence: sum over masked positions of log p(target | x_t), the term that the
+    NELBO of Eq. (2) / Eq. (3) weights by 1/t.
+
+    hidden bf16 bits [B, n, Dh]; w bf16 bits [V, Dh]; target int [B, n]; mask uint8 [B, n].
+    returns (out float64 [B], n_terms int [B]); weight (optional [B]) multiplies each sum.
+    """
+    B, n, Dh = hidden.shape
+    out = np.zeros(B, np.float64)
+    n_terms = np.zeros(B, np.int32)
+    for b in range(B):
+        idx = np.flatnonzero(mask[b]).astype(np.int32)
+        n_terms[b] = len(idx)
+        if len(idx):
+            r = lmhead(hidden[b], w, row_idx=idx, forbid_token=forbid_token, target=np.asarray(target[b])[idx])
+            terms = r["zt"] - r["lse"]              # log softmax at the target token
+            out[b] = float(np.sum(terms))
+        if weight is not None:
+            out[b] *= float(weight[b])
+    return out, n_terms

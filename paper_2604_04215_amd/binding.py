@@ -21,7 +21,7 @@ WB_NONE, WB_BLOCK_WHEN_DONE, WB_COMMITTED_ROWS = 0, 1, 2
 
 EXPORTS = ["dlm_block_attn", "dlm_block_attn_workspace_bytes", "dlm_lmhead_confidence",
            "dlm_lmhead_workspace_bytes", "dlm_unmask_commit", "dlm_mask_compact", "dlm_kv_refresh",
-           "dlm_set_option", "dlm_last_error", "dlm_version"]
+           "dlm_seq_logprob", "dlm_set_option", "dlm_last_error", "dlm_version"]
 
 
 class KvSeg(C.Structure):
@@ -99,6 +99,9 @@ def lib():
         L.dlm_kv_refresh.restype = C.c_int
         L.dlm_kv_refresh.argtypes = [C.POINTER(KvSeg), C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_void_p]
+        L.dlm_seq_logprob.restype = C.c_int
+        L.dlm_seq_logprob.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int32,
+                                      C.c_void_p, C.c_void_p, C.c_void_p]
         L.dlm_set_option.restype = C.c_int
         L.dlm_set_option.argtypes = [C.c_char_p, C.c_int]
         L.dlm_last_error.restype = C.c_char_p
@@ -286,3 +289,15 @@ def kv_refresh(src_k, src_v, cache_k, cache_v, cache_pos0: int, stream=None) -> 
     _check(lib().dlm_kv_refresh(C.byref(seg), B, Hkv, d, _dev(cache_k, torch.bfloat16, "cache_k"),
                                 _dev(cache_v, torch.bfloat16, "cache_v"), cache_k.stride(0), cache_k.stride(1),
                                 cache_k.stride(2), int(cache_pos0), _stream(stream)))
+
+
+def seq_logprob(ztarget, lse, mask, out, *, weight=None, n_terms=None, stream=None) -> None:
+    """out[b] = weight[b] * sum over masked positions of (ztarget - lse); ztarget, lse fp32 [B, n_pos]."""
+    import torch
+    B, n_pos = mask.shape
+    if not ztarget.is_contiguous() or not lse.is_contiguous() or ztarget.numel() != B * n_pos or lse.numel() != B * n_pos:
+        raise ValueError("ztarget / lse must be contiguous [B, n_pos]")
+    _check(lib().dlm_seq_logprob(_dev(ztarget, torch.float32, "ztarget"), _dev(lse, torch.float32, "lse"),
+                                 _dev(mask, torch.uint8, "mask"), mask.stride(0), _dev(weight, torch.float32, "weight"),
+                                 B, n_pos, _dev(out, torch.float32, "out"), _dev(n_terms, torch.int32, "n_terms"),
+                                 _stream(stream)))

@@ -418,6 +418,40 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(CopyParams p) {
         }
 }
 
+// One workgroup per sequence; every thread sums a strided slice in a fixed order, then a fixed tree.
+__global__ __launch_bounds__(256) void seq_logprob_kernel(const float* zt, const float* lse, const uint8_t* mask,
+                                                         int64_t mask_stride_b, const float* weight, int n_pos,
+                                                         float* out, int32_t* n_terms) {
+    __shared__ float ssum[4];
+    __shared__ int scnt[4];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const float* z = zt + (int64_t)b * n_pos;
+    const float* l = lse + (int64_t)b * n_pos;
+    const uint8_t* m = mask + b * mask_stride_b;
+    float acc = 0.f;
+    int cnt = 0;
+    for (int i = tid; i < n_pos; i += 256)
+        if (m[i]) {
+            acc += z[i] - l[i];
+            ++cnt;
+        }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        acc += shfl_xor(acc, off);
+        cnt += shfl_xor(cnt, off);
+    }
+    if ((tid & 63) == 0) {
+        ssum[tid >> 6] = acc;
+        scnt[tid >> 6] = cnt;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        const float tot = (ssum[0] + ssum[1]) + (ssum[2] + ssum[3]);
+        out[b] = (weight ? weight[b] : 1.0f) * tot;
+        if (n_terms) n_terms[b] = scnt[0] + scnt[1] + scnt[2] + scnt[3];
+    }
+}
+
 static int validate_seg_copy(const dlm_kv_seg* s, int B, int Hkv, int d, const void* ck, const void* cv,
                              int64_t c_sb, int64_t c_sh, int64_t c_st, int cache_pos0) {
     if (!s) return fail(DLM_ERR_INVALID_ARG, "kv copy: null source segment");
@@ -465,6 +499,19 @@ extern "C" int dlm_kv_refresh(const dlm_kv_seg* src, int32_t B, int32_t Hkv, int
     if (rc != DLM_OK) return rc;
     return launch_kv_copy(src, B, Hkv, d, cache_k, cache_v, c_stride_b, c_stride_h, c_stride_t, cache_pos0, 0, nullptr,
                           nullptr, nullptr, 0, (hipStream_t)stream);
+}
+
+extern "C" int dlm_seq_logprob(const float* ztarget, const float* lse, const uint8_t* mask, int64_t mask_stride_b,
+                               const float* weight, int32_t B, int32_t n_pos, float* out, int32_t* n_terms,
+                               void* stream) {
+    if (B < 0 || n_pos < 0) return fail(DLM_ERR_INVALID_ARG, "seq_logprob: negative size");
+    if (B == 0) return DLM_OK;
+    if (!out) return fail(DLM_ERR_INVALID_ARG, "seq_logprob: null out");
+    if (n_pos > 0 && (!ztarget || !lse || !mask)) return fail(DLM_ERR_INVALID_ARG, "seq_logprob: null ztarget/lse/mask");
+    if (n_pos > 0 && mask_stride_b < n_pos) return fail(DLM_ERR_INVALID_ARG, "seq_logprob: stride < n_pos");
+    hipLaunchKernelGGL(seq_logprob_kernel, dim3(B), dim3(256), 0, (hipStream_t)stream, ztarget, lse, mask, mask_stride_b,
+                       weight, n_pos, out, n_terms);
+    return check_hip(hipGetLastError(), "seq_logprob_kernel launch");
 }
 
 extern "C" int dlm_mask_compact(const uint8_t* mask, int64_t mask_stride_b, int32_t B, int32_t n_pos, int32_t* row_idx,
