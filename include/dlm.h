@@ -88,6 +88,19 @@ typedef struct dlm_kv_seg {
  * Supported: d in {64, 128}; Hq % Hkv == 0; all base pointers 16-byte aligned and
  * all strides multiples of 8 elements.  Lq, Hq/Hkv and segment lengths are arbitrary.
  * workspace: dlm_block_attn_workspace_bytes(args) bytes (may be 0; then NULL is fine).
+ *
+ * Packed variable-length mode (cu_seqlens != NULL; Section 3.3 "attention backend", the
+ * padding-free bidirectional attention used for SFT, the actor update and log-prob
+ * recomputation): the batch is one token-major buffer without PAD rows.
+ *   cu_seqlens    device int32 [B + 1], non-decreasing, cu_seqlens[0] = 0; sequence b owns tokens
+ *                 [cu_seqlens[b], cu_seqlens[b+1]) and attends only to itself
+ *   total_tokens  cu_seqlens[B]
+ *   q, out        bf16 [total_tokens, Hq, d]  (stride_t, stride_h; stride_b ignored)
+ *   block.k / v   bf16 [total_tokens, Hkv, d] (stride_t, stride_h; stride_b ignored)
+ *   Lq = block.len = an upper bound on the sequence lengths (the longest one); a sequence longer than
+ *                 that is truncated to its first Lq tokens (queries and keys alike)
+ *   prefix, suffix, prefix_len_b must be absent; lse is fp32 [Hq, total_tokens]
+ *   block-causal: positions restart in every sequence (query row i at q_pos0 + i, key j at block.pos0 + j).
  * ------------------------------------------------------------------------- */
 typedef struct dlm_attn_args {
     uint32_t struct_size;
@@ -104,6 +117,8 @@ typedef struct dlm_attn_args {
     float *lse;
     void *workspace;
     size_t workspace_bytes;
+    const int32_t *cu_seqlens;
+    int32_t total_tokens;
 } dlm_attn_args;
 
 int dlm_block_attn(const dlm_attn_args *args, void *stream);

@@ -11,5 +11,5 @@ Layers:
 Parity pins live in tests/test_oracle_*.py (pure-Python brute force on tiny
 inputs, closed forms, metamorphic identities, textbook special cases).
 """
-from .ref import KV, attention, lmhead, num_threads, build  # noqa: F401
+from .ref import KV, attention, attention_varlen, lmhead, num_threads, build  # noqa: F401
 from .denoise import select_commit, OracleRollout, full_pass, seq_logprob  # noqa: F401

@@ -122,6 +122,28 @@ def attention(q: np.ndarray, segments: Sequence[KV], *, mask_mode: str = "full",
     return out, lse
 
 
+def attention_varlen(q: np.ndarray, k: np.ndarray, v: np.ndarray, cu_seqlens, *, mask_mode: str = "full",
+                     bs: int = 0, scale: Optional[float] = None):
+    """Packed variable-length attention: the batch is one token-major buffer and sequence b, which owns
+    tokens [cu_seqlens[b], cu_seqlens[b+1]), attends only to itself (positions restart at 0 per sequence).
+
+    q bf16 bits [T, Hq, d]; k, v bf16 bits [T, Hkv, d]; returns (O [T, Hq, d], LSE [Hq, T]) in float64.
+    """
+    T, Hq, d = q.shape
+    out = np.zeros((T, Hq, d), np.float64)
+    lse = np.zeros((Hq, T), np.float64)
+    cu = [int(c) for c in cu_seqlens]
+    for b in range(len(cu) - 1):
+        a, e = cu[b], cu[b + 1]
+        if e <= a:
+            continue
+        seg = KV(np.ascontiguousarray(k[a:e].transpose(1, 0, 2))[None], np.ascontiguousarray(v[a:e].transpose(1, 0, 2))[None], 0)
+        o, l = attention(q[a:e][None], [seg], mask_mode=mask_mode, bs=bs, q_pos0=0, scale=scale)
+        out[a:e] = o[0]
+        lse[:, a:e] = l[0]
+    return out, lse
+
+
 def lmhead(hidden: np.ndarray, w: np.ndarray, *, row_idx: Optional[np.ndarray] = None,
            inv_temperature: float = 1.0, forbid_token: int = -1,
            target: Optional[np.ndarray] = None):

@@ -37,7 +37,8 @@ class AttnArgs(C.Structure):
                 ("prefix_len_b", C.c_void_p),
                 ("mask_mode", C.c_int32), ("block_size", C.c_int32), ("q_pos0", C.c_int32), ("scale", C.c_float),
                 ("out", C.c_void_p), ("o_stride_b", C.c_int64), ("o_stride_t", C.c_int64), ("o_stride_h", C.c_int64),
-                ("lse", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("lse", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("cu_seqlens", C.c_void_p), ("total_tokens", C.c_int32)]
 
 
 class LmheadArgs(C.Structure):
@@ -190,6 +191,32 @@ def block_attn(q, out, prefix: Optional[Tuple] = None, block: Optional[Tuple] = 
     a.lse = _dev(lse, torch.float32, "lse")
     a.workspace = _dev(workspace, None, "workspace")
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().dlm_block_attn(C.byref(a), _stream(stream)))
+
+
+def varlen_attn(q, k, v, out, cu_seqlens, max_seqlen: int, *, mask_mode: int = MASK_FULL, block_size: int = 0,
+                scale: float = 0.0, lse=None, stream=None) -> None:
+    """Packed variable-length attention through dlm_block_attn: q, out bf16 [T, Hq, d]; k, v bf16 [T, Hkv, d];
+    cu_seqlens int32 [B + 1] on the device; every sequence attends to itself only.  lse fp32 [Hq, T]."""
+    import torch
+    a = AttnArgs()
+    a.struct_size = C.sizeof(AttnArgs)
+    T, Hq, d = q.shape
+    if out.shape != q.shape or k.shape != v.shape or k.stride() != v.stride() or k.shape[0] != T or k.shape[2] != d:
+        raise ValueError("q/out [T, Hq, d] and k/v [T, Hkv, d] expected")
+    B = cu_seqlens.numel() - 1
+    a.B, a.Lq, a.Hq, a.Hkv, a.d = B, int(max_seqlen), Hq, k.shape[1], d
+    a.q, a.q_stride_b, a.q_stride_t, a.q_stride_h = _dev(q, torch.bfloat16, "q"), 0, q.stride(0), q.stride(1)
+    a.out, a.o_stride_b, a.o_stride_t, a.o_stride_h = _dev(out, torch.bfloat16, "out"), 0, out.stride(0), out.stride(1)
+    a.prefix, a.suffix = kv_seg(), kv_seg()
+    a.block.k, a.block.v = _dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v")
+    a.block.len, a.block.pos0 = int(max_seqlen), 0
+    a.block.stride_b, a.block.stride_t, a.block.stride_h = 0, k.stride(0), k.stride(1)
+    a.mask_mode, a.block_size, a.q_pos0, a.scale = int(mask_mode), int(block_size), 0, float(scale)
+    if lse is not None and (not lse.is_contiguous() or tuple(lse.shape) != (Hq, T)):
+        raise ValueError("lse must be contiguous fp32 [Hq, T]")
+    a.lse = _dev(lse, torch.float32, "lse")
+    a.cu_seqlens, a.total_tokens = _dev(cu_seqlens, torch.int32, "cu_seqlens"), T
     _check(lib().dlm_block_attn(C.byref(a), _stream(stream)))
 
 

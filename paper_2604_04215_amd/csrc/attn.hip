@@ -39,6 +39,8 @@ struct AttnParams {
     uint16_t* out;
     int64_t o_sb, o_st, o_sh;
     float* lse;
+    const int32_t* cu;  // packed variable-length mode: sequence b owns tokens [cu[b], cu[b+1])
+    int total;          // cu[B]
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
@@ -72,8 +74,22 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     // ---- visible extent of each segment for this workgroup -----------------
     int len0 = p.seg[0].len, len1 = p.seg[1].len, len2 = p.seg[2].len;
     if (p.prefix_len_b) len0 = min(len0, max(p.prefix_len_b[b], 0));
+    // Packed mode: this sequence's tokens start at row s0 of q / out / the block segment and there are
+    // sl of them; a workgroup whose rows all lie past the sequence's end has nothing to do.
+    int R = p.R, s0 = 0;
+    int64_t q_off = b * p.q_sb, o_off = b * p.o_sb, kv1_off = b * p.seg[1].sb;
+    if (p.cu) {
+        s0 = min(max(p.cu[b], 0), p.total);   // offsets are clamped to the buffer whatever the array holds
+        const int sl = max(min(min(p.cu[b + 1], p.total) - s0, p.Lq), 0);
+        R = p.g * sl;
+        if (r0 >= R) return;
+        len1 = min(len1, sl);
+        q_off = s0 * p.q_st;
+        o_off = s0 * p.o_st;
+        kv1_off = s0 * p.seg[1].st;
+    }
     if (BC) {
-        const int rmax = min(r0 + 32 * NWR * RTW, p.R) - 1;
+        const int rmax = min(r0 + 32 * NWR * RTW, R) - 1;
         const int lim = ((p.q_pos0 + rmax / p.g) / p.bs + 1) * p.bs;  // positions >= lim are invisible to every row here
         len0 = max(0, min(len0, lim - p.seg[0].pos0));
         len1 = max(0, min(len1, lim - p.seg[1].pos0));
@@ -87,8 +103,8 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
 
     const uint16_t* kb0 = p.seg[0].k + b * p.seg[0].sb + kvh * p.seg[0].sh;
     const uint16_t* vb0 = p.seg[0].v + b * p.seg[0].sb + kvh * p.seg[0].sh;
-    const uint16_t* kb1 = p.seg[1].k + b * p.seg[1].sb + kvh * p.seg[1].sh;
-    const uint16_t* vb1 = p.seg[1].v + b * p.seg[1].sb + kvh * p.seg[1].sh;
+    const uint16_t* kb1 = p.seg[1].k + kv1_off + kvh * p.seg[1].sh;
+    const uint16_t* vb1 = p.seg[1].v + kv1_off + kvh * p.seg[1].sh;
     const uint16_t* kb2 = p.seg[2].k + b * p.seg[2].sb + kvh * p.seg[2].sh;
     const uint16_t* vb2 = p.seg[2].v + b * p.seg[2].sb + kvh * p.seg[2].sh;
     const int64_t st0 = p.seg[0].st, st1 = p.seg[1].st, st2 = p.seg[2].st;
@@ -102,10 +118,10 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
 #pragma unroll
     for (int rt = 0; rt < RTW; ++rt) {
         const int r = r0 + (wr * RTW + rt) * 32 + n;
-        const bool valid = r < p.R;
+        const bool valid = r < R;
         const int i = valid ? r / p.g : 0;
         const int hg = valid ? r - i * p.g : 0;
-        const uint16_t* qp = p.q + b * p.q_sb + i * p.q_st + (int64_t)(kvh * p.g + hg) * p.q_sh;
+        const uint16_t* qp = p.q + q_off + i * p.q_st + (int64_t)(kvh * p.g + hg) * p.q_sh;
 #pragma unroll
         for (int c = 0; c < D / 16; ++c) {
             u32x4 v = {0, 0, 0, 0};
@@ -367,10 +383,10 @@ _Pragma("unroll") \
             const float l = l_run[rt] + shfl_xor(l_run[rt], 32);
             const float inv = l > 0.f ? 1.f / l : 0.f;
             const int r = r0 + (wr * RTW + rt) * 32 + n;
-            if (r < p.R) {
+            if (r < R) {
                 const int i = r / p.g, hg = r - i * p.g;
                 const int h = kvh * p.g + hg;
-                uint16_t* op = p.out + b * p.o_sb + i * p.o_st + (int64_t)h * p.o_sh;
+                uint16_t* op = p.out + o_off + i * p.o_st + (int64_t)h * p.o_sh;
 #pragma unroll
                 for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
@@ -381,7 +397,7 @@ _Pragma("unroll") \
                         *reinterpret_cast<u32x2*>(op + 32 * dt + 8 * q4 + 4 * hi) = v;
                     }
                 if (p.lse && hi == 0)
-                    p.lse[((int64_t)b * p.Hq + h) * p.Lq + i] = l > 0.f ? (m_run[rt] + log2f(l)) * LN2 : -INFINITY;
+                    p.lse[p.cu ? (int64_t)h * p.total + s0 + i : ((int64_t)b * p.Hq + h) * p.Lq + i] = l > 0.f ? (m_run[rt] + log2f(l)) * LN2 : -INFINITY;
             }
         }
     } else {
@@ -406,7 +422,7 @@ _Pragma("unroll") \
             for (int task = tid; task < 32 * C8; task += NT) {
                 const int rr = task / C8, c8 = task - rr * C8;
                 const int r = r0 + rt * 32 + rr;
-                if (r >= p.R) continue;
+                if (r >= R) continue;
                 float M = -INFINITY;
 #pragma unroll
                 for (int k = 0; k < NWK; ++k) M = fmaxf(M, mb[(k * 32 + rr) * MP + D]);
@@ -436,9 +452,9 @@ _Pragma("unroll") \
                 u32x4 v;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = pack_bf16x2(o[2 * e] * inv, o[2 * e + 1] * inv);
-                *reinterpret_cast<u32x4*>(p.out + b * p.o_sb + i * p.o_st + (int64_t)h * p.o_sh + 8 * c8) = v;
+                *reinterpret_cast<u32x4*>(p.out + o_off + i * p.o_st + (int64_t)h * p.o_sh + 8 * c8) = v;
                 if (p.lse && c8 == 0)
-                    p.lse[((int64_t)b * p.Hq + h) * p.Lq + i] = den > 0.f ? (M + log2f(den)) * LN2 : -INFINITY;
+                    p.lse[p.cu ? (int64_t)h * p.total + s0 + i : ((int64_t)b * p.Hq + h) * p.Lq + i] = den > 0.f ? (M + log2f(den)) * LN2 : -INFINITY;
             }
         }
     }
@@ -511,13 +527,21 @@ static int validate_attn(const dlm_attn_args* a) {
     }
     if (a->B > 65535 || a->Hkv > 65535) return fail(DLM_ERR_UNSUPPORTED, "block_attn: B or Hkv above 65535");
     if ((int64_t)a->Lq * (a->Hq / a->Hkv) > (1 << 30)) return fail(DLM_ERR_UNSUPPORTED, "block_attn: too many rows per KV head");
+    if (a->cu_seqlens) {
+        if (a->prefix.len || a->suffix.len || a->prefix_len_b)
+            return fail(DLM_ERR_INVALID_ARG, "block_attn: packed mode takes the block segment only");
+        if (a->block.len != a->Lq) return fail(DLM_ERR_INVALID_ARG, "block_attn: packed mode needs block.len == Lq (the longest sequence)");
+        if (a->total_tokens < 0) return fail(DLM_ERR_INVALID_ARG, "block_attn: total_tokens < 0");
+        if ((int64_t)a->total_tokens > (int64_t)a->B * a->Lq) return fail(DLM_ERR_INVALID_ARG, "block_attn: total_tokens > B * Lq");
+        if (a->total_tokens == 0) return DLM_OK;   // an empty packed batch: nothing is read
+    }
     int rc;
     if ((rc = validate_seg(a->prefix, "prefix", a->d)) != DLM_OK) return rc;
     if ((rc = validate_seg(a->block, "block", a->d)) != DLM_OK) return rc;
     if ((rc = validate_seg(a->suffix, "suffix", a->d)) != DLM_OK) return rc;
     if ((int64_t)a->prefix.len + a->block.len + a->suffix.len > (1 << 30))
         return fail(DLM_ERR_UNSUPPORTED, "block_attn: more than 2^30 keys");
-    if (a->B == 0 || a->Lq == 0) return DLM_OK;
+    if (a->B == 0 || a->Lq == 0 || (a->cu_seqlens && a->total_tokens == 0)) return DLM_OK;
     if (!a->q || !a->out) return fail(DLM_ERR_INVALID_ARG, "block_attn: null q/out");
     if (!aligned16(a->q) || !aligned16(a->out)) return fail(DLM_ERR_UNSUPPORTED, "block_attn: q/out not 16-byte aligned");
     if ((a->q_stride_b | a->q_stride_t | a->q_stride_h | a->o_stride_b | a->o_stride_t | a->o_stride_h) % 8)
@@ -550,7 +574,7 @@ extern "C" size_t dlm_block_attn_workspace_bytes(const dlm_attn_args* a) {
 extern "C" int dlm_block_attn(const dlm_attn_args* a, void* stream) {
     int rc = validate_attn(a);
     if (rc != DLM_OK) return rc;
-    if (a->B == 0 || a->Lq == 0) return DLM_OK;
+    if (a->B == 0 || a->Lq == 0 || (a->cu_seqlens && a->total_tokens == 0)) return DLM_OK;
     AttnParams p;
     p.B = a->B; p.Lq = a->Lq; p.Hq = a->Hq; p.Hkv = a->Hkv; p.g = a->Hq / a->Hkv; p.R = p.g * a->Lq;
     p.q = (const uint16_t*)a->q; p.q_sb = a->q_stride_b; p.q_st = a->q_stride_t; p.q_sh = a->q_stride_h;
@@ -566,6 +590,7 @@ extern "C" int dlm_block_attn(const dlm_attn_args* a, void* stream) {
     p.scale_log2 = scale * 1.4426950408889634f;
     p.out = (uint16_t*)a->out; p.o_sb = a->o_stride_b; p.o_st = a->o_stride_t; p.o_sh = a->o_stride_h;
     p.lse = a->lse;
+    p.cu = a->cu_seqlens; p.total = a->total_tokens;
     hipStream_t st = (hipStream_t)stream;
     const bool bc = a->mask_mode == DLM_MASK_BLOCK_CAUSAL;
     if (a->d == 128) return bc ? launch_attn<128, true>(p, st) : launch_attn<128, false>(p, st);

@@ -312,3 +312,71 @@ def fullpass_mask(cfg: FullPassConfig, seqs=None) -> np.ndarray:
     seqs = range(cfg.B) if seqs is None else seqs
     return np.stack([(stream(cfg.seed, TAG_MASK, 0, b).random(cfg.L) < cfg.mask_prob).astype(np.uint8)
                      for b in seqs])
+
+
+# packed variable-length batch ---------------------------------------------- #
+@dataclass(frozen=True)
+class VarlenConfig:
+    """Packed batch for padding-free bidirectional attention: B sequences, each a prompt of
+    prompt_lo..prompt_hi tokens followed by a response cut at its end-of-sequence token
+    (resp_lo..resp_hi valid tokens), laid out back to back without PAD rows."""
+    name: str
+    B: int
+    Hq: int
+    Hkv: int
+    d: int
+    prompt_lo: int
+    prompt_hi: int
+    resp_lo: int
+    resp_hi: int
+    seed: int = 20260415 + 7
+
+    @property
+    def max_len(self) -> int:
+        return self.prompt_hi + self.resp_hi
+
+    def replace(self, **kw) -> "VarlenConfig":
+        return dataclasses.replace(self, **kw)
+
+
+TAG_LEN = 10
+
+VARLEN: Dict[str, VarlenConfig] = {
+    # 8B-class masked diffusion LM heads (32 x 128), GSM8K-like prompts + responses up to 512 tokens
+    "v1": VarlenConfig("v1", B=128, Hq=32, Hkv=32, d=128, prompt_lo=64, prompt_hi=384, resp_lo=32, resp_hi=512),
+    # grouped-query variant (7B-class, 28 query / 4 KV heads)
+    "v2": VarlenConfig("v2", B=128, Hq=28, Hkv=4, d=128, prompt_lo=64, prompt_hi=384, resp_lo=32, resp_hi=512),
+    "miniv1": VarlenConfig("miniv1", B=7, Hq=4, Hkv=2, d=64, prompt_lo=1, prompt_hi=40, resp_lo=0, resp_hi=130,
+                           seed=777 + 7),
+}
+
+
+def varlen_seqlens(cfg: VarlenConfig) -> np.ndarray:
+    """int32 [B]: prompt + valid response length of every sequence (uniform in the configured ranges)."""
+    g = stream(cfg.seed, TAG_LEN, 0)
+    prompt = g.integers(cfg.prompt_lo, cfg.prompt_hi + 1, cfg.B)
+    resp = g.integers(cfg.resp_lo, cfg.resp_hi + 1, cfg.B)
+    return (prompt + resp).astype(np.int32)
+
+
+def varlen_cu_seqlens(cfg: VarlenConfig) -> np.ndarray:
+    """int32 [B + 1]: exclusive prefix sum of varlen_seqlens (token offset of each sequence)."""
+    return np.concatenate([[0], np.cumsum(varlen_seqlens(cfg))]).astype(np.int32)
+
+
+def varlen_qkv(cfg: VarlenConfig):
+    """Q [T, Hq, d], K, V [T, Hkv, d] for the packed batch (T = total tokens)."""
+    cu = varlen_cu_seqlens(cfg)
+    T = int(cu[-1])
+    q = np.empty((T, cfg.Hq, cfg.d), np.uint16)
+    k = np.empty((T, cfg.Hkv, cfg.d), np.uint16)
+    v = np.empty((T, cfg.Hkv, cfg.d), np.uint16)
+
+    def one(b):
+        a, e = int(cu[b]), int(cu[b + 1])
+        q[a:e] = normal_bf16(cfg.seed, TAG_Q, (1, b), (e - a, cfg.Hq, cfg.d))
+        k[a:e] = normal_bf16(cfg.seed, TAG_KBLK, (1, b), (e - a, cfg.Hkv, cfg.d))
+        v[a:e] = normal_bf16(cfg.seed, TAG_VBLK, (1, b), (e - a, cfg.Hkv, cfg.d))
+
+    _pmap(one, range(cfg.B))
+    return q, k, v, cu

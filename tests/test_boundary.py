@@ -38,7 +38,7 @@ def test_struct_layout_matches_header(tmp_path):
 #include "dlm.h"
 int main(void) {
   printf("%zu %zu %zu %zu\n", sizeof(dlm_kv_seg), sizeof(dlm_attn_args), sizeof(dlm_lmhead_args), sizeof(dlm_commit_args));
-  printf("%zu %zu %zu %zu\n", offsetof(dlm_attn_args, suffix), offsetof(dlm_attn_args, scale), offsetof(dlm_attn_args, lse), offsetof(dlm_attn_args, workspace_bytes));
+  printf("%zu %zu %zu %zu\n", offsetof(dlm_attn_args, suffix), offsetof(dlm_attn_args, scale), offsetof(dlm_attn_args, lse), offsetof(dlm_attn_args, total_tokens));
   printf("%zu %zu %zu %zu\n", offsetof(dlm_lmhead_args, w), offsetof(dlm_lmhead_args, forbid_token), offsetof(dlm_lmhead_args, conf), offsetof(dlm_lmhead_args, workspace));
   printf("%zu %zu %zu %zu\n", offsetof(dlm_commit_args, conf), offsetof(dlm_commit_args, x_pos0), offsetof(dlm_commit_args, src_block), offsetof(dlm_commit_args, d));
   return 0;
@@ -48,7 +48,7 @@ int main(void) {
     got = [[int(t) for t in line.split()] for line in subprocess.check_output([str(exe)], text=True).splitlines()]
     A, Lm, Cm = dlm.AttnArgs, dlm.LmheadArgs, dlm.CommitArgs
     want = [[C.sizeof(dlm.KvSeg), C.sizeof(A), C.sizeof(Lm), C.sizeof(Cm)],
-            [A.suffix.offset, A.scale.offset, A.lse.offset, A.workspace_bytes.offset],
+            [A.suffix.offset, A.scale.offset, A.lse.offset, A.total_tokens.offset],
             [Lm.w.offset, Lm.forbid_token.offset, Lm.conf.offset, Lm.workspace.offset],
             [Cm.conf.offset, Cm.x_pos0.offset, Cm.src_block.offset, Cm.d.offset]]
     assert got == want
@@ -89,6 +89,27 @@ def test_attn_validation():
     assert L.dlm_block_attn(C.byref(_attn(B=0)), None) == dlm.DLM_OK
     assert L.dlm_block_attn(C.byref(_attn(Lq=0)), None) == dlm.DLM_OK
     assert L.dlm_block_attn_workspace_bytes(C.byref(_attn())) == 0
+    # packed variable-length mode: block segment only, block.len == Lq, token count within B * Lq
+    def packed(**kw):
+        a = _attn(cu_seqlens=0x2000, total_tokens=4)
+        a.block.k = a.block.v = 0x3000
+        a.block.len, a.block.stride_t, a.block.stride_h = 4, 2 * 128, 128
+        for k, v in kw.items():
+            setattr(a, k, v)
+        return a
+    a = packed()
+    a.prefix.k = a.prefix.v = 0x3000
+    a.prefix.len, a.prefix.stride_t = 8, 128
+    assert L.dlm_block_attn(C.byref(a), None) == dlm.DLM_ERR_INVALID_ARG
+    assert "packed" in dlm.last_error()
+    assert L.dlm_block_attn(C.byref(packed(prefix_len_b=0x4000)), None) == dlm.DLM_ERR_INVALID_ARG
+    assert L.dlm_block_attn(C.byref(packed(Lq=8)), None) == dlm.DLM_ERR_INVALID_ARG          # block.len != Lq
+    assert L.dlm_block_attn(C.byref(packed(total_tokens=5)), None) == dlm.DLM_ERR_INVALID_ARG    # > B * Lq
+    assert L.dlm_block_attn(C.byref(packed(total_tokens=-1)), None) == dlm.DLM_ERR_INVALID_ARG
+    assert L.dlm_block_attn(C.byref(packed(B=0, total_tokens=0)), None) == dlm.DLM_OK
+    assert L.dlm_seq_logprob(None, None, None, 0, None, 2, 4, None, None, None) == dlm.DLM_ERR_INVALID_ARG
+    assert L.dlm_seq_logprob(None, None, None, 0, None, 0, 4, None, None, None) == dlm.DLM_OK
+    assert L.dlm_seq_logprob(0x1000, 0x1000, 0x1000, 2, None, 2, 4, 0x1000, None, None) == dlm.DLM_ERR_INVALID_ARG
 
 
 def _lm(**kw):
