@@ -89,7 +89,7 @@ typedef struct dlm_kv_seg {
  * all strides multiples of 8 elements.  Lq, Hq/Hkv and segment lengths are arbitrary.
  * workspace: dlm_block_attn_workspace_bytes(args) bytes (may be 0; then NULL is fine).
  *
- * Packed variable-length mode (cu_seqlens != NULL; Section 3.3 "attention backend", the
+ * Packed variable-length mode (cu_seqlens != NULL; Section 3.4, training-side optimization: the
  * padding-free bidirectional attention used for SFT, the actor update and log-prob
  * recomputation): the batch is one token-major buffer without PAD rows.
  *   cu_seqlens    device int32 [B + 1], non-decreasing, cu_seqlens[0] = 0; sequence b owns tokens
@@ -146,9 +146,17 @@ size_t dlm_block_attn_workspace_bytes(const dlm_attn_args *args);
  *   out_scatter  0: outputs are indexed by r; 1: by row(r) (dense per-position arrays)
  *   conf, tok    required; lse, zmax, z2nd, target+ztarget optional.  `target` is
  *           indexed like the outputs.
+ * Sampling (sample = 1; stochastic rollouts, e.g. the group of 8 rollouts per prompt of the
+ * implementation details in Section 4.1): tok is drawn from softmax(z) by the Gumbel-max identity,
+ *   tok = smallest v maximising z_v + g_v,   g_v = -log(-log u_v),   conf = exp(z_tok - lse),
+ * while lse, zmax, z2nd and ztarget keep their meaning.  u_v = (2k + 1) / 2^24 with k the top 23 bits of
+ * word v % 4 of Philox-4x32-10(counter = (v / 4, row(r), sample_step, sample_stream), key = (low, high
+ * 32 bits of sample_seed)): the draw depends on the row's index in `hidden`, not on r or M, and repeats
+ * exactly for equal (seed, step, stream).  Callers give every denoising step its own sample_step and
+ * every rollout replica its own sample_stream.
  * Arithmetic: bf16 operands, fp32 accumulation and softmax.
  * Supported: Dh % 64 == 0; hidden, w 16-byte aligned; strides multiples of 8.
- * workspace: dlm_lmhead_workspace_bytes(args) bytes, 16-byte aligned.
+ * workspace: dlm_lmhead_workspace_bytes(args) bytes (depends on M, V and sample), 16-byte aligned.
  * ------------------------------------------------------------------------- */
 typedef struct dlm_lmhead_args {
     uint32_t struct_size;
@@ -169,6 +177,9 @@ typedef struct dlm_lmhead_args {
     float *ztarget;
     void *workspace;
     size_t workspace_bytes;
+    int32_t sample;
+    uint32_t sample_step, sample_stream;
+    uint64_t sample_seed;
 } dlm_lmhead_args;
 
 int dlm_lmhead_confidence(const dlm_lmhead_args *args, void *stream);

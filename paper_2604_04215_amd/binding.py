@@ -50,7 +50,9 @@ class LmheadArgs(C.Structure):
                 ("conf", C.c_void_p), ("tok", C.c_void_p),
                 ("lse", C.c_void_p), ("zmax", C.c_void_p), ("z2nd", C.c_void_p),
                 ("target", C.c_void_p), ("ztarget", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("sample", C.c_int32), ("sample_step", C.c_uint32), ("sample_stream", C.c_uint32),
+                ("sample_seed", C.c_uint64)]
 
 
 class CommitArgs(C.Structure):
@@ -220,18 +222,21 @@ def varlen_attn(q, k, v, out, cu_seqlens, max_seqlen: int, *, mask_mode: int = M
     _check(lib().dlm_block_attn(C.byref(a), _stream(stream)))
 
 
-def lmhead_workspace_bytes(M: int, V: int) -> int:
+def lmhead_workspace_bytes(M: int, V: int, sample: bool = False) -> int:
     a = LmheadArgs()
     a.struct_size = C.sizeof(LmheadArgs)
     a.M, a.V, a.Dh = int(M), int(V), 64
+    a.sample = int(bool(sample))
     return int(lib().dlm_lmhead_workspace_bytes(C.byref(a)))
 
 
 def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=None, m_dev=None,
                       inv_temperature: float = 1.0, forbid_token: int = -1, out_scatter: bool = False,
                       lse=None, zmax=None, z2nd=None, target=None, ztarget=None, workspace=None,
+                      sample_seed: Optional[int] = None, sample_step: int = 0, sample_stream: int = 0,
                       stream=None) -> None:
-    """hidden bf16 [rows, Dh]; w bf16 [V, Dh]; conf fp32 / tok int32 outputs; workspace: a uint8 tensor."""
+    """hidden bf16 [rows, Dh]; w bf16 [V, Dh]; conf fp32 / tok int32 outputs; workspace: a uint8 tensor.
+    sample_seed: None = arg-max token; an integer = Gumbel-max sample with that seed."""
     import torch
     a = LmheadArgs()
     a.struct_size = C.sizeof(LmheadArgs)
@@ -253,6 +258,9 @@ def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=
     a.target, a.ztarget = _dev(target, torch.int32, "target"), _dev(ztarget, torch.float32, "ztarget")
     a.workspace = _dev(workspace, None, "workspace")
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if sample_seed is not None:
+        a.sample, a.sample_seed = 1, int(sample_seed) & 0xFFFFFFFFFFFFFFFF
+        a.sample_step, a.sample_stream = int(sample_step) & 0xFFFFFFFF, int(sample_stream) & 0xFFFFFFFF
     _check(lib().dlm_lmhead_confidence(C.byref(a), _stream(stream)))
 
 

@@ -13,6 +13,9 @@ SOURCES = ["core.hip", "commit.hip", "attn.hip", "lmhead.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE,
          # packed-fp32 code generation off (hipcc-only flag; the host pass warns that it ignores it)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # "#pragma unroll" must stay a full unroll however long the body gets: the MFMA accumulator arrays
+         # are only registers while every index into them is a compile-time constant
+         "-mllvm", "-pragma-unroll-threshold=200000",
          "-Wno-unused-command-line-argument"]
 
 

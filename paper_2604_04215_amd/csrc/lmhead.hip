@@ -36,6 +36,11 @@ struct LmParams {
     float* ztarget;
     f32x4* part;  // [n_vtiles][M] of (max, sumexp, runner-up, argmax bits)
     int n_vt, n_mc;
+    // Gumbel-max sampling (sample != 0): a second partial per (tile, row) of
+    // (perturbed max, logit of that token, its index bits, unused)
+    int sample;
+    uint32_t seed_lo, seed_hi, step, stream;
+    f32x4* part2;
 };
 
 struct Red {
@@ -65,6 +70,56 @@ __device__ __forceinline__ Red red_shfl_xor(const Red a, int off) {
     return o;
 }
 
+// ---- noise for sampling ------------------------------------------------------------------------
+// Philox-4x32, ten rounds (Salmon et al., SC 2011): a keyed bijection of a 128-bit counter.  The word for
+// (row key r, token v) is word v % 4 of Philox(counter = (v / 4, r, step, stream), key = seed).
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    u32x4 out = {c0, c1, c2, c3};
+    return out;
+}
+// Standard Gumbel variate -log(-log u) from the top 23 bits k of a word: u = (2k + 1) / 2^24, an odd 24-bit
+// numerator, so u and 1 - u are exact in single precision.  Close to u = 1, where the largest variates (the
+// ones that decide an arg-max) come from, -log u is summed as a series in 1 - u: the hardware logarithm's
+// absolute error would otherwise turn into a relative error of -log u and an absolute error of the variate.
+__device__ __forceinline__ float gumbel_from_bits(uint32_t bits) {
+    const uint32_t odd = 2u * (bits >> 9) + 1u;
+    const float u = (float)odd * 0x1p-24f;
+    const float w = (float)(0x1000000u - odd) * 0x1p-24f;   // 1 - u
+    constexpr float LN2 = 0.6931471805599453f;
+    const float e_series = w * (1.0f + w * (0.5f + w * (0.33333334f + w * (0.25f + w * 0.2f))));
+    const float e_log = -LN2 * __builtin_amdgcn_logf(u);
+    const float e = (w < 0x1p-6f) ? e_series : e_log;        // -log u, an Exp(1) variate
+    return -LN2 * __builtin_amdgcn_logf(e);
+}
+struct Smp {
+    float pm, pz;   // perturbed maximum, unperturbed logit of its token
+    int idx;
+};
+// the larger perturbed value wins; on equal values the lower index
+__device__ __forceinline__ Smp smp_merge(const Smp a, const Smp b) {
+    const bool takeb = (b.pm > a.pm) || (b.pm == a.pm && b.idx < a.idx);
+    const float apm = a.pm, apz = a.pz, bpm = b.pm, bpz = b.pz;
+    const int ai = a.idx, bi = b.idx;
+    Smp r;
+    r.pm = takeb ? bpm : apm;
+    r.pz = takeb ? bpz : apz;
+    r.idx = takeb ? bi : ai;
+    return r;
+}
+
 constexpr int KC = 64;             // Dh elements per pipeline stage (128 B per row); Dh must be a multiple of it
 constexpr int LP = KC * 2 + 16;    // LDS row pitch in bytes: 16-byte reads of 16 consecutive rows hit distinct banks
 
@@ -86,6 +141,7 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
     constexpr int MB = 32 * THW * WH;
     constexpr float LOG2E = 1.4426950408889634f;
     f32x4* redbuf = reinterpret_cast<f32x4*>(smem);  // [WV][MB] of (max, sumexp, runner-up, argmax bits)
+    f32x4* redbuf2 = redbuf + WV * MB;               // [WV][MB] of the sampling partial (only when sampling)
     // (the loop above ended with a barrier: the staging area is free)
 #pragma unroll
     for (int c = 0; c < THW; ++c) {
@@ -130,6 +186,38 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
             f32x4 packed = {red.m, red.s, red.m2, __int_as_float(red.idx)};
             redbuf[wv * MB + col] = packed;
         }
+        if (p.sample) {
+            // acc now holds the scaled, masked logits; noise is keyed by the row's index in `hidden`
+            const uint32_t rk = (r < M) ? (uint32_t)(p.row_idx ? p.row_idx[r] : r) : 0u;
+            Smp sm{-INFINITY, -INFINITY, 0x7fffffff};
+#pragma unroll
+            for (int a = 0; a < TVW; ++a) {
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const int vq = v0 + (wv * TVW + a) * 32 + 8 * i4 + 4 * hi;   // four consecutive tokens, vq % 4 == 0
+                    const u32x4 bits = philox4x32_10((uint32_t)vq >> 2, rk, p.step, p.stream, p.seed_lo, p.seed_hi);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float z = acc[a][c][4 * i4 + e];
+                        const float pert = z + gumbel_from_bits(bits[e]);
+                        if (pert > sm.pm) {
+                            sm.pm = pert;
+                            sm.pz = z;
+                            sm.idx = vq + e;
+                        }
+                    }
+                }
+            }
+            Smp o;
+            o.pm = shfl_xor(sm.pm, 32);
+            o.pz = shfl_xor(sm.pz, 32);
+            o.idx = shfl_xor(sm.idx, 32);
+            sm = smp_merge(sm, o);
+            if (hi == 0) {
+                f32x4 packed = {sm.pm, sm.pz, __int_as_float(sm.idx), 0.f};
+                redbuf2[wv * MB + col] = packed;
+            }
+        }
     }
     __syncthreads();
     for (int col = tid; col < MB; col += NT) {
@@ -144,6 +232,17 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
         }
         f32x4 out = {red.m, red.s, red.m2, __int_as_float(red.idx)};
         p.part[(int64_t)vt * p.M + r] = out;
+        if (p.sample) {
+            const f32x4 g = redbuf2[col];
+            Smp sm{g[0], g[1], __float_as_int(g[2])};
+#pragma unroll
+            for (int k = 1; k < WV; ++k) {
+                const f32x4 o = redbuf2[k * MB + col];
+                sm = smp_merge(sm, Smp{o[0], o[1], __float_as_int(o[2])});
+            }
+            f32x4 out2 = {sm.pm, sm.pz, __int_as_float(sm.idx), 0.f};
+            p.part2[(int64_t)vt * p.M + r] = out2;
+        }
     }
 }
 
@@ -162,7 +261,7 @@ __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
     constexpr int HLD = (MB + RPP - 1) / RPP;
     constexpr int STAGE = (TV + MB) * LP;
     constexpr int RED_BYTES = WV * MB * 16;
-    static_assert(2 * STAGE >= RED_BYTES, "reduction buffer must fit in the staging area");
+    static_assert(2 * STAGE >= 2 * RED_BYTES, "both reduction buffers must fit in the staging area");
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -349,7 +448,7 @@ __global__ __launch_bounds__(64 * WV) void lmhead_wdirect_kernel(LmParams p) {
     constexpr int RPP = NT / 8;
     constexpr int HLD = (MB + RPP - 1) / RPP;
     constexpr int HSTAGE = MB * LP;
-    static_assert(2 * HSTAGE >= WV * MB * 16, "reduction buffer must fit in the staging area");
+    static_assert(2 * HSTAGE >= 2 * WV * MB * 16, "both reduction buffers must fit in the staging area");
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * HSTAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -490,7 +589,7 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
     constexpr int IPW = (TV + MB) / 16 / NW;          // load instructions per wavefront per stage
     static_assert((TV + MB) / 16 % NW == 0, "rows must split evenly over the wavefronts");
     static_assert(NS >= 2 && NS <= 4, "ring of 2..4 stages");
-    static_assert(NS * STAGE >= WV * MB * 16, "reduction buffer must fit in the ring");
+    static_assert(NS * STAGE >= 2 * WV * MB * 16, "both reduction buffers must fit in the ring");
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -624,10 +723,31 @@ __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
     Red tot = red_merge(red_merge(red[0], red[1]), red_merge(red[2], red[3]));
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) tot = red_merge(tot, red_shfl_xor(tot, off));
+    Smp sm{-INFINITY, -INFINITY, 0x7fffffff};
+    if (p.sample) {
+        for (int t = lane; t < p.n_vt; t += 64) {
+            const f32x4 g = p.part2[(int64_t)t * p.M + r];
+            sm = smp_merge(sm, Smp{g[0], g[1], __float_as_int(g[2])});
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            Smp o;
+            o.pm = shfl_xor(sm.pm, off);
+            o.pz = shfl_xor(sm.pz, off);
+            o.idx = shfl_xor(sm.idx, off);
+            sm = smp_merge(sm, o);
+        }
+    }
     if (lane == 0) {
         const int64_t oidx = (p.out_scatter && p.row_idx) ? (int64_t)p.row_idx[r] : (int64_t)r;
-        p.conf[oidx] = 1.0f / tot.s;          // exp(zmax - lse) = 1 / sum_v exp(z_v - zmax)
-        p.tok[oidx] = tot.idx;
+        if (p.sample) {
+            // probability of the sampled token: exp(z_tok - lse) = exp(z_tok - zmax) / sum_v exp(z_v - zmax)
+            p.conf[oidx] = __expf(sm.pz - tot.m) / tot.s;
+            p.tok[oidx] = sm.idx;
+        } else {
+            p.conf[oidx] = 1.0f / tot.s;          // exp(zmax - lse) = 1 / sum_v exp(z_v - zmax)
+            p.tok[oidx] = tot.idx;
+        }
         if (p.lse) p.lse[oidx] = tot.m + logf(tot.s);
         if (p.zmax) p.zmax[oidx] = tot.m;
         if (p.z2nd) p.z2nd[oidx] = tot.m2;
@@ -702,6 +822,7 @@ static int validate_lm(const dlm_lmhead_args* a) {
     if (a->forbid_token >= 0 && a->V < 2) return fail(DLM_ERR_INVALID_ARG, "lmhead: forbid_token with V < 2 leaves no token");
     if (!(a->inv_temperature > 0.f) || a->inv_temperature > 3.0e38f) return fail(DLM_ERR_INVALID_ARG, "lmhead: inv_temperature must be positive and finite");
     if ((a->target == nullptr) != (a->ztarget == nullptr)) return fail(DLM_ERR_INVALID_ARG, "lmhead: target and ztarget go together");
+    if (a->sample != 0 && a->sample != 1) return fail(DLM_ERR_INVALID_ARG, "lmhead: sample must be 0 or 1");
     if (a->M == 0) return DLM_OK;
     if (!a->hidden || !a->w || !a->conf || !a->tok) return fail(DLM_ERR_INVALID_ARG, "lmhead: null hidden/w/conf/tok");
     if (!aligned16(a->hidden) || !aligned16(a->w)) return fail(DLM_ERR_UNSUPPORTED, "lmhead: hidden/w not 16-byte aligned");
@@ -717,7 +838,7 @@ using namespace dlm;
 extern "C" size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args* a) {
     if (!a || a->M <= 0 || a->V <= 0) return 0;
     const size_t n_vt = ((size_t)a->V + LM_MIN_TV - 1) / LM_MIN_TV;   // enough for every kernel shape
-    return n_vt * (size_t)a->M * sizeof(f32x4);
+    return n_vt * (size_t)a->M * sizeof(f32x4) * (a->sample ? 2 : 1);
 }
 
 extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
@@ -739,6 +860,10 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     p.target = a->target; p.ztarget = a->ztarget;
     p.part = (f32x4*)a->workspace;
     p.n_vt = (a->V + var.tv - 1) / var.tv;
+    p.sample = a->sample;
+    p.seed_lo = (uint32_t)a->sample_seed; p.seed_hi = (uint32_t)(a->sample_seed >> 32);
+    p.step = a->sample_step; p.stream = a->sample_stream;
+    p.part2 = p.part + (size_t)p.n_vt * a->M;
     p.n_mc = (a->M + var.mb - 1) / var.mb;
     const int64_t n_wg = (int64_t)((p.n_vt + 7) / 8) * 8 * p.n_mc;
     if (n_wg > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "lmhead: M * V too large for one launch");

@@ -1,0 +1,134 @@
+"""Gumbel-max sampling inside dlm_lmhead_confidence against the oracle (GPU).
+
+Both sides draw the same noise (same counter-based generator, same keys).  The sampled token must be
+identical unless the two largest perturbed logits are closer than MARGIN (single-precision logits and noise
+can then order them the other way); such rows are checked to have picked the runner-up instead."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import sampling
+from paper_2604_04215_amd import binding as dlm
+from paper_2604_04215_amd import synth
+from gpu_util import DEV, bf16_dev, dev, rnd
+
+pytestmark = pytest.mark.gpu
+
+MARGIN = 1e-3
+CONF_TOL = 1e-3
+Z_TOL = 2e-3
+
+
+def run_sampled(h, w, *, seed, step=0, stream=0, row_idx=None, inv_t=1.0, forbid=-1, scatter=False, m_dev=None):
+    R = h.shape[0]
+    V = w.shape[0]
+    M = R if row_idx is None else len(row_idx)
+    n_out = R if scatter else M
+    f = lambda: torch.full((n_out,), float("nan"), dtype=torch.float32, device=DEV)
+    conf, lse, zmax = f(), f(), f()
+    tok = torch.full((n_out,), -7, dtype=torch.int32, device=DEV)
+    ws = torch.empty(max(16, dlm.lmhead_workspace_bytes(M, V, sample=True)), dtype=torch.uint8, device=DEV)
+    dlm.lmhead_confidence(bf16_dev(h), bf16_dev(w), conf, tok, M=M,
+                          row_idx=None if row_idx is None else dev(np.asarray(row_idx, np.int32)),
+                          m_dev=None if m_dev is None else dev(np.asarray([m_dev], np.int32)),
+                          inv_temperature=inv_t, forbid_token=forbid, out_scatter=scatter, lse=lse, zmax=zmax,
+                          workspace=ws, sample_seed=seed, sample_step=step, sample_stream=stream)
+    torch.cuda.synchronize()
+    return dict(conf=conf.cpu().numpy(), tok=tok.cpu().numpy(), lse=lse.cpu().numpy(), zmax=zmax.cpu().numpy())
+
+
+def compare(got, ref, h, w, sel=None, inv_t=1.0):
+    g = {k: (v if sel is None else v[sel]) for k, v in got.items()}
+    clear = (ref["pmax"] - ref["p2nd"]) >= MARGIN
+    assert clear.mean() > 0.95
+    assert np.array_equal(g["tok"][clear], ref["tok"][clear])
+    same = g["tok"] == ref["tok"]
+    assert np.abs(g["conf"][same].astype(np.float64) - ref["conf"][same]).max() <= CONF_TOL
+    assert np.abs(g["lse"] - ref["lse"]).max() <= Z_TOL and np.abs(g["zmax"] - ref["zmax"]).max() <= Z_TOL
+    return int((~same).sum())
+
+
+@pytest.mark.parametrize("variant", range(16))
+def test_every_kernel_shape(variant):
+    M, Dh, V = 300, 192, 1100
+    h, w = rnd(910, (M, Dh)), rnd(911, (V, Dh), Dh ** -0.25)
+    ref = sampling.lmhead_sampled(h, w, seed=0xDEADBEEF12345, step=7, stream=3, forbid_token=V - 1)
+    dlm.set_option("lmhead_variant", variant)
+    try:
+        got = run_sampled(h, w, seed=0xDEADBEEF12345, step=7, stream=3, forbid=V - 1)
+    finally:
+        dlm.set_option("lmhead_variant", -1)
+    compare(got, ref, h, w)
+    assert np.all(got["tok"] != V - 1)
+    greedy = oracle.lmhead(h, w, forbid_token=V - 1)
+    assert (got["tok"] != greedy["tok"]).mean() > 0.3        # it really samples
+
+
+@pytest.mark.parametrize("M,Dh,V", [(1, 64, 300), (33, 128, 777), (90, 128, 601), (150, 128, 4099), (700, 64, 400)])
+def test_shapes_vs_oracle(M, Dh, V):
+    h, w = rnd(M + Dh + 1, (M, Dh)), rnd(V + Dh + 1, (V, Dh), Dh ** -0.25)
+    ref = sampling.lmhead_sampled(h, w, seed=M * 1000003 + V)
+    compare(run_sampled(h, w, seed=M * 1000003 + V), ref, h, w)
+
+
+def test_gather_scatter_temperature_and_row_keys():
+    R, Dh, V = 96, 128, 1000
+    h, w = rnd(5, (R, Dh)), rnd(6, (V, Dh), Dh ** -0.25)
+    idx = np.array(sorted(np.random.default_rng(0).permutation(R)[:41]), np.int32)
+    ref = sampling.lmhead_sampled(h, w, seed=11, step=2, stream=9, row_idx=idx, inv_temperature=0.6, forbid_token=5)
+    got = run_sampled(h, w, seed=11, step=2, stream=9, row_idx=idx, inv_t=0.6, forbid=5)
+    compare(got, ref, h, w)
+    dense = run_sampled(h, w, seed=11, step=2, stream=9, row_idx=idx, inv_t=0.6, forbid=5, scatter=True)
+    assert np.array_equal(dense["tok"][idx], got["tok"])       # the draw does not depend on where it is stored
+    rest = np.setdiff1d(np.arange(R), idx)
+    assert np.all(dense["tok"][rest] == -7)
+    # ... nor on which other rows are in the call, nor on the kernel shape the row count selects
+    full = run_sampled(h, w, seed=11, step=2, stream=9, inv_t=0.6, forbid=5)
+    ref_full = sampling.lmhead_sampled(h, w, seed=11, step=2, stream=9, inv_temperature=0.6, forbid_token=5)
+    clear = (ref_full["pmax"] - ref_full["p2nd"]) >= MARGIN
+    ok = clear[idx]
+    assert np.array_equal(full["tok"][idx][ok], got["tok"][ok])
+    # device-side row count
+    part = run_sampled(h, w, seed=11, step=2, stream=9, row_idx=idx, inv_t=0.6, forbid=5, m_dev=17)
+    assert np.array_equal(part["tok"][:17], got["tok"][:17]) and np.all(part["tok"][17:] == -7)
+    # another step, stream or seed: other draws; the same triple: the same draws, bit for bit
+    again = run_sampled(h, w, seed=11, step=2, stream=9, row_idx=idx, inv_t=0.6, forbid=5)
+    assert np.array_equal(again["tok"], got["tok"]) and np.array_equal(again["conf"], got["conf"])
+    for kw in (dict(seed=12, step=2, stream=9), dict(seed=11, step=3, stream=9), dict(seed=11, step=2, stream=10)):
+        other = run_sampled(h, w, row_idx=idx, inv_t=0.6, forbid=5, **kw)
+        assert (other["tok"] != got["tok"]).mean() > 0.3
+
+
+def test_token_frequencies_follow_the_softmax():
+    # 4096 copies of one hidden row, 8 steps: 32768 draws from one distribution over a small vocabulary
+    Dh, V, n = 64, 40, 4096
+    h1, w = rnd(7, (1, Dh)), rnd(8, (V, Dh), 0.3)
+    h = np.repeat(h1, n, axis=0)
+    z = (synth.bf16_bits_to_f64(h1) @ synth.bf16_bits_to_f64(w).T)[0]
+    p = np.exp(z - z.max())
+    p /= p.sum()
+    counts = np.zeros(V)
+    for step in range(8):
+        got = run_sampled(h, w, seed=31337, step=step)
+        counts += np.bincount(got["tok"], minlength=V)
+        assert np.abs(got["conf"] - p[got["tok"]]).max() <= CONF_TOL
+    import scipy.stats
+    assert scipy.stats.chisquare(counts, p * n * 8).pvalue > 1e-3
+
+
+def test_full_size_vocabulary_sampled_rows():
+    """LLaDA-sized head (4096 x 126464), 86 rows as in a mid-block step: six sampled rows against the oracle."""
+    cfg = synth.CONFIGS["c2"]
+    w = synth.w_vocab(cfg)
+    hid = synth.step_hidden(cfg, 0, 0).reshape(-1, cfg.Dh)
+    idx = np.sort(np.random.default_rng(3).permutation(hid.shape[0])[:86]).astype(np.int32)
+    got = run_sampled(hid, w, seed=2026, step=1, stream=0, row_idx=idx, forbid=cfg.forbid_token)
+    pick = np.array([0, 17, 40, 63, 84, 85])
+    ref = sampling.lmhead_sampled(hid, w, seed=2026, step=1, stream=0, row_idx=idx[pick], forbid_token=cfg.forbid_token)
+    sub = {k: v[pick] for k, v in got.items()}
+    clear = (ref["pmax"] - ref["p2nd"]) >= MARGIN
+    assert np.array_equal(sub["tok"][clear], ref["tok"][clear]) and clear.sum() >= 5
+    same = sub["tok"] == ref["tok"]
+    assert np.abs(sub["conf"][same] - ref["conf"][same]).max() <= CONF_TOL
+    assert np.abs(sub["lse"] - ref["lse"]).max() <= Z_TOL
