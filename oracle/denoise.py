@@ -21,6 +21,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 from .ref import KV, attention, lmhead
+from .sampling import lmhead_sampled
 
 
 def select_commit(conf: np.ndarray, mask: np.ndarray, *, rule: str, tau: float = 0.0, k: int = 0,
@@ -90,7 +91,11 @@ class OracleRollout:
     State (x, mask, cache_k, cache_v) is public so a lock-step checker can re-sync it.
     """
 
-    def __init__(self, cfg, synth, seqs: Optional[Sequence[int]] = None, w: Optional[np.ndarray] = None):
+    def __init__(self, cfg, synth, seqs: Optional[Sequence[int]] = None, w: Optional[np.ndarray] = None,
+                 sample_seed: Optional[int] = None, sample_stream: int = 0, inv_temperature: float = 1.0):
+        # sample_seed None: arg-max tokens; else Gumbel-max samples, step s of block b drawing with
+        # step counter (b << 16) | s and rows keyed by their index b * Lb + i among ALL B sequences
+        self.sample_seed, self.sample_stream, self.inv_temperature = sample_seed, sample_stream, inv_temperature
         self.cfg, self.synth = cfg, synth
         self.seqs = list(range(cfg.B)) if seqs is None else list(seqs)
         self.w = synth.w_vocab(cfg) if w is None else w
@@ -150,7 +155,16 @@ class OracleRollout:
                            q_pos0=self.P, rows=attn_rows)
         mask_before = self.mask.copy()
         row_idx = np.flatnonzero(mask_before.ravel()).astype(np.int32)
-        lm = lmhead(hid.reshape(n * Lb, cfg.Dh), self.w, row_idx=row_idx, forbid_token=cfg.forbid_token)
+        if self.sample_seed is None:
+            lm = lmhead(hid.reshape(n * Lb, cfg.Dh), self.w, row_idx=row_idx, forbid_token=cfg.forbid_token,
+                        inv_temperature=self.inv_temperature)
+        else:
+            if self.seqs != list(range(cfg.B)):
+                raise ValueError("a sampled rollout keys its noise by row index: run all sequences")
+            lm = lmhead_sampled(hid.reshape(n * Lb, cfg.Dh), self.w, row_idx=row_idx,
+                                forbid_token=cfg.forbid_token, inv_temperature=self.inv_temperature,
+                                seed=self.sample_seed, step=(self.block << 16) | self.step_idx,
+                                stream=self.sample_stream)
         conf = np.zeros(n * Lb, np.float64)
         tok = np.full(n * Lb, -1, np.int32)
         conf[row_idx] = lm["conf"]

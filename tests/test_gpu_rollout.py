@@ -28,14 +28,15 @@ def load_state(g: GpuRollout, o: oracle.OracleRollout):
     g.cache_v.copy_(bf16_dev(o.cache_v))
 
 
-def lockstep(cfg, blocks=None):
+def lockstep(cfg, blocks=None, **sample):
     """Run oracle and GPU side by side; both start every step from the same state.  A step may differ
     only where the oracle says the decision is numerically ambiguous (confidence within NEAR of the
     threshold, top-2 logit margin below NEAR, or a rank gap below NEAR between the last selected and
     the first unselected confidence); then the oracle is re-synchronised to the GPU's state."""
     w = synth.w_vocab(cfg)
-    o = oracle.OracleRollout(cfg, synth, w=w)
-    g = GpuRollout(cfg, bf16_dev(w), DEV, record_steps=True)
+    o = oracle.OracleRollout(cfg, synth, w=w, **sample)
+    g = GpuRollout(cfg, bf16_dev(w), DEV, record_steps=True, **sample)
+    sampled = sample.get("sample_seed") is not None
     load_state(g, o)
     stats = dict(steps=0, seq_steps=0, excluded=0, committed=0)
     for b in (range(cfg.n_blocks) if blocks is None else blocks):
@@ -47,6 +48,7 @@ def lockstep(cfg, blocks=None):
         g.begin_block(b, init_mask=dev(o.mask), refresh_k=rk, refresh_v=rv)
         torch.cuda.synchronize()
         assert np.array_equal(bf16_host(g.cache_k), o.cache_k), "cache refresh is a bitwise copy"
+        traj = np.full((cfg.B, cfg.Lb), -1, np.int16)      # step at which each position was committed
         while o.mask.any():
             mask_before = o.mask.copy()
             r = o.step()
@@ -61,8 +63,13 @@ def lockstep(cfg, blocks=None):
             conf_g = g.conf.cpu().numpy().ravel()[rows].astype(np.float64)
             tok_g = g.tok.cpu().numpy().ravel()[rows]
             lm = r["lm"]
-            assert np.abs(conf_g - lm["conf"]).max() <= CONF_TOL
-            clear_tok = (lm["zmax"] - lm["z2nd"]) >= NEAR
+            if sampled:   # the decision is the arg-max of the perturbed logits; confidence belongs to the drawn token
+                clear_tok = (lm["pmax"] - lm["p2nd"]) >= NEAR
+                same = tok_g == lm["tok"]
+                assert np.abs(conf_g[same] - lm["conf"][same]).max() <= CONF_TOL
+            else:
+                assert np.abs(conf_g - lm["conf"]).max() <= CONF_TOL
+                clear_tok = (lm["zmax"] - lm["z2nd"]) >= NEAR
             assert np.array_equal(tok_g[clear_tok], lm["tok"][clear_tok])
             # selection: per sequence, exact unless flagged ambiguous
             commit_g = g.commit_now.cpu().numpy()
@@ -85,6 +92,7 @@ def lockstep(cfg, blocks=None):
                     amb |= bool(len(top) > kk and top[kk - 1] - top[kk] < NEAR)
                 sel = r["commit"][s].astype(bool)
                 amb_tok = bool((~clear_tok[(rows // cfg.Lb) == s]).any())
+                amb |= sampled and amb_tok      # another token drawn: another confidence, maybe another selection
                 if np.array_equal(commit_g[s], r["commit"][s]):
                     same_tok = np.array_equal(x_g[s, o.P:o.P + cfg.Lb][sel], r["tok"][s][sel])
                     assert same_tok or amb_tok, f"token mismatch in block {b} step {r['step']} seq {s}"
@@ -100,6 +108,7 @@ def lockstep(cfg, blocks=None):
             assert np.array_equal(remaining_g, mask_g.sum(axis=1)) and np.all(mask_g <= mask_before)
             assert np.array_equal(commit_g, mask_before - mask_g)
             stats["committed"] += int(n_commit_g.sum())
+            traj[commit_g.astype(bool)] = r["step"]
             # re-synchronise the oracle to the GPU state (a no-op unless an ambiguous step differed)
             o.x[:] = x_g
             o.mask[:] = mask_g
@@ -107,8 +116,27 @@ def lockstep(cfg, blocks=None):
             o.cache_v[:] = bf16_host(g.cache_v)
         # block done: nothing masked, the final step's block K/V sits in the cache
         assert not g.mask.any().item()
+        init = synth.initial_block_mask(cfg, b).astype(bool)
+        assert np.array_equal(g.commit_step.cpu().numpy()[init], traj[init]), "trajectory record"
     assert stats["excluded"] <= 0.05 * max(1, stats["seq_steps"]), stats
     return o, g, stats
+
+
+@pytest.mark.parametrize("name,stream", [("mini2", 0), ("mini2", 5), ("mini3", 1), ("mini4", 2)])
+def test_sampled_lockstep_rollout(name, stream):
+    """Stochastic rollouts (tokens drawn from the softmax at temperature 1 / 0.9) stay in lock-step with the
+    oracle, and two rollout replicas that differ only in their stream draw different tokens."""
+    cfg = synth.CONFIGS[name]
+    o, g, stats = lockstep(cfg, sample_seed=0xC0FFEE, sample_stream=stream, inv_temperature=0.9)
+    n_init = cfg.init_masked if cfg.init_masked is not None else cfg.Lb
+    assert stats["committed"] == cfg.B * (n_init + (cfg.n_blocks - 1) * cfg.Lb)
+    if cfg.rule == "topk":
+        assert stats["steps"] == cfg.n_blocks * cfg.Lb // cfg.k
+    x = g.x.cpu().numpy()
+    assert not (x[:, cfg.prompt:] == cfg.forbid_token).any()
+    if name == "mini2" and stream == 5:
+        _, g0, _ = lockstep(cfg, sample_seed=0xC0FFEE, sample_stream=0, inv_temperature=0.9)
+        assert (g0.x.cpu().numpy()[:, cfg.prompt:] != x[:, cfg.prompt:]).mean() > 0.3
 
 
 @pytest.mark.parametrize("name", ["mini1", "mini2", "mini3", "mini4", "mini5a", "c1"])
