@@ -55,14 +55,21 @@ extern "C" {
 #define DLM_WB_BLOCK_WHEN_DONE 1    /* copy the whole block's K/V when a sequence's last masked position commits */
 #define DLM_WB_COMMITTED_ROWS  2    /* copy the K/V rows of the positions committed by this call */
 
+/* Which blocks of a segment a query may see under DLM_MASK_BLOCK_CAUSAL (kb, qb = block index of key, query) */
+#define DLM_SEG_CAUSAL         0    /* kb <= qb: the query's block and every earlier one                */
+#define DLM_SEG_EARLIER_BLOCKS 1    /* kb <  qb: e.g. the clean copy x_0 seen from a noisy block (Eq. 3) */
+#define DLM_SEG_SAME_BLOCK     2    /* kb == qb: e.g. the noisy copy x_t seen from its own block (Eq. 3) */
+
 /* One segment of keys/values: k, v are bf16 [B, Hkv, len, d] addressed as
  * base + b*stride_b + h*stride_h + t*stride_t + c.  len == 0 means "absent".
- * pos0 is the absolute sequence position of row 0 (block-causal mask only). */
+ * pos0 is the absolute sequence position of row 0 (block-causal mask only).
+ * rule: one of DLM_SEG_* (block-causal mask only; must be 0 under DLM_MASK_FULL). */
 typedef struct dlm_kv_seg {
     const void *k, *v;
     int32_t len;
     int32_t pos0;
     int64_t stride_b, stride_h, stride_t;
+    int32_t rule;
 } dlm_kv_seg;
 
 /* ------------------------------------------------------------------------- *
@@ -81,6 +88,10 @@ typedef struct dlm_kv_seg {
  *           `prefix` exist for sequence b (0 <= value <= prefix.len)
  *   mask_mode DLM_MASK_BLOCK_CAUSAL: key at absolute position p is visible to
  *           query row i iff floor(p / block_size) <= floor((q_pos0 + i) / block_size)
+ *           for a segment with rule DLM_SEG_CAUSAL; the other two rules replace <= by < and ==.
+ *           Block-diffusion training over the pair (noisy x_t, clean x_0) of Eq. 3 is two calls:
+ *           noisy queries with prefix = clean K/V (EARLIER_BLOCKS) and block = noisy K/V (SAME_BLOCK),
+ *           both at pos0 = 0, and clean queries with block = clean K/V (CAUSAL).
  *   scale   <= 0 selects 1/sqrt(d)
  * Arithmetic: bf16 operands, fp32 scores / softmax / accumulation, probabilities
  * rounded to bf16 for the second product, bf16 output.  A row that sees no key

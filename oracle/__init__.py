@@ -12,6 +12,7 @@ Layers:
 Parity pins live in tests/test_oracle_*.py (pure-Python brute force on tiny
 inputs, closed forms, metamorphic identities, textbook special cases).
 """
-from .ref import KV, attention, attention_varlen, lmhead, num_threads, build  # noqa: F401
+from .ref import (KV, attention, attention_varlen, block_diffusion_train_attention, lmhead,  # noqa: F401
+                  num_threads, build)  # noqa: F401
 from .denoise import select_commit, OracleRollout, full_pass, seq_logprob  # noqa: F401
 from . import sampling  # noqa: F401,E402

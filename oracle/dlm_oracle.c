@@ -55,6 +55,10 @@ int oracle_num_threads(void) {
  *   key_ok   optional [B, Lk] bytes; 0 = key absent for that sequence (ragged prefix)
  *   mode     0 full, 1 block-causal with block size bs: key j visible to query i iff
  *            floor(key_pos[j] / bs) <= floor((q_pos0 + i) / bs)
+ *   key_rule optional [Lk] (mode 1 only), per key: 0 the rule above; 1 only keys of EARLIER blocks
+ *            (block index <); 2 only keys of the query's OWN block (block index ==).  Rules 1 and 2 are
+ *            the two halves of block-diffusion training (Eq. 3): the noisy block b is predicted from
+ *            itself (rule 2 on the noisy keys) and from the clean blocks before it (rule 1 on the clean keys).
  *   rows     [n, 3] int32 (b, h, i);   GQA: kv head = h / (Hq / Hkv)
  *   out      [n, d] doubles; lse [n] doubles (natural log).  A row that sees no key
  *            gets out = 0 and lse = -inf.
@@ -62,7 +66,7 @@ int oracle_num_threads(void) {
 int oracle_attention_rows(const uint16_t *q, int64_t q_sb, int64_t q_st, int64_t q_sh,
                           const uint16_t *k, const uint16_t *v,
                           int64_t kv_sb, int64_t kv_sh, int64_t kv_st,
-                          const int32_t *key_pos, const uint8_t *key_ok,
+                          const int32_t *key_pos, const uint8_t *key_ok, const int32_t *key_rule,
                           int32_t Hq, int32_t Hkv, int32_t d, int32_t Lk,
                           int32_t mode, int32_t bs, int32_t q_pos0, double scale,
                           const int32_t *rows, int64_t n_rows,
@@ -85,7 +89,11 @@ int oracle_attention_rows(const uint16_t *q, int64_t q_sb, int64_t q_st, int64_t
             if (key_ok && !key_ok[(int64_t)b * Lk + j]) ok = 0;
             if (ok && mode == 1) {
                 /* positions are non-negative, so integer division is the floor */
-                if (key_pos[j] / bs > (q_pos0 + i) / bs) ok = 0;
+                const int32_t kb = key_pos[j] / bs, qb = (q_pos0 + i) / bs;
+                const int32_t rule = key_rule ? key_rule[j] : 0;
+                if (rule == 0 && kb > qb) ok = 0;
+                if (rule == 1 && kb >= qb) ok = 0;
+                if (rule == 2 && kb != qb) ok = 0;
             }
             vis[j] = (uint8_t)ok;
             if (!ok) continue;

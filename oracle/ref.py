@@ -35,7 +35,7 @@ def _load():
         lib = ctypes.CDLL(build())
         i32, i64, f64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
         lib.oracle_attention_rows.restype = ctypes.c_int
-        lib.oracle_attention_rows.argtypes = [vp, i64, i64, i64, vp, vp, i64, i64, i64, vp, vp,
+        lib.oracle_attention_rows.argtypes = [vp, i64, i64, i64, vp, vp, i64, i64, i64, vp, vp, vp,
                                               i32, i32, i32, i32, i32, i32, i32, f64, vp, i64, vp, vp]
         lib.oracle_lmhead_rows.restype = ctypes.c_int
         lib.oracle_lmhead_rows.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, f64, i32, vp,
@@ -56,10 +56,12 @@ def _ptr(a: Optional[np.ndarray]):
 @dataclass
 class KV:
     """One segment of the visible context: k, v are bf16 bits [B, Hkv, len, d];
-    pos0 is the absolute position of its first row."""
+    pos0 is the absolute position of its first row.  rule (block-causal mode only): "causal" = keys of
+    the query's block and earlier ones, "earlier" = earlier blocks only, "same" = the query's block only."""
     k: np.ndarray
     v: np.ndarray
     pos0: int = 0
+    rule: str = "causal"
 
     @property
     def len(self) -> int:
@@ -84,13 +86,17 @@ def attention(q: np.ndarray, segments: Sequence[KV], *, mask_mode: str = "full",
         k = np.ascontiguousarray(np.concatenate([s.k for s in segments], axis=2), dtype=np.uint16)
         v = np.ascontiguousarray(np.concatenate([s.v for s in segments], axis=2), dtype=np.uint16)
         key_pos = np.concatenate([s.pos0 + np.arange(s.len, dtype=np.int32) for s in segments])
+        key_rule = np.concatenate([np.full(s.len, {"causal": 0, "earlier": 1, "same": 2}[s.rule], np.int32)
+                                   for s in segments])
         Hkv = k.shape[1]
     else:
         Hkv = Hq
         k = np.zeros((B, Hkv, 0, d), dtype=np.uint16)
         v = np.zeros((B, Hkv, 0, d), dtype=np.uint16)
         key_pos = np.zeros((0,), dtype=np.int32)
+        key_rule = np.zeros((0,), dtype=np.int32)
     key_pos = np.ascontiguousarray(key_pos, dtype=np.int32)
+    key_rule = np.ascontiguousarray(key_rule, dtype=np.int32)
     Lk = k.shape[2]
     key_ok = None
     if prefix_len_b is not None and segments:
@@ -113,7 +119,7 @@ def attention(q: np.ndarray, segments: Sequence[KV], *, mask_mode: str = "full",
     vd = v if Lk else np.zeros((1,), dtype=np.uint16)
     rc = _load().oracle_attention_rows(
         _ptr(q), Lq * Hq * d, Hq * d, d, _ptr(kd), _ptr(vd), Hkv * Lk * d, Lk * d, d,
-        _ptr(key_pos), _ptr(key_ok), Hq, Hkv, d, Lk, mode, int(bs), int(q_pos0), float(scale),
+        _ptr(key_pos), _ptr(key_ok), _ptr(key_rule), Hq, Hkv, d, Lk, mode, int(bs), int(q_pos0), float(scale),
         _ptr(rows), n, _ptr(out), _ptr(lse))
     if rc != 0:
         raise ValueError(f"oracle_attention_rows failed: {rc}")
@@ -185,3 +191,18 @@ def lmhead(hidden: np.ndarray, w: np.ndarray, *, row_idx: Optional[np.ndarray] =
     if zt is not None:
         res["zt"] = zt
     return res
+
+
+def block_diffusion_train_attention(q_noisy, k_noisy, v_noisy, q_clean, k_clean, v_clean, *, bs: int,
+                                    scale: Optional[float] = None):
+    """Attention of one block-diffusion training pass over the pair (noisy x_t, clean x_0) of a sequence
+    (Eq. 3: block b of x_t is denoised given itself and the clean blocks before it):
+      noisy query in block b  sees noisy keys of block b and clean keys of blocks < b,
+      clean query in block b  sees clean keys of blocks <= b.
+    q_* bf16 bits [B, L, Hq, d]; k_*, v_* bf16 bits [B, Hkv, L, d].
+    returns (O_noisy, LSE_noisy, O_clean, LSE_clean)."""
+    On, Ln = attention(q_noisy, [KV(k_clean, v_clean, 0, "earlier"), KV(k_noisy, v_noisy, 0, "same")],
+                       mask_mode="block_causal", bs=bs, q_pos0=0, scale=scale)
+    Oc, Lc = attention(q_clean, [KV(k_clean, v_clean, 0, "causal")], mask_mode="block_causal", bs=bs, q_pos0=0,
+                       scale=scale)
+    return On, Ln, Oc, Lc

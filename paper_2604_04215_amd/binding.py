@@ -14,6 +14,7 @@ from typing import Optional, Sequence, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdlm.so")
 
+SEG_CAUSAL, SEG_EARLIER_BLOCKS, SEG_SAME_BLOCK = 0, 1, 2
 DLM_OK, DLM_ERR_INVALID_ARG, DLM_ERR_UNSUPPORTED, DLM_ERR_WORKSPACE, DLM_ERR_HIP = 0, -1, -2, -3, -4
 MASK_FULL, MASK_BLOCK_CAUSAL = 0, 1
 RULE_THRESHOLD, RULE_TOPK = 0, 1
@@ -26,7 +27,7 @@ EXPORTS = ["dlm_block_attn", "dlm_block_attn_workspace_bytes", "dlm_lmhead_confi
 
 class KvSeg(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("len", C.c_int32), ("pos0", C.c_int32),
-                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_t", C.c_int64)]
+                ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_t", C.c_int64), ("rule", C.c_int32)]
 
 
 class AttnArgs(C.Structure):
@@ -145,10 +146,12 @@ def set_option(name: str, value: int) -> None:
     _check(lib().dlm_set_option(name.encode(), int(value)))
 
 
-def kv_seg(k=None, v=None, pos0: int = 0) -> KvSeg:
-    """k, v: bf16 [B, Hkv, len, d] views (any batch/head/row strides) or None for an absent segment."""
+def kv_seg(k=None, v=None, pos0: int = 0, rule: int = 0) -> KvSeg:
+    """k, v: bf16 [B, Hkv, len, d] views (any batch/head/row strides) or None for an absent segment.
+    rule: SEG_CAUSAL / SEG_EARLIER_BLOCKS / SEG_SAME_BLOCK (block-causal mask only)."""
     import torch
     s = KvSeg()
+    s.rule = int(rule)
     if k is None or k.shape[2] == 0:
         s.k = s.v = None
         s.len = 0
@@ -166,7 +169,7 @@ def block_attn(q, out, prefix: Optional[Tuple] = None, block: Optional[Tuple] = 
                suffix: Optional[Tuple] = None, *, n_kv_heads: Optional[int] = None,
                mask_mode: int = MASK_FULL, block_size: int = 0, q_pos0: int = 0, scale: float = 0.0,
                prefix_len_b=None, lse=None, workspace=None, stream=None) -> None:
-    """q, out: bf16 [B, Lq, Hq, d]; each segment is (k, v, pos0) with k, v bf16 [B, Hkv, len, d]."""
+    """q, out: bf16 [B, Lq, Hq, d]; each segment is (k, v, pos0[, rule]) with k, v bf16 [B, Hkv, len, d]."""
     import torch
     a = AttnArgs()
     a.struct_size = C.sizeof(AttnArgs)

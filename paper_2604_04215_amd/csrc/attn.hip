@@ -26,6 +26,7 @@ struct SegDev {
     const uint16_t *k, *v;
     int len, pos0;
     int64_t sb, sh, st;
+    int rule;   // block-causal visibility of this segment's keys: DLM_SEG_CAUSAL / _EARLIER_BLOCKS / _SAME_BLOCK
 };
 
 struct AttnParams {
@@ -88,16 +89,32 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
         o_off = s0 * p.o_st;
         kv1_off = s0 * p.seg[1].st;
     }
+    // Block-causal visibility, per segment: a key at position pos is visible to a query whose block ends at
+    // qlim (exclusive) iff  lo <= pos < hi  with  hi = qlim - hoff_s  (hoff_s = block size for "earlier blocks
+    // only", else 0)  and  lo = qlim - block size for "own block only" (else no lower bound).
+    int F0 = 0, F1 = 0, F2 = 0;                    // first 32-key tile of each segment that some row here can see
+    int ho0 = 0, ho1 = 0, ho2 = 0;
+    bool same0 = false, same1 = false, same2 = false;
     if (BC) {
-        const int rmax = min(r0 + 32 * NWR * RTW, R) - 1;
-        const int lim = ((p.q_pos0 + rmax / p.g) / p.bs + 1) * p.bs;  // positions >= lim are invisible to every row here
-        len0 = max(0, min(len0, lim - p.seg[0].pos0));
-        len1 = max(0, min(len1, lim - p.seg[1].pos0));
-        len2 = max(0, min(len2, lim - p.seg[2].pos0));
+        const int rows_end = min(r0 + 32 * NWR * RTW, R);
+        const int lim = ((p.q_pos0 + (rows_end - 1) / p.g) / p.bs + 1) * p.bs;  // positions >= lim are invisible to every row here
+        const int first = ((p.q_pos0 + r0 / p.g) / p.bs) * p.bs;               // start of the first row's block
+        ho0 = (p.seg[0].rule == DLM_SEG_EARLIER_BLOCKS) ? p.bs : 0;
+        ho1 = (p.seg[1].rule == DLM_SEG_EARLIER_BLOCKS) ? p.bs : 0;
+        ho2 = (p.seg[2].rule == DLM_SEG_EARLIER_BLOCKS) ? p.bs : 0;
+        same0 = p.seg[0].rule == DLM_SEG_SAME_BLOCK;
+        same1 = p.seg[1].rule == DLM_SEG_SAME_BLOCK;
+        same2 = p.seg[2].rule == DLM_SEG_SAME_BLOCK;
+        len0 = max(0, min(len0, lim - ho0 - p.seg[0].pos0));
+        len1 = max(0, min(len1, lim - ho1 - p.seg[1].pos0));
+        len2 = max(0, min(len2, lim - ho2 - p.seg[2].pos0));
+        if (same0) F0 = min(max(first - p.seg[0].pos0, 0) >> 5, (len0 + 31) >> 5);
+        if (same1) F1 = min(max(first - p.seg[1].pos0, 0) >> 5, (len1 + 31) >> 5);
+        if (same2) F2 = min(max(first - p.seg[2].pos0, 0) >> 5, (len2 + 31) >> 5);
     }
     // Key tiles never straddle two segments: each segment is cut into its own 32-key tiles (its last one may
     // be ragged), so a tile's rows share one base pointer, stride and position origin (all wave-uniform).
-    const int T0 = (len0 + 31) >> 5, T1 = (len1 + 31) >> 5, T2 = (len2 + 31) >> 5;
+    const int T0 = ((len0 + 31) >> 5) - F0, T1 = ((len1 + 31) >> 5) - F1, T2 = ((len2 + 31) >> 5) - F2;
     const int T = T0 + T1 + T2;
     const int n_it = (T + NWK - 1) / NWK;
 
@@ -130,12 +147,21 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
         }
         qlim[rt] = BC ? ((p.q_pos0 + i) / p.bs + 1) * p.bs : 0;
     }
-    int qlim_min = 0x7fffffff;   // first position that some row of this wavefront cannot see
+    int qlim_min = 0x7fffffff;   // smallest and largest block end over the rows of this wavefront
+    int qlim_max = 0;
     if (BC) {
 #pragma unroll
-        for (int rt = 0; rt < RTW; ++rt) qlim_min = min(qlim_min, qlim[rt]);
+        for (int rt = 0; rt < RTW; ++rt) {
+            qlim_min = min(qlim_min, qlim[rt]);
+            qlim_max = max(qlim_max, qlim[rt]);
+        }
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) qlim_min = min(qlim_min, shfl_xor(qlim_min, off));
+        for (int off = 32; off >= 1; off >>= 1) {
+            qlim_min = min(qlim_min, shfl_xor(qlim_min, off));
+            qlim_max = max(qlim_max, shfl_xor(qlim_max, off));
+        }
+        qlim_min = __builtin_amdgcn_readfirstlane(qlim_min);   // wave-uniform now: keep them in scalar registers
+        qlim_max = __builtin_amdgcn_readfirstlane(qlim_max);
     }
 
     f32x16 O[RTW][D / 32];
@@ -160,7 +186,7 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     // segment of tile t (t < T), its index inside the segment, and the segment's extent
 #define ATTN_TILE(t, sg, lt, slen)                                                                       \
     const int sg = ((t) < T0) ? 0 : (((t) < T0 + T1) ? 1 : 2);                                           \
-    const int lt = ((t) < T0) ? (t) : (((t) < T0 + T1) ? (t) - T0 : (t) - T0 - T1);                     \
+    const int lt = ((t) < T0) ? (t) + F0 : (((t) < T0 + T1) ? (t) - T0 + F1 : (t) - T0 - T1 + F2);      \
     const int slen = (sg == 0) ? len0 : ((sg == 1) ? len1 : len2);
 #define ATTN_PREFETCH(slot, t)                                                                           \
     {                                                                                                    \
@@ -234,19 +260,28 @@ _Pragma("unroll") \
         } \
         ATTN_TILE(t, sg, lt, slen) \
         const int spos0 = ((sg == 0) ? sp0 : ((sg == 1) ? sp1 : sp2)) + lt * 32; \
-        const bool ragged = (lt * 32 + 32 > slen) || (BC && spos0 + 31 >= qlim_min); \
+        const int hoff = (sg == 0) ? ho0 : ((sg == 1) ? ho1 : ho2); \
+        const bool same = (sg == 0) ? same0 : ((sg == 1) ? same1 : same2); \
+        const bool ragged = (lt * 32 + 32 > slen) || \
+                            (BC && (spos0 + 31 >= qlim_min - hoff || (same && spos0 < qlim_max - p.bs))); \
         bf16x8 pf[RTW][2]; \
 _Pragma("unroll") \
         for (int rt = 0; rt < RTW; ++rt) { \
             float mx = -INFINITY; \
             if (ragged) { \
-_Pragma("unroll") \
-                for (int i = 0; i < 16; ++i) { \
-                    const int jl = 8 * (i >> 2) + 4 * hi + (i & 3); \
-                    bool ok = lt * 32 + jl < slen; \
-                    if (BC) ok = ok && (spos0 + jl < qlim[rt]); \
-                    if (!ok) S[rt][i] = -INFINITY; \
+                /* element i sits at position pbase + 8 * (i / 4) + i % 4; visible iff lo_r <= position < hi_r */ \
+                const int pbase = spos0 + 4 * hi; \
+                int hi_r = spos0 - lt * 32 + slen;   /* end of the segment */ \
+                int lo_r = -(1 << 30); \
+                if (BC) { \
+                    hi_r = min(hi_r, qlim[rt] - hoff); \
+                    if (same) lo_r = qlim[rt] - p.bs; \
                 } \
+                const unsigned span = (unsigned)max(hi_r - lo_r, 0); \
+                const unsigned off0 = (unsigned)(pbase - lo_r); \
+_Pragma("unroll") \
+                for (int i = 0; i < 16; ++i) \
+                    if (off0 + (unsigned)(8 * (i >> 2) + (i & 3)) >= span) S[rt][i] = -INFINITY; \
             } \
 _Pragma("unroll") \
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[rt][i]); \
@@ -501,6 +536,7 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
 
 static int validate_seg(const dlm_kv_seg& s, const char* name, int d) {
     if (s.len < 0) return fail(DLM_ERR_INVALID_ARG, "block_attn: %s.len < 0", name);
+    if (s.rule < DLM_SEG_CAUSAL || s.rule > DLM_SEG_SAME_BLOCK) return fail(DLM_ERR_INVALID_ARG, "block_attn: %s.rule %d unknown", name, s.rule);
     if (s.len == 0) return DLM_OK;
     if (!s.k || !s.v) return fail(DLM_ERR_INVALID_ARG, "block_attn: %s has null k/v", name);
     if (!aligned16(s.k) || !aligned16(s.v)) return fail(DLM_ERR_UNSUPPORTED, "block_attn: %s k/v not 16-byte aligned", name);
@@ -520,6 +556,8 @@ static int validate_attn(const dlm_attn_args* a) {
     if (a->d != 64 && a->d != 128) return fail(DLM_ERR_UNSUPPORTED, "block_attn: head_dim %d (supported: 64, 128)", a->d);
     if (a->mask_mode != DLM_MASK_FULL && a->mask_mode != DLM_MASK_BLOCK_CAUSAL)
         return fail(DLM_ERR_INVALID_ARG, "block_attn: unknown mask_mode %d", a->mask_mode);
+    if (a->mask_mode == DLM_MASK_FULL && (a->prefix.rule | a->block.rule | a->suffix.rule))
+        return fail(DLM_ERR_INVALID_ARG, "block_attn: segment rules need the block-causal mask mode");
     if (a->mask_mode == DLM_MASK_BLOCK_CAUSAL) {
         if (a->block_size < 1) return fail(DLM_ERR_INVALID_ARG, "block_attn: block-causal needs block_size >= 1");
         if (a->q_pos0 < 0 || (int64_t)a->q_pos0 + a->Lq + a->block_size > (1 << 30))
@@ -583,6 +621,7 @@ extern "C" int dlm_block_attn(const dlm_attn_args* a, void* stream) {
         p.seg[s].k = (const uint16_t*)segs[s]->k; p.seg[s].v = (const uint16_t*)segs[s]->v;
         p.seg[s].len = segs[s]->len; p.seg[s].pos0 = segs[s]->pos0;
         p.seg[s].sb = segs[s]->stride_b; p.seg[s].sh = segs[s]->stride_h; p.seg[s].st = segs[s]->stride_t;
+        p.seg[s].rule = segs[s]->rule;
     }
     p.prefix_len_b = a->prefix_len_b;
     p.bs = a->block_size; p.q_pos0 = a->q_pos0;

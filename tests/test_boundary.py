@@ -85,6 +85,11 @@ def test_attn_validation():
     assert L.dlm_block_attn(C.byref(bad), None) == dlm.DLM_ERR_INVALID_ARG
     bad.prefix.len = -1
     assert L.dlm_block_attn(C.byref(bad), None) == dlm.DLM_ERR_INVALID_ARG
+    bad = _attn()
+    bad.block.rule = 3
+    assert L.dlm_block_attn(C.byref(bad), None) == dlm.DLM_ERR_INVALID_ARG
+    bad.block.rule = dlm.SEG_SAME_BLOCK       # a segment rule without the block-causal mask
+    assert L.dlm_block_attn(C.byref(bad), None) == dlm.DLM_ERR_INVALID_ARG
     # empty problems are fine and do nothing
     assert L.dlm_block_attn(C.byref(_attn(B=0)), None) == dlm.DLM_OK
     assert L.dlm_block_attn(C.byref(_attn(Lq=0)), None) == dlm.DLM_OK

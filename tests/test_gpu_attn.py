@@ -158,3 +158,11 @@ def test_planted_one_hot_values_expose_every_key(variant):
         got = bf16_bits_to_f64(bf16_host(out))
         # every channel is a sum of 3-4 probabilities: a per-element relative check is meaningful here
         assert np.abs(got - ref).max() <= 2e-2 * ref.min()
+
+
+def test_prefix_only_cache_with_block_and_suffix_queries():
+    """Prefix-only caching: only the prompt and finished blocks are cached, and the step recomputes the current
+    block AND the still-masked suffix, so the query set is block + suffix (Lq = Lb + S) against
+    [cached prefix | those same Lb + S fresh rows].  Same kernel, larger Lq."""
+    for Lb, S, P in [(32, 96, 200), (32, 224, 72)]:
+        run_case(B=2, Lq=Lb + S, Hq=4, Hkv=2, d=128, P=P, Lb=Lb + S, S=0, seed=77 + S)
