@@ -136,6 +136,53 @@ int dlm_block_attn(const dlm_attn_args *args, void *stream);
 size_t dlm_block_attn_workspace_bytes(const dlm_attn_args *args);
 
 /* ------------------------------------------------------------------------- *
+ * dlm_block_attn_bwd -- gradients of dlm_block_attn for training through the attention of a mask
+ * predictor (the NELBO objectives of Eq. 2 and Eq. 3 are minimised by gradient descent; the masks are
+ * the forward pass's: full, block-causal with per-segment rules, packed variable-length).
+ * With P = softmax(scale Q K^T + mask), O = P V and the upstream gradient d_out:
+ *   d_v = P^T d_out;   dP = d_out V^T;   dS = P * (dP - rowsum(d_out * O));
+ *   d_q = scale dS K;  d_k = scale dS^T Q      (d_k, d_v summed over the query heads of a KV group)
+ *
+ *   q, out, d_out  bf16 [B, Lq, Hq, d] with their own strides; out and lse are the forward results
+ *   lse            fp32, the forward layout ([B, Hq, Lq], or [Hq, total_tokens] in packed mode)
+ *   d_q            bf16 [B, Lq, Hq, d] (dq_stride_*), written; NULL: not wanted
+ *   d_<seg>_k / _v bf16, laid out exactly like that segment's k / v (same strides), written for every row
+ *                  of the segment (zeros where no query sees the key); NULL pair: not wanted.  A tensor that
+ *                  serves as K/V in several calls (e.g. the clean copy in block-diffusion training) gets
+ *                  one gradient per call; adding them is the caller's.
+ *   prefix_len_b is not supported here (ragged caches belong to rollout, not to training).
+ * P is recomputed from q, k and lse: no Lq x Lk tensor is stored.  bf16 operands (P and dS are rounded to
+ * bf16 for their second products), fp32 accumulation, bf16 results.  No atomics: results are deterministic.
+ * workspace: dlm_block_attn_bwd_workspace_bytes(args) bytes, 16-byte aligned (one fp32 per query row and head).
+ * Supported sizes and alignment: as dlm_block_attn.
+ * ------------------------------------------------------------------------- */
+typedef struct dlm_attn_bwd_args {
+    uint32_t struct_size;
+    int32_t B, Lq, Hq, Hkv, d;
+    const void *q;
+    int64_t q_stride_b, q_stride_t, q_stride_h;
+    const void *out;
+    int64_t o_stride_b, o_stride_t, o_stride_h;
+    const void *d_out;
+    int64_t do_stride_b, do_stride_t, do_stride_h;
+    const float *lse;
+    dlm_kv_seg prefix, block, suffix;
+    int32_t mask_mode;
+    int32_t block_size, q_pos0;
+    float scale;
+    void *d_q;
+    int64_t dq_stride_b, dq_stride_t, dq_stride_h;
+    void *d_prefix_k, *d_prefix_v, *d_block_k, *d_block_v, *d_suffix_k, *d_suffix_v;
+    void *workspace;
+    size_t workspace_bytes;
+    const int32_t *cu_seqlens;
+    int32_t total_tokens;
+} dlm_attn_bwd_args;
+
+int dlm_block_attn_bwd(const dlm_attn_bwd_args *args, void *stream);
+size_t dlm_block_attn_bwd_workspace_bytes(const dlm_attn_bwd_args *args);
+
+/* ------------------------------------------------------------------------- *
  * dlm_lmhead_confidence -- for each of M selected rows r of `hidden`:
  *   z_v  = (hidden[row(r), :] . w[v, :]) * inv_temperature,  v in [0, V)
  *   z_forbid_token = -inf (when forbid_token >= 0)

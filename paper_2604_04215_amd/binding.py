@@ -22,7 +22,7 @@ WB_NONE, WB_BLOCK_WHEN_DONE, WB_COMMITTED_ROWS = 0, 1, 2
 
 EXPORTS = ["dlm_block_attn", "dlm_block_attn_workspace_bytes", "dlm_lmhead_confidence",
            "dlm_lmhead_workspace_bytes", "dlm_unmask_commit", "dlm_mask_compact", "dlm_kv_refresh",
-           "dlm_seq_logprob", "dlm_set_option", "dlm_last_error", "dlm_version"]
+           "dlm_block_attn_bwd", "dlm_block_attn_bwd_workspace_bytes", "dlm_seq_logprob", "dlm_set_option", "dlm_last_error", "dlm_version"]
 
 
 class KvSeg(C.Structure):
@@ -39,6 +39,22 @@ class AttnArgs(C.Structure):
                 ("mask_mode", C.c_int32), ("block_size", C.c_int32), ("q_pos0", C.c_int32), ("scale", C.c_float),
                 ("out", C.c_void_p), ("o_stride_b", C.c_int64), ("o_stride_t", C.c_int64), ("o_stride_h", C.c_int64),
                 ("lse", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("cu_seqlens", C.c_void_p), ("total_tokens", C.c_int32)]
+
+
+class AttnBwdArgs(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32),
+                ("B", C.c_int32), ("Lq", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32),
+                ("q", C.c_void_p), ("q_stride_b", C.c_int64), ("q_stride_t", C.c_int64), ("q_stride_h", C.c_int64),
+                ("out", C.c_void_p), ("o_stride_b", C.c_int64), ("o_stride_t", C.c_int64), ("o_stride_h", C.c_int64),
+                ("d_out", C.c_void_p), ("do_stride_b", C.c_int64), ("do_stride_t", C.c_int64), ("do_stride_h", C.c_int64),
+                ("lse", C.c_void_p),
+                ("prefix", KvSeg), ("block", KvSeg), ("suffix", KvSeg),
+                ("mask_mode", C.c_int32), ("block_size", C.c_int32), ("q_pos0", C.c_int32), ("scale", C.c_float),
+                ("d_q", C.c_void_p), ("dq_stride_b", C.c_int64), ("dq_stride_t", C.c_int64), ("dq_stride_h", C.c_int64),
+                ("d_prefix_k", C.c_void_p), ("d_prefix_v", C.c_void_p), ("d_block_k", C.c_void_p),
+                ("d_block_v", C.c_void_p), ("d_suffix_k", C.c_void_p), ("d_suffix_v", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
                 ("cu_seqlens", C.c_void_p), ("total_tokens", C.c_int32)]
 
 
@@ -103,6 +119,10 @@ def lib():
         L.dlm_kv_refresh.restype = C.c_int
         L.dlm_kv_refresh.argtypes = [C.POINTER(KvSeg), C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int64, C.c_int64, C.c_int32, C.c_void_p]
+        L.dlm_block_attn_bwd.restype = C.c_int
+        L.dlm_block_attn_bwd.argtypes = [C.c_void_p, C.c_void_p]
+        L.dlm_block_attn_bwd_workspace_bytes.restype = C.c_size_t
+        L.dlm_block_attn_bwd_workspace_bytes.argtypes = [C.c_void_p]
         L.dlm_seq_logprob.restype = C.c_int
         L.dlm_seq_logprob.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_int32,
                                       C.c_void_p, C.c_void_p, C.c_void_p]
@@ -223,6 +243,77 @@ def varlen_attn(q, k, v, out, cu_seqlens, max_seqlen: int, *, mask_mode: int = M
     a.lse = _dev(lse, torch.float32, "lse")
     a.cu_seqlens, a.total_tokens = _dev(cu_seqlens, torch.int32, "cu_seqlens"), T
     _check(lib().dlm_block_attn(C.byref(a), _stream(stream)))
+
+
+def block_attn_bwd(q, out, d_out, lse, d_q, prefix: Optional[Tuple] = None, block: Optional[Tuple] = None,
+                   suffix: Optional[Tuple] = None, *, d_prefix: Optional[Tuple] = None, d_block: Optional[Tuple] = None,
+                   d_suffix: Optional[Tuple] = None, mask_mode: int = MASK_FULL, block_size: int = 0, q_pos0: int = 0,
+                   scale: float = 0.0, cu_seqlens=None, max_seqlen: Optional[int] = None, workspace=None,
+                   stream=None) -> None:
+    """Gradients of block_attn.  Dense mode: q, out, d_out, d_q bf16 [B, Lq, Hq, d]; segments (k, v, pos0[, rule])
+    with k, v [B, Hkv, len, d]; d_<segment> = (dk, dv) tensors with that segment's shape and strides, or None.
+    Packed mode (cu_seqlens given): q, out, d_out, d_q [T, Hq, d]; block = (k, v) with k, v [T, Hkv, d]."""
+    import torch
+    a = AttnBwdArgs()
+    a.struct_size = C.sizeof(AttnBwdArgs)
+    packed = cu_seqlens is not None
+    if packed:
+        T, Hq, d = q.shape
+        B, Lq = cu_seqlens.numel() - 1, int(max_seqlen)
+        sb = lambda t: (0, t.stride(0), t.stride(1))
+    else:
+        B, Lq, Hq, d = q.shape
+        sb = lambda t: (t.stride(0), t.stride(1), t.stride(2))
+    for t, name in ((out, "out"), (d_out, "d_out")) + (((d_q, "d_q"),) if d_q is not None else ()):
+        if t.shape != q.shape:
+            raise ValueError(f"{name} must have q's shape")
+    a.q, (a.q_stride_b, a.q_stride_t, a.q_stride_h) = _dev(q, torch.bfloat16, "q"), sb(q)
+    a.out, (a.o_stride_b, a.o_stride_t, a.o_stride_h) = _dev(out, torch.bfloat16, "out"), sb(out)
+    a.d_out, (a.do_stride_b, a.do_stride_t, a.do_stride_h) = _dev(d_out, torch.bfloat16, "d_out"), sb(d_out)
+    if d_q is not None:
+        a.d_q, (a.dq_stride_b, a.dq_stride_t, a.dq_stride_h) = _dev(d_q, torch.bfloat16, "d_q"), sb(d_q)
+    if not lse.is_contiguous():
+        raise ValueError("lse must be contiguous")
+    a.lse = _dev(lse, torch.float32, "lse")
+    hkv = Hq
+    if packed:
+        k, v = block[0], block[1]
+        if k.shape != v.shape or k.stride() != v.stride():
+            raise ValueError("k and v must share shape and strides")
+        hkv = k.shape[1]
+        a.prefix, a.suffix = kv_seg(), kv_seg()
+        a.block.k, a.block.v = _dev(k, torch.bfloat16, "k"), _dev(v, torch.bfloat16, "v")
+        a.block.len, a.block.pos0, a.block.rule = Lq, 0, int(block[3]) if len(block) > 3 else 0
+        a.block.stride_b, a.block.stride_t, a.block.stride_h = 0, k.stride(0), k.stride(1)
+        a.cu_seqlens, a.total_tokens = _dev(cu_seqlens, torch.int32, "cu_seqlens"), T
+    else:
+        for sg in (prefix, block, suffix):
+            if sg is not None and sg[0] is not None:
+                hkv = sg[0].shape[1]
+        a.prefix = kv_seg(*prefix) if prefix else kv_seg()
+        a.block = kv_seg(*block) if block else kv_seg()
+        a.suffix = kv_seg(*suffix) if suffix else kv_seg()
+    a.B, a.Lq, a.Hq, a.Hkv, a.d = B, Lq, Hq, hkv, d
+    for name, grads, seg in (("prefix", d_prefix, prefix), ("block", d_block, block), ("suffix", d_suffix, suffix)):
+        if grads is None:
+            continue
+        dk, dv = grads
+        if seg is None or dk.shape != seg[0].shape or dk.stride() != seg[0].stride() or dv.stride() != seg[0].stride():
+            raise ValueError(f"d_{name} must match the {name} segment's shape and strides")
+        setattr(a, f"d_{name}_k", _dev(dk, torch.bfloat16, "dk"))
+        setattr(a, f"d_{name}_v", _dev(dv, torch.bfloat16, "dv"))
+    a.mask_mode, a.block_size, a.q_pos0, a.scale = int(mask_mode), int(block_size), int(q_pos0), float(scale)
+    need = int(lib().dlm_block_attn_bwd_workspace_bytes(C.byref(a)))
+    if workspace is None:
+        raise ValueError(f"workspace of {need} bytes required")
+    a.workspace = _dev(workspace, None, "workspace")
+    a.workspace_bytes = workspace.numel() * workspace.element_size()
+    _check(lib().dlm_block_attn_bwd(C.byref(a), _stream(stream)))
+
+
+def block_attn_bwd_workspace_bytes(n_rows: int, Hq: int) -> int:
+    """n_rows = B * Lq (dense) or the total token count (packed)."""
+    return int(n_rows) * int(Hq) * 4
 
 
 def lmhead_workspace_bytes(M: int, V: int, sample: bool = False) -> int:

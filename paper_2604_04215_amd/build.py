@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libdlm.so")
-SOURCES = ["core.hip", "commit.hip", "attn.hip", "lmhead.hip"]
+SOURCES = ["core.hip", "commit.hip", "attn.hip", "attn_bwd.hip", "lmhead.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE,
          # packed-fp32 code generation off (hipcc-only flag; the host pass warns that it ignores it)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
