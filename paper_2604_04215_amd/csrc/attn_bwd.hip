@@ -13,12 +13,13 @@
 //                             keys of ONE query row and LSE / delta are per-lane scalars), dS^T in registers is
 //                             already the B operand of dQ^T += K^T dS^T; K^T fragments come from LDS through the
 //                             transposing 64-bit LDS read.
-//   * attn_bwd_dkv_kernel   : the mirror image.  A workgroup owns 128 keys of ONE segment of one (sequence, KV
-//                             head), each wavefront 32 of them, and walks the 32-row tiles of (query, head in
-//                             group) rows that can see them: S = Q K^T and dP = dO V^T (rows are the MFMA rows, a
-//                             lane holds 16 rows of ONE key), P and dS in registers are the B operands of
-//                             dV^T += dO^T P and dK^T += Q^T dS; the sum over the heads of a group happens in the
-//                             accumulators because the rows of all its heads pass through the same workgroup.
+//   * attn_bwd_dkv_kernel   : the mirror image, run once for dV and once for dK.  A workgroup owns 128 keys of
+//                             ONE segment of one (sequence, KV head), each wavefront 32 of them, and walks the
+//                             32-row tiles of (query, head in group) rows that can see them: S = Q K^T and
+//                             dP = dO V^T (rows are the MFMA rows, a lane holds 16 rows of ONE key), P and dS in
+//                             registers are the B operands of dV^T += dO^T P and dK^T += Q^T dS; the sum over the
+//                             heads of a group happens in the accumulators because the rows of all its heads pass
+//                             through the same workgroup.
 #include "common.hpp"
 
 namespace dlm {
@@ -94,15 +95,9 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(BwdParams p) {
     if (i < sl && c == 0) p.delta[stat_index(p, b, h, i, s0)] = acc;
 }
 
-// visible extent of the three segments for a workgroup whose rows are [r0, r_end) (forward kernel's rule)
-struct SegView {
-    int len0, len1, len2, F0, F1, F2, ho0, ho1, ho2;
-    bool same0, same1, same2;
-};
-
 // ---------------------------------------------------------------------------------------------------------
 template <int D, bool BC>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(BwdParams p) {
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(BwdParams p) {
     constexpr int KP = D * 2 + 16;         // row-read image pitch (bytes)
     constexpr int TP = D * 2 + 64;         // transposing-read image pitch
     constexpr int C8 = D / 8;
@@ -334,26 +329,35 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-template <int D, bool BC>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(BwdParams p, int sidx) {
+// DK = false: dV of the workgroup's keys (S -> P, dV^T += dO^T P).  DK = true: dK (S, dP -> dS, dK^T += Q^T dS).
+// Two passes instead of one: a pass that holds both accumulators (2 x 64 registers at d = 128) next to the K and
+// V fragments leaves one wavefront per SIMD or spills, and either way every tile waits out the full memory
+// latency; apart, the passes keep two to three workgroups per CU with nothing spilled.  Price: S is formed twice.
+template <int D, bool BC, bool DK>
+__global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams p, int sidx) {
     constexpr int KP = D * 2 + 16;
     constexpr int TP = D * 2 + 64;
     constexpr int C8 = D / 8;
     constexpr int NLD = (32 * C8) / 256;
-    constexpr int IMG = 32 * KP + 32 * TP;            // one tensor's two images
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * IMG + 3 * 32 * 4];
+    // images: Q rows (both passes); DK: Q transposing + dO rows; DV: dO transposing
+    constexpr int IMG_BYTES = DK ? (2 * 32 * KP + 32 * TP) : (32 * KP + 32 * TP);
+    __shared__ __attribute__((aligned(16))) unsigned char smem[IMG_BYTES + 3 * 32 * 4];
     unsigned char* Qrow = smem;
-    unsigned char* Qtr = smem + 32 * KP;
-    unsigned char* Grow = smem + IMG;                 // dO
-    unsigned char* Gtr = smem + IMG + 32 * KP;
-    float* s_lse2 = reinterpret_cast<float*>(smem + 2 * IMG);
+    unsigned char* Xtr = smem + 32 * KP;              // Q^T source (DK) or dO^T source (DV)
+    unsigned char* Grow = smem + 32 * KP + 32 * TP;   // dO rows (DK only)
+    float* s_lse2 = reinterpret_cast<float*>(smem + IMG_BYTES);
     float* s_delta = s_lse2 + 32;
     int* s_qlim = reinterpret_cast<int*>(s_delta + 32);
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n = lane & 31, hi = lane >> 5;
     const int b = blockIdx.z, kvh = blockIdx.y;
-    const int j0 = blockIdx.x * 128;                  // first key of the workgroup inside the segment
+    // Workgroups go round-robin to the 8 XCDs, and under a block-causal mask a key slab's work shrinks with its
+    // index: slab = blockIdx.x would give every XCD the same residues, the heaviest to XCD 0.  Every second
+    // group of 8 slabs is therefore taken in reverse, which evens the sums out.
+    const int bx = blockIdx.x, oct = bx >> 3;
+    const int slab = ((oct & 1) && (oct * 8 + 7 < (int)gridDim.x)) ? oct * 8 + 7 - (bx & 7) : bx;
+    const int j0 = slab * 128;                        // first key of the workgroup inside the segment
 
     // plain locals per segment field (a dynamically indexed struct member would go through memory)
     const uint16_t* sk = (sidx == 0) ? p.seg[0].k : ((sidx == 1) ? p.seg[1].k : p.seg[2].k);
@@ -381,10 +385,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(BwdParams p, int sidx
     }
     if (j0 >= slen) return;
 
-    // ---- this lane's key: K and V fragments (B operands) ----------------------------------------------------
+    // ---- this lane's key: K (and V) fragments (B operands) ----------------------------------------------------
     const int j = j0 + w * 32 + n;
     const bool kvalid = j < slen;
-    bf16x8 kf[D / 16], vf[D / 16];
+    bf16x8 kf[D / 16], vf[DK ? D / 16 : 1];
     {
         const uint16_t* kp = sk + kv_off + kvh * ssh + (int64_t)min(j, slen - 1) * sst;
         const uint16_t* vp = sv + kv_off + kvh * ssh + (int64_t)min(j, slen - 1) * sst;
@@ -393,10 +397,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(BwdParams p, int sidx
             u32x4 a = {0, 0, 0, 0}, d = {0, 0, 0, 0};
             if (kvalid) {
                 a = *reinterpret_cast<const u32x4*>(kp + 16 * c + 8 * hi);
-                d = *reinterpret_cast<const u32x4*>(vp + 16 * c + 8 * hi);
+                if (DK) d = *reinterpret_cast<const u32x4*>(vp + 16 * c + 8 * hi);
             }
             kf[c] = bw_as_bf16x8(a);
-            vf[c] = bw_as_bf16x8(d);
+            if (DK) vf[c] = bw_as_bf16x8(d);
         }
     }
     const int kpos = spos + j;
@@ -415,14 +419,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(BwdParams p, int sidx
         }
     }
 
-    f32x16 dk[D / 32], dv[D / 32];
+    f32x16 acc[D / 32];   // dK^T or dV^T: lane = key, registers = 16 of the 32 head-dim entries of tile dt
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            dk[dt][i] = 0.f;
-            dv[dt][i] = 0.f;
-        }
+        for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
 
     // staging: thread -> NLD chunks of the 32-row tile; rows are (query, head) pairs gathered from Q / dO
     u32x4 qreg[NLD], greg[NLD];
@@ -438,19 +439,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(BwdParams p, int sidx
             qreg[q] = *reinterpret_cast<const u32x4*>(p.q + q_off + ii * p.q_st + (int64_t)hh * p.q_sh + c * 8);      \
             greg[q] = *reinterpret_cast<const u32x4*>(p.dout + do_off + ii * p.do_st + (int64_t)hh * p.do_sh + c * 8); \
         }                                                                                                \
-        if (tid < 32) {                                                                                  \
-            const int rr = (rt) * 32 + tid;                                                              \
-            st_lse2 = INFINITY;                                                                          \
-            st_delta = 0.f;                                                                              \
-            st_qlim = 0;                                                                                 \
-            if (rr < R) {                                                                                \
-                const int ii = rr / p.g, hh = kvh * p.g + (rr - ii * p.g);                               \
-                const int64_t si = stat_index(p, b, hh, ii, s0);                                         \
-                const float l = p.lse[si];                                                               \
-                if (l > -INFINITY) st_lse2 = l * 1.4426950408889634f;                                    \
-                st_delta = p.delta[si];                                                                  \
-                st_qlim = BC ? ((p.q_pos0 + ii) / p.bs + 1) * p.bs : 0;                                  \
-            }                                                                                            \
+        /* per-row statistics: every thread loads (row = tid mod 32, clamped) so that no load sits under a   */ \
+        /* condition (the load counter stays exact and the prefetch really overlaps the tile's arithmetic)  */ \
+        {                                                                                                \
+            const int rr = (rt) * 32 + (tid & 31);                                                       \
+            const int rc_ = min(rr, R - 1);                                                              \
+            const int ii = rc_ / p.g, hh = kvh * p.g + (rc_ - ii * p.g);                                 \
+            const int64_t si = stat_index(p, b, hh, ii, s0);                                             \
+            const float l = p.lse[si];                                                                   \
+            const float dl_ = DK ? p.delta[si] : 0.f;                                                    \
+            const bool ok_ = rr < R;                                                                     \
+            st_lse2 = (ok_ && l > -INFINITY) ? l * 1.4426950408889634f : INFINITY;                       \
+            st_delta = ok_ ? dl_ : 0.f;                                                                  \
+            /* an absent row: its probabilities are 0 through lse2; INT_MAX forces the masked path */    \
+            st_qlim = ok_ ? (BC ? ((p.q_pos0 + ii) / p.bs + 1) * p.bs : 0) : 0x7fffffff;                 \
         }                                                                                                \
     }
 #define BW_STORE_ROWS(rt)                                                                                \
@@ -462,22 +464,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(BwdParams p, int sidx
             const u32x4 z = {0, 0, 0, 0};                                                                \
             const u32x4 qq = live ? qreg[q] : z, gg = live ? greg[q] : z;                                \
             *reinterpret_cast<u32x4*>(Qrow + row * KP + c * 16) = qq;                                    \
-            *reinterpret_cast<u32x4*>(Qtr + row * TP + c * 16) = qq;                                     \
-            *reinterpret_cast<u32x4*>(Grow + row * KP + c * 16) = gg;                                    \
-            *reinterpret_cast<u32x4*>(Gtr + row * TP + c * 16) = gg;                                     \
+            if (DK) {                                                                                    \
+                *reinterpret_cast<u32x4*>(Xtr + row * TP + c * 16) = qq;                                 \
+                *reinterpret_cast<u32x4*>(Grow + row * KP + c * 16) = gg;                                \
+            } else {                                                                                     \
+                *reinterpret_cast<u32x4*>(Xtr + row * TP + c * 16) = gg;                                 \
+            }                                                                                            \
         }                                                                                                \
         if (tid < 32) {                                                                                  \
             s_lse2[tid] = st_lse2;                                                                       \
-            s_delta[tid] = st_delta;                                                                     \
+            if (DK) s_delta[tid] = st_delta;                                                             \
             s_qlim[tid] = st_qlim;                                                                       \
         }                                                                                                \
     }
 
-    if (rt_begin < rt_end) BW_FETCH_ROWS(rt_begin);
-    for (int rt = rt_begin; rt < rt_end; ++rt) {
+    // Row tiles are walked from the last one down: under a block-causal mask the workgroups of one (sequence,
+    // KV head) differ in where their range BEGINS, so this way they all start on the same tile and stay in step.
+    if (rt_begin < rt_end) BW_FETCH_ROWS(rt_end - 1);
+    for (int rt = rt_end - 1; rt >= rt_begin; --rt) {
         BW_STORE_ROWS(rt);
         __syncthreads();
-        BW_FETCH_ROWS(min(rt + 1, rt_end - 1));   // unconditional (clamped) prefetch of the next tile
+        BW_FETCH_ROWS(max(rt - 1, rt_begin));     // unconditional (clamped) prefetch of the next tile
         f32x16 S, dP;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -487,58 +494,66 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(BwdParams p, int sidx
 #pragma unroll
         for (int c = 0; c < D / 16; ++c) {
             const bf16x8 qa = *reinterpret_cast<const bf16x8*>(Qrow + n * KP + (16 * c + 8 * hi) * 2);
-            const bf16x8 ga = *reinterpret_cast<const bf16x8*>(Grow + n * KP + (16 * c + 8 * hi) * 2);
             S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[c], S, 0, 0, 0);      // S[row, key]: lane = key
-            dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vf[c], dP, 0, 0, 0);
+            if (DK) {
+                const bf16x8 ga = *reinterpret_cast<const bf16x8*>(Grow + n * KP + (16 * c + 8 * hi) * 2);
+                dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vf[c], dP, 0, 0, 0);
+            }
         }
-        uint32_t pk[8], dsk[8];
+        // Masking is needed only where some (row, key) pair of this tile is hidden: rows' block ends are monotone,
+        // so the first and the last row bound them (an absent last row carries INT_MAX: masked path for "own block").
+        bool masked = !(j0 + w * 32 + 31 < slen);
+        if (BC) {
+            const int ql_first = s_qlim[0], ql_last = s_qlim[31];
+            const int kp0 = spos + j0 + w * 32;
+            masked = masked || !(kp0 + 31 + hoff < ql_first) || (same && !(ql_last <= kp0 + p.bs));
+        }
+        uint32_t pk[8];   // P (DV pass) or dS (DK pass) as bf16 pairs: the B operand of the second product
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
             // registers 4 g4 .. 4 g4 + 3 hold rows 8 g4 + 4 hi + 0..3 of the tile
             const f32x4 l2 = *reinterpret_cast<const f32x4*>(s_lse2 + 8 * g4 + 4 * hi);
-            const f32x4 dl = *reinterpret_cast<const f32x4*>(s_delta + 8 * g4 + 4 * hi);
-            i32x4 ql = {0, 0, 0, 0};
-            if (BC) ql = *reinterpret_cast<const i32x4*>(s_qlim + 8 * g4 + 4 * hi);
-            float pe[4], ds[4];
+            float pe[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int i = 4 * g4 + e;
-                float pv = fast_exp2(fmaf(S[i], p.scale_log2, -l2[e]));
-                bool vis = kvalid;
-                if (BC) vis = vis && (ql[e] > kpos + hoff) && (!same || ql[e] <= kpos + p.bs);
-                pv = vis ? pv : 0.f;
-                pe[e] = pv;
-                ds[e] = pv * (dP[i] - dl[e]);
+            for (int e = 0; e < 4; ++e) pe[e] = fast_exp2(fmaf(S[4 * g4 + e], p.scale_log2, -l2[e]));
+            if (masked) {
+                i32x4 ql = {0, 0, 0, 0};
+                if (BC) ql = *reinterpret_cast<const i32x4*>(s_qlim + 8 * g4 + 4 * hi);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    bool vis = kvalid;
+                    if (BC) vis = vis && (ql[e] > kpos + hoff) && (!same || ql[e] <= kpos + p.bs);
+                    pe[e] = vis ? pe[e] : 0.f;
+                }
+            }
+            if (DK) {
+                const f32x4 dl = *reinterpret_cast<const f32x4*>(s_delta + 8 * g4 + 4 * hi);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pe[e] = pe[e] * (dP[4 * g4 + e] - dl[e]);
             }
             pk[2 * g4] = pack_bf16x2(pe[0], pe[1]);
             pk[2 * g4 + 1] = pack_bf16x2(pe[2], pe[3]);
-            dsk[2 * g4] = pack_bf16x2(ds[0], ds[1]);
-            dsk[2 * g4 + 1] = pack_bf16x2(ds[2], ds[3]);
         }
-        bf16x8 pf[2], dsf[2];
+        bf16x8 bf[2];
         {
             u32x4 a = {pk[0], pk[1], pk[2], pk[3]}, c4 = {pk[4], pk[5], pk[6], pk[7]};
-            u32x4 d0 = {dsk[0], dsk[1], dsk[2], dsk[3]}, d1 = {dsk[4], dsk[5], dsk[6], dsk[7]};
-            pf[0] = bw_as_bf16x8(a);
-            pf[1] = bw_as_bf16x8(c4);
-            dsf[0] = bw_as_bf16x8(d0);
-            dsf[1] = bw_as_bf16x8(d1);
+            bf[0] = bw_as_bf16x8(a);
+            bf[1] = bw_as_bf16x8(c4);
         }
         const int s16 = lane & 15, blk = (lane >> 4) & 1;
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt) {
 #pragma unroll
             for (int j2 = 0; j2 < 2; ++j2) {
-                union { s16x4 h[2]; bf16x8 v; } gt, qt;
+                union { s16x4 h[2]; bf16x8 v; } xt;
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
                     const int rrow = 16 * j2 + 8 * q + 4 * hi + (s16 >> 2);
                     const int dcol = 32 * dt + 16 * blk + 4 * (s16 & 3);
-                    gt.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Gtr + rrow * TP + dcol * 2));
-                    qt.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Qtr + rrow * TP + dcol * 2));
+                    xt.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Xtr + rrow * TP + dcol * 2));
                 }
-                dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt.v, pf[j2], dv[dt], 0, 0, 0);   // dV^T += dO^T P
-                dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt.v, dsf[j2], dk[dt], 0, 0, 0);  // dK^T += Q^T dS
+                // DV: dV^T += dO^T P;  DK: dK^T += Q^T dS
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xt.v, bf[j2], acc[dt], 0, 0, 0);
             }
         }
         __syncthreads();
@@ -547,19 +562,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(BwdParams p, int sidx
 #undef BW_STORE_ROWS
 
     if (kvalid) {
-        uint16_t* okp = sdk + kv_off + kvh * ssh + (int64_t)j * sst;
-        uint16_t* ovp = sdv + kv_off + kvh * ssh + (int64_t)j * sst;
+        uint16_t* op = (DK ? sdk : sdv) + kv_off + kvh * ssh + (int64_t)j * sst;
+        const float f = DK ? p.scale : 1.0f;
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                u32x2 a, c;
-                a[0] = pack_bf16x2(dk[dt][4 * q4] * p.scale, dk[dt][4 * q4 + 1] * p.scale);
-                a[1] = pack_bf16x2(dk[dt][4 * q4 + 2] * p.scale, dk[dt][4 * q4 + 3] * p.scale);
-                c[0] = pack_bf16x2(dv[dt][4 * q4], dv[dt][4 * q4 + 1]);
-                c[1] = pack_bf16x2(dv[dt][4 * q4 + 2], dv[dt][4 * q4 + 3]);
-                *reinterpret_cast<u32x2*>(okp + 32 * dt + 8 * q4 + 4 * hi) = a;
-                *reinterpret_cast<u32x2*>(ovp + 32 * dt + 8 * q4 + 4 * hi) = c;
+                u32x2 a;
+                a[0] = pack_bf16x2(acc[dt][4 * q4] * f, acc[dt][4 * q4 + 1] * f);
+                a[1] = pack_bf16x2(acc[dt][4 * q4 + 2] * f, acc[dt][4 * q4 + 3] * f);
+                *reinterpret_cast<u32x2*>(op + 32 * dt + 8 * q4 + 4 * hi) = a;
             }
     }
 }
@@ -578,7 +590,9 @@ static int launch_bwd(const BwdParams& p, hipStream_t st) {
     }
     for (int s = 0; s < 3; ++s) {
         if (!p.seg[s].dk || p.seg[s].len == 0) continue;
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC>), dim3((p.seg[s].len + 127) / 128, p.Hkv, p.B), dim3(256), 0, st, p, s);
+        const dim3 grid((p.seg[s].len + 127) / 128, p.Hkv, p.B);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, false>), grid, dim3(256), 0, st, p, s);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, true>), grid, dim3(256), 0, st, p, s);
         rc = check_hip(hipGetLastError(), "attn_bwd_dkv_kernel launch");
         if (rc != DLM_OK) return rc;
     }
