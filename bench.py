@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip per-step LM-head event timing")
     ap.add_argument("--sync-loop", action="store_true", help="poll every step synchronously (no one-step-late poll)")
+    ap.add_argument("--dump-steps", default=None, metavar="FILE",
+                    help="write one line per timed step: block, rows masked before / after, row bound, LM-head us")
     return ap.parse_args()
 
 
@@ -120,7 +122,7 @@ def main():
         e0.record(torch.cuda.current_stream())
         orig_lmhead(*a, **kw)
         e1.record(torch.cuda.current_stream())
-        lm_events.append((e0, e1))
+        lm_events.append((e0, e1, kw.get("M")))
 
     import paper_2604_04215_amd.rollout as ro_mod
 
@@ -150,10 +152,14 @@ def main():
         log = runner.log[log0:]
         assert len(log) == len(lm_events)
         ms, rows = [], []
-        for (a, b), (_, before, _after) in zip(lm_events, log):
+        for (a, b, _bound), (_, before, _after) in zip(lm_events, log):
             if before > 0:                      # launches that found nothing masked move no data
                 ms.append(a.elapsed_time(b))
                 rows.append(before)
+        if args.dump_steps:                     # per step: rows masked before, host-side row bound, LM-head call in us
+            with open(args.dump_steps, "w") as f:
+                for (a, b, bound), (blk, before, after) in zip(lm_events, log):
+                    f.write(f"{blk} {before} {after} {bound} {a.elapsed_time(b) * 1e3:.1f}\n")
         avg_ms = sum(ms) / len(ms)
         mean_rows = sum(rows) / len(rows)
         bytes_per_launch = w_bytes + mean_rows * cfg.Dh * 2 + mean_rows * 8
