@@ -341,6 +341,8 @@ int dlm_kv_refresh(const dlm_kv_seg *src, int32_t B, int32_t Hkv, int32_t d,
  *                   8..10 = key-split alternatives (deeper prefetch, 8 wavefronts) for g*Lq <= 32.
  *   "lmhead_variant" -1 = pick the LM-head kernel shape (workgroup tile, wavefront layout, prefetch
  *                   depth) from M (default); >= 0 forces one entry of the library's shape table.
+ *   "lmhead_block"  -1 = automatic blocking of LM-head workgroups per XCD (default); 0 = none (row chunks of one
+ *                   vocabulary tile side by side); 1..8 = that many vocabulary tiles per block.
  * Every shape computes the same function; the knobs exist for tests and tuning sweeps. */
 int dlm_set_option(const char *name, int value);
 

@@ -601,6 +601,7 @@ extern "C" int dlm_set_option(const char* name, int value) {
         return DLM_OK;
     }
     if (!strcmp(name, "lmhead_variant")) return lm_set_variant(value);
+    if (!strcmp(name, "lmhead_block")) return lm_set_block(value);
     return fail(DLM_ERR_INVALID_ARG, "set_option: unknown option '%s'", name);
 }
 

@@ -36,6 +36,7 @@ struct LmParams {
     float* ztarget;
     f32x4* part;  // [n_vtiles][M] of (max, sumexp, runner-up, argmax bits)
     int n_vt, n_mc;
+    int gm, gv;   // workgroup blocking per XCD: gm row chunks x gv vocabulary tiles run side by side
     // Gumbel-max sampling (sample != 0): a second partial per (tile, row) of
     // (perturbed max, logit of that token, its index bits, unused)
     int sample;
@@ -124,12 +125,20 @@ constexpr int KC = 64;             // Dh elements per pipeline stage (128 B per 
 constexpr int LP = KC * 2 + 16;    // LDS row pitch in bytes: 16-byte reads of 16 consecutive rows hit distinct banks
 
 // Workgroup -> (vocabulary tile, row chunk).  Workgroups are dealt round-robin to the 8 XCDs (each with
-// its own L2), so the row chunks that share one W tile get consecutive slots on the SAME XCD: the tile
-// comes from HBM once and the other chunks hit it in that XCD's L2.
-__device__ __forceinline__ void lm_tile_of_block(int bid, int n_mc, int& vt, int& mc) {
+// its own L2), so what one XCD runs at the same time is a run of consecutive slots of ITS list.  Those slots
+// are laid out as blocks of gv vocabulary tiles x gm row chunks: with one row chunk (the rollout) a W tile
+// comes from HBM once; with many row chunks a block of gv x gm workgroups shares gv W panels and gm H panels
+// through that XCD's L2 instead of streaming all of H once per vocabulary tile.  group = index of the block's
+// vocabulary-tile group: workgroups of one block start their walk over Dh at the same chunk.
+__device__ __forceinline__ void lm_tile_of_block(int bid, int n_mc, int gm, int gv, int& vt, int& mc, int& group) {
     const int xcd = bid & 7, slot = bid >> 3;
-    mc = slot % n_mc;
-    vt = (slot / n_mc) * 8 + xcd;
+    const int per_super = gv * n_mc;
+    const int super = slot / per_super, within = slot - super * per_super;
+    const int blk = within / (gv * gm), r = within - blk * (gv * gm);
+    const int v_local = r / gm;
+    mc = blk * gm + (r - v_local * gm);
+    vt = (super * gv + v_local) * 8 + xcd;
+    group = super;
 }
 
 // Per hidden row (matrix column): reduce over this workgroup's vocabulary rows and write one partial.
@@ -267,8 +276,8 @@ __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wv = w % WV, wh = w / WV;
     const int n = lane & 31, hi = lane >> 5;
-    int vt, mc;
-    lm_tile_of_block(blockIdx.x, p.n_mc, vt, mc);
+    int vt, mc, kgroup;
+    lm_tile_of_block(blockIdx.x, p.n_mc, p.gm, p.gv, vt, mc, kgroup);
     if (vt >= p.n_vt) return;
     const int v0 = vt * TV;
     const int m0 = mc * MB;
@@ -307,7 +316,7 @@ __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
     // Every workgroup walks the Dh axis from a different starting chunk (and wraps).  Rows of W are a power
     // of two apart, so workgroups marching in step over the same columns would all hit the same few HBM
     // channels; the rotation spreads them (measured: 5.0 -> 6.2 TB/s on a pure read of W in this pattern).
-    const int kstart = (int)(((long)vt * 11) % nk);
+    const int kstart = (int)(((long)(p.gv > 1 ? kgroup : vt) * 11) % nk);
 #define LM_CHUNK(kc) (((kc) + kstart) >= nk ? ((kc) + kstart - nk) : ((kc) + kstart))
 #define LM_GLOAD(slot, kc)                                                                               \
     {                                                                                                    \
@@ -453,8 +462,8 @@ __global__ __launch_bounds__(64 * WV) void lmhead_wdirect_kernel(LmParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int n = lane & 31, hi = lane >> 5;
-    int vt, mc;
-    lm_tile_of_block(blockIdx.x, p.n_mc, vt, mc);
+    int vt, mc, kgroup;
+    lm_tile_of_block(blockIdx.x, p.n_mc, p.gm, p.gv, vt, mc, kgroup);
     if (vt >= p.n_vt) return;
     const int v0 = vt * TV;
     const int m0 = mc * MB;
@@ -487,7 +496,7 @@ __global__ __launch_bounds__(64 * WV) void lmhead_wdirect_kernel(LmParams p) {
             for (int i = 0; i < 16; ++i) acc[a][c][i] = 0.f;
 
     const int nk = p.Dh / KC;
-    const int kstart = (int)(((long)vt * 11) % nk);
+    const int kstart = (int)(((long)(p.gv > 1 ? kgroup : vt) * 11) % nk);
 #define LM_CHUNK(kc) (((kc) + kstart) >= nk ? ((kc) + kstart - nk) : ((kc) + kstart))
 #define WD_GLOAD_W(slot, kc)                                                                             \
     {                                                                                                    \
@@ -595,8 +604,8 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wv = w % WV, wh = w / WV;
     const int n = lane & 31, hi = lane >> 5;
-    int vt, mc;
-    lm_tile_of_block(blockIdx.x, p.n_mc, vt, mc);
+    int vt, mc, kgroup;
+    lm_tile_of_block(blockIdx.x, p.n_mc, p.gm, p.gv, vt, mc, kgroup);
     if (vt >= p.n_vt) return;
     const int v0 = vt * TV, m0 = mc * MB;
     int M = p.M;
@@ -619,7 +628,7 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
         }
     }
     const int nk = p.Dh / KCD;
-    const int kstart = (int)(((long)vt * 11) % nk);
+    const int kstart = (int)(((long)(p.gv > 1 ? kgroup : vt) * 11) % nk);
 #define DMA_CHUNK(kc) (((kc) + kstart) >= nk ? ((kc) + kstart - nk) : ((kc) + kstart))
 #define DMA_ISSUE(stage, kc)                                                                             \
     {                                                                                                    \
@@ -801,6 +810,7 @@ static const LmVariant g_lm_variants[] = {
 constexpr int N_LM_VARIANTS = sizeof(g_lm_variants) / sizeof(g_lm_variants[0]);
 constexpr int LM_MIN_TV = 128;   // smallest vocabulary tile of any variant: sizes the workspace
 int g_lm_variant = -1;           // -1 = choose by M; otherwise force an entry of the table (dlm_set_option)
+int g_lm_block_gv = -1;          // -1 = automatic XCD blocking; 0 = none; n = n vocabulary tiles per block (tuning)
 
 static int plan_lmhead(int M) {
     if (g_lm_variant >= 0) return g_lm_variant;
@@ -865,7 +875,17 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     p.step = a->sample_step; p.stream = a->sample_stream;
     p.part2 = p.part + (size_t)p.n_vt * a->M;
     p.n_mc = (a->M + var.mb - 1) / var.mb;
-    const int64_t n_wg = (int64_t)((p.n_vt + 7) / 8) * 8 * p.n_mc;
+    // several row chunks: blocks of gm x gv workgroups for the 32 CUs of an XCD; gm is the largest divisor of the
+    // chunk count up to 8 (measured at V = 126464, Dh = 4096: +6 % at M >= 1024, +10..17 % at M = 512)
+    p.gm = 1; p.gv = 1;
+    if (p.n_mc >= 2) {
+        for (int c = 8; c >= 1; --c)
+            if (p.n_mc % c == 0) { p.gm = c; break; }
+        p.gv = 32 / p.gm > 8 ? 8 : 32 / p.gm;
+    }
+    if (g_lm_block_gv >= 0) { p.gv = g_lm_block_gv > 0 ? g_lm_block_gv : 1; if (g_lm_block_gv == 0) p.gm = 1; }
+    const int64_t n_vt8 = ((int64_t)(p.n_vt + 7) / 8 + p.gv - 1) / p.gv * p.gv;   // vocabulary tiles per XCD, padded to gv
+    const int64_t n_wg = n_vt8 * 8 * p.n_mc;
     if (n_wg > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "lmhead: M * V too large for one launch");
     hipStream_t st = (hipStream_t)stream;
     var.launch(dim3((unsigned)n_wg), st, p);
@@ -876,6 +896,11 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
 }
 
 namespace dlm {
+int lm_set_block(int v) {
+    if (v < -1 || v > 8) return fail(DLM_ERR_INVALID_ARG, "set_option: lmhead_block must be -1..8");
+    g_lm_block_gv = v;
+    return DLM_OK;
+}
 int lm_set_variant(int v) {
     if (v < -1 || v >= N_LM_VARIANTS) return fail(DLM_ERR_INVALID_ARG, "set_option: lmhead_variant must be -1..%d", N_LM_VARIANTS - 1);
     g_lm_variant = v;
