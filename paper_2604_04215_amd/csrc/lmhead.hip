@@ -802,6 +802,8 @@ static const LmVariant g_lm_variants[] = {
     /*13*/ LMA(4, 2, 2, 4, 4),  // 8 waves x (64 x 128)
     /*14*/ LMA(2, 2, 2, 4, 4),  // 128 x 256, 4 waves x (64 x 128)
     /*15*/ LMA(2, 2, 4, 2, 4),  // 256 x 128, 4 waves x (128 x 64)
+    /*16*/ LMA(4, 4, 2, 2, 4),  // 256 x 256, 16 waves x (64 x 64): four wavefronts per SIMD, 118 registers each
+    /*17*/ LMA(4, 4, 2, 2, 3),  // same, 3 stages      (both within 3 % of entry 5 from M = 224 to 8192)
 };
 #undef LMV
 #undef LMA
