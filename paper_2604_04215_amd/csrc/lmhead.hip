@@ -34,7 +34,7 @@ struct LmParams {
     float *lse, *zmax, *z2nd;
     const int32_t* target;
     float* ztarget;
-    f32x4* part;  // [n_vtiles][M] of (max, sumexp, runner-up, argmax bits)
+    f32x4* part;  // [M][n_vtiles] of (max, sumexp, runner-up, argmax bits)
     int n_vt, n_mc;
     int gm, gv;   // workgroup blocking per XCD: gm row chunks x gv vocabulary tiles run side by side
     // Gumbel-max sampling (sample != 0): a second partial per (tile, row) of
@@ -240,7 +240,7 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
             red = red_merge(red, Red{o[0], o[1], o[2], __float_as_int(o[3])});
         }
         f32x4 out = {red.m, red.s, red.m2, __int_as_float(red.idx)};
-        p.part[(int64_t)vt * p.M + r] = out;
+        p.part[(int64_t)r * p.n_vt + vt] = out;
         if (p.sample) {
             const f32x4 g = redbuf2[col];
             Smp sm{g[0], g[1], __float_as_int(g[2])};
@@ -250,7 +250,7 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
                 sm = smp_merge(sm, Smp{o[0], o[1], __float_as_int(o[2])});
             }
             f32x4 out2 = {sm.pm, sm.pz, __int_as_float(sm.idx), 0.f};
-            p.part2[(int64_t)vt * p.M + r] = out2;
+            p.part2[(int64_t)r * p.n_vt + vt] = out2;
         }
     }
 }
@@ -707,35 +707,36 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
     lm_epilogue<WV, WH, TVW, THW>(p, acc, ring, v0, m0, M, vt, wv, wh, n, hi, tid);
 }
 
-// One wavefront per row: merge the per-vocabulary-tile partials in a fixed order (four independent
-// chains per lane so the loads overlap, then a fixed tree).
+// One workgroup per row: merge the per-vocabulary-tile partials (contiguous per row) in a fixed order: every thread
+// takes the tiles t = tid, tid + 256, ... (all loads issued before the first merge), then a fixed tree over the
+// lanes and the four wavefronts.  The merge is associative and its tie rule (lowest index) does not depend on order.
 __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    __shared__ f32x4 s_red[4], s_smp[4];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r = blockIdx.x;
     int M = p.M;
     if (p.m_dev) M = min(M, max(*p.m_dev, 0));
     if (r >= M) return;
-    Red red[4];
-#pragma unroll
-    for (int a = 0; a < 4; ++a) red[a] = Red{-INFINITY, 0.f, -INFINITY, 0x7fffffff};
-    for (int t0 = 0; t0 < p.n_vt; t0 += 256) {
+    const f32x4* row = p.part + (int64_t)r * p.n_vt;
+    Red tot{-INFINITY, 0.f, -INFINITY, 0x7fffffff};
+    for (int t0 = 0; t0 < p.n_vt; t0 += 1024) {
         f32x4 v[4];
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-            const int t = t0 + a * 64 + lane;
+            const int t = t0 + a * 256 + tid;
             v[a] = f32x4{-INFINITY, 0.f, -INFINITY, __int_as_float(0x7fffffff)};
-            if (t < p.n_vt) v[a] = p.part[(int64_t)t * p.M + r];
+            if (t < p.n_vt) v[a] = row[t];
         }
 #pragma unroll
-        for (int a = 0; a < 4; ++a) red[a] = red_merge(red[a], Red{v[a][0], v[a][1], v[a][2], __float_as_int(v[a][3])});
+        for (int a = 0; a < 4; ++a) tot = red_merge(tot, Red{v[a][0], v[a][1], v[a][2], __float_as_int(v[a][3])});
     }
-    Red tot = red_merge(red_merge(red[0], red[1]), red_merge(red[2], red[3]));
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) tot = red_merge(tot, red_shfl_xor(tot, off));
     Smp sm{-INFINITY, -INFINITY, 0x7fffffff};
     if (p.sample) {
-        for (int t = lane; t < p.n_vt; t += 64) {
-            const f32x4 g = p.part2[(int64_t)t * p.M + r];
+        const f32x4* row2 = p.part2 + (int64_t)r * p.n_vt;
+        for (int t = tid; t < p.n_vt; t += 256) {
+            const f32x4 g = row2[t];
             sm = smp_merge(sm, Smp{g[0], g[1], __float_as_int(g[2])});
         }
 #pragma unroll
@@ -748,6 +749,17 @@ __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
         }
     }
     if (lane == 0) {
+        s_red[w] = f32x4{tot.m, tot.s, tot.m2, __int_as_float(tot.idx)};
+        s_smp[w] = f32x4{sm.pm, sm.pz, __int_as_float(sm.idx), 0.f};
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int k = 1; k < 4; ++k) {
+            const f32x4 o = s_red[k], g = s_smp[k];
+            tot = red_merge(tot, Red{o[0], o[1], o[2], __float_as_int(o[3])});
+            sm = smp_merge(sm, Smp{g[0], g[1], __float_as_int(g[2])});
+        }
         const int64_t oidx = (p.out_scatter && p.row_idx) ? (int64_t)p.row_idx[r] : (int64_t)r;
         if (p.sample) {
             // probability of the sampled token: exp(z_tok - lse) = exp(z_tok - zmax) / sum_v exp(z_v - zmax)
@@ -893,7 +905,7 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     var.launch(dim3((unsigned)n_wg), st, p);
     rc = check_hip(hipGetLastError(), "lmhead_kernel launch");
     if (rc != DLM_OK) return rc;
-    hipLaunchKernelGGL(lmhead_reduce_kernel, dim3((a->M + 3) / 4), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(lmhead_reduce_kernel, dim3(a->M), dim3(256), 0, st, p);
     return check_hip(hipGetLastError(), "lmhead_reduce_kernel launch");
 }
 
