@@ -334,7 +334,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(BwdParams p) {
 // V fragments leaves one wavefront per SIMD or spills, and either way every tile waits out the full memory
 // latency; apart, the passes keep two to three workgroups per CU with nothing spilled.  Price: S is formed twice.
 template <int D, bool BC, bool DK>
-__global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams p, int sidx) {
+__global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams p, int sidx, int n_slabs, int pair) {
     constexpr int KP = D * 2 + 16;
     constexpr int TP = D * 2 + 64;
     constexpr int C8 = D / 8;
@@ -352,13 +352,6 @@ __global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n = lane & 31, hi = lane >> 5;
     const int b = blockIdx.z, kvh = blockIdx.y;
-    // Workgroups go round-robin to the 8 XCDs, and under a block-causal mask a key slab's work shrinks with its
-    // index: slab = blockIdx.x would give every XCD the same residues, the heaviest to XCD 0.  Every second
-    // group of 8 slabs is therefore taken in reverse, which evens the sums out.
-    const int bx = blockIdx.x, oct = bx >> 3;
-    const int slab = ((oct & 1) && (oct * 8 + 7 < (int)gridDim.x)) ? oct * 8 + 7 - (bx & 7) : bx;
-    const int j0 = slab * 128;                        // first key of the workgroup inside the segment
-
     // plain locals per segment field (a dynamically indexed struct member would go through memory)
     const uint16_t* sk = (sidx == 0) ? p.seg[0].k : ((sidx == 1) ? p.seg[1].k : p.seg[2].k);
     const uint16_t* sv = (sidx == 0) ? p.seg[0].v : ((sidx == 1) ? p.seg[1].v : p.seg[2].v);
@@ -383,7 +376,23 @@ __global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams
         do_off = s0 * p.do_st;
         kv_off = s0 * sst;
     }
-    if (j0 >= slen) return;
+    // Under a block-causal mask the work of a key slab shrinks with its index (later keys are seen by fewer rows).
+    // pair != 0: a workgroup takes slab x and then slab n_slabs - 1 - x, so every workgroup does the same amount
+    // of work and the workgroups of one (sequence, KV head) stay in step on the same Q / dO tiles (L2 reuse).
+    // pair == 0: one slab per workgroup; every second group of 8 slabs is taken in reverse so that the 8 XCDs,
+    // which get workgroups round-robin, receive equal sums.
+    const int bx = blockIdx.x;
+    for (int pass = 0; pass < (pair ? 2 : 1); ++pass) {
+    int slab = bx;
+    if (pair) {
+        slab = pass ? n_slabs - 1 - bx : bx;
+        if (pass && slab <= bx) break;
+    } else {
+        const int oct = bx >> 3;
+        if ((oct & 1) && (oct * 8 + 7 < n_slabs)) slab = oct * 8 + 7 - (bx & 7);
+    }
+    const int j0 = slab * 128;                        // first key of this pass inside the segment
+    if (j0 >= slen) continue;
 
     // ---- this lane's key: K (and V) fragments (B operands) ----------------------------------------------------
     const int j = j0 + w * 32 + n;
@@ -574,6 +583,8 @@ __global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams
                 *reinterpret_cast<u32x2*>(op + 32 * dt + 8 * q4 + 4 * hi) = a;
             }
     }
+    __syncthreads();   // the LDS images are reused by the next pass
+    }
 }
 
 template <int D, bool BC>
@@ -590,9 +601,12 @@ static int launch_bwd(const BwdParams& p, hipStream_t st) {
     }
     for (int s = 0; s < 3; ++s) {
         if (!p.seg[s].dk || p.seg[s].len == 0) continue;
-        const dim3 grid((p.seg[s].len + 127) / 128, p.Hkv, p.B);
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, false>), grid, dim3(256), 0, st, p, s);
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, true>), grid, dim3(256), 0, st, p, s);
+        const int n_slabs = (p.seg[s].len + 127) / 128;
+        // equal-work pairing where the mask makes slabs unequal (not for "own block only": every slab sees one block's rows)
+        const int pair = (BC && p.seg[s].rule != DLM_SEG_SAME_BLOCK && n_slabs >= 4) ? 1 : 0;
+        const dim3 grid(pair ? (n_slabs + 1) / 2 : n_slabs, p.Hkv, p.B);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, false>), grid, dim3(256), 0, st, p, s, n_slabs, pair);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, true>), grid, dim3(256), 0, st, p, s, n_slabs, pair);
         rc = check_hip(hipGetLastError(), "attn_bwd_dkv_kernel launch");
         if (rc != DLM_OK) return rc;
     }
