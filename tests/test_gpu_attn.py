@@ -166,3 +166,17 @@ def test_prefix_only_cache_with_block_and_suffix_queries():
     [cached prefix | those same Lb + S fresh rows].  Same kernel, larger Lq."""
     for Lb, S, P in [(32, 96, 200), (32, 224, 72)]:
         run_case(B=2, Lq=Lb + S, Hq=4, Hkv=2, d=128, P=P, Lb=Lb + S, S=0, seed=77 + S)
+
+
+def test_largest_batch_the_grid_takes():
+    """B = 65535 (the launch grid's limit; one more is refused): one query row, one key, per sequence."""
+    B, d = 65535, 64
+    q, k, v = rnd(991, (B, 1, 1, d)), rnd(992, (B, 1, 1, d)), rnd(993, (B, 1, 1, d))
+    out = torch.full((B, 1, 1, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dlm.block_attn(bf16_dev(q), out, block=(bf16_dev(k), bf16_dev(v), 0))
+    torch.cuda.synchronize()
+    got = synth.bf16_bits_to_f64(bf16_host(out)).reshape(B, d)
+    assert np.array_equal(got, synth.bf16_bits_to_f64(v).reshape(B, d))        # softmax over one key: O = V exactly
+    big = torch.zeros((65536, 1, 1, d), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(dlm.DlmError):
+        dlm.block_attn(big, big.clone(), block=(big.view(65536, 1, 1, d), big.view(65536, 1, 1, d), 0))

@@ -57,7 +57,10 @@ def check_against_oracle(conf, tok, mask, x, x_pos0, got, *, rule, tau=0.0, k=0,
                                         ("threshold", 0.0, 0), ("topk", 0, 1), ("topk", 0, 4), ("topk", 0, 40)])
 @pytest.mark.parametrize("B,n,group_len", [(8, 32, None), (3, 32, 4), (2, 200, 100), (2, 600, 300), (1, 1024, None),
                                            (5, 64, 1), (20, 200, None), (40, 512, None),
-                                           (4, 64, 2), (4, 64, 8), (2, 30, 3), (70, 1000, 4)])
+                                           (4, 64, 2), (4, 64, 8), (2, 30, 3), (70, 1000, 4),
+                                           (16, 1024, None),     # the longest group, 16384 positions: largest one-workgroup problem
+                                           (17, 1024, None),     # one sequence more: the wave-per-group path
+                                           (15, 1023, None)])
 def test_selection_bit_exact(rule, tau, k, B, n, group_len):
     import zlib
     rng = np.random.default_rng(zlib.crc32(repr((rule, tau, k, B, n, group_len)).encode()))
