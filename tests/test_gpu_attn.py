@@ -6,6 +6,7 @@ import torch
 import oracle
 from oracle import KV
 from paper_2604_04215_amd import binding as dlm
+from paper_2604_04215_amd import synth
 from gpu_util import DEV, attn_rel_err, bf16_dev, bf16_host, dev, rnd
 
 pytestmark = pytest.mark.gpu
