@@ -338,7 +338,9 @@ int dlm_kv_refresh(const dlm_kv_seg *src, int32_t B, int32_t Hkv, int32_t d,
  *                   1 = 32-row workgroups whose wavefronts split the keys (needs g*Lq <= 32,
  *                       otherwise falls back to 2); 2 = 128-row; 3 = 256-row workgroups (one per CU);
  *                   4..7 = 128-row workgroups sized for 2, 3, 3, 4 resident workgroups per CU;
- *                   8..10 = key-split alternatives (deeper prefetch, 8 wavefronts) for g*Lq <= 32.
+ *                   8..10 = key-split alternatives (deeper prefetch, 8 wavefronts) for g*Lq <= 32;
+ *                   11 = 32-row key-split workgroups for any row count, the row tiles of one (sequence,
+ *                   KV head) grouped on one XCD (chosen when 128-row workgroups would leave most CUs idle).
  *   "lmhead_variant" -1 = pick the LM-head kernel shape (workgroup tile, wavefront layout, prefetch
  *                   depth) from M (default); >= 0 forces one entry of the library's shape table.
  *   "lmhead_block"  -1 = automatic blocking of LM-head workgroups per XCD (default); 0 = none (row chunks of one

@@ -42,6 +42,7 @@ struct AttnParams {
     float* lse;
     const int32_t* cu;  // packed variable-length mode: sequence b owns tokens [cu[b], cu[b+1])
     int total;          // cu[B]
+    int remap_nx;       // > 0: 1-D grid; the remap_nx row tiles of one (sequence, KV head) get consecutive slots of one XCD
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
@@ -69,8 +70,18 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wr = w % NWR, wk = w / NWR;
     const int n = lane & 31, hi = lane >> 5;
-    const int b = blockIdx.z, kvh = blockIdx.y;
-    const int r0 = blockIdx.x * (32 * NWR * RTW);
+    int b = blockIdx.z, kvh = blockIdx.y, bx = blockIdx.x;
+    if (p.remap_nx > 0) {
+        // Workgroups go round-robin to the 8 XCDs.  Row tiles of one (sequence, KV head) read the same K/V, so they
+        // are given consecutive slots of ONE XCD: K/V then comes from HBM once and the other tiles hit that L2.
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int grp = xcd + 8 * (slot / p.remap_nx);
+        if (grp >= p.B * p.Hkv) return;
+        bx = slot % p.remap_nx;
+        kvh = grp % p.Hkv;
+        b = grp / p.Hkv;
+    }
+    const int r0 = bx * (32 * NWR * RTW);
 
     // ---- visible extent of each segment for this workgroup -----------------
     int len0 = p.seg[0].len, len1 = p.seg[1].len, len2 = p.seg[2].len;
@@ -333,7 +344,7 @@ _Pragma("unroll") \
 
     // tile of iteration `it` for this wave group: it * NWK + wk; it sits in register slot it % PF
     if (n_it > 0) {
-        const int rot0 = DB ? 0 : (int)((blockIdx.z * (unsigned)gridDim.y + blockIdx.y) * 5u % (unsigned)n_it);
+        const int rot0 = DB ? 0 : (int)(((unsigned)b * (unsigned)p.Hkv + (unsigned)kvh) * 5u % (unsigned)n_it);
 #pragma unroll
         for (int s = 0; s < PF; ++s)
             if (s < n_it) ATTN_PREFETCH(s, ((s + rot0 >= n_it) ? s + rot0 - n_it : s + rot0) * NWK + wk);
@@ -378,7 +389,7 @@ _Pragma("unroll") \
         // Each (sequence, KV head) starts its walk over the key tiles at a different tile and wraps: the K/V
         // blocks of different heads are a large power-of-two-ish stride apart, so workgroups that all begin at
         // tile 0 hit the same few HBM channels together.  Softmax is order-independent up to rounding.
-        const int rot = (n_it > 0) ? (int)((blockIdx.z * (unsigned)gridDim.y + blockIdx.y) * 5u % (unsigned)n_it) : 0;
+        const int rot = (n_it > 0) ? (int)(((unsigned)b * (unsigned)p.Hkv + (unsigned)kvh) * 5u % (unsigned)n_it) : 0;
 #define ATTN_KS_TILE(i) ((((i) + rot) >= n_it ? (i) + rot - n_it : (i) + rot) * NWK + wk)
         int it = 0;
         const int n_steady = (n_it - PF > 0) ? ((n_it - PF) / PF) * PF : 0;
@@ -504,10 +515,22 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
     if (variant == 0) {
         const int64_t wgs128 = BH * ((p.R + 127) / 128);
         if (p.R <= 32) variant = 1;           // waves split the keys, merge on chip
+        // far too few 128-row workgroups for 256 CUs: 32-row key-split tiles (K/V re-read per row tile, through one L2)
+        else if (wgs128 <= 64 || (wgs128 <= 128 && p.R <= 64)) variant = 11;
         else if (wgs128 >= 768) variant = 6;  // 128-row workgroups, three resident per CU (softmax of one overlaps MFMA of another)
         else variant = 4;                     // 128-row workgroups, two resident per CU, deeper prefetch
     }
-    if (variant == 1 && p.R > 32) variant = 2;
+    if (variant == 0 + 11 || (variant == 1 && p.R > 32)) {
+        // 32-row workgroups whose wavefronts split the keys, several row tiles per (sequence, KV head), XCD-grouped
+        AttnParams q = p;
+        q.remap_nx = (p.R + 31) / 32;
+        const int64_t n_wg = (BH + 7) / 8 * 8 * q.remap_nx;
+        if (n_wg <= 0x7fffffff) {
+            hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1>), dim3((unsigned)n_wg), dim3(256), 0, st, q);
+            return check_hip(hipGetLastError(), "attn_kernel launch");
+        }
+        variant = 2;
+    }
     if (variant >= 8 && p.R <= 32) {   // key-split alternatives (tuning)
         const dim3 grid(1, p.Hkv, p.B);
         if (variant == 8) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2>), grid, dim3(256), 0, st, p);
@@ -596,7 +619,7 @@ using namespace dlm;
 extern "C" int dlm_set_option(const char* name, int value) {
     if (!name) return fail(DLM_ERR_INVALID_ARG, "set_option: null name");
     if (!strcmp(name, "attn_variant")) {
-        if (value < 0 || value > 10) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..10");
+        if (value < 0 || value > 11) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..11");
         g_attn_variant = value;
         return DLM_OK;
     }
@@ -631,6 +654,7 @@ extern "C" int dlm_block_attn(const dlm_attn_args* a, void* stream) {
     p.out = (uint16_t*)a->out; p.o_sb = a->o_stride_b; p.o_st = a->o_stride_t; p.o_sh = a->o_stride_h;
     p.lse = a->lse;
     p.cu = a->cu_seqlens; p.total = a->total_tokens;
+    p.remap_nx = 0;
     hipStream_t st = (hipStream_t)stream;
     const bool bc = a->mask_mode == DLM_MASK_BLOCK_CAUSAL;
     if (a->d == 128) return bc ? launch_attn<128, true>(p, st) : launch_attn<128, false>(p, st);

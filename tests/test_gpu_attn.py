@@ -59,7 +59,7 @@ def test_rollout_shape_mha(variant):
     run_case(B=2, Lq=32, Hq=4, Hkv=4, d=128, P=200, Lb=32, S=0, variant=variant, seed=1)
 
 
-@pytest.mark.parametrize("variant", [0, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("variant", [0, 2, 3, 4, 5, 6, 7, 11])
 def test_dual_cache_and_gqa7(variant):
     # 7 query heads per KV head (224 packed rows), prefix | block | suffix, ragged suffix
     run_case(B=2, Lq=32, Hq=14, Hkv=2, d=128, P=96, Lb=32, S=45, variant=variant, seed=2)

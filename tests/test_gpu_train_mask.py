@@ -46,7 +46,7 @@ def check(B, L, Hq, Hkv, d, bs, variant=0, seed=0):
     assert np.abs(Ln - rLn).max() <= LSE_TOL and np.abs(Lc - rLc).max() <= LSE_TOL
 
 
-@pytest.mark.parametrize("variant", [0, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("variant", [0, 2, 3, 4, 5, 6, 7, 11])
 def test_row_split_shapes(variant):
     check(B=2, L=204, Hq=4, Hkv=2, d=128, bs=4, variant=variant, seed=100)
 

@@ -43,7 +43,7 @@ def run_varlen(lens, Hq, Hkv, d, mode="full", bs=0, variant=0, seed=0, max_seqle
     assert np.abs(lse.cpu().numpy().astype(np.float64) - ref_lse).max() <= LSE_TOL
 
 
-@pytest.mark.parametrize("variant", [0, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("variant", [0, 2, 3, 4, 5, 6, 7, 11])
 def test_ragged_mix_row_split_shapes(variant):
     # lengths around the 32-key tile and the 128-row workgroup, an empty sequence, one-token sequences
     run_varlen([1, 31, 32, 33, 200, 0, 129, 1, 257], Hq=4, Hkv=2, d=128, variant=variant, seed=10)
