@@ -80,7 +80,9 @@ def main():
             images[block] = (to_dev(k), to_dev(v))
         return images[block]
 
-    init_masks = {b: torch.from_numpy(synth.initial_block_mask(cfg, b)).to(dev) for b in range(cfg.n_blocks)}
+    init_host = {b: synth.initial_block_mask(cfg, b) for b in range(cfg.n_blocks)}
+    init_masks = {b: torch.from_numpy(m).to(dev) for b, m in init_host.items()}
+    n_masked0 = {b: int(m.sum()) for b, m in init_host.items()}      # known on the host: no device reduction per block
     pool = {}
 
     def inputs(block, step):
@@ -94,7 +96,7 @@ def main():
     def setup(block):
         # block 0 installs the prompt cache image; later blocks refresh it when the workload says so
         refresh = image(block) if (block == 0 or cfg.refresh) else None
-        return dict(init_mask=init_masks[block], refresh=refresh, n_masked=int(init_masks[block].sum()))
+        return dict(init_mask=init_masks[block], refresh=refresh, n_masked=n_masked0[block])
 
     def restart():
         g.x.copy_(x0)

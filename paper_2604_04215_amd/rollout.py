@@ -99,6 +99,10 @@ class GpuRollout:
             self.commit_step.fill_(-1)
         dlm.mask_compact(self.mask, self.row_idx, self.m_dev)
         self.m_host = cfg.B * Lb
+        # the cache views of this block's prefix / suffix are the same for all of its steps
+        S = self.S
+        self._prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
+        self._suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
 
     def step(self, q: torch.Tensor, kblk: torch.Tensor, vblk: torch.Tensor, hidden: torch.Tensor) -> None:
         """Enqueue one denoising step.  q [B, Lb, Hq, d]; kblk, vblk [B, Hkv, Lb, d]; hidden [B, Lb, Dh]."""
@@ -107,8 +111,7 @@ class GpuRollout:
         ev, host = self._ring[self._ring_pos]
         self._ring_pos = (self._ring_pos + 1) % len(self._ring)
         st = torch.cuda.current_stream()     # looked up once per step: the query is a third of the enqueue time
-        prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
-        suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
+        prefix, suffix = self._prefix, self._suffix
         dlm.block_attn(q, self.O, prefix=prefix, block=(kblk, vblk, P), suffix=suffix,
                        mask_mode=_MASKS[cfg.mask_mode], block_size=cfg.bs, q_pos0=P,
                        lse=self.lse_attn if self.diagnostics else None, stream=st)
