@@ -48,6 +48,10 @@ extern "C" {
 #define DLM_MASK_FULL          0    /* every query sees every key (masked diffusion LM)       */
 #define DLM_MASK_BLOCK_CAUSAL  1    /* key visible iff its block index <= the query's (Eq. 3) */
 
+#define DLM_CONF_TOKEN_PROB    0    /* confidence = probability of the chosen token                          */
+#define DLM_CONF_MARGIN        1    /* confidence = p(top-1) - p(top-2)                                      */
+#define DLM_CONF_NEG_ENTROPY   2    /* confidence = sum_v p_v log p_v (0 = one-hot, -log V = uniform)         */
+
 #define DLM_RULE_THRESHOLD     0
 #define DLM_RULE_TOPK          1
 
@@ -212,9 +216,13 @@ size_t dlm_block_attn_bwd_workspace_bytes(const dlm_attn_bwd_args *args);
  * 32 bits of sample_seed)): the draw depends on the row's index in `hidden`, not on r or M, and repeats
  * exactly for equal (seed, step, stream).  Callers give every denoising step its own sample_step and
  * every rollout replica its own sample_stream.
+ * conf_mode selects what `conf` holds (the score dlm_unmask_commit ranks and thresholds; the paper leaves the
+ * confidence of its decoding open, the model families it names decode with the token probability, the top-2
+ * margin or the negative entropy): DLM_CONF_TOKEN_PROB (default; the sampled token's probability when sampling),
+ * DLM_CONF_MARGIN, DLM_CONF_NEG_ENTROPY; the latter two score the distribution, whichever token is chosen.
  * Arithmetic: bf16 operands, fp32 accumulation and softmax.
  * Supported: Dh % 64 == 0; hidden, w 16-byte aligned; strides multiples of 8.
- * workspace: dlm_lmhead_workspace_bytes(args) bytes (depends on M, V and sample), 16-byte aligned.
+ * workspace: dlm_lmhead_workspace_bytes(args) bytes (depends on M, V, sample and conf_mode), 16-byte aligned.
  * ------------------------------------------------------------------------- */
 typedef struct dlm_lmhead_args {
     uint32_t struct_size;
@@ -238,6 +246,7 @@ typedef struct dlm_lmhead_args {
     int32_t sample;
     uint32_t sample_step, sample_stream;
     uint64_t sample_seed;
+    int32_t conf_mode;
 } dlm_lmhead_args;
 
 int dlm_lmhead_confidence(const dlm_lmhead_args *args, void *stream);

@@ -92,7 +92,11 @@ class OracleRollout:
     """
 
     def __init__(self, cfg, synth, seqs: Optional[Sequence[int]] = None, w: Optional[np.ndarray] = None,
-                 sample_seed: Optional[int] = None, sample_stream: int = 0, inv_temperature: float = 1.0):
+                 sample_seed: Optional[int] = None, sample_stream: int = 0, inv_temperature: float = 1.0,
+                 confidence: str = "prob"):
+        # confidence: the score the commit rule ranks: "prob" (of the chosen token), "margin" (top-1 minus
+        # top-2 probability) or "neg_entropy" (sum p log p); the latter two score the distribution
+        self.confidence = confidence
         # sample_seed None: arg-max tokens; else Gumbel-max samples, step s of block b drawing with
         # step counter (b << 16) | s and rows keyed by their index b * Lb + i among ALL B sequences
         self.sample_seed, self.sample_stream, self.inv_temperature = sample_seed, sample_stream, inv_temperature
@@ -165,6 +169,11 @@ class OracleRollout:
                                 forbid_token=cfg.forbid_token, inv_temperature=self.inv_temperature,
                                 seed=self.sample_seed, step=(self.block << 16) | self.step_idx,
                                 stream=self.sample_stream)
+        if self.confidence != "prob":
+            det = lm if self.sample_seed is None else lmhead(hid.reshape(n * Lb, cfg.Dh), self.w, row_idx=row_idx,
+                                                             forbid_token=cfg.forbid_token,
+                                                             inv_temperature=self.inv_temperature)
+            lm = dict(lm, conf=det[self.confidence])
         conf = np.zeros(n * Lb, np.float64)
         tok = np.full(n * Lb, -1, np.int32)
         conf[row_idx] = lm["conf"]

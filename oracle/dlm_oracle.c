@@ -137,12 +137,14 @@ int oracle_attention_rows(const uint16_t *q, int64_t q_sb, int64_t q_st, int64_t
  *   lse   = zmax + log sum_v exp(z_v - zmax);  conf = exp(zmax - lse)
  *   z2nd  = max over v != tok of z_v  (-inf when V == 1)
  *   zt[r] = z at target[r] (only when target != NULL): the numerator of log p(target)
+ *   nent[r] = sum_v p_v log p_v with p = softmax(z) (optional): the negative entropy of the categorical,
+ *             an alternative confidence score (0 for a one-hot distribution, -log V for a uniform one)
  */
 int oracle_lmhead_rows(const uint16_t *hidden, int64_t h_stride, const int32_t *row_idx, int64_t M,
                        const uint16_t *w, int64_t w_stride, int32_t Dh, int32_t V,
                        double inv_T, int32_t forbid, const int32_t *target,
                        double *conf, int32_t *tok, double *lse, double *zmax, double *z2nd,
-                       double *zt) {
+                       double *zt, double *nent) {
     if (V <= 0 || Dh <= 0) return -1;
     double *z = (double *)malloc(sizeof(double) * (size_t)V);
     double *hrow = (double *)malloc(sizeof(double) * (size_t)Dh);
@@ -174,6 +176,12 @@ int oracle_lmhead_rows(const uint16_t *hidden, int64_t h_stride, const int32_t *
         zmax[r] = m;
         z2nd[r] = second;
         if (target && zt) zt[r] = z[target[r]];
+        if (nent) {
+            double acc = 0.0;
+            for (int32_t vv = 0; vv < V; ++vv)
+                if (z[vv] > -INFINITY) acc += exp(z[vv] - L) * (z[vv] - L);     /* p log p; p = 0 contributes 0 */
+            nent[r] = acc;
+        }
     }
     free(z); free(hrow);
     return 0;

@@ -39,7 +39,7 @@ def _load():
                                               i32, i32, i32, i32, i32, i32, i32, f64, vp, i64, vp, vp]
         lib.oracle_lmhead_rows.restype = ctypes.c_int
         lib.oracle_lmhead_rows.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, f64, i32, vp,
-                                           vp, vp, vp, vp, vp, vp]
+                                           vp, vp, vp, vp, vp, vp, vp]
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -155,9 +155,11 @@ def lmhead(hidden: np.ndarray, w: np.ndarray, *, row_idx: Optional[np.ndarray] =
            target: Optional[np.ndarray] = None):
     """Per row: arg-max token of hidden @ W^T, its softmax probability, LSE, the
     max and the runner-up logit (and the target's logit when targets are given).
+    Two alternative confidence scores come with it: `margin` = p(top-1) - p(top-2) and
+    `neg_entropy` = sum_v p_v log p_v.
 
     hidden bf16 bits [R, Dh]; w bf16 bits [V, Dh]; row_idx optional [M] gather.
-    returns dict(conf, tok, lse, zmax, z2nd[, zt]) of length-M arrays.
+    returns dict(conf, tok, lse, zmax, z2nd, margin, neg_entropy[, zt]) of length-M arrays.
     """
     hidden = np.ascontiguousarray(hidden, dtype=np.uint16)
     w = np.ascontiguousarray(w, dtype=np.uint16)
@@ -175,6 +177,7 @@ def lmhead(hidden: np.ndarray, w: np.ndarray, *, row_idx: Optional[np.ndarray] =
     lse = np.zeros(M, np.float64)
     zmax = np.zeros(M, np.float64)
     z2nd = np.zeros(M, np.float64)
+    nent = np.zeros(M, np.float64)
     zt = None
     if target is not None:
         target = np.ascontiguousarray(target, dtype=np.int32)
@@ -184,10 +187,11 @@ def lmhead(hidden: np.ndarray, w: np.ndarray, *, row_idx: Optional[np.ndarray] =
         rc = _load().oracle_lmhead_rows(_ptr(hidden), Dh, _ptr(row_idx), M, _ptr(w), Dh, Dh, V,
                                         float(inv_temperature), int(forbid_token), _ptr(target),
                                         _ptr(conf), _ptr(tok), _ptr(lse), _ptr(zmax), _ptr(z2nd),
-                                        _ptr(zt))
+                                        _ptr(zt), _ptr(nent))
         if rc != 0:
             raise ValueError(f"oracle_lmhead_rows failed: {rc}")
-    res = dict(conf=conf, tok=tok, lse=lse, zmax=zmax, z2nd=z2nd)
+    res = dict(conf=conf, tok=tok, lse=lse, zmax=zmax, z2nd=z2nd,
+               margin=conf - np.exp(z2nd - lse), neg_entropy=nent)
     if zt is not None:
         res["zt"] = zt
     return res

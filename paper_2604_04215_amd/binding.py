@@ -18,6 +18,7 @@ SEG_CAUSAL, SEG_EARLIER_BLOCKS, SEG_SAME_BLOCK = 0, 1, 2
 DLM_OK, DLM_ERR_INVALID_ARG, DLM_ERR_UNSUPPORTED, DLM_ERR_WORKSPACE, DLM_ERR_HIP = 0, -1, -2, -3, -4
 MASK_FULL, MASK_BLOCK_CAUSAL = 0, 1
 RULE_THRESHOLD, RULE_TOPK = 0, 1
+CONF_TOKEN_PROB, CONF_MARGIN, CONF_NEG_ENTROPY = 0, 1, 2
 WB_NONE, WB_BLOCK_WHEN_DONE, WB_COMMITTED_ROWS = 0, 1, 2
 
 EXPORTS = ["dlm_block_attn", "dlm_block_attn_workspace_bytes", "dlm_lmhead_confidence",
@@ -69,7 +70,7 @@ class LmheadArgs(C.Structure):
                 ("target", C.c_void_p), ("ztarget", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
                 ("sample", C.c_int32), ("sample_step", C.c_uint32), ("sample_stream", C.c_uint32),
-                ("sample_seed", C.c_uint64)]
+                ("sample_seed", C.c_uint64), ("conf_mode", C.c_int32)]
 
 
 class CommitArgs(C.Structure):
@@ -316,11 +317,11 @@ def block_attn_bwd_workspace_bytes(n_rows: int, Hq: int) -> int:
     return int(n_rows) * int(Hq) * 4
 
 
-def lmhead_workspace_bytes(M: int, V: int, sample: bool = False) -> int:
+def lmhead_workspace_bytes(M: int, V: int, sample: bool = False, conf_mode: int = CONF_TOKEN_PROB) -> int:
     a = LmheadArgs()
     a.struct_size = C.sizeof(LmheadArgs)
     a.M, a.V, a.Dh = int(M), int(V), 64
-    a.sample = int(bool(sample))
+    a.sample, a.conf_mode = int(bool(sample)), int(conf_mode)
     return int(lib().dlm_lmhead_workspace_bytes(C.byref(a)))
 
 
@@ -328,7 +329,7 @@ def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=
                       inv_temperature: float = 1.0, forbid_token: int = -1, out_scatter: bool = False,
                       lse=None, zmax=None, z2nd=None, target=None, ztarget=None, workspace=None,
                       sample_seed: Optional[int] = None, sample_step: int = 0, sample_stream: int = 0,
-                      stream=None) -> None:
+                      conf_mode: int = CONF_TOKEN_PROB, stream=None) -> None:
     """hidden bf16 [rows, Dh]; w bf16 [V, Dh]; conf fp32 / tok int32 outputs; workspace: a uint8 tensor.
     sample_seed: None = arg-max token; an integer = Gumbel-max sample with that seed."""
     import torch
@@ -352,6 +353,7 @@ def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=
     a.target, a.ztarget = _dev(target, torch.int32, "target"), _dev(ztarget, torch.float32, "ztarget")
     a.workspace = _dev(workspace, None, "workspace")
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    a.conf_mode = int(conf_mode)
     if sample_seed is not None:
         a.sample, a.sample_seed = 1, int(sample_seed) & 0xFFFFFFFFFFFFFFFF
         a.sample_step, a.sample_stream = int(sample_step) & 0xFFFFFFFF, int(sample_stream) & 0xFFFFFFFF

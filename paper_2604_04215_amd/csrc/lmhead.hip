@@ -42,6 +42,9 @@ struct LmParams {
     int sample;
     uint32_t seed_lo, seed_hi, step, stream;
     f32x4* part2;
+    // conf_mode: DLM_CONF_*.  For the negative entropy, slot 3 of the second partial carries
+    // U = sum_v exp(z_v - max) * (z_v - max) of the tile (entropy = log(sumexp) - U / sumexp).
+    int conf_mode;
 };
 
 struct Red {
@@ -121,6 +124,16 @@ __device__ __forceinline__ Smp smp_merge(const Smp a, const Smp b) {
     return r;
 }
 
+// U of the union of two partials a, b (each relative to its own maximum), relative to the joint maximum
+__device__ __forceinline__ float u_merge(const Red a, float ua, const Red b, float ub) {
+    constexpr float LOG2E = 1.4426950408889634f;
+    const float mx = fmaxf(a.m, b.m);
+    float r = 0.f;
+    if (a.m > -INFINITY) r += fast_exp2((a.m - mx) * LOG2E) * (ua + (a.m - mx) * a.s);
+    if (b.m > -INFINITY) r += fast_exp2((b.m - mx) * LOG2E) * (ub + (b.m - mx) * b.s);
+    return r;
+}
+
 constexpr int KC = 64;             // Dh elements per pipeline stage (128 B per row); Dh must be a multiple of it
 constexpr int LP = KC * 2 + 16;    // LDS row pitch in bytes: 16-byte reads of 16 consecutive rows hit distinct banks
 
@@ -150,7 +163,9 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
     constexpr int MB = 32 * THW * WH;
     constexpr float LOG2E = 1.4426950408889634f;
     f32x4* redbuf = reinterpret_cast<f32x4*>(smem);  // [WV][MB] of (max, sumexp, runner-up, argmax bits)
-    f32x4* redbuf2 = redbuf + WV * MB;               // [WV][MB] of the sampling partial (only when sampling)
+    f32x4* redbuf2 = redbuf + WV * MB;               // [WV][MB] of the second partial (sampling and / or entropy)
+    const bool ent = p.conf_mode == DLM_CONF_NEG_ENTROPY;
+    const bool second = p.sample || ent;
     // (the loop above ended with a barrier: the staging area is free)
 #pragma unroll
     for (int c = 0; c < THW; ++c) {
@@ -181,24 +196,41 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
                 }
             }
         }
+        float uent = 0.f;
         if (red.m > -INFINITY) {
             const float mb = red.m * LOG2E;
             float s = 0.f;
+            if (ent) {
 #pragma unroll
-            for (int a = 0; a < TVW; ++a)
+                for (int a = 0; a < TVW; ++a)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) s += fast_exp2(acc[a][c][i] * LOG2E - mb);
+                    for (int i = 0; i < 16; ++i) {
+                        const float z = acc[a][c][i];
+                        const float e = fast_exp2(z * LOG2E - mb);
+                        s += e;
+                        uent += (z > -INFINITY) ? e * (z - red.m) : 0.f;
+                    }
+            } else {
+#pragma unroll
+                for (int a = 0; a < TVW; ++a)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) s += fast_exp2(acc[a][c][i] * LOG2E - mb);
+            }
             red.s = s;
         }
-        red = red_merge(red, red_shfl_xor(red, 32));
+        {
+            const Red o = red_shfl_xor(red, 32);
+            if (ent) uent = u_merge(red, uent, o, shfl_xor(uent, 32));
+            red = red_merge(red, o);
+        }
         if (hi == 0) {
             f32x4 packed = {red.m, red.s, red.m2, __int_as_float(red.idx)};
             redbuf[wv * MB + col] = packed;
         }
+        Smp sm{-INFINITY, -INFINITY, 0x7fffffff};
         if (p.sample) {
             // acc now holds the scaled, masked logits; noise is keyed by the row's index in `hidden`
             const uint32_t rk = (r < M) ? (uint32_t)(p.row_idx ? p.row_idx[r] : r) : 0u;
-            Smp sm{-INFINITY, -INFINITY, 0x7fffffff};
 #pragma unroll
             for (int a = 0; a < TVW; ++a) {
 #pragma unroll
@@ -222,10 +254,10 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
             o.pz = shfl_xor(sm.pz, 32);
             o.idx = shfl_xor(sm.idx, 32);
             sm = smp_merge(sm, o);
-            if (hi == 0) {
-                f32x4 packed = {sm.pm, sm.pz, __int_as_float(sm.idx), 0.f};
-                redbuf2[wv * MB + col] = packed;
-            }
+        }
+        if (second && hi == 0) {
+            f32x4 packed = {sm.pm, sm.pz, __int_as_float(sm.idx), uent};
+            redbuf2[wv * MB + col] = packed;
         }
     }
     __syncthreads();
@@ -234,22 +266,25 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
         if (r >= M) continue;
         const f32x4 f = redbuf[col];
         Red red{f[0], f[1], f[2], __float_as_int(f[3])};
+        f32x4 g = {-INFINITY, -INFINITY, __int_as_float(0x7fffffff), 0.f};
+        if (second) g = redbuf2[col];
+        Smp sm{g[0], g[1], __float_as_int(g[2])};
+        float uent = g[3];
 #pragma unroll
         for (int k = 1; k < WV; ++k) {
             const f32x4 o = redbuf[k * MB + col];
-            red = red_merge(red, Red{o[0], o[1], o[2], __float_as_int(o[3])});
+            const Red ro{o[0], o[1], o[2], __float_as_int(o[3])};
+            if (second) {
+                const f32x4 o2 = redbuf2[k * MB + col];
+                sm = smp_merge(sm, Smp{o2[0], o2[1], __float_as_int(o2[2])});
+                if (ent) uent = u_merge(red, uent, ro, o2[3]);
+            }
+            red = red_merge(red, ro);
         }
         f32x4 out = {red.m, red.s, red.m2, __int_as_float(red.idx)};
         p.part[(int64_t)r * p.n_vt + vt] = out;
-        if (p.sample) {
-            const f32x4 g = redbuf2[col];
-            Smp sm{g[0], g[1], __float_as_int(g[2])};
-#pragma unroll
-            for (int k = 1; k < WV; ++k) {
-                const f32x4 o = redbuf2[k * MB + col];
-                sm = smp_merge(sm, Smp{o[0], o[1], __float_as_int(o[2])});
-            }
-            f32x4 out2 = {sm.pm, sm.pz, __int_as_float(sm.idx), 0.f};
+        if (second) {
+            f32x4 out2 = {sm.pm, sm.pz, __int_as_float(sm.idx), uent};
             p.part2[(int64_t)r * p.n_vt + vt] = out2;
         }
     }
@@ -717,58 +752,75 @@ __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
     int M = p.M;
     if (p.m_dev) M = min(M, max(*p.m_dev, 0));
     if (r >= M) return;
+    const bool ent = p.conf_mode == DLM_CONF_NEG_ENTROPY;
+    const bool second = p.sample || ent;
     const f32x4* row = p.part + (int64_t)r * p.n_vt;
+    const f32x4* row2 = p.part2 + (int64_t)r * p.n_vt;
     Red tot{-INFINITY, 0.f, -INFINITY, 0x7fffffff};
+    Smp sm{-INFINITY, -INFINITY, 0x7fffffff};
+    float uent = 0.f;
     for (int t0 = 0; t0 < p.n_vt; t0 += 1024) {
-        f32x4 v[4];
+        f32x4 v[4], g[4];
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             const int t = t0 + a * 256 + tid;
             v[a] = f32x4{-INFINITY, 0.f, -INFINITY, __int_as_float(0x7fffffff)};
-            if (t < p.n_vt) v[a] = row[t];
+            g[a] = f32x4{-INFINITY, -INFINITY, __int_as_float(0x7fffffff), 0.f};
+            if (t < p.n_vt) {
+                v[a] = row[t];
+                if (second) g[a] = row2[t];
+            }
         }
 #pragma unroll
-        for (int a = 0; a < 4; ++a) tot = red_merge(tot, Red{v[a][0], v[a][1], v[a][2], __float_as_int(v[a][3])});
+        for (int a = 0; a < 4; ++a) {
+            const Red o{v[a][0], v[a][1], v[a][2], __float_as_int(v[a][3])};
+            if (ent) uent = u_merge(tot, uent, o, g[a][3]);
+            tot = red_merge(tot, o);
+            if (p.sample) sm = smp_merge(sm, Smp{g[a][0], g[a][1], __float_as_int(g[a][2])});
+        }
     }
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) tot = red_merge(tot, red_shfl_xor(tot, off));
-    Smp sm{-INFINITY, -INFINITY, 0x7fffffff};
-    if (p.sample) {
-        const f32x4* row2 = p.part2 + (int64_t)r * p.n_vt;
-        for (int t = tid; t < p.n_vt; t += 256) {
-            const f32x4 g = row2[t];
-            sm = smp_merge(sm, Smp{g[0], g[1], __float_as_int(g[2])});
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            Smp o;
-            o.pm = shfl_xor(sm.pm, off);
-            o.pz = shfl_xor(sm.pz, off);
-            o.idx = shfl_xor(sm.idx, off);
-            sm = smp_merge(sm, o);
+    for (int off = 32; off >= 1; off >>= 1) {
+        const Red o = red_shfl_xor(tot, off);
+        if (ent) uent = u_merge(tot, uent, o, shfl_xor(uent, off));
+        tot = red_merge(tot, o);
+        if (p.sample) {
+            Smp so;
+            so.pm = shfl_xor(sm.pm, off);
+            so.pz = shfl_xor(sm.pz, off);
+            so.idx = shfl_xor(sm.idx, off);
+            sm = smp_merge(sm, so);
         }
     }
     if (lane == 0) {
         s_red[w] = f32x4{tot.m, tot.s, tot.m2, __int_as_float(tot.idx)};
-        s_smp[w] = f32x4{sm.pm, sm.pz, __int_as_float(sm.idx), 0.f};
+        s_smp[w] = f32x4{sm.pm, sm.pz, __int_as_float(sm.idx), uent};
     }
     __syncthreads();
     if (tid == 0) {
 #pragma unroll
         for (int k = 1; k < 4; ++k) {
             const f32x4 o = s_red[k], g = s_smp[k];
-            tot = red_merge(tot, Red{o[0], o[1], o[2], __float_as_int(o[3])});
+            const Red ro{o[0], o[1], o[2], __float_as_int(o[3])};
+            if (ent) uent = u_merge(tot, uent, ro, g[3]);
+            tot = red_merge(tot, ro);
             sm = smp_merge(sm, Smp{g[0], g[1], __float_as_int(g[2])});
         }
         const int64_t oidx = (p.out_scatter && p.row_idx) ? (int64_t)p.row_idx[r] : (int64_t)r;
-        if (p.sample) {
+        float conf;
+        if (p.conf_mode == DLM_CONF_MARGIN) {
+            // p(top-1) - p(top-2) = (1 - exp(z2nd - zmax)) / sum_v exp(z_v - zmax)
+            conf = (1.0f - __expf(tot.m2 - tot.m)) / tot.s;
+        } else if (ent) {
+            conf = uent / tot.s - logf(tot.s);      // sum_v p_v log p_v
+        } else if (p.sample) {
             // probability of the sampled token: exp(z_tok - lse) = exp(z_tok - zmax) / sum_v exp(z_v - zmax)
-            p.conf[oidx] = __expf(sm.pz - tot.m) / tot.s;
-            p.tok[oidx] = sm.idx;
+            conf = __expf(sm.pz - tot.m) / tot.s;
         } else {
-            p.conf[oidx] = 1.0f / tot.s;          // exp(zmax - lse) = 1 / sum_v exp(z_v - zmax)
-            p.tok[oidx] = tot.idx;
+            conf = 1.0f / tot.s;                    // exp(zmax - lse) = 1 / sum_v exp(z_v - zmax)
         }
+        p.conf[oidx] = conf;
+        p.tok[oidx] = p.sample ? sm.idx : tot.idx;
         if (p.lse) p.lse[oidx] = tot.m + logf(tot.s);
         if (p.zmax) p.zmax[oidx] = tot.m;
         if (p.z2nd) p.z2nd[oidx] = tot.m2;
@@ -847,6 +899,8 @@ static int validate_lm(const dlm_lmhead_args* a) {
     if (!(a->inv_temperature > 0.f) || a->inv_temperature > 3.0e38f) return fail(DLM_ERR_INVALID_ARG, "lmhead: inv_temperature must be positive and finite");
     if ((a->target == nullptr) != (a->ztarget == nullptr)) return fail(DLM_ERR_INVALID_ARG, "lmhead: target and ztarget go together");
     if (a->sample != 0 && a->sample != 1) return fail(DLM_ERR_INVALID_ARG, "lmhead: sample must be 0 or 1");
+    if (a->conf_mode < DLM_CONF_TOKEN_PROB || a->conf_mode > DLM_CONF_NEG_ENTROPY)
+        return fail(DLM_ERR_INVALID_ARG, "lmhead: unknown conf_mode %d", a->conf_mode);
     if (a->M == 0) return DLM_OK;
     if (!a->hidden || !a->w || !a->conf || !a->tok) return fail(DLM_ERR_INVALID_ARG, "lmhead: null hidden/w/conf/tok");
     if (!aligned16(a->hidden) || !aligned16(a->w)) return fail(DLM_ERR_UNSUPPORTED, "lmhead: hidden/w not 16-byte aligned");
@@ -862,7 +916,7 @@ using namespace dlm;
 extern "C" size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args* a) {
     if (!a || a->M <= 0 || a->V <= 0) return 0;
     const size_t n_vt = ((size_t)a->V + LM_MIN_TV - 1) / LM_MIN_TV;   // enough for every kernel shape
-    return n_vt * (size_t)a->M * sizeof(f32x4) * (a->sample ? 2 : 1);
+    return n_vt * (size_t)a->M * sizeof(f32x4) * ((a->sample || a->conf_mode == DLM_CONF_NEG_ENTROPY) ? 2 : 1);
 }
 
 extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
@@ -885,6 +939,7 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     p.part = (f32x4*)a->workspace;
     p.n_vt = (a->V + var.tv - 1) / var.tv;
     p.sample = a->sample;
+    p.conf_mode = a->conf_mode;
     p.seed_lo = (uint32_t)a->sample_seed; p.seed_hi = (uint32_t)(a->sample_seed >> 32);
     p.step = a->sample_step; p.stream = a->sample_stream;
     p.part2 = p.part + (size_t)p.n_vt * a->M;

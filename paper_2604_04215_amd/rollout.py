@@ -26,12 +26,15 @@ _MASKS = {"full": dlm.MASK_FULL, "block_causal": dlm.MASK_BLOCK_CAUSAL}
 
 class GpuRollout:
     def __init__(self, cfg, w: torch.Tensor, device: str = "cuda:0", record_steps: bool = False,
-                 sample_seed: Optional[int] = None, sample_stream: int = 0, inv_temperature: float = 1.0):
+                 sample_seed: Optional[int] = None, sample_stream: int = 0, inv_temperature: float = 1.0,
+                 confidence: str = "prob"):
         """sample_seed None: greedy (arg-max) tokens.  An integer: tokens are sampled from the softmax at
         inv_temperature; step s of block b draws with sample_step = (b << 16) | s, so no two steps of a
         rollout share noise, and rollouts of one prompt differ by sample_stream."""
         self.cfg, self.dev = cfg, torch.device(device)
         self.sample_seed, self.sample_stream, self.inv_temperature = sample_seed, sample_stream, inv_temperature
+        # which score the commit rule ranks: token probability, top-2 margin or negative entropy
+        self.conf_mode = {"prob": dlm.CONF_TOKEN_PROB, "margin": dlm.CONF_MARGIN, "neg_entropy": dlm.CONF_NEG_ENTROPY}[confidence]
         B, Lb, L = cfg.B, cfg.Lb, cfg.L
         dev = self.dev
         self.w = w
@@ -53,7 +56,7 @@ class GpuRollout:
         self.row_idx = torch.zeros(n, dtype=torch.int32, device=dev)
         self.m_dev = torch.zeros(1, dtype=torch.int32, device=dev)
         self.commit_step = torch.full((B, Lb), -1, dtype=torch.int16, device=dev) if record_steps else None
-        self.workspace = torch.empty(max(16, dlm.lmhead_workspace_bytes(n, cfg.V, sample=sample_seed is not None)), dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(max(16, dlm.lmhead_workspace_bytes(n, cfg.V, sample=sample_seed is not None, conf_mode=self.conf_mode)), dtype=torch.uint8, device=dev)
         self.total_committed = torch.zeros(1, dtype=torch.int64, device=dev)
         self.block = -1
         self.step_idx = 0
@@ -123,6 +126,7 @@ class GpuRollout:
                               z2nd=self.z2nd if diag else None, workspace=self.workspace,
                               inv_temperature=self.inv_temperature, sample_seed=self.sample_seed,
                               sample_step=(self.block << 16) | self.step_idx, sample_stream=self.sample_stream,
+                              conf_mode=self.conf_mode,
                               stream=st)
         dlm.unmask_commit(self.conf, self.tok, self.x, self.mask, self.n_commit, self.remaining,
                           x_pos0=P, rule=_RULES[cfg.rule], threshold=cfg.tau, force_top1=True, k=cfg.k,

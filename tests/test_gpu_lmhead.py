@@ -163,3 +163,55 @@ def test_full_vocabulary_sampled_rows():
     assert np.all((got["tok"] >= 0) & (got["tok"] < cfg.V - 1))
     assert np.all(got["z2nd"] <= got["zmax"]) and np.all(got["lse"] >= got["zmax"])
     assert np.allclose(got["conf"], np.exp(got["zmax"] - got["lse"]), atol=1e-5)
+
+
+@pytest.mark.parametrize("variant", [-1, 0, 3, 5, 7, 10, 16])
+@pytest.mark.parametrize("mode", ["margin", "neg_entropy"])
+def test_alternative_confidence_scores(mode, variant):
+    """conf = p(top-1) - p(top-2) or sum_v p_v log p_v instead of the token probability; every other output unchanged."""
+    M, Dh, V = 300, 192, 1100
+    h, w = rnd(920, (M, Dh)), rnd(921, (V, Dh), Dh ** -0.25)
+    ref = oracle.lmhead(h, w, forbid_token=V - 1, inv_temperature=0.8)
+    hd, wd = bf16_dev(h), bf16_dev(w)
+    cm = dlm.CONF_MARGIN if mode == "margin" else dlm.CONF_NEG_ENTROPY
+    conf = torch.full((M,), float("nan"), dtype=torch.float32, device=DEV)
+    lse = torch.full((M,), float("nan"), dtype=torch.float32, device=DEV)
+    tok = torch.full((M,), -7, dtype=torch.int32, device=DEV)
+    ws = torch.empty(dlm.lmhead_workspace_bytes(M, V, conf_mode=cm), dtype=torch.uint8, device=DEV)
+    dlm.set_option("lmhead_variant", variant)
+    try:
+        dlm.lmhead_confidence(hd, wd, conf, tok, forbid_token=V - 1, inv_temperature=0.8, lse=lse, workspace=ws, conf_mode=cm)
+        torch.cuda.synchronize()
+    finally:
+        dlm.set_option("lmhead_variant", -1)
+    got = conf.cpu().numpy().astype(np.float64)
+    tol = CONF_TOL if mode == "margin" else Z_TOL          # the entropy lives on the logits' scale
+    assert np.abs(got - ref[mode]).max() <= tol
+    clear = (ref["zmax"] - ref["z2nd"]) >= MARGIN
+    assert np.array_equal(tok.cpu().numpy()[clear], ref["tok"][clear])
+    assert np.abs(lse.cpu().numpy() - ref["lse"]).max() <= Z_TOL
+    if mode == "neg_entropy":
+        assert np.all(got <= 1e-4) and np.all(got >= -np.log(V) - 1e-3)
+
+
+def test_entropy_full_vocabulary_and_sampling_together():
+    """LLaDA-sized head: negative entropy on sampled rows; with sampling on, the score is that of the distribution
+    while the token is the drawn one."""
+    from oracle import sampling
+    cfg = synth.CONFIGS["c2"]
+    w = synth.w_vocab(cfg)
+    hid = synth.step_hidden(cfg, 0, 1).reshape(-1, cfg.Dh)
+    idx = np.sort(np.random.default_rng(5).permutation(hid.shape[0])[:70]).astype(np.int32)
+    M = len(idx)
+    conf = torch.zeros(M, dtype=torch.float32, device=DEV)
+    tok = torch.zeros(M, dtype=torch.int32, device=DEV)
+    ws = torch.empty(dlm.lmhead_workspace_bytes(M, cfg.V, sample=True, conf_mode=dlm.CONF_NEG_ENTROPY), dtype=torch.uint8, device=DEV)
+    dlm.lmhead_confidence(bf16_dev(hid), bf16_dev(w), conf, tok, M=M, row_idx=dev(idx), forbid_token=cfg.forbid_token,
+                          workspace=ws, conf_mode=dlm.CONF_NEG_ENTROPY, sample_seed=99, sample_step=4)
+    torch.cuda.synchronize()
+    pick = np.array([0, 13, 41, 69])
+    ref = oracle.lmhead(hid, w, row_idx=idx[pick], forbid_token=cfg.forbid_token)
+    smp = sampling.lmhead_sampled(hid, w, seed=99, step=4, row_idx=idx[pick], forbid_token=cfg.forbid_token)
+    assert np.abs(conf.cpu().numpy()[pick] - ref["neg_entropy"]).max() <= Z_TOL
+    clear = (smp["pmax"] - smp["p2nd"]) >= MARGIN
+    assert np.array_equal(tok.cpu().numpy()[pick][clear], smp["tok"][clear])

@@ -139,6 +139,16 @@ def test_sampled_lockstep_rollout(name, stream):
         assert (g0.x.cpu().numpy()[:, cfg.prompt:] != x[:, cfg.prompt:]).mean() > 0.3
 
 
+@pytest.mark.parametrize("name,confidence,tau", [("mini2", "margin", 0.4), ("mini2", "neg_entropy", -1.5),
+                                                 ("mini3", "neg_entropy", 0.0), ("mini4", "margin", 0.0)])
+def test_lockstep_rollout_other_confidence_scores(name, confidence, tau):
+    """The commit rule ranking the top-2 margin or the negative entropy instead of the token probability."""
+    cfg = synth.CONFIGS[name].replace(tau=tau)
+    o, g, stats = lockstep(cfg, confidence=confidence)
+    n_init = cfg.init_masked if cfg.init_masked is not None else cfg.Lb
+    assert stats["committed"] == cfg.B * (n_init + (cfg.n_blocks - 1) * cfg.Lb)
+
+
 @pytest.mark.parametrize("name", ["mini1", "mini2", "mini3", "mini4", "mini5a", "c1"])
 def test_lockstep_rollout(name):
     cfg = synth.CONFIGS[name]

@@ -124,3 +124,36 @@ def test_row_gather_and_target_logit():
     assert np.allclose(sub2["zt"] - sub2["lse"], np.log(sub2["conf"]), atol=1e-12)
     empty = oracle.lmhead(h, w, row_idx=np.zeros(0, np.int32))
     assert empty["conf"].shape == (0,)
+
+
+def test_margin_and_negative_entropy_scores():
+    import scipy.stats
+    M, Dh, V = 6, 16, 23
+    h, w = rnd(31, (M, Dh)), rnd(32, (V, Dh), 0.6)
+    r = oracle.lmhead(h, w, forbid_token=4)
+    z = f64(h) @ f64(w).T
+    z[:, 4] = -np.inf
+    p = np.exp(z - z.max(1, keepdims=True))
+    p /= p.sum(1, keepdims=True)
+    top2 = np.sort(p, axis=1)[:, -2:]
+    assert np.allclose(r["margin"], top2[:, 1] - top2[:, 0], atol=1e-13)
+    assert np.allclose(r["neg_entropy"], -scipy.stats.entropy(p, axis=1), atol=1e-12)     # library routine
+    # closed forms: uniform logits -> -log V (one token forbidden: -log(V - 1)), margin 0
+    h0 = np.zeros((2, Dh), np.uint16)
+    u = oracle.lmhead(h0, w)
+    assert np.allclose(u["neg_entropy"], -math.log(V), atol=1e-13) and np.allclose(u["margin"], 0, atol=1e-15)
+    u = oracle.lmhead(h0, w, forbid_token=0)
+    assert np.allclose(u["neg_entropy"], -math.log(V - 1), atol=1e-13)
+    # z = (a, b, 0, ..., 0): margin = (e^a - e^b) / Z, entropy from the three distinct probabilities
+    a, b, Vs = 3.0, 1.5, 40
+    wf = np.zeros((Vs, Dh), np.float32)
+    wf[7, 0], wf[20, 0] = a, b
+    s = oracle.lmhead(bits(np.eye(1, Dh, dtype=np.float32)), bits(wf))
+    Z = math.exp(a) + math.exp(b) + Vs - 2
+    pa, pb, p0 = math.exp(a) / Z, math.exp(b) / Z, 1 / Z
+    assert abs(s["margin"][0] - (pa - pb)) < 1e-14
+    assert abs(s["neg_entropy"][0] - (pa * math.log(pa) + pb * math.log(pb) + (Vs - 2) * p0 * math.log(p0))) < 1e-13
+    # a sharper distribution (lower temperature) has higher negative entropy
+    cold = oracle.lmhead(h, w, inv_temperature=3.0)
+    warm = oracle.lmhead(h, w, inv_temperature=0.3)
+    assert np.all(cold["neg_entropy"] > warm["neg_entropy"]) and np.all(cold["neg_entropy"] <= 1e-15)
