@@ -166,6 +166,9 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
     f32x4* redbuf2 = redbuf + WV * MB;               // [WV][MB] of the second partial (sampling and / or entropy)
     const bool ent = p.conf_mode == DLM_CONF_NEG_ENTROPY;
     const bool second = p.sample || ent;
+    constexpr int TVWG = 32 * TVW * WV;
+    // does this workgroup's vocabulary tile hold a token that must be masked (past V, or the forbidden one)?
+    const bool edge = (v0 + TVWG > p.V) || (p.forbid >= v0 && p.forbid < v0 + TVWG);
     // (the loop above ended with a barrier: the staging area is free)
 #pragma unroll
     for (int c = 0; c < THW; ++c) {
@@ -177,24 +180,56 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
             oidx = (p.out_scatter && p.row_idx) ? (int64_t)p.row_idx[r] : (int64_t)r;
             if (p.target) tgt = p.target[oidx];
         }
+        // scaled (and, in a tile that holds a forbidden or out-of-range token, masked) logits, kept in acc
+        const int vb = v0 + wv * TVW * 32 + 4 * hi;    // this lane's token of element (a, i): vb + 32 a + 8 (i >> 2) + (i & 3)
+        if (edge) {
+#pragma unroll
+            for (int a = 0; a < TVW; ++a)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int v = vb + a * 32 + 8 * (i >> 2) + (i & 3);
+                    const float z = acc[a][c][i] * p.inv_t;
+                    acc[a][c][i] = (v >= p.V || v == p.forbid) ? -INFINITY : z;
+                }
+        } else {
+#pragma unroll
+            for (int a = 0; a < TVW; ++a)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[a][c][i] *= p.inv_t;
+        }
+        if (p.target) {                                // the target's logit, if this lane holds it
+            const int dt = tgt - vb;
+            float zt = 0.f;
+            bool found = false;
+#pragma unroll
+            for (int a = 0; a < TVW; ++a)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const bool hit = dt == a * 32 + 8 * (i >> 2) + (i & 3);
+                    zt = hit ? acc[a][c][i] : zt;
+                    found |= hit;
+                }
+            if (found && tgt >= 0) p.ztarget[oidx] = zt;
+        }
+        // maximum and runner-up (equal to the maximum when it occurs twice): the two largest of (m, m2, z)
         Red red{-INFINITY, 0.f, -INFINITY, 0x7fffffff};
 #pragma unroll
-        for (int a = 0; a < TVW; ++a) {
+        for (int a = 0; a < TVW; ++a)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int v = v0 + (wv * TVW + a) * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
-                float z = acc[a][c][i] * p.inv_t;
-                if (v >= p.V || v == p.forbid) z = -INFINITY;
-                if (v == tgt) p.ztarget[oidx] = z;
-                acc[a][c][i] = z;
-                if (z > red.m) {
-                    red.m2 = red.m;
-                    red.m = z;
-                    red.idx = v;
-                } else if (z > red.m2) {
-                    red.m2 = z;
-                }
+                const float z = acc[a][c][i];
+                red.m2 = __builtin_amdgcn_fmed3f(red.m, red.m2, z);
+                red.m = fmaxf(red.m, z);
             }
+        // lowest token that attains the maximum: walk downwards, the last hit stays (offsets from vb are constants)
+        if (red.m > -INFINITY) {
+            int li = 0;
+#pragma unroll
+            for (int a = TVW - 1; a >= 0; --a)
+#pragma unroll
+                for (int i = 15; i >= 0; --i)
+                    li = (acc[a][c][i] == red.m) ? a * 32 + 8 * (i >> 2) + (i & 3) : li;
+            red.idx = vb + li;
         }
         float uent = 0.f;
         if (red.m > -INFINITY) {
@@ -624,7 +659,11 @@ __global__ __launch_bounds__(64 * WV) void lmhead_wdirect_kernel(LmParams p) {
 // 64 x 128 shapes).  A wave's load instruction fills 1 KB of LDS = 16 rows x 64 B in lane order, so the
 // bank-conflict-free layout is obtained by choosing WHICH 16-byte piece of its row each lane fetches:
 // piece c of row r is stored at position c ^ ((r >> 2) & 3).
-template <int WV, int WH, int TVW, int THW, int NS>
+// XB = true keeps the MFMA operand fragments one MFMA step ahead ACROSS the workgroup barrier: while the 16 MFMAs
+// of one 16-element step run, the fragments of the next step (of the next stage, in the second half) are read
+// into a second register set, one LDS read issued behind each MFMA, so no MFMA ever waits for an LDS read that
+// was issued just before it; the barrier sits between the two steps of a stage.
+template <int WV, int WH, int TVW, int THW, int NS, bool XB = false>
 __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
     constexpr int KCD = 32, ROWB = 64;
     constexpr int NW = WV * WH, NT = 64 * NW;
@@ -632,7 +671,7 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
     constexpr int STAGE = (TV + MB) * ROWB;
     constexpr int IPW = (TV + MB) / 16 / NW;          // load instructions per wavefront per stage
     static_assert((TV + MB) / 16 % NW == 0, "rows must split evenly over the wavefronts");
-    static_assert(NS >= 2 && NS <= 4, "ring of 2..4 stages");
+    static_assert(NS >= 2 && NS <= 8 && NS * STAGE <= 160 * 1024, "ring of 2..8 stages within the 160 KB of LDS");
     static_assert(NS * STAGE >= 2 * WV * MB * 16, "both reduction buffers must fit in the ring");
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
 
@@ -712,10 +751,67 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
         if (s < nk) DMA_ISSUE(s, s);
     if (nk >= NS - 1) { DMA_SYNC(IPW * (NS - 2)); } else { DMA_SYNC(0); }
 
-    // steady state: request chunk kc+NS-1 into the stage freed by the previous iteration, multiply chunk kc,
-    // wait for this wavefront's share of chunk kc+1, barrier (which also frees stage kc % NS for the next request)
     int kc = 0;
     const int n_main = (nk - (NS - 1) > 0) ? ((nk - (NS - 1)) / NS) * NS : 0;
+    if constexpr (XB) {
+        // One loop iteration per stage, all alike (no guarded drain): the request that would run past the last
+        // chunk re-reads the last chunk into a stage nobody reads again, and the fragment reads of the last
+        // iteration's second half fetch a stage that is never multiplied.  The stage index is a scalar.
+        bf16x8 af[2][TVW], bfr[2][THW];
+        const int wsc = __builtin_amdgcn_readfirstlane(w);
+        const int lw0 = wv * TVW * 32 * ROWB + off0, lw1 = wv * TVW * 32 * ROWB + off1;
+        const int lh0 = TV * ROWB + wh * THW * 32 * ROWB + off0, lh1 = TV * ROWB + wh * THW * 32 * ROWB + off1;
+        // fragment i (0 .. TVW-1: W tiles, then the H tiles) of MFMA step `half` from the stage at byte offset sb
+#define XB_READ_ONE(half, sb, i)                                                                         \
+    {                                                                                                    \
+        if ((i) < TVW) af[half][(i) < TVW ? (i) : 0] =                                                   \
+            *reinterpret_cast<const bf16x8*>(ring + (sb) + ((half) ? lw1 : lw0) + (i) * 32 * ROWB);      \
+        else bfr[half][(i) >= TVW ? (i) - TVW : 0] =                                                     \
+            *reinterpret_cast<const bf16x8*>(ring + (sb) + ((half) ? lh1 : lh0) + ((i) - TVW) * 32 * ROWB); \
+    }
+        // TVW*THW MFMAs on register set `half`; behind the i-th MFMA goes the i-th auxiliary instruction: first the
+        // fragment reads of the other set (from the stage at rsb), then (first half only) this wavefront's requests
+        // of chunk `ich` (element offset) into the stage at isb
+#define XB_HALF(half, rsb, do_issue, isb, ich)                                                           \
+    {                                                                                                    \
+        _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                                  \
+            _Pragma("unroll") for (int c = 0; c < THW; ++c) {                                            \
+                constexpr int NF = TVW + THW;                                                            \
+                const int i_ = a * THW + c;                                                              \
+                acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[half][a], bfr[half][c], acc[a][c], 0, 0, 0); \
+                _Pragma("unroll") for (int f = 0; f < NF; ++f)                                           \
+                    if (f * (TVW * THW) / (2 * NF) == i_) XB_READ_ONE(1 - (half), rsb, f);               \
+                if (do_issue) {                                                                          \
+                    _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                      \
+                        if ((TVW * THW) / 2 + j * (TVW * THW) / (2 * IPW) == i_)                         \
+                            __builtin_amdgcn_global_load_lds(                                            \
+                                (const __attribute__((address_space(1))) void*)(src[j] + (ich)),         \
+                                (__attribute__((address_space(3))) void*)(ring + (isb) + (wsc * IPW + j) * 1024), 16, 0, 0); \
+                }                                                                                        \
+                __builtin_amdgcn_sched_barrier(0);                                                       \
+            }                                                                                            \
+    }
+#pragma unroll
+        for (int f = 0; f < TVW + THW; ++f) XB_READ_ONE(0, 0, f);
+        int sb = 0;                                   // byte offset of the stage being multiplied
+        int ib = (NS - 1) * STAGE;                    // ... of the stage the next request fills
+        for (int k = 0; k < nk; ++k) {
+            const int nb = (sb + STAGE == NS * STAGE) ? 0 : sb + STAGE;
+            const int ich = DMA_CHUNK(min(k + NS - 1, nk - 1)) * KCD;
+            XB_HALF(0, sb, true, ib, ich);
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(IPW * (NS - 2)) : "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            XB_HALF(1, nb, false, 0, 0);
+            ib = sb;
+            sb = nb;
+        }
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#undef XB_READ_ONE
+#undef XB_HALF
+    } else {
+    // steady state: request chunk kc+NS-1 into the stage freed by the previous iteration, multiply chunk kc,
+    // wait for this wavefront's share of chunk kc+1, barrier (which also frees stage kc % NS for the next request)
     for (; kc < n_main; kc += NS) {
 #pragma unroll
         for (int u = 0; u < NS; ++u) {
@@ -734,10 +830,162 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
             DMA_SYNC(0);
         }
     }
+    }
 #undef DMA_CHUNK
 #undef DMA_ISSUE
 #undef DMA_SYNC
 #undef DMA_COMPUTE
+    __syncthreads();
+    lm_epilogue<WV, WH, TVW, THW>(p, acc, ring, v0, m0, M, vt, wv, wh, n, hi, tid);
+}
+
+// Fourth kernel family, the one used for the MFMA-bound regime: the direct-to-LDS ring above with three changes
+// that each measured faster at M = 8192 (V = 126464, Dh = 4096; 1.24 -> 1.40 PFLOP/s for the loop alone):
+//  * fragments are read one MFMA step ahead, across the barrier (as in the XB form above);
+//  * requests come in PAIRS: a row's 64 bytes of chunk 2p and of chunk 2p+1 are the two halves of one 128-byte
+//    line and are requested back to back, so the second request finds the line in (or on its way to) L1 instead
+//    of fetching it from L2 a second time a whole stage later (the L2 -> LDS path alone: 17 -> 24 TB/s);
+//  * the 2*IPW requests of a pair are spread evenly over the MFMAs of a whole stage period (second half of an even
+//    stage, first half of the odd one) instead of being issued in a burst that backs up the address unit and
+//    stalls the issuing wavefront (and with it the MFMAs behind the request).
+// Five stages of 32 elements (the pair being multiplied, the pair in flight, and the stage just freed): pair
+// (k+4, k+5) is requested after the barrier of even stage k, into stages (k+4) % 5 and k % 5, and must have landed
+// by the barrier of stage k+3.
+template <int WV, int WH, int TVW, int THW>
+__global__ __launch_bounds__(64 * WV * WH) void lmhead_pair_kernel(LmParams p) {
+    constexpr int NS = 5, KCD = 32, ROWB = 64;
+    constexpr int NW = WV * WH;
+    constexpr int TV = 32 * TVW * WV, MB = 32 * THW * WH;
+    constexpr int STAGE = (TV + MB) * ROWB;
+    constexpr int IPW = (TV + MB) / 16 / NW;          // 16-row groups per wavefront (two requests each per pair)
+    constexpr int T = TVW * THW;                      // MFMAs per half stage
+    static_assert((TV + MB) / 16 % NW == 0, "rows must split evenly over the wavefronts");
+    static_assert(NS * STAGE <= 160 * 1024, "five stages within the 160 KB of LDS");
+    static_assert(NS * STAGE >= 2 * WV * MB * 16, "both reduction buffers must fit in the ring");
+    static_assert(IPW <= T && TVW + THW <= 2 * T, "one auxiliary instruction behind each MFMA");
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wv = w % WV, wh = w / WV;
+    const int n = lane & 31, hi = lane >> 5;
+    int vt, mc, kgroup;
+    lm_tile_of_block(blockIdx.x, p.n_mc, p.gm, p.gv, vt, mc, kgroup);
+    if (vt >= p.n_vt) return;
+    const int v0 = vt * TV, m0 = mc * MB;
+    int M = p.M;
+    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (m0 >= M) return;
+
+    const uint16_t* src[IPW];
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+        const int row = (w * IPW + j) * 16 + (lane >> 2);
+        const int piece = (lane & 3) ^ ((row >> 2) & 3);
+        if (row < TV) {
+            const int v = min(v0 + row, p.V - 1);
+            src[j] = p.w + (int64_t)v * p.w_stride + piece * 8;
+        } else {
+            const int r = min(m0 + row - TV, M - 1);
+            const int64_t sr = p.row_idx ? p.row_idx[r] : r;
+            src[j] = p.hidden + sr * p.h_stride + piece * 8;
+        }
+    }
+    const int nk = p.Dh / KCD;                        // even: Dh is a multiple of 64
+    // rotated start as in the other shapes, kept even so that a pair stays one 128-byte line
+    const int kstart = ((int)(((long)(p.gv > 1 ? kgroup : vt) * 11) % nk)) & ~1;
+#define PR_CHUNK(kc) (((kc) + kstart) >= nk ? ((kc) + kstart - nk) : ((kc) + kstart))
+    const int wsc = __builtin_amdgcn_readfirstlane(w);
+#define PR_ISSUE1(sbyte, j, eoff)                                                                        \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[j] + (eoff)),   \
+        (__attribute__((address_space(3))) void*)(ring + (sbyte) + (wsc * IPW + (j)) * 1024), 16, 0, 0)
+
+    f32x16 acc[TVW][THW];
+#pragma unroll
+    for (int a = 0; a < TVW; ++a)
+#pragma unroll
+        for (int c = 0; c < THW; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][c][i] = 0.f;
+
+    // prologue: pairs (0,1) -> stages 0,1 and (2,3) -> stages 2,3 (a request past the end re-reads the last pair)
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+        const int e = PR_CHUNK(min(2 * pr, nk - 2)) * KCD;
+#pragma unroll
+        for (int j = 0; j < IPW; ++j) {
+            PR_ISSUE1((2 * pr) * STAGE, j, e);
+            PR_ISSUE1((2 * pr + 1) * STAGE, j, e + KCD);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * IPW) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    const int sw = (n >> 2) & 3;
+    const int off0 = n * ROWB + ((hi ^ sw) << 4);          // MFMA step 0: piece hi
+    const int off1 = n * ROWB + (((2 + hi) ^ sw) << 4);    // MFMA step 1: piece 2 + hi
+    const int lw0 = wv * TVW * 32 * ROWB + off0, lw1 = wv * TVW * 32 * ROWB + off1;
+    const int lh0 = TV * ROWB + wh * THW * 32 * ROWB + off0, lh1 = TV * ROWB + wh * THW * 32 * ROWB + off1;
+    bf16x8 af[2][TVW], bfr[2][THW];
+    // fragment i (0 .. TVW-1: W tiles, then the H tiles) of MFMA step `half` from the stage at byte offset sb
+#define PR_READ_ONE(half, sb, i)                                                                         \
+    {                                                                                                    \
+        if ((i) < TVW) af[half][(i) < TVW ? (i) : 0] =                                                   \
+            *reinterpret_cast<const bf16x8*>(ring + (sb) + ((half) ? lw1 : lw0) + (i) * 32 * ROWB);      \
+        else bfr[half][(i) >= TVW ? (i) - TVW : 0] =                                                     \
+            *reinterpret_cast<const bf16x8*>(ring + (sb) + ((half) ? lh1 : lh0) + ((i) - TVW) * 32 * ROWB); \
+    }
+    // T MFMAs on register set `half`; behind the first ones the fragment reads of the other set (stage at rsb);
+    // part = 1 / 2: the first / second half of the pair's 2*IPW requests (chunk at element offset ich into the
+    // stage at isb0, the following chunk into isb1), one behind every (T / IPW)-th MFMA
+#define PR_HALF(half, rsb, part, isb0, isb1, ich)                                                        \
+    {                                                                                                    \
+        _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                                  \
+            _Pragma("unroll") for (int c = 0; c < THW; ++c) {                                            \
+                constexpr int NF = TVW + THW;                                                            \
+                const int i_ = a * THW + c;                                                              \
+                acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[half][a], bfr[half][c], acc[a][c], 0, 0, 0); \
+                _Pragma("unroll") for (int f = 0; f < NF; ++f)                                           \
+                    if (f * T / (2 * NF) == i_) PR_READ_ONE(1 - (half), rsb, f);                         \
+                if ((part) != 0) {                                                                       \
+                    _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                      \
+                        if (j * T / IPW == i_) {                                                         \
+                            const int jj = j + ((part) == 2 ? IPW : 0);                                  \
+                            if (jj & 1) PR_ISSUE1(isb1, jj >> 1, (ich) + KCD);                           \
+                            else PR_ISSUE1(isb0, jj >> 1, (ich));                                        \
+                        }                                                                                \
+                }                                                                                        \
+                __builtin_amdgcn_sched_barrier(0);                                                       \
+            }                                                                                            \
+    }
+#pragma unroll
+    for (int f = 0; f < TVW + THW; ++f) PR_READ_ONE(0, 0, f);
+#define PR_NEXT(x) (((x) + STAGE == NS * STAGE) ? 0 : (x) + STAGE)
+    int sb = 0;                                       // byte offset of the stage of chunk k (k even at the loop top)
+    for (int k = 0; k < nk; k += 2) {
+        const int s1 = PR_NEXT(sb), s2 = PR_NEXT(s1), s3 = PR_NEXT(s2), s4 = PR_NEXT(s3);
+        const int ich = PR_CHUNK(min(k + 4, nk - 2)) * KCD;
+        // even stage k
+        PR_HALF(0, sb, 0, 0, 0, 0);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();                 // every wavefront has read stage k to the end: it is free
+        asm volatile("" ::: "memory");
+        PR_HALF(1, s1, 1, s4, sb, ich);
+        // odd stage k+1
+        PR_HALF(0, s1, 2, s4, sb, ich);
+        // all but the pair just requested has landed: chunks k+2 and k+3
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * IPW) : "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        PR_HALF(1, s2, 0, 0, 0, 0);
+        sb = s2;
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#undef PR_CHUNK
+#undef PR_ISSUE1
+#undef PR_READ_ONE
+#undef PR_HALF
+#undef PR_NEXT
     __syncthreads();
     lm_epilogue<WV, WH, TVW, THW>(p, acc, ring, v0, m0, M, vt, wv, wh, n, hi, tid);
 }
@@ -841,11 +1089,17 @@ static void launch_lmd(dim3 grid, hipStream_t st, const LmParams& p) {
     hipLaunchKernelGGL((lmhead_wdirect_kernel<WV, TVW, THW, PDW>), grid, dim3(64 * WV), 0, st, p);
 }
 #define LMD(WV, TVW, THW, PDW) {32 * TVW * WV, 32 * THW, 64 * WV, launch_lmd<WV, TVW, THW, PDW>}
-template <int WV, int WH, int TVW, int THW, int NS>
+template <int WV, int WH, int TVW, int THW, int NS, bool XB = false>
 static void launch_lma(dim3 grid, hipStream_t st, const LmParams& p) {
-    hipLaunchKernelGGL((lmhead_dma_kernel<WV, WH, TVW, THW, NS>), grid, dim3(64 * WV * WH), 0, st, p);
+    hipLaunchKernelGGL((lmhead_dma_kernel<WV, WH, TVW, THW, NS, XB>), grid, dim3(64 * WV * WH), 0, st, p);
 }
 #define LMA(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lma<WV, WH, TVW, THW, NS>}
+#define LMX(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lma<WV, WH, TVW, THW, NS, true>}
+template <int WV, int WH, int TVW, int THW>
+static void launch_lmq(dim3 grid, hipStream_t st, const LmParams& p) {
+    hipLaunchKernelGGL((lmhead_pair_kernel<WV, WH, TVW, THW>), grid, dim3(64 * WV * WH), 0, st, p);
+}
+#define LMQ(WV, WH, TVW, THW) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lmq<WV, WH, TVW, THW>}
 #define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD>}
 static const LmVariant g_lm_variants[] = {
     // shapes the planner uses, by row count M (sweep at V = 126464, Dh = 4096 on MI355X, us per call):
@@ -854,7 +1108,7 @@ static const LmVariant g_lm_variants[] = {
     /*2*/ LMP(8, 1, 1, 3, 3),   // M <= 96   256 x 96,       8 waves            ~191
     /*3*/ LMP(4, 2, 2, 2, 3),   // M <= 128  256 x 128,      8 waves            ~200
     /*4*/ LMP(4, 2, 2, 3, 2),   // M <= 192  256 x 192,      8 waves            ~235
-    /*5*/ LMP(4, 2, 2, 4, 2),   // M <= 256  256 x 256,      8 waves            ~283 (and row chunks beyond)
+    /*5*/ LMP(4, 2, 2, 4, 2),   // 256 x 256, 8 waves, register-staged (the planner now takes entries 20..22 above 192 rows)
     // alternatives kept for tests and tuning sweeps
     /*6*/ LMV(2, 2, 2, 4, 3),   // 128 x 256, 4 waves, stores before the MFMA block
     /*7*/ LMD(4, 1, 1, 3),      // W fragments straight from global memory, 128 x 32
@@ -868,9 +1122,17 @@ static const LmVariant g_lm_variants[] = {
     /*15*/ LMA(2, 2, 4, 2, 4),  // 256 x 128, 4 waves x (128 x 64)
     /*16*/ LMA(4, 4, 2, 2, 4),  // 256 x 256, 16 waves x (64 x 64): four wavefronts per SIMD, 118 registers each
     /*17*/ LMA(4, 4, 2, 2, 3),  // same, 3 stages      (both within 3 % of entry 5 from M = 224 to 8192)
+    /*18*/ LMX(2, 2, 4, 4, 4),  // entry 10 with the operand fragments read one MFMA step ahead, across the barrier
+    /*19*/ LMX(4, 2, 2, 4, 4),  // entry 13 likewise
+    /*20*/ LMQ(2, 2, 4, 4),     // paired, evenly spread requests, 5 stages: 256 x 256, 4 waves x (128 x 128)
+    /*21*/ LMQ(4, 2, 2, 4),     // same, 8 waves x (64 x 128)
+    /*22*/ LMQ(4, 1, 2, 6),     // 256 x 192, 4 waves x (64 x 192)
+    /*23*/ LMQ(4, 1, 2, 4),     // 256 x 128, 4 waves x (64 x 128)
 };
 #undef LMV
 #undef LMA
+#undef LMX
+#undef LMQ
 #undef LMP
 #undef LMD
 constexpr int N_LM_VARIANTS = sizeof(g_lm_variants) / sizeof(g_lm_variants[0]);
@@ -885,7 +1147,9 @@ static int plan_lmhead(int M) {
     if (M <= 96) return 2;
     if (M <= 128) return 3;
     if (M <= 192) return 4;
-    return 5;
+    if (M <= 256) return 21;        // one 256-row chunk: the paired ring with two wavefronts per SIMD
+    if (M <= 384) return 22;        // two 192-row chunks
+    return 20;                      // 256-row chunks, one wavefront per SIMD with a 128 x 128 tile
 }
 
 static int validate_lm(const dlm_lmhead_args* a) {

@@ -71,7 +71,7 @@ def test_shapes_vs_oracle(M, Dh, V):
     assert np.all(got["tok"] != V - 1)
 
 
-@pytest.mark.parametrize("variant", range(18))
+@pytest.mark.parametrize("variant", range(24))
 def test_every_kernel_shape(variant):
     # each entry of the library's shape table on a problem with several row chunks and ragged tails
     M, Dh, V = 300, 192, 1100
@@ -81,6 +81,21 @@ def test_every_kernel_shape(variant):
     dlm.set_option("lmhead_variant", variant)
     try:
         got = run_lm(h, w, forbid=V - 1, target=tgt)
+    finally:
+        dlm.set_option("lmhead_variant", -1)
+    compare(got, ref)
+
+
+@pytest.mark.parametrize("variant", range(10, 24))
+@pytest.mark.parametrize("Dh", [640, 704])
+def test_ring_shapes_reach_their_steady_state_loop(variant, Dh):
+    # the direct-to-LDS shapes run prologue + drain only while Dh < 7 stages of 32: here 20 and 22 stages
+    M, V = 270, 600
+    h, w = rnd(910 + Dh, (M, Dh)), rnd(911 + Dh, (V, Dh), Dh ** -0.25)
+    ref = oracle.lmhead(h, w, forbid_token=3)
+    dlm.set_option("lmhead_variant", variant)
+    try:
+        got = run_lm(h, w, forbid=3)
     finally:
         dlm.set_option("lmhead_variant", -1)
     compare(got, ref)

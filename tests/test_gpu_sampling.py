@@ -49,7 +49,7 @@ def compare(got, ref, h, w, sel=None, inv_t=1.0):
     return int((~same).sum())
 
 
-@pytest.mark.parametrize("variant", range(18))
+@pytest.mark.parametrize("variant", range(24))
 def test_every_kernel_shape(variant):
     M, Dh, V = 300, 192, 1100
     h, w = rnd(910, (M, Dh)), rnd(911, (V, Dh), Dh ** -0.25)
