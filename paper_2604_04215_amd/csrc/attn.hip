@@ -194,6 +194,19 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     // PF tiles of K/V are in flight in registers per wave group; addresses are clamped so that the loads
     // are unconditional (the load-counter waits stay exact) and rows past the end are zeroed when staged.
     u32x4 kreg[PF][NLD], vreg[PF][NLD];
+    // Full tiles are addressed as (wave-uniform tile base) + (this thread's element offset inside a tile): no
+    // 64-bit per-thread arithmetic per tile.  Needs every segment that is present to have the same row stride
+    // (views of one cache tensor, the usual case) and 32 rows of it to fit 32 bits.
+    const int64_t st_c = p.seg[0].len ? st0 : (p.seg[1].len ? st1 : st2);
+    const bool fast_addr = st_c >= 0 && st_c < (1 << 25) && (!p.seg[0].len || st0 == st_c) &&
+                           (!p.seg[1].len || st1 == st_c) && (!p.seg[2].len || st2 == st_c);
+    uint32_t toff[NLD];
+#pragma unroll
+    for (int q = 0; q < NLD; ++q) {
+        const int cidx = tl + q * (64 * NWR);
+        const int row = cidx / C8, c = cidx - row * C8;
+        toff[q] = (uint32_t)(row * (int)st_c + c * 8);
+    }
     // segment of tile t (t < T), its index inside the segment, and the segment's extent
 #define ATTN_TILE(t, sg, lt, slen)                                                                       \
     const int sg = ((t) < T0) ? 0 : (((t) < T0 + T1) ? 1 : 2);                                           \
@@ -206,13 +219,23 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
         const uint16_t* kb = (sg_ == 0) ? kb0 : ((sg_ == 1) ? kb1 : kb2);                                \
         const uint16_t* vb = (sg_ == 0) ? vb0 : ((sg_ == 1) ? vb1 : vb2);                                \
         const int64_t stt = (sg_ == 0) ? st0 : ((sg_ == 1) ? st1 : st2);                                 \
-        _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
-            const int cidx = tl + q * (64 * NWR);                                                        \
-            const int row = cidx / C8, c = cidx - row * C8;                                              \
-            const int loc = min(lt_ * 32 + row, slen_ - 1);                                              \
-            const int64_t off = loc * stt + c * 8;                                                       \
-            kreg[slot][q] = *reinterpret_cast<const u32x4*>(kb + off);                                   \
-            vreg[slot][q] = *reinterpret_cast<const u32x4*>(vb + off);                                   \
+        if (fast_addr && lt_ * 32 + 32 <= slen_) {                                                       \
+            /* a full tile: wave-uniform tile base + this thread's fixed 32-bit offset */                \
+            const uint16_t* kt = kb + (int64_t)(lt_ * 32) * stt;                                         \
+            const uint16_t* vt = vb + (int64_t)(lt_ * 32) * stt;                                         \
+            _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                            \
+                kreg[slot][q] = *reinterpret_cast<const u32x4*>(kt + toff[q]);                           \
+                vreg[slot][q] = *reinterpret_cast<const u32x4*>(vt + toff[q]);                           \
+            }                                                                                            \
+        } else {                                                                                         \
+            _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                            \
+                const int cidx = tl + q * (64 * NWR);                                                    \
+                const int row = cidx / C8, c = cidx - row * C8;                                          \
+                const int loc = min(lt_ * 32 + row, slen_ - 1);                                          \
+                const int64_t off = loc * stt + c * 8;                                                   \
+                kreg[slot][q] = *reinterpret_cast<const u32x4*>(kb + off);                               \
+                vreg[slot][q] = *reinterpret_cast<const u32x4*>(vb + off);                               \
+            }                                                                                            \
         }                                                                                                \
     }
 // Key-split wave groups are single wavefronts with private LDS tiles: LDS operations of one wavefront are
@@ -244,13 +267,22 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
         (void)sg_;                                                                                       \
         unsigned char* Kd = smem + (buf) * TILE_BYTES;                                                   \
         unsigned char* Vd = Kd + 32 * KP;                                                                \
-        _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
-            const int cidx = tl + q * (64 * NWR);                                                        \
-            const int row = cidx / C8, c = cidx - row * C8;                                              \
-            const bool live = ((t) < T) && (lt_ * 32 + row < slen_);                                     \
-            const u32x4 z = {0, 0, 0, 0};                                                                \
-            *reinterpret_cast<u32x4*>(Kd + row * KP + c * 16) = live ? kreg[slot][q] : z;                \
-            *reinterpret_cast<u32x4*>(Vd + row * VP + c * 16) = live ? vreg[slot][q] : z;                \
+        if ((t) < T && lt_ * 32 + 32 <= slen_) {   /* a full tile: every row is live */                  \
+            _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                            \
+                const int cidx = tl + q * (64 * NWR);                                                    \
+                const int row = cidx / C8, c = cidx - row * C8;                                          \
+                *reinterpret_cast<u32x4*>(Kd + row * KP + c * 16) = kreg[slot][q];                       \
+                *reinterpret_cast<u32x4*>(Vd + row * VP + c * 16) = vreg[slot][q];                       \
+            }                                                                                            \
+        } else {                                                                                         \
+            _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                            \
+                const int cidx = tl + q * (64 * NWR);                                                    \
+                const int row = cidx / C8, c = cidx - row * C8;                                          \
+                const bool live = ((t) < T) && (lt_ * 32 + row < slen_);                                 \
+                const u32x4 z = {0, 0, 0, 0};                                                            \
+                *reinterpret_cast<u32x4*>(Kd + row * KP + c * 16) = live ? kreg[slot][q] : z;            \
+                *reinterpret_cast<u32x4*>(Vd + row * VP + c * 16) = live ? vreg[slot][q] : z;            \
+            }                                                                                            \
         }                                                                                                \
     }
 
@@ -295,8 +327,11 @@ _Pragma("unroll") \
                     if (off0 + (unsigned)(8 * (i >> 2) + (i & 3)) >= span) S[rt][i] = -INFINITY; \
             } \
 _Pragma("unroll") \
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[rt][i]); \
-            mx = fmaxf(mx, shfl_xor(mx, 32)) * p.scale_log2; \
+            for (int i = 0; i < 16; i += 2) mx = __builtin_fmaxf(__builtin_fmaxf(mx, S[rt][i]), S[rt][i + 1]); /* v_max3 */ \
+            { /* other half of the wavefront: one lane-half swap instead of a permute through LDS */ \
+                const auto sw_ = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false); \
+                mx = __builtin_fmaxf(__uint_as_float(sw_[0]), __uint_as_float(sw_[1])) * p.scale_log2; \
+            } \
             constexpr float LAZY = 8.0f; \
             const bool grow = mx > m_run[rt] + LAZY; \
             const float m_new = grow ? mx : m_run[rt]; \

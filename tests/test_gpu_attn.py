@@ -97,6 +97,15 @@ def test_ragged_prefix_per_sequence():
     run_case(B=3, Lq=32, Hq=4, Hkv=2, d=128, P=100, Lb=32, S=20, plen=[100, 37, 0], seed=8)
 
 
+@pytest.mark.parametrize("mode,bs", [("full", 0), ("block_causal", 4), ("block_causal", 32)])
+@pytest.mark.parametrize("L", [1, 33, 64, 65, 97, 300])
+def test_tile_counts_and_two_segments(mode, bs, L):
+    # 1, 2, 3, 4 ... key tiles, even and odd counts, ragged tails; one segment and two (full-tile fast path of the
+    # loads and stores next to the clamped path of the ragged last tile of each segment)
+    run_case(B=1, Lq=L, Hq=4, Hkv=2, d=128, P=0, Lb=L, S=0, mode=mode, bs=bs, q_pos0=0, seed=40 + L)
+    run_case(B=2, Lq=40, Hq=2, Hkv=2, d=128, P=L, Lb=40, S=0, mode=mode, bs=bs, seed=41 + L)
+
+
 def test_degenerate_contexts():
     # no prefix and no suffix; a single key; no key at all (output 0, lse -inf)
     run_case(B=1, Lq=32, Hq=2, Hkv=2, d=128, P=0, Lb=32, S=0, seed=9)
