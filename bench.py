@@ -169,7 +169,7 @@ def main():
         roof = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4),
                     traffic=int(LMHEAD_C2_TRAFFIC_BYTES) if args.config == "c2" else None,
-                    kernel="lmhead_kernel + lmhead_reduce_kernel (one dlm_lmhead_confidence call)",
+                    kernel="lmhead_kernel (M <= 192) or lmhead_pair_kernel (above) + lmhead_reduce_kernel (one dlm_lmhead_confidence call)",
                     avg_us=round(avg_ms * 1e3, 2), median_us=round(sorted(ms)[len(ms) // 2] * 1e3, 2),
                     launches=len(ms), bytes_per_launch=int(bytes_per_launch), mean_rows=round(mean_rows, 1),
                     flops_per_launch=int(2 * mean_rows * cfg.Dh * cfg.V),
