@@ -41,7 +41,78 @@ def parse():
     ap.add_argument("--sync-loop", action="store_true", help="poll every step synchronously (no one-step-late poll)")
     ap.add_argument("--dump-steps", default=None, metavar="FILE",
                     help="write one line per timed step: block, rows masked before / after, row bound, LM-head us")
+    ap.add_argument("--kernel", default=None, choices=["lmhead", "attn_fullseq"],
+                    help="time ONE kernel on random inputs instead of the rollout (record only, for profiles): "
+                         "lmhead = dlm_lmhead_confidence at --rows rows on the config's W shape; attn_fullseq = "
+                         "dlm_block_attn (and, with --backward, dlm_block_attn_bwd) on 64 x 4096 tokens, 32/8 heads, d = 128")
+    ap.add_argument("--rows", type=int, default=8192, help="--kernel lmhead: number of hidden rows M")
+    ap.add_argument("--lmhead-variant", default="-1", help="--kernel lmhead: comma-separated entries of the shape table (-1 = planner)")
+    ap.add_argument("--zeros", action="store_true", help="--kernel lmhead: all-zero operands (no data-dependent power)")
+    ap.add_argument("--mask", default="block_causal", choices=["full", "block_causal"], help="--kernel attn_fullseq")
+    ap.add_argument("--batch", type=int, default=64, help="--kernel attn_fullseq: sequences")
+    ap.add_argument("--backward", action="store_true", help="--kernel attn_fullseq: also time the backward pass")
+    ap.add_argument("--reps", type=int, default=3, help="--kernel: timed calls per measurement")
     return ap.parse_args()
+
+
+def micro(args):
+    """One kernel on random inputs (normal bf16 values, the rollout's W scale): a JSON line per measurement."""
+    import torch
+    from paper_2604_04215_amd import binding as dlm
+    from paper_2604_04215_amd import synth
+    dlm.lib()
+    dev = "cuda:0"
+    torch.manual_seed(0)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    if args.kernel == "lmhead":
+        cfg = synth.CONFIGS[args.config]
+        M, V, Dh = args.rows, cfg.V, cfg.Dh
+        if args.zeros:
+            w = torch.zeros((V, Dh), device=dev, dtype=torch.bfloat16)
+            h = torch.zeros((M, Dh), device=dev, dtype=torch.bfloat16)
+        else:
+            w = (torch.randn((V, Dh), device=dev) * Dh ** -0.25).bfloat16()
+            h = torch.randn((M, Dh), device=dev).bfloat16()
+        conf = torch.empty(M, device=dev)
+        tok = torch.empty(M, dtype=torch.int32, device=dev)
+        ws = torch.empty(dlm.lmhead_workspace_bytes(M, V), dtype=torch.uint8, device=dev)
+        for variant in [int(x) for x in args.lmhead_variant.split(",")]:
+            dlm.set_option("lmhead_variant", variant)
+            ms = timed(lambda: dlm.lmhead_confidence(h, w, conf, tok, workspace=ws, forbid_token=V - 1), args.reps)
+            print(json.dumps({"kernel": "dlm_lmhead_confidence", "M": M, "V": V, "Dh": Dh, "variant": variant,
+                              "data": "zeros" if args.zeros else "normal", "us": round(ms * 1e3, 1),
+                              "tflops": round(2.0 * M * V * Dh / ms / 1e9, 1),
+                              "w_stream_gbs": round(V * Dh * 2 / ms / 1e6, 1)}), flush=True)
+        dlm.set_option("lmhead_variant", -1)
+        return
+    B, L, Hq, Hkv, d, bs = args.batch, 4096, 32, 8, 128, 4
+    mk = lambda *shape: torch.randn(shape, device=dev).bfloat16()
+    q, do, k, v = mk(B, L, Hq, d), mk(B, L, Hq, d), mk(B, Hkv, L, d), mk(B, Hkv, L, d)
+    out = torch.empty_like(q)
+    lse = torch.empty((B, Hq, L), dtype=torch.float32, device=dev)
+    mode = dlm.MASK_FULL if args.mask == "full" else dlm.MASK_BLOCK_CAUSAL
+    pairs = L * L if args.mask == "full" else L * (L + bs) / 2
+    ms = timed(lambda: dlm.block_attn(q, out, block=(k, v, 0), mask_mode=mode, block_size=bs, lse=lse), args.reps)
+    print(json.dumps({"kernel": "dlm_block_attn", "mask": args.mask, "B": B, "L": L, "heads": [Hq, Hkv], "d": d,
+                      "ms": round(ms, 3), "tflops": round(4.0 * B * Hq * d * pairs / ms / 1e9, 1)}), flush=True)
+    if args.backward:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        ws = torch.empty(dlm.block_attn_bwd_workspace_bytes(B * L, Hq), dtype=torch.uint8, device=dev)
+        ms = timed(lambda: dlm.block_attn_bwd(q, out, do, lse, dq, block=(k, v, 0), d_block=(dk, dv), mask_mode=mode,
+                                              block_size=bs, workspace=ws), args.reps)
+        print(json.dumps({"kernel": "dlm_block_attn_bwd", "mask": args.mask, "B": B, "L": L, "heads": [Hq, Hkv], "d": d,
+                          "ms": round(ms, 3), "tflops": round(10.0 * B * Hq * d * pairs / ms / 1e9, 1)}), flush=True)
 
 
 def main():
@@ -60,6 +131,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dlm.lib()  # fail loudly if the HIP library is missing
+    if args.kernel:
+        micro(args)
+        return
     dev = "cuda:0"
     cfg = synth.CONFIGS[args.config]
     t_setup = time.time()
