@@ -123,6 +123,27 @@ def test_gather_scatter_mdev_temperature_target():
     assert np.all(np.isnan(got["conf"])) and np.all(got["tok"] == -7)
 
 
+@pytest.mark.parametrize("R,n_sel,variant", [(400, 300, -1), (900, 700, -1), (300, 230, 21), (300, 230, 20)])
+def test_gather_mdev_target_on_the_ring_shapes(R, n_sel, variant):
+    """Row gather, a device-side row count, a temperature, a forbidden token and target logits through the
+    direct-to-LDS shapes the planner takes above 192 rows (two 192-row chunks, 256-row chunks, one 256-row chunk)."""
+    Dh, V = 256, 1300
+    h, w = rnd(31 + R, (R, Dh)), rnd(32 + R, (V, Dh), Dh ** -0.25)
+    idx = np.array(sorted(np.random.default_rng(3).permutation(R)[:n_sel]), np.int32)
+    tgt = np.random.default_rng(4).integers(0, V, size=n_sel).astype(np.int32)
+    ref = oracle.lmhead(h, w, row_idx=idx, inv_temperature=1.3, forbid_token=777, target=tgt)
+    dlm.set_option("lmhead_variant", variant)
+    try:
+        got = run_lm(h, w, row_idx=idx, inv_t=1.3, forbid=777, target=tgt)
+        compare(got, ref)
+        m = n_sel - 37
+        got = run_lm(h, w, row_idx=idx, M=n_sel, m_dev=m, inv_t=1.3, forbid=777)
+    finally:
+        dlm.set_option("lmhead_variant", -1)
+    compare({k: v[:m] for k, v in got.items()}, {k: v[:m] for k, v in ref.items() if k != "zt"})
+    assert np.all(np.isnan(got["conf"][m:])) and np.all(got["tok"][m:] == -7)
+
+
 def test_ties_pick_lowest_index():
     Dh, V = 64, 700
     h = synth.f32_to_bf16_bits(np.ones((40, Dh), np.float32))
@@ -180,7 +201,7 @@ def test_full_vocabulary_sampled_rows():
     assert np.allclose(got["conf"], np.exp(got["zmax"] - got["lse"]), atol=1e-5)
 
 
-@pytest.mark.parametrize("variant", [-1, 0, 3, 5, 7, 10, 16])
+@pytest.mark.parametrize("variant", [-1, 0, 3, 5, 7, 10, 16, 20, 21])
 @pytest.mark.parametrize("mode", ["margin", "neg_entropy"])
 def test_alternative_confidence_scores(mode, variant):
     """conf = p(top-1) - p(top-2) or sum_v p_v log p_v instead of the token probability; every other output unchanged."""
