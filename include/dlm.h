@@ -354,6 +354,10 @@ int dlm_kv_refresh(const dlm_kv_seg *src, int32_t B, int32_t Hkv, int32_t d,
  *                   depth) from M (default); >= 0 forces one entry of the library's shape table.
  *   "lmhead_block"  -1 = automatic blocking of LM-head workgroups per XCD (default); 0 = none (row chunks of one
  *                   vocabulary tile side by side); 1..8 = that many vocabulary tiles per block.
+ *   "lmhead_nt"     1 = when a launch has one row chunk (every element of W used once) fetch W with non-temporal
+ *                   loads (default); 0 = never.
+ *   "attn_nt"       1 = non-temporal K/V loads when one workgroup is the only reader of its (sequence, KV head)
+ *                   (g*Lq <= 32; default); 0 = never.
  * Every shape computes the same function; the knobs exist for tests and tuning sweeps. */
 int dlm_set_option(const char *name, int value);
 

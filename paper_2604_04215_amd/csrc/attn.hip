@@ -51,7 +51,9 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
     return x.b;
 }
 
-template <int D, int NWR, int NWK, int RTW, bool BC, int PF = 1, int OCC = 1>
+// NTKV: K/V are fetched with non-temporal loads, for launches in which one workgroup is the only reader of its
+// (sequence, KV head): the rollout step streams 70 - 1000 MB of cache that nothing reads twice.
+template <int D, int NWR, int NWK, int RTW, bool BC, int PF = 1, int OCC = 1, bool NTKV = false>
 __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p) {
     static_assert(NWR == 1 || NWK == 1, "waves split either rows or keys");
     constexpr int NT = 64 * NWR * NWK;
@@ -212,6 +214,7 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     const int sg = ((t) < T0) ? 0 : (((t) < T0 + T1) ? 1 : 2);                                           \
     const int lt = ((t) < T0) ? (t) + F0 : (((t) < T0 + T1) ? (t) - T0 + F1 : (t) - T0 - T1 + F2);      \
     const int slen = (sg == 0) ? len0 : ((sg == 1) ? len1 : len2);
+#define ATTN_LD(ptr) (NTKV ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ptr)) : *reinterpret_cast<const u32x4*>(ptr))
 #define ATTN_PREFETCH(slot, t)                                                                           \
     {                                                                                                    \
         const int tc_ = min((t), T - 1);                                                                 \
@@ -224,8 +227,8 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
             const uint16_t* kt = kb + (int64_t)(lt_ * 32) * stt;                                         \
             const uint16_t* vt = vb + (int64_t)(lt_ * 32) * stt;                                         \
             _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                            \
-                kreg[slot][q] = *reinterpret_cast<const u32x4*>(kt + toff[q]);                           \
-                vreg[slot][q] = *reinterpret_cast<const u32x4*>(vt + toff[q]);                           \
+                kreg[slot][q] = ATTN_LD(kt + toff[q]);                                                   \
+                vreg[slot][q] = ATTN_LD(vt + toff[q]);                                                   \
             }                                                                                            \
         } else {                                                                                         \
             _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                            \
@@ -233,8 +236,8 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
                 const int row = cidx / C8, c = cidx - row * C8;                                          \
                 const int loc = min(lt_ * 32 + row, slen_ - 1);                                          \
                 const int64_t off = loc * stt + c * 8;                                                   \
-                kreg[slot][q] = *reinterpret_cast<const u32x4*>(kb + off);                               \
-                vreg[slot][q] = *reinterpret_cast<const u32x4*>(vb + off);                               \
+                kreg[slot][q] = ATTN_LD(kb + off);                                                       \
+                vreg[slot][q] = ATTN_LD(vb + off);                                                       \
             }                                                                                            \
         }                                                                                                \
     }
@@ -453,6 +456,7 @@ _Pragma("unroll") \
 #undef ATTN_TILE_SYNC
 #undef ATTN_COMPUTE
 #undef ATTN_PREFETCH
+#undef ATTN_LD
 #undef ATTN_TILE
 #undef ATTN_STAGE
 
@@ -541,6 +545,7 @@ _Pragma("unroll") \
     }
 }
 
+int g_attn_nt = 1;       // 1 = non-temporal K/V loads in the one-workgroup-per-KV-head shape (default); 0 = never (tuning)
 int g_attn_variant = 0;  // 0 = choose by shape; 1..3 force a kernel shape (dlm_set_option "attn_variant")
 
 template <int D, bool BC>
@@ -583,7 +588,8 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
         return check_hip(hipGetLastError(), "attn_kernel launch");
     }
     if (variant == 1) {
-        hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
+        if (g_attn_nt) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1, 1, true>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
     } else if (variant == 2) {
         hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 3>), dim3((p.R + 127) / 128, p.Hkv, p.B), dim3(256), 0, st, p);
     } else {
@@ -660,6 +666,12 @@ extern "C" int dlm_set_option(const char* name, int value) {
     }
     if (!strcmp(name, "lmhead_variant")) return lm_set_variant(value);
     if (!strcmp(name, "lmhead_block")) return lm_set_block(value);
+    if (!strcmp(name, "lmhead_nt")) return lm_set_nt(value);
+    if (!strcmp(name, "attn_nt")) {
+        if (value < 0 || value > 1) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_nt must be 0 or 1");
+        g_attn_nt = value;
+        return DLM_OK;
+    }
     return fail(DLM_ERR_INVALID_ARG, "set_option: unknown option '%s'", name);
 }
 

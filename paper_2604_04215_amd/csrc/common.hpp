@@ -24,6 +24,7 @@ int check_hip(hipError_t e, const char* what);
 
 int lm_set_variant(int v);   // lmhead.hip
 int lm_set_block(int v);     // lmhead.hip
+int lm_set_nt(int v);        // lmhead.hip
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -327,7 +327,8 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
 
 // WV x WH wavefronts; each owns TVW x THW accumulator tiles of 32 (vocab) x 32 (hidden rows).
 // PD = how many 64-element chunks of W / H are in flight in registers ahead of the one being multiplied.
-template <int WV, int WH, int TVW, int THW, int PD, int KCH = 64, int OCC = 1, bool PIPE = false>
+// NTW: W is fetched with non-temporal loads (see the launch table: for launches with one row chunk).
+template <int WV, int WH, int TVW, int THW, int PD, int KCH = 64, int OCC = 1, bool PIPE = false, bool NTW = false>
 __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
     constexpr int NT = 64 * WV * WH;
     constexpr int TV = 32 * TVW * WV;   // vocabulary rows per workgroup
@@ -391,7 +392,8 @@ __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
 #define LM_GLOAD(slot, kc)                                                                               \
     {                                                                                                    \
         _Pragma("unroll") for (int q = 0; q < WLD; ++q) if (W_ON(q))                                     \
-            wreg[slot][q] = *reinterpret_cast<const u32x4*>(wsrc[q] + LM_CHUNK(kc) * KC);                \
+            wreg[slot][q] = NTW ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wsrc[q] + LM_CHUNK(kc) * KC)) \
+                                : *reinterpret_cast<const u32x4*>(wsrc[q] + LM_CHUNK(kc) * KC);          \
         _Pragma("unroll") for (int q = 0; q < HLD; ++q) if (H_ON(q))                                     \
             hreg[slot][q] = *reinterpret_cast<const u32x4*>(hsrc[q] + LM_CHUNK(kc) * KC);                \
     }
@@ -1078,29 +1080,35 @@ __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
 struct LmVariant {
     int tv, mb, threads;
     void (*launch)(dim3, hipStream_t, const LmParams&);
+    // The same shape with W fetched by non-temporal loads, for launches with ONE row chunk, where every element of
+    // W is used exactly once: W then streams through L2 without being kept.  Measured on one box, V = 126464,
+    // Dh = 4096: 192 -> 170 us at M <= 64, 198 -> 180 at 96, 203 -> 188 at 128, 236 -> 228 at 160 - 192 rows.  With
+    // several row chunks W is re-read from L2 and the hint costs 30 - 40 %; in the direct-to-LDS ring it undoes the
+    // pairing of half-line requests (268 -> 305 us at 256 rows).  Null where the shape has no such form.
+    void (*launch_nt)(dim3, hipStream_t, const LmParams&);
 };
-template <int WV, int WH, int TVW, int THW, int PD, int KCH = 64, int OCC = 1, bool PIPE = false>
+template <int WV, int WH, int TVW, int THW, int PD, int KCH = 64, int OCC = 1, bool PIPE = false, bool NTW = false>
 static void launch_lm(dim3 grid, hipStream_t st, const LmParams& p) {
-    hipLaunchKernelGGL((lmhead_kernel<WV, WH, TVW, THW, PD, KCH, OCC, PIPE>), grid, dim3(64 * WV * WH), 0, st, p);
+    hipLaunchKernelGGL((lmhead_kernel<WV, WH, TVW, THW, PD, KCH, OCC, PIPE, NTW>), grid, dim3(64 * WV * WH), 0, st, p);
 }
-#define LMP(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD, 64, 1, true>}
+#define LMP(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD, 64, 1, true>, launch_lm<WV, WH, TVW, THW, PD, 64, 1, true, true>}
 template <int WV, int TVW, int THW, int PDW>
 static void launch_lmd(dim3 grid, hipStream_t st, const LmParams& p) {
     hipLaunchKernelGGL((lmhead_wdirect_kernel<WV, TVW, THW, PDW>), grid, dim3(64 * WV), 0, st, p);
 }
-#define LMD(WV, TVW, THW, PDW) {32 * TVW * WV, 32 * THW, 64 * WV, launch_lmd<WV, TVW, THW, PDW>}
+#define LMD(WV, TVW, THW, PDW) {32 * TVW * WV, 32 * THW, 64 * WV, launch_lmd<WV, TVW, THW, PDW>, nullptr}
 template <int WV, int WH, int TVW, int THW, int NS, bool XB = false>
 static void launch_lma(dim3 grid, hipStream_t st, const LmParams& p) {
     hipLaunchKernelGGL((lmhead_dma_kernel<WV, WH, TVW, THW, NS, XB>), grid, dim3(64 * WV * WH), 0, st, p);
 }
-#define LMA(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lma<WV, WH, TVW, THW, NS>}
-#define LMX(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lma<WV, WH, TVW, THW, NS, true>}
+#define LMA(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lma<WV, WH, TVW, THW, NS>, nullptr}
+#define LMX(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lma<WV, WH, TVW, THW, NS, true>, nullptr}
 template <int WV, int WH, int TVW, int THW>
 static void launch_lmq(dim3 grid, hipStream_t st, const LmParams& p) {
     hipLaunchKernelGGL((lmhead_pair_kernel<WV, WH, TVW, THW>), grid, dim3(64 * WV * WH), 0, st, p);
 }
-#define LMQ(WV, WH, TVW, THW) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lmq<WV, WH, TVW, THW>}
-#define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD>}
+#define LMQ(WV, WH, TVW, THW) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lmq<WV, WH, TVW, THW>, nullptr}
+#define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD>, launch_lm<WV, WH, TVW, THW, PD, 64, 1, false, true>}
 static const LmVariant g_lm_variants[] = {
     // shapes the planner uses, by row count M (sweep at V = 126464, Dh = 4096 on MI355X, us per call):
     /*0*/ LMV(4, 1, 1, 1, 3),   // M <= 32   128 x 32 tile,  4 waves            ~181
@@ -1138,6 +1146,7 @@ static const LmVariant g_lm_variants[] = {
 constexpr int N_LM_VARIANTS = sizeof(g_lm_variants) / sizeof(g_lm_variants[0]);
 constexpr int LM_MIN_TV = 128;   // smallest vocabulary tile of any variant: sizes the workspace
 int g_lm_variant = -1;           // -1 = choose by M; otherwise force an entry of the table (dlm_set_option)
+int g_lm_nt = 1;                 // 1 = non-temporal W loads when there is one row chunk (default); 0 = never (tuning)
 int g_lm_block_gv = -1;          // -1 = automatic XCD blocking; 0 = none; n = n vocabulary tiles per block (tuning)
 
 static int plan_lmhead(int M) {
@@ -1221,7 +1230,7 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     const int64_t n_wg = n_vt8 * 8 * p.n_mc;
     if (n_wg > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "lmhead: M * V too large for one launch");
     hipStream_t st = (hipStream_t)stream;
-    var.launch(dim3((unsigned)n_wg), st, p);
+    ((p.n_mc == 1 && var.launch_nt && g_lm_nt) ? var.launch_nt : var.launch)(dim3((unsigned)n_wg), st, p);
     rc = check_hip(hipGetLastError(), "lmhead_kernel launch");
     if (rc != DLM_OK) return rc;
     hipLaunchKernelGGL(lmhead_reduce_kernel, dim3(a->M), dim3(256), 0, st, p);
@@ -1232,6 +1241,11 @@ namespace dlm {
 int lm_set_block(int v) {
     if (v < -1 || v > 8) return fail(DLM_ERR_INVALID_ARG, "set_option: lmhead_block must be -1..8");
     g_lm_block_gv = v;
+    return DLM_OK;
+}
+int lm_set_nt(int v) {
+    if (v < 0 || v > 1) return fail(DLM_ERR_INVALID_ARG, "set_option: lmhead_nt must be 0 or 1");
+    g_lm_nt = v;
     return DLM_OK;
 }
 int lm_set_variant(int v) {
