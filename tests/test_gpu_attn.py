@@ -138,6 +138,23 @@ def test_rerun_is_bitwise_identical():
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
 
 
+def test_non_temporal_kv_stream_changes_nothing():
+    """g * Lq <= 32: one workgroup reads its K/V once, with non-temporal loads unless the option turns that off."""
+    B, Lq, Hq, Hkv, d, P = 2, 8, 8, 2, 128, 500
+    q, k, v = bf16_dev(rnd(141, (B, Lq, Hq, d))), bf16_dev(rnd(142, (B, Hkv, P, d))), bf16_dev(rnd(143, (B, Hkv, P, d)))
+    o1, o2 = torch.empty_like(q), torch.empty_like(q)
+    dlm.block_attn(q, o1, prefix=(k, v, 0))
+    dlm.set_option("attn_nt", 0)
+    try:
+        dlm.block_attn(q, o2, prefix=(k, v, 0))
+    finally:
+        dlm.set_option("attn_nt", 1)
+    torch.cuda.synchronize()
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+    ref, _ = oracle.attention(rnd(141, (B, Lq, Hq, d)), [KV(rnd(142, (B, Hkv, P, d)), rnd(143, (B, Hkv, P, d)), 0)])
+    assert attn_rel_err(bf16_host(o1), ref) <= TOL
+
+
 @pytest.mark.parametrize("variant", [0, 1, 2])
 def test_planted_one_hot_values_expose_every_key(variant):
     """V[j] = e_(j mod d): output channel c is the total probability of keys j = c (mod d), so a

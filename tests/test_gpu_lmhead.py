@@ -144,6 +144,21 @@ def test_gather_mdev_target_on_the_ring_shapes(R, n_sel, variant):
     assert np.all(np.isnan(got["conf"][m:])) and np.all(got["tok"][m:] == -7)
 
 
+def test_non_temporal_w_stream_changes_nothing():
+    """One row chunk: W is fetched with non-temporal loads unless the option turns that off; same bits either way."""
+    h, w = rnd(71, (150, 256)), rnd(72, (3000, 256), 0.25)
+    a = run_lm(h, w, forbid=11)
+    dlm.set_option("lmhead_nt", 0)
+    try:
+        b = run_lm(h, w, forbid=11)
+    finally:
+        dlm.set_option("lmhead_nt", 1)
+    for k in a:
+        assert np.array_equal(a[k], b[k])
+    with pytest.raises(dlm.DlmError):
+        dlm.set_option("lmhead_nt", 2)
+
+
 def test_ties_pick_lowest_index():
     Dh, V = 64, 700
     h = synth.f32_to_bf16_bits(np.ones((40, Dh), np.float32))
