@@ -104,6 +104,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2604_04215_amd.build` "
                                "(there is no CPU fallback)")
+        # PyTorch ships its own HIP runtime: load it first so that the library binds to the runtime that owns the
+        # tensors' memory and streams (loaded the other way round, launches fail with "no ROCm-capable device")
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.dlm_block_attn.restype = C.c_int
         L.dlm_block_attn.argtypes = [C.POINTER(AttnArgs), C.c_void_p]

@@ -573,9 +573,9 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
     }
     if (variant >= 8 && p.R <= 32) {   // key-split alternatives (tuning)
         const dim3 grid(1, p.Hkv, p.B);
-        if (variant == 8) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2>), grid, dim3(256), 0, st, p);
-        else if (variant == 9) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 3>), grid, dim3(256), 0, st, p);
-        else hipLaunchKernelGGL((attn_kernel<D, 1, 8, 1, BC, 1>), grid, dim3(512), 0, st, p);
+        if (variant == 8) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2, 1, true>), grid, dim3(256), 0, st, p);
+        else if (variant == 9) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 3, 1, true>), grid, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((attn_kernel<D, 1, 8, 1, BC, 1, 1, true>), grid, dim3(512), 0, st, p);
         return check_hip(hipGetLastError(), "attn_kernel launch");
     }
     if (variant >= 8) variant = 0 + 4;
