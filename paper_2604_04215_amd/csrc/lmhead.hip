@@ -1110,12 +1110,13 @@ static void launch_lmq(dim3 grid, hipStream_t st, const LmParams& p) {
 #define LMQ(WV, WH, TVW, THW) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lmq<WV, WH, TVW, THW>, nullptr}
 #define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD>, launch_lm<WV, WH, TVW, THW, PD, 64, 1, false, true>}
 static const LmVariant g_lm_variants[] = {
-    // shapes the planner uses, by row count M (sweep at V = 126464, Dh = 4096 on MI355X, us per call):
-    /*0*/ LMV(4, 1, 1, 1, 3),   // M <= 32   128 x 32 tile,  4 waves            ~181
-    /*1*/ LMP(4, 1, 1, 2, 3),   // M <= 64   128 x 64,       4 waves            ~181
-    /*2*/ LMP(8, 1, 1, 3, 3),   // M <= 96   256 x 96,       8 waves            ~191
-    /*3*/ LMP(4, 2, 2, 2, 3),   // M <= 128  256 x 128,      8 waves            ~200
-    /*4*/ LMP(4, 2, 2, 3, 2),   // M <= 192  256 x 192,      8 waves            ~235
+    // shapes the planner uses, by row count M (V = 126464, Dh = 4096 on MI355X, us per main-kernel launch in the
+    // rollout, non-temporal W stream; entries 21, 22, 20 above 192 rows):
+    /*0*/ LMV(4, 1, 1, 1, 3),   // M <= 32   128 x 32 tile,  4 waves            ~161
+    /*1*/ LMP(4, 1, 1, 2, 3),   // M <= 64   128 x 64,       4 waves            ~159
+    /*2*/ LMP(8, 1, 1, 3, 3),   // M <= 96   256 x 96,       8 waves            ~166
+    /*3*/ LMP(4, 2, 2, 2, 3),   // M <= 128  256 x 128,      8 waves            ~172
+    /*4*/ LMP(4, 2, 2, 3, 2),   // M <= 192  256 x 192,      8 waves            ~203
     /*5*/ LMP(4, 2, 2, 4, 2),   // 256 x 256, 8 waves, register-staged (the planner now takes entries 20..22 above 192 rows)
     // alternatives kept for tests and tuning sweeps
     /*6*/ LMV(2, 2, 2, 4, 3),   // 128 x 256, 4 waves, stores before the MFMA block
@@ -1133,7 +1134,7 @@ static const LmVariant g_lm_variants[] = {
     /*18*/ LMX(2, 2, 4, 4, 4),  // entry 10 with the operand fragments read one MFMA step ahead, across the barrier
     /*19*/ LMX(4, 2, 2, 4, 4),  // entry 13 likewise
     /*20*/ LMQ(2, 2, 4, 4),     // paired, evenly spread requests, 5 stages: 256 x 256, 4 waves x (128 x 128)
-    /*21*/ LMQ(4, 2, 2, 4),     // same, 8 waves x (64 x 128)
+    /*21*/ LMQ(4, 2, 2, 4),     // same, 8 waves x (64 x 128)                      M <= 256: ~245
     /*22*/ LMQ(4, 1, 2, 6),     // 256 x 192, 4 waves x (64 x 192)
     /*23*/ LMQ(4, 1, 2, 4),     // 256 x 128, 4 waves x (64 x 128)
 };
