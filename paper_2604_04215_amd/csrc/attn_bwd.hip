@@ -438,8 +438,41 @@ __global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams
     u32x4 qreg[NLD], greg[NLD];
     float st_lse2 = INFINITY, st_delta = 0.f;
     int st_qlim = 0;
+    // Fast path for a full tile when the group size divides 32 (so a tile holds whole queries) and Q and dO share
+    // their strides: row r of tile rt is query rt * (32 / g) + r / g, head r % g, i.e. a wave-uniform tile base plus
+    // an offset that is fixed per thread: no division and no 64-bit per-thread arithmetic per tile.
+    const bool rows_fast = (32 % p.g == 0) && p.q_st == p.do_st && p.q_sh == p.do_sh && p.q_st >= 0 && p.q_sh >= 0 &&
+                           p.q_st < (1 << 25) && p.q_sh < (1 << 25);
+    const int qpt = 32 / max(p.g, 1);                 // queries per tile (fast path)
+    const int bs_shift = (BC && (p.bs & (p.bs - 1)) == 0) ? __builtin_ctz(p.bs) : -1;
+    uint32_t roff[NLD];
+#pragma unroll
+    for (int q = 0; q < NLD; ++q) {
+        const int cidx = tid + q * 256;
+        const int row = cidx / C8, c = cidx - row * C8;
+        roff[q] = (uint32_t)((row / p.g) * (int)p.q_st + (row % p.g) * (int)p.q_sh + c * 8);
+    }
+    const int st_r = tid & 31;
+    const int st_i = st_r / p.g, st_h = kvh * p.g + st_r % p.g;     // this thread's statistics row inside a tile
+    const int64_t st_base = stat_index(p, b, st_h, st_i, s0);       // ... of tile 0; tile rt is qpt entries further
 #define BW_FETCH_ROWS(rt)                                                                                \
     {                                                                                                    \
+        if (rows_fast && (rt) * 32 + 32 <= R) {                                                          \
+            const int64_t tb_ = (int64_t)((rt) * qpt) * p.q_st + (int64_t)(kvh * p.g) * p.q_sh;          \
+            const uint16_t* qb_ = p.q + q_off + tb_;                                                     \
+            const uint16_t* gb_ = p.dout + do_off + tb_;                                                 \
+            _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                            \
+                qreg[q] = *reinterpret_cast<const u32x4*>(qb_ + roff[q]);                                \
+                greg[q] = *reinterpret_cast<const u32x4*>(gb_ + roff[q]);                                \
+            }                                                                                            \
+            const int64_t si = st_base + (rt) * qpt;                                                     \
+            const float l = p.lse[si];                                                                   \
+            const float dl_ = DK ? p.delta[si] : 0.f;                                                    \
+            st_lse2 = (l > -INFINITY) ? l * 1.4426950408889634f : INFINITY;                              \
+            st_delta = dl_;                                                                              \
+            const int qp_ = p.q_pos0 + (rt) * qpt + st_i;                                                \
+            st_qlim = BC ? (bs_shift >= 0 ? (((qp_ >> bs_shift) + 1) << bs_shift) : (qp_ / p.bs + 1) * p.bs) : 0; \
+        } else {                                                                                         \
         _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
             const int cidx = tid + q * 256;                                                              \
             const int row = cidx / C8, c = cidx - row * C8;                                              \
@@ -463,13 +496,15 @@ __global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams
             /* an absent row: its probabilities are 0 through lse2; INT_MAX forces the masked path */    \
             st_qlim = ok_ ? (BC ? ((p.q_pos0 + ii) / p.bs + 1) * p.bs : 0) : 0x7fffffff;                 \
         }                                                                                                \
+        }                                                                                                \
     }
 #define BW_STORE_ROWS(rt)                                                                                \
     {                                                                                                    \
+        const bool full_ = (rt) * 32 + 32 <= R;                                                          \
         _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
             const int cidx = tid + q * 256;                                                              \
             const int row = cidx / C8, c = cidx - row * C8;                                              \
-            const bool live = (rt) * 32 + row < R;                                                       \
+            const bool live = full_ || ((rt) * 32 + row < R);                                            \
             const u32x4 z = {0, 0, 0, 0};                                                                \
             const u32x4 qq = live ? qreg[q] : z, gg = live ? greg[q] : z;                                \
             *reinterpret_cast<u32x4*>(Qrow + row * KP + c * 16) = qq;                                    \
