@@ -172,6 +172,7 @@ __device__ __forceinline__ void lm_epilogue(const LmParams& p, f32x16 (&acc)[TVW
     // (the loop above ended with a barrier: the staging area is free)
 #pragma unroll
     for (int c = 0; c < THW; ++c) {
+        if (m0 + (wh * THW + c) * 32 >= M) continue;   // a row tile past the last row: nothing reads its partials
         const int col = (wh * THW + c) * 32 + n;       // hidden row inside the workgroup's MB
         const int r = m0 + col;
         int tgt = -1;
@@ -860,11 +861,9 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_pair_kernel(LmParams p) {
     constexpr int TV = 32 * TVW * WV, MB = 32 * THW * WH;
     constexpr int STAGE = (TV + MB) * ROWB;
     constexpr int IPW = (TV + MB) / 16 / NW;          // 16-row groups per wavefront (two requests each per pair)
-    constexpr int T = TVW * THW;                      // MFMAs per half stage
     static_assert((TV + MB) / 16 % NW == 0, "rows must split evenly over the wavefronts");
     static_assert(NS * STAGE <= 160 * 1024, "five stages within the 160 KB of LDS");
     static_assert(NS * STAGE >= 2 * WV * MB * 16, "both reduction buffers must fit in the ring");
-    static_assert(IPW <= T && TVW + THW <= 2 * T, "one auxiliary instruction behind each MFMA");
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -909,20 +908,6 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_pair_kernel(LmParams p) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][c][i] = 0.f;
 
-    // prologue: pairs (0,1) -> stages 0,1 and (2,3) -> stages 2,3 (a request past the end re-reads the last pair)
-#pragma unroll
-    for (int pr = 0; pr < 2; ++pr) {
-        const int e = PR_CHUNK(min(2 * pr, nk - 2)) * KCD;
-#pragma unroll
-        for (int j = 0; j < IPW; ++j) {
-            PR_ISSUE1((2 * pr) * STAGE, j, e);
-            PR_ISSUE1((2 * pr + 1) * STAGE, j, e + KCD);
-        }
-    }
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * IPW) : "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-
     const int sw = (n >> 2) & 3;
     const int off0 = n * ROWB + ((hi ^ sw) << 4);          // MFMA step 0: piece hi
     const int off1 = n * ROWB + (((2 + hi) ^ sw) << 4);    // MFMA step 1: piece 2 + hi
@@ -937,21 +922,32 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_pair_kernel(LmParams p) {
         else bfr[half][(i) >= TVW ? (i) - TVW : 0] =                                                     \
             *reinterpret_cast<const bf16x8*>(ring + (sb) + ((half) ? lh1 : lh0) + ((i) - TVW) * 32 * ROWB); \
     }
-    // T MFMAs on register set `half`; behind the first ones the fragment reads of the other set (stage at rsb);
-    // part = 1 / 2: the first / second half of the pair's 2*IPW requests (chunk at element offset ich into the
-    // stage at isb0, the following chunk into isb1), one behind every (T / IPW)-th MFMA
-#define PR_HALF(half, rsb, part, isb0, isb1, ich)                                                        \
+    // One half stage for a wavefront with NL live row tiles (NL <= THW; the tiles past the last row of the
+    // launch are never multiplied): TVW * NL MFMAs on register set `half`; behind the first ones the fragment reads
+    // of the other set (stage at rsb); part = 1 / 2: the first / second half of the pair's 2*IPW requests (chunk at
+    // element offset ich into the stage at isb0, the following chunk into isb1), spread evenly over the MFMAs.
+    // NL = 0 (every row tile of this wavefront is past the end): only its share of the requests.
+#define PR_HALF(half, rsb, part, isb0, isb1, ich, NL)                                                    \
     {                                                                                                    \
+        constexpr int T_ = TVW * (NL), NF_ = TVW + (NL);                                                 \
+        if constexpr ((NL) == 0) {                                                                       \
+            if ((part) != 0) {                                                                           \
+                _Pragma("unroll") for (int j = 0; j < IPW; ++j) {                                        \
+                    const int jj = j + ((part) == 2 ? IPW : 0);                                          \
+                    if (jj & 1) PR_ISSUE1(isb1, jj >> 1, (ich) + KCD);                                   \
+                    else PR_ISSUE1(isb0, jj >> 1, (ich));                                                \
+                }                                                                                        \
+            }                                                                                            \
+        } else {                                                                                         \
         _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                                  \
-            _Pragma("unroll") for (int c = 0; c < THW; ++c) {                                            \
-                constexpr int NF = TVW + THW;                                                            \
-                const int i_ = a * THW + c;                                                              \
+            _Pragma("unroll") for (int c = 0; c < (NL); ++c) {                                           \
+                const int i_ = a * (NL) + c;                                                             \
                 acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[half][a], bfr[half][c], acc[a][c], 0, 0, 0); \
-                _Pragma("unroll") for (int f = 0; f < NF; ++f)                                           \
-                    if (f * T / (2 * NF) == i_) PR_READ_ONE(1 - (half), rsb, f);                         \
+                _Pragma("unroll") for (int f = 0; f < NF_; ++f)                                          \
+                    if (f * T_ / (2 * NF_) == i_) PR_READ_ONE(1 - (half), rsb, f);                       \
                 if ((part) != 0) {                                                                       \
                     _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                      \
-                        if (j * T / IPW == i_) {                                                         \
+                        if (j * T_ / IPW == i_) {                                                        \
                             const int jj = j + ((part) == 2 ? IPW : 0);                                  \
                             if (jj & 1) PR_ISSUE1(isb1, jj >> 1, (ich) + KCD);                           \
                             else PR_ISSUE1(isb0, jj >> 1, (ich));                                        \
@@ -959,30 +955,62 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_pair_kernel(LmParams p) {
                 }                                                                                        \
                 __builtin_amdgcn_sched_barrier(0);                                                       \
             }                                                                                            \
+        }                                                                                                \
     }
-#pragma unroll
-    for (int f = 0; f < TVW + THW; ++f) PR_READ_ONE(0, 0, f);
 #define PR_NEXT(x) (((x) + STAGE == NS * STAGE) ? 0 : (x) + STAGE)
-    int sb = 0;                                       // byte offset of the stage of chunk k (k even at the loop top)
-    for (int k = 0; k < nk; k += 2) {
-        const int s1 = PR_NEXT(sb), s2 = PR_NEXT(s1), s3 = PR_NEXT(s2), s4 = PR_NEXT(s3);
-        const int ich = PR_CHUNK(min(k + 4, nk - 2)) * KCD;
-        // even stage k
-        PR_HALF(0, sb, 0, 0, 0, 0);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_s_barrier();                 // every wavefront has read stage k to the end: it is free
-        asm volatile("" ::: "memory");
-        PR_HALF(1, s1, 1, s4, sb, ich);
-        // odd stage k+1
-        PR_HALF(0, s1, 2, s4, sb, ich);
-        // all but the pair just requested has landed: chunks k+2 and k+3
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * IPW) : "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        PR_HALF(1, s2, 0, 0, 0, 0);
-        sb = s2;
+    // prologue: pairs (0,1) -> stages 0,1 and (2,3) -> stages 2,3 (a request past the end re-reads the last pair);
+    // then the loop over pairs of stages
+#define PR_MAIN(NL)                                                                                      \
+    {                                                                                                    \
+        _Pragma("unroll") for (int pr = 0; pr < 2; ++pr) {                                               \
+            const int e = PR_CHUNK(min(2 * pr, nk - 2)) * KCD;                                           \
+            _Pragma("unroll") for (int j = 0; j < IPW; ++j) {                                            \
+                PR_ISSUE1((2 * pr) * STAGE, j, e);                                                       \
+                PR_ISSUE1((2 * pr + 1) * STAGE, j, e + KCD);                                             \
+            }                                                                                            \
+        }                                                                                                \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * IPW) : "memory");                                   \
+        __builtin_amdgcn_s_barrier();                                                                    \
+        asm volatile("" ::: "memory");                                                                   \
+        if constexpr ((NL) > 0) {                                                                        \
+            _Pragma("unroll") for (int f = 0; f < TVW + (NL); ++f) PR_READ_ONE(0, 0, f);                 \
+        }                                                                                                \
+        int sb = 0; /* byte offset of the stage of chunk k (k even at the loop top) */                   \
+        for (int k = 0; k < nk; k += 2) {                                                                \
+            const int s1 = PR_NEXT(sb), s2 = PR_NEXT(s1), s3 = PR_NEXT(s2), s4 = PR_NEXT(s3);            \
+            const int ich = PR_CHUNK(min(k + 4, nk - 2)) * KCD;                                          \
+            /* even stage k */                                                                           \
+            PR_HALF(0, sb, 0, 0, 0, 0, NL);                                                              \
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                           \
+            __builtin_amdgcn_s_barrier(); /* every wavefront has read stage k to the end: it is free */  \
+            asm volatile("" ::: "memory");                                                               \
+            PR_HALF(1, s1, 1, s4, sb, ich, NL);                                                          \
+            /* odd stage k+1 */                                                                          \
+            PR_HALF(0, s1, 2, s4, sb, ich, NL);                                                          \
+            /* all but the pair just requested has landed: chunks k+2 and k+3 */                         \
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * IPW) : "memory");                    \
+            __builtin_amdgcn_s_barrier();                                                                \
+            asm volatile("" ::: "memory");                                                               \
+            PR_HALF(1, s2, 0, 0, 0, 0, NL);                                                              \
+            sb = s2;                                                                                     \
+        }                                                                                                \
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                                      \
     }
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    // Row tiles of this wavefront that hold a row of the launch: the loop exists once per count, so that the row
+    // count of a step that the host only knows an upper bound of (device-side M) costs what its rows cost.  Every
+    // copy runs the same barriers and the same requests.
+    const int nl = __builtin_amdgcn_readfirstlane(min(max((M - m0 - wh * THW * 32 + 31) >> 5, 0), THW));
+#define PR_CASE(k)                                                                                       \
+    case k:                                                                                              \
+        if constexpr ((k) <= THW) { PR_MAIN(k) }                                                         \
+        break;
+    switch (nl) {
+        PR_CASE(0) PR_CASE(1) PR_CASE(2) PR_CASE(3) PR_CASE(4) PR_CASE(5) PR_CASE(6)
+        default: break;
+    }
+    static_assert(THW <= 6, "one copy of the loop per live-tile count");
+#undef PR_CASE
+#undef PR_MAIN
 #undef PR_CHUNK
 #undef PR_ISSUE1
 #undef PR_READ_ONE
