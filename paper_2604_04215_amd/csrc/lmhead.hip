@@ -408,18 +408,19 @@ __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
             *reinterpret_cast<u32x4*>(Hl_ + (lrow + q * RPP) * LP + lc * 16) = hreg[slot][q];            \
     }
 
-#define LM_COMPUTE(buf)                                                                                  \
-    {                                                                                                    \
+    // NL = live 32-row tiles of this wavefront (the tiles past the launch's last row are never multiplied)
+#define LM_COMPUTE(buf, NL)                                                                              \
+    if constexpr ((NL) > 0) {                                                                            \
         const unsigned char* Wl = smem + (buf) * STAGE + (wv * TVW * 32 + n) * LP + hi * 16;             \
         const unsigned char* Hl = smem + (buf) * STAGE + TV * LP + (wh * THW * 32 + n) * LP + hi * 16;   \
         _Pragma("unroll") for (int ks = 0; ks < KC / 16; ++ks) {                                         \
             bf16x8 af[TVW], bfr[THW];                                                                    \
             _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
                 af[a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP + ks * 32);                    \
-            _Pragma("unroll") for (int c = 0; c < THW; ++c)                                              \
+            _Pragma("unroll") for (int c = 0; c < (NL); ++c)                                             \
                 bfr[c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + ks * 32);                   \
             _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
-                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
+                _Pragma("unroll") for (int c = 0; c < (NL); ++c)                                         \
                     acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[c], acc[a][c], 0, 0, 0); \
         }                                                                                                \
     }
@@ -436,23 +437,27 @@ __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
         if ((i) < WLD) { if (W_ON(i)) *reinterpret_cast<u32x4*>(Wl_ + (lrow + (i) * RPP) * LP + lc * 16) = wreg[slot][(i) < WLD ? (i) : 0]; } \
         else { if (H_ON((i) - WLD)) *reinterpret_cast<u32x4*>(Hl_ + (lrow + ((i) - WLD) * RPP) * LP + lc * 16) = hreg[slot][(i) >= WLD ? (i) - WLD : 0]; } \
     }
-#define LM_ITER_PIPE(buf, do_store, slot, nbuf)                                                          \
+#define LM_ITER_PIPE(buf, do_store, slot, nbuf, NL)                                                      \
     {                                                                                                    \
         const unsigned char* Wl = smem + (buf) * STAGE + (wv * TVW * 32 + n) * LP + hi * 16;             \
         const unsigned char* Hl = smem + (buf) * STAGE + TV * LP + (wh * THW * 32 + n) * LP + hi * 16;   \
         bf16x8 af[2][TVW], bfr[2][THW];                                                                  \
-        _Pragma("unroll") for (int a = 0; a < TVW; ++a) af[0][a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP); \
-        _Pragma("unroll") for (int c = 0; c < THW; ++c) bfr[0][c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP); \
+        if constexpr ((NL) > 0) {                                                                        \
+            _Pragma("unroll") for (int a = 0; a < TVW; ++a) af[0][a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP); \
+            _Pragma("unroll") for (int c = 0; c < (NL); ++c) bfr[0][c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP); \
+        }                                                                                                \
         _Pragma("unroll") for (int ks = 0; ks < KSTEPS; ++ks) {                                          \
-            if (ks + 1 < KSTEPS) {                                                                       \
+            if constexpr ((NL) > 0) {                                                                    \
+                if (ks + 1 < KSTEPS) {                                                                   \
+                    _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                      \
+                        af[(ks + 1) & 1][a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP + (ks + 1) * 32); \
+                    _Pragma("unroll") for (int c = 0; c < (NL); ++c)                                     \
+                        bfr[(ks + 1) & 1][c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + (ks + 1) * 32); \
+                }                                                                                        \
                 _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                          \
-                    af[(ks + 1) & 1][a] = *reinterpret_cast<const bf16x8*>(Wl + a * 32 * LP + (ks + 1) * 32); \
-                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
-                    bfr[(ks + 1) & 1][c] = *reinterpret_cast<const bf16x8*>(Hl + c * 32 * LP + (ks + 1) * 32); \
+                    _Pragma("unroll") for (int c = 0; c < (NL); ++c)                                     \
+                        acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][a], bfr[ks & 1][c], acc[a][c], 0, 0, 0); \
             }                                                                                            \
-            _Pragma("unroll") for (int a = 0; a < TVW; ++a)                                              \
-                _Pragma("unroll") for (int c = 0; c < THW; ++c)                                          \
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][a], bfr[ks & 1][c], acc[a][c], 0, 0, 0); \
             if (do_store) {                                                                              \
                 _Pragma("unroll") for (int i = 0; i < NST; ++i)                                          \
                     if (i * KSTEPS / NST == ks) LM_STORE_ONE(slot, nbuf, i);                             \
@@ -461,46 +466,64 @@ __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
         }                                                                                                \
     }
 
-    // prologue: chunks 0 .. PD-1 in flight, chunk 0 staged, chunk PD requested
-#pragma unroll
-    for (int s = 0; s < PD; ++s)
-        if (s < nk) LM_GLOAD(s, s);
-    LM_LSTORE(0, 0);
-    if (PD < nk) LM_GLOAD(0, PD);
-    __syncthreads();
-
+    // prologue: chunks 0 .. PD-1 in flight, chunk 0 staged, chunk PD requested.
     // Steady state, free of conditions so that the load counter waits can be exact: iteration kc stages
     // chunk kc+1 (requested PD chunks ago) into the other LDS buffer, requests chunk kc+1+PD into the
     // register slot just freed, multiplies chunk kc.  Chunk c lives in register slot c % PD.
-    int kc = 0;
-    const int n_main = (nk - PD - 1 > 0) ? ((nk - PD - 1) / PD) * PD : 0;
-    for (; kc < n_main; kc += PD) {
-#pragma unroll
-        for (int u = 0; u < PD; ++u) {
-            if (PIPE) {
-                LM_ITER_PIPE((kc + u) & 1, true, (u + 1) % PD, (kc + u + 1) & 1);
-                LM_GLOAD((u + 1) % PD, kc + u + 1 + PD);
-            } else {
-                LM_LSTORE((u + 1) % PD, (kc + u + 1) & 1);
-                LM_GLOAD((u + 1) % PD, kc + u + 1 + PD);
-                LM_COMPUTE((kc + u) & 1);
-            }
-            __syncthreads();
-        }
-    }
     // Drain (at most 2*PD chunks): same steps, each guarded.
-#pragma unroll
-    for (int u = 0; u < 2 * PD; ++u) {
-        const int k = kc + u;
-        if (k < nk) {
-            if (k + 1 < nk) {
-                LM_LSTORE((u + 1) % PD, (k + 1) & 1);
-                if (k + 1 + PD < nk) LM_GLOAD((u + 1) % PD, k + 1 + PD);
-            }
-            LM_COMPUTE(k & 1);
-            __syncthreads();
-        }
+#define LM_MAIN(NL)                                                                                      \
+    {                                                                                                    \
+        _Pragma("unroll") for (int s = 0; s < PD; ++s)                                                   \
+            if (s < nk) LM_GLOAD(s, s);                                                                  \
+        LM_LSTORE(0, 0);                                                                                 \
+        if (PD < nk) LM_GLOAD(0, PD);                                                                    \
+        __syncthreads();                                                                                 \
+        int kc = 0;                                                                                      \
+        const int n_main = (nk - PD - 1 > 0) ? ((nk - PD - 1) / PD) * PD : 0;                            \
+        for (; kc < n_main; kc += PD) {                                                                  \
+            _Pragma("unroll") for (int u = 0; u < PD; ++u) {                                             \
+                if (PIPE) {                                                                              \
+                    LM_ITER_PIPE((kc + u) & 1, true, (u + 1) % PD, (kc + u + 1) & 1, NL);                \
+                    LM_GLOAD((u + 1) % PD, kc + u + 1 + PD);                                             \
+                } else {                                                                                 \
+                    LM_LSTORE((u + 1) % PD, (kc + u + 1) & 1);                                           \
+                    LM_GLOAD((u + 1) % PD, kc + u + 1 + PD);                                             \
+                    LM_COMPUTE((kc + u) & 1, NL);                                                        \
+                }                                                                                        \
+                __syncthreads();                                                                         \
+            }                                                                                            \
+        }                                                                                                \
+        _Pragma("unroll") for (int u = 0; u < 2 * PD; ++u) {                                             \
+            const int k = kc + u;                                                                        \
+            if (k < nk) {                                                                                \
+                if (k + 1 < nk) {                                                                        \
+                    LM_LSTORE((u + 1) % PD, (k + 1) & 1);                                                \
+                    if (k + 1 + PD < nk) LM_GLOAD((u + 1) % PD, k + 1 + PD);                             \
+                }                                                                                        \
+                LM_COMPUTE(k & 1, NL);                                                                   \
+                __syncthreads();                                                                         \
+            }                                                                                            \
+        }                                                                                                \
     }
+    // Where the wavefronts split the rows (WH > 1), the loop exists once per count of live row tiles of a
+    // wavefront: the rollout's host knows a step's row count only as an upper bound, and a launch sized for it
+    // should cost what the rows that exist cost.  Every copy runs the same loads, stores and barriers.
+    if constexpr (WH > 1 && PIPE) {
+        const int nl = __builtin_amdgcn_readfirstlane(min(max((M - m0 - wh * THW * 32 + 31) >> 5, 0), THW));
+#define LM_CASE(k)                                                                                       \
+    case k:                                                                                              \
+        if constexpr ((k) <= THW) { LM_MAIN(k) }                                                         \
+        break;
+        switch (nl) {
+            LM_CASE(0) LM_CASE(1) LM_CASE(2) LM_CASE(3) LM_CASE(4)
+            default: break;
+        }
+        static_assert(THW <= 4, "one copy of the loop per live-tile count");
+#undef LM_CASE
+    } else {
+        LM_MAIN(THW)
+    }
+#undef LM_MAIN
 #undef W_ON
 #undef H_ON
 #undef LM_COMPUTE
