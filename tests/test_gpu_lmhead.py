@@ -41,6 +41,16 @@ def run_lm(hidden, w, *, row_idx=None, M=None, m_dev=None, forbid=-1, inv_t=1.0,
     return out
 
 
+def compare_prefix(got, ref, m):
+    """The first m outputs against the oracle's; the rest must be untouched.  Few rows: confidences only."""
+    if m >= 20:
+        compare({k: v[:m] for k, v in got.items()}, {k: v[:m] for k, v in ref.items() if k != "zt"})
+    elif m > 0:
+        assert np.abs(got["conf"][:m].astype(np.float64) - ref["conf"][:m]).max() <= CONF_TOL
+        assert np.abs(got["lse"][:m] - ref["lse"][:m]).max() <= Z_TOL
+    assert np.all(np.isnan(got["conf"][m:])) and np.all(got["tok"][m:] == -7)
+
+
 def compare(got, ref, sel=None):
     """got arrays indexed by output slot; ref from the oracle in the same order (sel picks got's slots)."""
     g = {k: (v if sel is None else v[sel]) for k, v in got.items()}
@@ -142,6 +152,30 @@ def test_gather_mdev_target_on_the_ring_shapes(R, n_sel, variant):
         dlm.set_option("lmhead_variant", -1)
     compare({k: v[:m] for k, v in got.items()}, {k: v[:m] for k, v in ref.items() if k != "zt"})
     assert np.all(np.isnan(got["conf"][m:])) and np.all(got["tok"][m:] == -7)
+    # far fewer rows on the device than the host's bound: most row tiles of the launch are dead (their wavefronts
+    # only take part in the loads and barriers), down to one row and to none
+    dlm.set_option("lmhead_variant", variant)
+    try:
+        for m in (n_sel // 2, 33, 1, 0):
+            compare_prefix(run_lm(h, w, row_idx=idx, M=n_sel, m_dev=m, inv_t=1.3, forbid=777), ref, m)
+    finally:
+        dlm.set_option("lmhead_variant", -1)
+
+
+@pytest.mark.parametrize("bound,variant", [(100, 3), (128, 3), (192, 4), (250, 5), (256, 21)])
+def test_device_row_count_below_the_bound_in_row_split_shapes(bound, variant):
+    """Shapes whose wavefronts split the rows run one copy of their loop per count of live row tiles."""
+    Dh, V = 320, 900
+    h, w = rnd(51 + bound, (bound, Dh)), rnd(52 + bound, (V, Dh), Dh ** -0.25)
+    ref = oracle.lmhead(h, w, forbid_token=V - 1)
+    dlm.set_option("lmhead_variant", variant)
+    try:
+        for m in sorted({bound, bound - 31, bound - 32, bound // 2 + 1, 65, 64, 33, 32, 1}, reverse=True):
+            if m < 1 or m > bound:
+                continue
+            compare_prefix(run_lm(h, w, M=bound, m_dev=m, forbid=V - 1), ref, m)
+    finally:
+        dlm.set_option("lmhead_variant", -1)
 
 
 def test_non_temporal_w_stream_changes_nothing():
