@@ -41,10 +41,12 @@ def parse():
     ap.add_argument("--sync-loop", action="store_true", help="poll every step synchronously (no one-step-late poll)")
     ap.add_argument("--dump-steps", default=None, metavar="FILE",
                     help="write one line per timed step: block, rows masked before / after, row bound, LM-head us")
-    ap.add_argument("--kernel", default=None, choices=["lmhead", "attn_fullseq"],
+    ap.add_argument("--kernel", default=None, choices=["lmhead", "attn_fullseq", "fullpass"],
                     help="time ONE kernel on random inputs instead of the rollout (record only, for profiles): "
                          "lmhead = dlm_lmhead_confidence at --rows rows on the config's W shape; attn_fullseq = "
-                         "dlm_block_attn (and, with --backward, dlm_block_attn_bwd) on 64 x 4096 tokens, 32/8 heads, d = 128")
+                         "dlm_block_attn (and, with --backward, dlm_block_attn_bwd) on 64 x 4096 tokens, 32/8 heads, d = 128; "
+                         "fullpass = one full-sequence block-diffusion pass of workload c5b (attention, row compaction, "
+                         "LM head on the masked rows, one commit per block of 4), each part timed")
     ap.add_argument("--rows", type=int, default=8192, help="--kernel lmhead: number of hidden rows M")
     ap.add_argument("--lmhead-variant", default="-1", help="--kernel lmhead: comma-separated entries of the shape table (-1 = planner)")
     ap.add_argument("--zeros", action="store_true", help="--kernel lmhead: all-zero operands (no data-dependent power)")
@@ -95,6 +97,54 @@ def micro(args):
                               "tflops": round(2.0 * M * V * Dh / ms / 1e9, 1),
                               "w_stream_gbs": round(V * Dh * 2 / ms / 1e6, 1)}), flush=True)
         dlm.set_option("lmhead_variant", -1)
+        return
+    if args.kernel == "fullpass":
+        cfg = synth.FULLPASS["c5b"]
+        B, L = cfg.B, cfg.L
+        rb = lambda *shape, std=1.0: (torch.randn(*shape, device=dev) * std).to(torch.bfloat16)
+        w = rb(cfg.V, cfg.Dh, std=cfg.Dh ** -0.25)
+        q, k, v = rb(B, L, cfg.Hq, cfg.d), rb(B, cfg.Hkv, L, cfg.d), rb(B, cfg.Hkv, L, cfg.d)
+        hid = rb(B * L, cfg.Dh)
+        out = torch.empty_like(q)
+        mask0 = (torch.rand(B, L, device=dev) < 0.5).to(torch.uint8)     # Bernoulli(0.5) masking
+        mask = mask0.clone()
+        row_idx = torch.zeros(B * L, dtype=torch.int32, device=dev)
+        m_dev = torch.zeros(1, dtype=torch.int32, device=dev)
+        dlm.mask_compact(mask, row_idx, m_dev)
+        torch.cuda.synchronize()
+        M = int(m_dev.item())
+        conf = torch.zeros(B, L, device=dev)
+        tok = torch.zeros(B, L, dtype=torch.int32, device=dev)
+        x = torch.zeros(B, L, dtype=torch.int32, device=dev)
+        n_commit = torch.zeros(B, dtype=torch.int32, device=dev)
+        remaining = torch.zeros(B, dtype=torch.int32, device=dev)
+        ws = torch.empty(dlm.lmhead_workspace_bytes(M, cfg.V), dtype=torch.uint8, device=dev)
+        pairs = (L // cfg.bs) * (L // cfg.bs + 1) // 2 * cfg.bs * cfg.bs
+
+        def commit():
+            mask.copy_(mask0)
+            dlm.unmask_commit(conf, tok, x, mask, n_commit, remaining, x_pos0=0, group_len=cfg.bs,
+                              rule=dlm.RULE_THRESHOLD, threshold=cfg.tau)
+
+        parts = [("dlm_block_attn", lambda: dlm.block_attn(q, out, block=(k, v, 0), mask_mode=dlm.MASK_BLOCK_CAUSAL,
+                                                            block_size=cfg.bs, q_pos0=0), 4.0 * B * cfg.Hq * cfg.d * pairs),
+                 ("dlm_mask_compact", lambda: dlm.mask_compact(mask0, row_idx, m_dev), 0.0),
+                 ("dlm_lmhead_confidence", lambda: dlm.lmhead_confidence(hid, w, conf, tok, row_idx=row_idx, M=M,
+                                                                         forbid_token=cfg.V - 1, out_scatter=True,
+                                                                         workspace=ws), 2.0 * M * cfg.V * cfg.Dh),
+                 ("dlm_unmask_commit (incl. a mask reset copy)", commit, 0.0)]
+        total = 0.0
+        for name, fn, flop in parts:
+            ms = timed(fn, args.reps)
+            total += ms
+            rec = {"kernel": name, "workload": "c5b full pass", "ms": round(ms, 3)}
+            if flop:
+                rec["tflops"] = round(flop / ms / 1e9, 1)
+            if name == "dlm_lmhead_confidence":
+                rec["M"] = M
+            print(json.dumps(rec), flush=True)
+        print(json.dumps({"kernel": "whole pass", "workload": "c5b full pass", "ms": round(total, 2),
+                          "positions": B * L, "masked": M}), flush=True)
         return
     B, L, Hq, Hkv, d, bs = args.batch, 4096, 32, 8, 128, 4
     mk = lambda *shape: torch.randn(shape, device=dev).bfloat16()
