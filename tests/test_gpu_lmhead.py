@@ -193,6 +193,30 @@ def test_non_temporal_w_stream_changes_nothing():
         dlm.set_option("lmhead_nt", 2)
 
 
+def test_extreme_logits_and_tiny_vocabularies():
+    """Logits of magnitude ~500 (max-subtracted soft-max must not overflow), a vocabulary of one token, and one of
+    two tokens with one of them forbidden (confidence exactly 1)."""
+    Dh = 128
+    h = synth.f32_to_bf16_bits(np.random.default_rng(1).normal(size=(70, Dh)).astype(np.float32) * 6.0)
+    w = synth.f32_to_bf16_bits(np.random.default_rng(2).normal(size=(500, Dh)).astype(np.float32) * 6.0)
+    ref = oracle.lmhead(h, w, forbid_token=3)
+    assert np.abs(ref["zmax"]).max() > 300
+    got = run_lm(h, w, forbid=3)
+    assert np.all(np.isfinite(got["conf"])) and np.all(np.isfinite(got["lse"]))
+    clear = (ref["zmax"] - ref["z2nd"]) >= 1e-1
+    assert np.array_equal(got["tok"][clear], ref["tok"][clear])
+    assert np.abs(got["conf"] - ref["conf"])[clear].max() <= 2e-2      # |logit| ~ 500 at bf16-product precision
+    assert np.abs(got["lse"] - ref["lse"]).max() <= 1e-3 * np.abs(ref["lse"]).max()
+    for V, forbid in ((1, -1), (2, 1), (2, 0)):
+        w1 = rnd(7 + V, (V, Dh), 0.3)
+        got = run_lm(rnd(8, (40, Dh)), w1, forbid=forbid)
+        want_tok = 0 if forbid != 0 else 1
+        assert np.all(got["tok"] == want_tok)
+        if V == 1 or forbid >= 0:
+            assert np.allclose(got["conf"], 1.0, atol=1e-6)
+            assert np.all(got["z2nd"] == -np.inf)
+
+
 def test_ties_pick_lowest_index():
     Dh, V = 64, 700
     h = synth.f32_to_bf16_bits(np.ones((40, Dh), np.float32))
