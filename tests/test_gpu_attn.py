@@ -138,6 +138,24 @@ def test_rerun_is_bitwise_identical():
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
 
 
+@pytest.mark.parametrize("Lq,Hq,Hkv", [(8, 4, 4), (64, 8, 2)])
+def test_peaked_softmax_large_scores(Lq, Hq, Hkv):
+    """Scores of magnitude ~50 (Q and K four times the usual scale): nearly one-hot rows, the running maximum
+    jumps by far more than the lazy-rescale threshold from tile to tile."""
+    B, d, P = 2, 128, 300
+    q = synth.f32_to_bf16_bits(np.random.default_rng(3).normal(size=(B, Lq, Hq, d)).astype(np.float32) * 4.0)
+    k = synth.f32_to_bf16_bits(np.random.default_rng(4).normal(size=(B, Hkv, P, d)).astype(np.float32) * 4.0)
+    v = rnd(305, (B, Hkv, P, d))
+    ref, ref_lse = oracle.attention(q, [KV(k, v, 0)])
+    out = torch.full((B, Lq, Hq, d), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lse = torch.full((B, Hq, Lq), float("nan"), dtype=torch.float32, device=DEV)
+    dlm.block_attn(bf16_dev(q), out, prefix=(bf16_dev(k), bf16_dev(v), 0), lse=lse)
+    torch.cuda.synchronize()
+    assert np.abs(ref_lse).max() > 50
+    assert attn_rel_err(bf16_host(out), ref) <= TOL
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() <= 1e-4 * np.abs(ref_lse).max() + LSE_TOL
+
+
 def test_non_temporal_kv_stream_changes_nothing():
     """g * Lq <= 32: one workgroup reads its K/V once, with non-temporal loads unless the option turns that off."""
     B, Lq, Hq, Hkv, d, P = 2, 8, 8, 2, 128, 500
