@@ -1,0 +1,53 @@
+"""Seeded random problem shapes through the planner's own choices, against the oracle (GPU).
+
+The hand-picked cases elsewhere aim at known tile and segment boundaries; these walk the space between them."""
+import numpy as np
+import pytest
+
+import oracle
+from test_gpu_attn import run_case
+from test_gpu_lmhead import compare_prefix, rnd, run_lm
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("seed", range(28))
+def test_attention_random_shape(seed):
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    g = int(rng.choice([1, 2, 4, 7]))
+    B = int(rng.integers(1, 4))
+    Lq = int(rng.choice([1, 3, 8, 31, 32, 33, 50, 96, 130]))
+    P = int(rng.choice([0, 1, 31, 32, 33, 100, 257]))
+    S = int(rng.choice([0, 0, 7, 64]))
+    mode = str(rng.choice(["full", "block_causal"]))
+    bs = int(rng.choice([1, 4, 8, 32])) if mode == "block_causal" else 0
+    plen = None
+    if P > 0 and rng.random() < 0.3:
+        plen = [int(x) for x in rng.integers(0, P + 1, size=B)]
+    # block-causal with a suffix: the suffix lies in later blocks and is hidden, which is fine
+    run_case(B=B, Lq=Lq, Hq=Hkv * g, Hkv=Hkv, d=d, P=P, Lb=Lq, S=S, mode=mode, bs=bs, plen=plen, seed=2000 + seed)
+
+
+@pytest.mark.parametrize("seed", range(28))
+def test_lmhead_random_shape(seed):
+    rng = np.random.default_rng(3000 + seed)
+    R = int(rng.choice([1, 7, 32, 33, 64, 65, 97, 128, 129, 193, 250, 257, 300, 385, 520, 700]))
+    Dh = 64 * int(rng.integers(1, 7))
+    V = int(rng.choice([1, 2, 127, 128, 129, 255, 256, 257, 1000, 2500]))
+    h, w = rnd(4000 + seed, (R, Dh)), rnd(5000 + seed, (V, Dh), Dh ** -0.25)
+    forbid = int(rng.integers(0, V)) if (V > 1 and rng.random() < 0.7) else -1
+    inv_t = float(rng.choice([1.0, 0.6, 1.7]))
+    idx = None
+    if rng.random() < 0.5 and R > 3:
+        idx = np.array(sorted(rng.permutation(R)[:max(1, R - int(rng.integers(0, R // 2 + 1)))]), np.int32)
+    n = R if idx is None else len(idx)
+    ref = oracle.lmhead(h, w, row_idx=idx, inv_temperature=inv_t, forbid_token=forbid)
+    m = int(rng.integers(0, n + 1)) if rng.random() < 0.5 else n
+    got = run_lm(h, w, row_idx=idx, M=n, m_dev=m, inv_t=inv_t, forbid=forbid)
+    if V >= 100:
+        compare_prefix(got, ref, m)
+    else:   # tiny vocabularies: few rows clear the top-2 margin that the token comparison asks for
+        assert np.abs(got["conf"][:m].astype(np.float64) - ref["conf"][:m]).max(initial=0.0) <= 1e-3
+        assert np.all(np.isnan(got["conf"][m:])) and np.all(got["tok"][m:] == -7)
