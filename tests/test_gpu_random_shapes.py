@@ -51,3 +51,20 @@ def test_lmhead_random_shape(seed):
     else:   # tiny vocabularies: few rows clear the top-2 margin that the token comparison asks for
         assert np.abs(got["conf"][:m].astype(np.float64) - ref["conf"][:m]).max(initial=0.0) <= 1e-3
         assert np.all(np.isnan(got["conf"][m:])) and np.all(got["tok"][m:] == -7)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_attention_backward_random_shape(seed):
+    from test_gpu_attn_bwd import check, make
+    rng = np.random.default_rng(6000 + seed)
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    g = int(rng.choice([1, 2, 4, 7]))
+    B = int(rng.integers(1, 3))
+    Lq = int(rng.choice([1, 5, 31, 32, 33, 65, 100, 130]))
+    P = int(rng.choice([0, 1, 33, 64, 150]))
+    S = int(rng.choice([0, 0, 9, 40]))
+    mode = str(rng.choice(["full", "block_causal"]))
+    bs = int(rng.choice([1, 4, 8, 32])) if mode == "block_causal" else 0
+    q, segs, d_out = make(B, Lq, Hkv * g, Hkv, d, (P, Lq, S), seed=7000 + 10 * seed)
+    check(q, segs, d_out, mode=mode, bs=bs, q_pos0=P)
