@@ -42,7 +42,7 @@ struct AttnParams {
     float* lse;
     const int32_t* cu;  // packed variable-length mode: sequence b owns tokens [cu[b], cu[b+1])
     int total;          // cu[B]
-    int remap_nx;       // > 0: 1-D grid; the remap_nx row tiles of one (sequence, KV head) get consecutive slots of one XCD
+    GridRemap remap;
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
@@ -73,13 +73,9 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     const int wr = w % NWR, wk = w / NWR;
     const int n = lane & 31, hi = lane >> 5;
     int b = blockIdx.z, kvh = blockIdx.y, bx = blockIdx.x;
-    if (p.remap_nx > 0) {
-        // Workgroups go round-robin to the 8 XCDs.  Row tiles of one (sequence, KV head) read the same K/V, so they
-        // are given consecutive slots of ONE XCD: K/V then comes from HBM once and the other tiles hit that L2.
-        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        const int grp = xcd + 8 * (slot / p.remap_nx);
-        if (grp >= p.B * p.Hkv) return;
-        bx = slot % p.remap_nx;
+    if (p.remap.nx > 0) {
+        int grp;
+        if (!remap_decode(p.remap, p.B * p.Hkv, grp, bx)) return;
         kvh = grp % p.Hkv;
         b = grp / p.Hkv;
     }
@@ -547,6 +543,7 @@ _Pragma("unroll") \
 
 int g_attn_nt = 1;       // 1 = non-temporal K/V loads in the one-workgroup-per-KV-head shape (default); 0 = never (tuning)
 int g_attn_variant = 0;  // 0 = choose by shape; 1..3 force a kernel shape (dlm_set_option "attn_variant")
+int g_attn_remap = 7;    // XCD-grouped grids: bit 0 forward and dQ, bit 1 longest key range first, bit 2 dK / dV (dlm_set_option "attn_remap")
 
 template <int D, bool BC>
 static int launch_attn(const AttnParams& p, hipStream_t st) {
@@ -563,9 +560,8 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
     if (variant == 0 + 11 || (variant == 1 && p.R > 32)) {
         // 32-row workgroups whose wavefronts split the keys, several row tiles per (sequence, KV head), XCD-grouped
         AttnParams q = p;
-        q.remap_nx = (p.R + 31) / 32;
-        const int64_t n_wg = (BH + 7) / 8 * 8 * q.remap_nx;
-        if (n_wg <= 0x7fffffff) {
+        const int64_t n_wg = set_remap(q.remap, BH, (p.R + 31) / 32, BC && (g_attn_remap & 2));
+        if (n_wg > 0) {
             hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1>), dim3((unsigned)n_wg), dim3(256), 0, st, q);
             return check_hip(hipGetLastError(), "attn_kernel launch");
         }
@@ -580,11 +576,17 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
     }
     if (variant >= 8) variant = 0 + 4;
     if (variant >= 4) {   // 128-row workgroups, several resident per CU
-        const dim3 grid((p.R + 127) / 128, p.Hkv, p.B);
-        if (variant == 4) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 2, 2>), grid, dim3(256), 0, st, p);
-        else if (variant == 5) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 2, 3>), grid, dim3(256), 0, st, p);
-        else if (variant == 6) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 1, 3>), grid, dim3(256), 0, st, p);
-        else hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 1, 4>), grid, dim3(256), 0, st, p);
+        dim3 grid((p.R + 127) / 128, p.Hkv, p.B);
+        AttnParams q = p;
+        if ((g_attn_remap & 1) && grid.x >= 2) {
+            const int64_t n_wg = set_remap(q.remap, BH, (int)grid.x, BC && (g_attn_remap & 2));
+            if (n_wg > 0) grid = dim3((unsigned)n_wg);
+            else q = p;
+        }
+        if (variant == 4) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 2, 2>), grid, dim3(256), 0, st, q);
+        else if (variant == 5) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 2, 3>), grid, dim3(256), 0, st, q);
+        else if (variant == 6) hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 1, 3>), grid, dim3(256), 0, st, q);
+        else hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 1, 4>), grid, dim3(256), 0, st, q);
         return check_hip(hipGetLastError(), "attn_kernel launch");
     }
     if (variant == 1) {
@@ -667,6 +669,11 @@ extern "C" int dlm_set_option(const char* name, int value) {
     if (!strcmp(name, "lmhead_variant")) return lm_set_variant(value);
     if (!strcmp(name, "lmhead_block")) return lm_set_block(value);
     if (!strcmp(name, "lmhead_nt")) return lm_set_nt(value);
+    if (!strcmp(name, "attn_remap")) {
+        if (value < 0 || value > 7) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_remap must be 0..7");
+        g_attn_remap = value;
+        return DLM_OK;
+    }
     if (!strcmp(name, "attn_nt")) {
         if (value < 0 || value > 1) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_nt must be 0 or 1");
         g_attn_nt = value;
@@ -701,7 +708,7 @@ extern "C" int dlm_block_attn(const dlm_attn_args* a, void* stream) {
     p.out = (uint16_t*)a->out; p.o_sb = a->o_stride_b; p.o_st = a->o_stride_t; p.o_sh = a->o_stride_h;
     p.lse = a->lse;
     p.cu = a->cu_seqlens; p.total = a->total_tokens;
-    p.remap_nx = 0;
+    p.remap = no_remap();
     hipStream_t st = (hipStream_t)stream;
     const bool bc = a->mask_mode == DLM_MASK_BLOCK_CAUSAL;
     if (a->d == 128) return bc ? launch_attn<128, true>(p, st) : launch_attn<128, false>(p, st);

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(BwdParams p) {
 
 // ---------------------------------------------------------------------------------------------------------
 template <int D, bool BC>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(BwdParams p) {
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(BwdParams p, GridRemap rm) {
     constexpr int KP = D * 2 + 16;         // row-read image pitch (bytes)
     constexpr int TP = D * 2 + 64;         // transposing-read image pitch
     constexpr int C8 = D / 8;
@@ -109,8 +109,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(BwdParams p) {
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n = lane & 31, hi = lane >> 5;
-    const int b = blockIdx.z, kvh = blockIdx.y;
-    const int r0 = blockIdx.x * 128;
+    int b = blockIdx.z, kvh = blockIdx.y, bx0 = blockIdx.x;
+    if (rm.nx > 0) {
+        int grp;
+        if (!remap_decode(rm, p.B * p.Hkv, grp, bx0)) return;
+        kvh = grp % p.Hkv;
+        b = grp / p.Hkv;
+    }
+    const int r0 = bx0 * 128;
 
     int len0 = p.seg[0].len, len1 = p.seg[1].len, len2 = p.seg[2].len;
     int R = p.R, s0 = 0;
@@ -334,7 +340,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(BwdParams p) {
 // V fragments leaves one wavefront per SIMD or spills, and either way every tile waits out the full memory
 // latency; apart, the passes keep two to three workgroups per CU with nothing spilled.  Price: S is formed twice.
 template <int D, bool BC, bool DK>
-__global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams p, int sidx, int n_slabs, int pair) {
+__global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams p, int sidx, int n_slabs, int pair, GridRemap rm) {
     constexpr int KP = D * 2 + 16;
     constexpr int TP = D * 2 + 64;
     constexpr int C8 = D / 8;
@@ -351,7 +357,13 @@ __global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n = lane & 31, hi = lane >> 5;
-    const int b = blockIdx.z, kvh = blockIdx.y;
+    int b = blockIdx.z, kvh = blockIdx.y, bx = blockIdx.x;
+    if (rm.nx > 0) {
+        int grp;
+        if (!remap_decode(rm, p.B * p.Hkv, grp, bx)) return;
+        kvh = grp % p.Hkv;
+        b = grp / p.Hkv;
+    }
     // plain locals per segment field (a dynamically indexed struct member would go through memory)
     const uint16_t* sk = (sidx == 0) ? p.seg[0].k : ((sidx == 1) ? p.seg[1].k : p.seg[2].k);
     const uint16_t* sv = (sidx == 0) ? p.seg[0].v : ((sidx == 1) ? p.seg[1].v : p.seg[2].v);
@@ -381,7 +393,6 @@ __global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams
     // of work and the workgroups of one (sequence, KV head) stay in step on the same Q / dO tiles (L2 reuse).
     // pair == 0: one slab per workgroup; every second group of 8 slabs is taken in reverse so that the 8 XCDs,
     // which get workgroups round-robin, receive equal sums.
-    const int bx = blockIdx.x;
     for (int pass = 0; pass < (pair ? 2 : 1); ++pass) {
     int slab = bx;
     if (pair) {
@@ -524,11 +535,16 @@ __global__ __launch_bounds__(256, DK ? 2 : 3) void attn_bwd_dkv_kernel(BwdParams
 
     // Row tiles are walked from the last one down: under a block-causal mask the workgroups of one (sequence,
     // KV head) differ in where their range BEGINS, so this way they all start on the same tile and stay in step.
-    if (rt_begin < rt_end) BW_FETCH_ROWS(rt_end - 1);
-    for (int rt = rt_end - 1; rt >= rt_begin; --rt) {
+    // The second slab of a pair is walked upwards: its range begins where the first slab's walk ended (slab x ends
+    // after n - x steps, slab n - 1 - x begins at tile n - 1 - x), so at any time all the workgroups of the group
+    // that are in their second pass are on one tile again, whatever their x.
+    const bool up = pair && pass;
+    if (rt_begin < rt_end) BW_FETCH_ROWS(up ? rt_begin : rt_end - 1);
+    for (int it = 0; it < rt_end - rt_begin; ++it) {
+        const int rt = up ? rt_begin + it : rt_end - 1 - it;
         BW_STORE_ROWS(rt);
         __syncthreads();
-        BW_FETCH_ROWS(max(rt - 1, rt_begin));     // unconditional (clamped) prefetch of the next tile
+        BW_FETCH_ROWS(up ? min(rt + 1, rt_end - 1) : max(rt - 1, rt_begin));     // unconditional (clamped) prefetch of the next tile
         f32x16 S, dP;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -630,7 +646,14 @@ static int launch_bwd(const BwdParams& p, hipStream_t st) {
     int rc = check_hip(hipGetLastError(), "attn_bwd_delta_kernel launch");
     if (rc != DLM_OK) return rc;
     if (p.dq) {
-        hipLaunchKernelGGL((attn_bwd_dq_kernel<D, BC>), dim3((p.R + 127) / 128, p.Hkv, p.B), dim3(256), 0, st, p);
+        dim3 grid((p.R + 127) / 128, p.Hkv, p.B);
+        GridRemap rm = no_remap();
+        if ((g_attn_remap & 1) && grid.x >= 2) {
+            const int64_t n_wg = set_remap(rm, (int64_t)p.B * p.Hkv, (int)grid.x, BC && (g_attn_remap & 2));
+            if (n_wg > 0) grid = dim3((unsigned)n_wg);
+            else rm = no_remap();
+        }
+        hipLaunchKernelGGL((attn_bwd_dq_kernel<D, BC>), grid, dim3(256), 0, st, p, rm);
         rc = check_hip(hipGetLastError(), "attn_bwd_dq_kernel launch");
         if (rc != DLM_OK) return rc;
     }
@@ -639,9 +662,15 @@ static int launch_bwd(const BwdParams& p, hipStream_t st) {
         const int n_slabs = (p.seg[s].len + 127) / 128;
         // equal-work pairing where the mask makes slabs unequal (not for "own block only": every slab sees one block's rows)
         const int pair = (BC && p.seg[s].rule != DLM_SEG_SAME_BLOCK && n_slabs >= 4) ? 1 : 0;
-        const dim3 grid(pair ? (n_slabs + 1) / 2 : n_slabs, p.Hkv, p.B);
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, false>), grid, dim3(256), 0, st, p, s, n_slabs, pair);
-        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, true>), grid, dim3(256), 0, st, p, s, n_slabs, pair);
+        dim3 grid(pair ? (n_slabs + 1) / 2 : n_slabs, p.Hkv, p.B);
+        GridRemap rm = no_remap();
+        if ((g_attn_remap & 4) && grid.x >= 2) {
+            const int64_t n_wg = set_remap(rm, (int64_t)p.B * p.Hkv, (int)grid.x, false);
+            if (n_wg > 0) grid = dim3((unsigned)n_wg);
+            else rm = no_remap();
+        }
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, false>), grid, dim3(256), 0, st, p, s, n_slabs, pair, rm);
+        hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, true>), grid, dim3(256), 0, st, p, s, n_slabs, pair, rm);
         rc = check_hip(hipGetLastError(), "attn_bwd_dkv_kernel launch");
         if (rc != DLM_OK) return rc;
     }
