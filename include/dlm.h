@@ -358,6 +358,10 @@ int dlm_kv_refresh(const dlm_kv_seg *src, int32_t B, int32_t Hkv, int32_t d,
  *                   loads (default); 0 = never.
  *   "attn_nt"       1 = non-temporal K/V loads when one workgroup is the only reader of its (sequence, KV head)
  *                   (g*Lq <= 32; default); 0 = never.
+ *   "attn_remap"    bit mask, default 7: 1 = 128-row workgroups of one (sequence, KV head) run on ONE XCD (1-D
+ *                   grid; forward and the dQ pass), 2 = under a block-causal mask the row tile with the longest
+ *                   key range is dispatched first, 4 = the same grouping for the dK / dV passes; 0 = plain
+ *                   (tile, KV head, sequence) grids.
  * Every shape computes the same function; the knobs exist for tests and tuning sweeps. */
 int dlm_set_option(const char *name, int value);
 

@@ -173,6 +173,31 @@ def test_non_temporal_kv_stream_changes_nothing():
     assert attn_rel_err(bf16_host(o1), ref) <= TOL
 
 
+@pytest.mark.parametrize("B,Hkv,g,Lq", [(1, 1, 2, 300), (1, 3, 4, 130), (2, 2, 1, 700), (4, 2, 2, 129), (3, 4, 2, 257)])
+@pytest.mark.parametrize("variant", [4, 6, 11])
+def test_xcd_grouped_grid_covers_every_tile_once(B, Hkv, g, Lq, variant):
+    """Group counts 1, 3, 4, 8, 12 (tiles of a group dealt to 8, 8, 2, 1, 2 XCDs) and ragged tile counts, both masks:
+    the 1-D grid must produce what the plain (tile, KV head, sequence) grid does, bit for bit, and the oracle's result."""
+    d, P = 64, 40
+    for mode, bs in (("full", 0), ("block_causal", 8)):
+        run_case(B=B, Lq=Lq, Hq=Hkv * g, Hkv=Hkv, d=d, P=P, Lb=Lq, S=0, mode=mode, bs=bs, variant=variant, seed=900 + Lq)
+        q = bf16_dev(rnd(9001, (B, Lq, Hkv * g, d)))
+        k, v = bf16_dev(rnd(9002, (B, Hkv, Lq, d))), bf16_dev(rnd(9003, (B, Hkv, Lq, d)))
+        outs = []
+        dlm.set_option("attn_variant", variant)
+        try:
+            for remap in (7, 1, 0):
+                dlm.set_option("attn_remap", remap)
+                o = torch.full_like(q, float("nan"))
+                dlm.block_attn(q, o, block=(k, v, 0), mask_mode=dlm.MASK_BLOCK_CAUSAL if bs else dlm.MASK_FULL, block_size=bs)
+                torch.cuda.synchronize()
+                outs.append(o.view(torch.int16))
+        finally:
+            dlm.set_option("attn_remap", 7)
+            dlm.set_option("attn_variant", 0)
+        assert torch.equal(outs[0], outs[2]) and torch.equal(outs[1], outs[2])
+
+
 @pytest.mark.parametrize("variant", [0, 1, 2])
 def test_planted_one_hot_values_expose_every_key(variant):
     """V[j] = e_(j mod d): output channel c is the total probability of keys j = c (mod d), so a

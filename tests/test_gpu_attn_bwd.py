@@ -186,3 +186,21 @@ def test_full_size_training_shape_sampled_against_oracle():
     gq, gk, gv = bf16_host(dq)[b:b + 1, :, hs], bf16_host(dk)[b:b + 1, kvh:kvh + 1], bf16_host(dv)[b:b + 1, kvh:kvh + 1]
     assert max(attn_rel_err(gq, rq), attn_rel_err(gk, rk), attn_rel_err(gv, rv)) <= TOL
     assert max(fro_err(gq, rq), fro_err(gk, rk), fro_err(gv, rv)) <= FRO_TOL
+
+
+@pytest.mark.parametrize("B,Hkv,g,L", [(1, 1, 2, 600), (1, 3, 4, 300), (4, 2, 2, 520)])
+def test_xcd_grouped_grids_give_the_plain_grids_bits(B, Hkv, g, L):
+    """Group counts 1, 3, 8: the 1-D grids of the dQ and dK / dV passes against the plain ones, bit for bit, and the
+    oracle's gradients; 520 and 600 keys make 5 slabs, so block-causal slabs are paired (second one walked upwards)."""
+    for mode, bs in (("full", 0), ("block_causal", 8)):
+        q, segs, d_out = make(B, L, Hkv * g, Hkv, 64, (0, L, 0), seed=1200 + L)
+        res = []
+        try:
+            for remap in (7, 0):
+                dlm.set_option("attn_remap", remap)
+                res.append(run_bwd(q, segs, d_out, mode=mode, bs=bs))
+        finally:
+            dlm.set_option("attn_remap", 7)
+        assert np.array_equal(res[0][0], res[1][0])
+        assert np.array_equal(res[0][1][1][0], res[1][1][1][0]) and np.array_equal(res[0][1][1][1], res[1][1][1][1])
+        check(q, segs, d_out, mode=mode, bs=bs)
