@@ -58,6 +58,7 @@ extern "C" {
 #define DLM_WB_NONE            0
 #define DLM_WB_BLOCK_WHEN_DONE 1    /* copy the whole block's K/V when a sequence's last masked position commits */
 #define DLM_WB_COMMITTED_ROWS  2    /* copy the K/V rows of the positions committed by this call */
+#define DLM_WB_WHILE_ACTIVE    3    /* copy the whole block's K/V for every sequence that entered this call with masked positions */
 
 /* Which blocks of a segment a query may see under DLM_MASK_BLOCK_CAUSAL (kb, qb = block index of key, query) */
 #define DLM_SEG_CAUSAL         0    /* kb <= qb: the query's block and every earlier one                */
@@ -277,7 +278,14 @@ size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args *args);
  *               cache_k / cache_v (bf16, strides c_stride_*) at rows cache_pos0 + t.
  *               BLOCK_WHEN_DONE: all rows, for sequences whose remaining becomes 0 in this
  *               call with n_commit > 0.  COMMITTED_ROWS: row i for each committed i
- *               (needs src_block.len == n_pos).
+ *               (needs src_block.len == n_pos).  WHILE_ACTIVE: all rows, for sequences with
+ *               active_in[b] != 0.  Called on every step of a block with active_in = the previous step's
+ *               `remaining` (a DIFFERENT buffer from this call's `remaining` and `n_commit`: the copy reads
+ *               it while the selection writes those), the cache ends up holding each sequence's
+ *               final-step K/V exactly as with BLOCK_WHEN_DONE, but the copy needs nothing this call
+ *               computes, so on the single-workgroup path it runs inside the same launch, beside the
+ *               selection (one launch fewer per denoising step; block-sized extra writes per step).
+ *   active_in   int32 [B], WHILE_ACTIVE only (see above); ignored otherwise
  *   host_remaining_total  optional pointer to ONE int32 in pinned host memory that the device can
  *               address (hipHostMalloc): receives sum_b remaining[b] with a system-scope store, so a
  *               caller that records an event after the call can learn "block finished" without
@@ -312,6 +320,7 @@ typedef struct dlm_commit_args {
     int64_t c_stride_b, c_stride_h, c_stride_t;
     int32_t cache_pos0, Hkv, d;
     int32_t *host_remaining_total;
+    const int32_t *active_in;
 } dlm_commit_args;
 
 int dlm_unmask_commit(const dlm_commit_args *args, void *stream);

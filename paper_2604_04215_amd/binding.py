@@ -19,7 +19,7 @@ DLM_OK, DLM_ERR_INVALID_ARG, DLM_ERR_UNSUPPORTED, DLM_ERR_WORKSPACE, DLM_ERR_HIP
 MASK_FULL, MASK_BLOCK_CAUSAL = 0, 1
 RULE_THRESHOLD, RULE_TOPK = 0, 1
 CONF_TOKEN_PROB, CONF_MARGIN, CONF_NEG_ENTROPY = 0, 1, 2
-WB_NONE, WB_BLOCK_WHEN_DONE, WB_COMMITTED_ROWS = 0, 1, 2
+WB_NONE, WB_BLOCK_WHEN_DONE, WB_COMMITTED_ROWS, WB_WHILE_ACTIVE = 0, 1, 2, 3
 
 EXPORTS = ["dlm_block_attn", "dlm_block_attn_workspace_bytes", "dlm_lmhead_confidence",
            "dlm_lmhead_workspace_bytes", "dlm_unmask_commit", "dlm_mask_compact", "dlm_kv_refresh",
@@ -85,7 +85,7 @@ class CommitArgs(C.Structure):
                 ("src_block", KvSeg), ("cache_k", C.c_void_p), ("cache_v", C.c_void_p),
                 ("c_stride_b", C.c_int64), ("c_stride_h", C.c_int64), ("c_stride_t", C.c_int64),
                 ("cache_pos0", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32),
-                ("host_remaining_total", C.c_void_p)]
+                ("host_remaining_total", C.c_void_p), ("active_in", C.c_void_p)]
 
 
 class DlmError(RuntimeError):
@@ -367,7 +367,7 @@ def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group
                   rule: int = RULE_THRESHOLD, threshold: float = 0.0, force_top1: bool = True, k: int = 0,
                   commit_now=None, next_row_idx=None, next_m=None, commit_step=None, step: int = 0,
                   writeback: int = WB_NONE, src_block: Optional[Tuple] = None, cache_k=None, cache_v=None,
-                  cache_pos0: int = 0, host_remaining_total=None, stream=None) -> None:
+                  cache_pos0: int = 0, host_remaining_total=None, active_in=None, stream=None) -> None:
     """conf fp32 / tok int32 dense [B, n_pos]; x int32 [B, L]; mask uint8 [B, n_pos] (row-strided views are fine).
     host_remaining_total: optional pinned CPU int32 tensor (1 element) the kernel writes through."""
     import torch
@@ -396,6 +396,10 @@ def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group
         a.cache_k, a.cache_v = _dev(cache_k, torch.bfloat16, "cache_k"), _dev(cache_v, torch.bfloat16, "cache_v")
         a.c_stride_b, a.c_stride_h, a.c_stride_t = cache_k.stride(0), cache_k.stride(1), cache_k.stride(2)
         a.cache_pos0, a.Hkv, a.d = int(cache_pos0), int(cache_k.shape[1]), int(cache_k.shape[3])
+        if active_in is not None:
+            if active_in.numel() != B or not active_in.is_contiguous():
+                raise ValueError("active_in must be contiguous [B]")
+            a.active_in = _dev(active_in, torch.int32, "active_in")
     if host_remaining_total is not None:
         if host_remaining_total.is_cuda or not host_remaining_total.is_pinned() or host_remaining_total.dtype != torch.int32:
             raise ValueError("host_remaining_total must be a pinned CPU int32 tensor")

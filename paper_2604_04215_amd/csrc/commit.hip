@@ -137,16 +137,52 @@ __global__ __launch_bounds__(256) void commit_wave_kernel(CommitParams p) {
     }
 }
 
+struct CopyParams {
+    const uint16_t *sk, *sv;
+    int64_t s_sb, s_sh, s_st;
+    uint16_t *ck, *cv;
+    int64_t c_sb, c_sh, c_st;
+    int len, d8;  // rows, 16-byte chunks per row
+    int cache_pos0;
+    // conditional write-back
+    int mode;  // 0 unconditional, DLM_WB_BLOCK_WHEN_DONE, DLM_WB_COMMITTED_ROWS, DLM_WB_WHILE_ACTIVE
+    const int32_t *n_commit, *remaining;
+    const uint8_t* commit_now;
+    int n_pos;
+    const int32_t* active_in;  // DLM_WB_WHILE_ACTIVE: copy sequence b iff active_in[b] != 0
+    int Hkv;
+};
+
 // Rollout-sized problems (one commit group per sequence, at most 16384 positions in all): ONE workgroup
 // selects for every sequence (a wavefront per sequence, 16 at a time), then compacts the still-masked rows
 // in order and publishes the total, so a denoising step needs a single small launch here.
 constexpr int FUSED_MAX_POS = 16384;
 template <int CH>
 __global__ __launch_bounds__(1024) void commit_fused_kernel(CommitParams p, int32_t* row_idx, int32_t* next_m,
-                                                            int32_t* host_total) {
+                                                            int32_t* host_total, CopyParams cp) {
     __shared__ uint8_t newmask[FUSED_MAX_POS];
     __shared__ int wave_tot[16];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (blockIdx.x > 0) {
+        // DLM_WB_WHILE_ACTIVE: workgroups 1.. copy the block's K/V of one (sequence, KV head) each.  They read
+        // nothing that workgroup 0 writes (active_in is the caller's copy of the previous step's counts), so the
+        // write-back shares the selection's launch instead of following it.
+        const int g = blockIdx.x - 1, b = g / cp.Hkv, h = g - b * cp.Hkv;
+        if (cp.active_in[b] == 0) return;
+        const uint16_t* sk = cp.sk + b * cp.s_sb + h * cp.s_sh;
+        const uint16_t* sv = cp.sv + b * cp.s_sb + h * cp.s_sh;
+        uint16_t* ck = cp.ck + b * cp.c_sb + h * cp.c_sh + (int64_t)cp.cache_pos0 * cp.c_st;
+        uint16_t* cv = cp.cv + b * cp.c_sb + h * cp.c_sh + (int64_t)cp.cache_pos0 * cp.c_st;
+        const int total = cp.len * cp.d8;
+        for (int e = tid; e < total; e += 1024) {
+            const int t = e / cp.d8, c = e - t * cp.d8;
+            const u32x4 kk = *reinterpret_cast<const u32x4*>(sk + t * cp.s_st + c * 8);
+            const u32x4 vv = *reinterpret_cast<const u32x4*>(sv + t * cp.s_st + c * 8);
+            *reinterpret_cast<u32x4*>(ck + t * cp.c_st + c * 8) = kk;
+            *reinterpret_cast<u32x4*>(cv + t * cp.c_st + c * 8) = vv;
+        }
+        return;
+    }
     for (int b = w; b < p.B; b += 16) {
         const int64_t base = (int64_t)b * p.n_pos;
         uint8_t* mrow = p.mask + b * p.mask_stride_b;
@@ -366,19 +402,6 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* mask, int6
     if (tid == 0) *m_out = running;
 }
 
-struct CopyParams {
-    const uint16_t *sk, *sv;
-    int64_t s_sb, s_sh, s_st;
-    uint16_t *ck, *cv;
-    int64_t c_sb, c_sh, c_st;
-    int len, d8;  // rows, 16-byte chunks per row
-    int cache_pos0;
-    // conditional write-back
-    int mode;  // 0 unconditional, DLM_WB_BLOCK_WHEN_DONE, DLM_WB_COMMITTED_ROWS
-    const int32_t *n_commit, *remaining;
-    const uint8_t* commit_now;
-    int n_pos;
-};
 
 template <int U>
 __global__ __launch_bounds__(256) void kv_copy_kernel(CopyParams p) {
@@ -386,6 +409,7 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(CopyParams p) {
     if (p.mode == DLM_WB_BLOCK_WHEN_DONE) {
         if (!(p.remaining[b] == 0 && p.n_commit[b] > 0)) return;
     }
+    if (p.mode == DLM_WB_WHILE_ACTIVE && p.active_in[b] == 0) return;
     const int64_t total = (int64_t)p.len * p.d8;
     const uint16_t* sk = p.sk + b * p.s_sb + h * p.s_sh;
     const uint16_t* sv = p.sv + b * p.s_sb + h * p.s_sh;
@@ -468,10 +492,9 @@ static int validate_seg_copy(const dlm_kv_seg* s, int B, int Hkv, int d, const v
     return DLM_OK;
 }
 
-static int launch_kv_copy(const dlm_kv_seg* s, int B, int Hkv, int d, void* ck, void* cv, int64_t c_sb, int64_t c_sh,
-                          int64_t c_st, int cache_pos0, int mode, const int32_t* n_commit, const int32_t* remaining,
-                          const uint8_t* commit_now, int n_pos, hipStream_t st) {
-    if (s->len == 0 || B == 0) return DLM_OK;
+static CopyParams copy_params(const dlm_kv_seg* s, int Hkv, int d, void* ck, void* cv, int64_t c_sb, int64_t c_sh,
+                              int64_t c_st, int cache_pos0, int mode, const int32_t* n_commit, const int32_t* remaining,
+                              const uint8_t* commit_now, int n_pos, const int32_t* active_in) {
     CopyParams p;
     p.sk = (const uint16_t*)s->k; p.sv = (const uint16_t*)s->v;
     p.s_sb = s->stride_b; p.s_sh = s->stride_h; p.s_st = s->stride_t;
@@ -479,6 +502,16 @@ static int launch_kv_copy(const dlm_kv_seg* s, int B, int Hkv, int d, void* ck, 
     p.c_sb = c_sb; p.c_sh = c_sh; p.c_st = c_st;
     p.len = s->len; p.d8 = d / 8; p.cache_pos0 = cache_pos0;
     p.mode = mode; p.n_commit = n_commit; p.remaining = remaining; p.commit_now = commit_now; p.n_pos = n_pos;
+    p.active_in = active_in; p.Hkv = Hkv;
+    return p;
+}
+
+static int launch_kv_copy(const dlm_kv_seg* s, int B, int Hkv, int d, void* ck, void* cv, int64_t c_sb, int64_t c_sh,
+                          int64_t c_st, int cache_pos0, int mode, const int32_t* n_commit, const int32_t* remaining,
+                          const uint8_t* commit_now, int n_pos, hipStream_t st, const int32_t* active_in = nullptr) {
+    if (s->len == 0 || B == 0) return DLM_OK;
+    const CopyParams p = copy_params(s, Hkv, d, ck, cv, c_sb, c_sh, c_st, cache_pos0, mode, n_commit, remaining, commit_now,
+                                     n_pos, active_in);
     const int64_t total = (int64_t)s->len * p.d8;
     if (Hkv > 65535 || B > 65535) return fail(DLM_ERR_UNSUPPORTED, "kv copy: B or Hkv above 65535");
     constexpr int U = 4;
@@ -539,7 +572,7 @@ extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
     if (a->rule == DLM_RULE_TOPK && a->k < 1) return fail(DLM_ERR_INVALID_ARG, "unmask_commit: top-k needs k >= 1");
     if (a->rule == DLM_RULE_THRESHOLD && !(a->threshold == a->threshold))
         return fail(DLM_ERR_INVALID_ARG, "unmask_commit: threshold is NaN");
-    if (a->writeback < DLM_WB_NONE || a->writeback > DLM_WB_COMMITTED_ROWS)
+    if (a->writeback < DLM_WB_NONE || a->writeback > DLM_WB_WHILE_ACTIVE)
         return fail(DLM_ERR_INVALID_ARG, "unmask_commit: unknown writeback mode %d", a->writeback);
     const int64_t N = (int64_t)a->B * a->n_pos;
     if (N > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "unmask_commit: more than 2^31 positions");
@@ -562,6 +595,13 @@ extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
             if (!a->commit_now && N > 0)
                 return fail(DLM_ERR_INVALID_ARG, "unmask_commit: COMMITTED_ROWS needs commit_now");
         }
+        if (a->writeback == DLM_WB_WHILE_ACTIVE) {
+            if (!a->active_in && a->B > 0) return fail(DLM_ERR_INVALID_ARG, "unmask_commit: WHILE_ACTIVE needs active_in");
+            if (a->active_in == a->remaining || a->active_in == a->n_commit)
+                return fail(DLM_ERR_INVALID_ARG, "unmask_commit: active_in must not alias remaining / n_commit");
+            if ((int64_t)a->B * a->Hkv >= 0x7fffffff || (int64_t)a->src_block.len * (a->d / 8) > 0x7fffffff)
+                return fail(DLM_ERR_UNSUPPORTED, "unmask_commit: B * Hkv or src_block.len * d too large");
+        }
     }
     hipStream_t st = (hipStream_t)stream;
     if (a->B == 0) return DLM_OK;
@@ -575,10 +615,18 @@ extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
     p.conf = a->conf; p.tok = a->tok; p.x = a->x; p.x_stride_b = a->x_stride_b; p.x_pos0 = a->x_pos0;
     p.mask = a->mask; p.mask_stride_b = a->mask_stride_b; p.commit_now = a->commit_now;
     p.n_commit = a->n_commit; p.remaining = a->remaining; p.commit_step = a->commit_step; p.step = a->step;
+    const bool wb_inside = fused && a->writeback == DLM_WB_WHILE_ACTIVE;   // the copy rides in the selection's launch
     if (fused) {
-        if (a->group_len <= 64) hipLaunchKernelGGL(commit_fused_kernel<1>, dim3(1), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total);
-        else if (a->group_len <= 256) hipLaunchKernelGGL(commit_fused_kernel<4>, dim3(1), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total);
-        else hipLaunchKernelGGL(commit_fused_kernel<16>, dim3(1), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total);
+        CopyParams cp = {};
+        unsigned grid = 1;
+        if (wb_inside) {
+            cp = copy_params(&a->src_block, a->Hkv, a->d, a->cache_k, a->cache_v, a->c_stride_b, a->c_stride_h, a->c_stride_t,
+                             a->cache_pos0, a->writeback, a->n_commit, a->remaining, a->commit_now, a->n_pos, a->active_in);
+            grid += (unsigned)(a->B * a->Hkv);
+        }
+        if (a->group_len <= 64) hipLaunchKernelGGL(commit_fused_kernel<1>, dim3(grid), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total, cp);
+        else if (a->group_len <= 256) hipLaunchKernelGGL(commit_fused_kernel<4>, dim3(grid), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total, cp);
+        else hipLaunchKernelGGL(commit_fused_kernel<16>, dim3(grid), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total, cp);
         int rc = check_hip(hipGetLastError(), "commit_fused_kernel launch");
         if (rc != DLM_OK) return rc;
     } else {
@@ -610,10 +658,10 @@ extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
             if (rc != DLM_OK) return rc;
         }
     }
-    if (a->writeback != DLM_WB_NONE && N > 0) {
+    if (a->writeback != DLM_WB_NONE && N > 0 && !wb_inside) {
         return launch_kv_copy(&a->src_block, a->B, a->Hkv, a->d, a->cache_k, a->cache_v, a->c_stride_b, a->c_stride_h,
                               a->c_stride_t, a->cache_pos0, a->writeback, a->n_commit, a->remaining, a->commit_now,
-                              a->n_pos, st);
+                              a->n_pos, st, a->active_in);
     }
     return DLM_OK;
 }

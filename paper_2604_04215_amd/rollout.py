@@ -52,7 +52,9 @@ class GpuRollout:
         self.z2nd = torch.zeros(n, dtype=torch.float32, device=dev)
         self.commit_now = torch.zeros((B, Lb), dtype=torch.uint8, device=dev)
         self.n_commit = torch.zeros(B, dtype=torch.int32, device=dev)
-        self.remaining = torch.zeros(B, dtype=torch.int32, device=dev)
+        # two buffers: a step's write-back reads the previous step's counts while its selection writes the new ones
+        self._remaining2 = [torch.zeros(B, dtype=torch.int32, device=dev) for _ in range(2)]
+        self.remaining = self._remaining2[0]     # the counts written by the step queued last
         self.row_idx = torch.zeros(n, dtype=torch.int32, device=dev)
         self.m_dev = torch.zeros(1, dtype=torch.int32, device=dev)
         self.commit_step = torch.full((B, Lb), -1, dtype=torch.int16, device=dev) if record_steps else None
@@ -128,13 +130,21 @@ class GpuRollout:
                               sample_step=(self.block << 16) | self.step_idx, sample_stream=self.sample_stream,
                               conf_mode=self.conf_mode,
                               stream=st)
-        dlm.unmask_commit(self.conf, self.tok, self.x, self.mask, self.n_commit, self.remaining,
+        # Cache write-back of the block's K/V.  First step of a block: a sequence that finishes right away is copied
+        # by a launch of its own.  Later steps: every sequence that was still masked after the previous step is
+        # copied inside the selection's launch (the last such copy is its final step's K/V: the same cache contents,
+        # one launch fewer per step).
+        prev, rem = self.remaining, self._remaining2[self.step_idx & 1]
+        first = self.step_idx == 0
+        dlm.unmask_commit(self.conf, self.tok, self.x, self.mask, self.n_commit, rem,
                           x_pos0=P, rule=_RULES[cfg.rule], threshold=cfg.tau, force_top1=True, k=cfg.k,
                           commit_now=self.commit_now, next_row_idx=self.row_idx, next_m=self.m_dev,
                           commit_step=self.commit_step, step=self.step_idx,
-                          writeback=dlm.WB_BLOCK_WHEN_DONE, src_block=(kblk, vblk, 0),
+                          writeback=dlm.WB_BLOCK_WHEN_DONE if first else dlm.WB_WHILE_ACTIVE,
+                          active_in=None if first else prev, src_block=(kblk, vblk, 0),
                           cache_k=self.cache_k, cache_v=self.cache_v, cache_pos0=P,
                           host_remaining_total=host, stream=st)
+        self.remaining = rem
         ev.record(st)
         self._last_poll = (ev, host)
         self.step_idx += 1

@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 
 
 def run_commit(conf, tok, mask, x, x_pos0, *, rule, tau=0.0, k=0, force=True, group_len=None, step=3,
-               writeback=dlm.WB_NONE, src=None, cache=None, cache_pos0=0):
+               writeback=dlm.WB_NONE, src=None, cache=None, cache_pos0=0, active_in=None):
     B, n = mask.shape
     d_conf, d_tok = dev(conf.astype(np.float32)), dev(tok.astype(np.int32))
     big_mask = torch.zeros((B, n + 8), dtype=torch.uint8, device=DEV)        # strided view on purpose
@@ -27,6 +27,8 @@ def run_commit(conf, tok, mask, x, x_pos0, *, rule, tau=0.0, k=0, force=True, gr
     kw = {}
     if writeback != dlm.WB_NONE:
         kw = dict(src_block=(src[0], src[1], 0), cache_k=cache[0], cache_v=cache[1], cache_pos0=cache_pos0)
+        if active_in is not None:
+            kw["active_in"] = dev(np.asarray(active_in, np.int32))
     dlm.unmask_commit(d_conf, d_tok, d_x, d_mask, n_commit, remaining, x_pos0=x_pos0, group_len=group_len,
                       rule=dlm.RULE_THRESHOLD if rule == "threshold" else dlm.RULE_TOPK, threshold=tau,
                       force_top1=force, k=k, commit_now=commit_now, next_row_idx=row_idx, next_m=next_m,
@@ -153,6 +155,52 @@ def test_writeback(mode):
                 want_v[b, :, P + i] = src_v[b, :, i]
     assert np.array_equal(bf16_host(dk), want_k) and np.array_equal(bf16_host(dv), want_v)
     assert not np.array_equal(want_k, c_k)
+
+
+@pytest.mark.parametrize("B,Hkv,Lb,d,group_len", [(5, 2, 32, 128, None), (3, 3, 40, 64, None), (2, 1, 700, 64, None),
+                                                   (40, 2, 512, 64, None), (6, 2, 64, 128, 4)])
+def test_writeback_while_active(B, Hkv, Lb, d, group_len):
+    """Sequences flagged by active_in get the whole block copied, the others keep their cache rows, whatever this
+    call's selection does; rows outside [P, P + Lb) are untouched.  Covers the copy inside the single-workgroup
+    launch (first three), and the separate copy launch (more than 16384 positions; several groups per sequence)."""
+    L, P = Lb + 50, 37
+    rng = np.random.default_rng(Lb)
+    src_k, src_v = rnd(21, (B, Hkv, Lb, d)), rnd(22, (B, Hkv, Lb, d))
+    c_k, c_v = rnd(23, (B, Hkv, L, d)), rnd(24, (B, Hkv, L, d))
+    conf = rng.random((B, Lb))
+    conf[0] = 0.99
+    mask = (rng.random((B, Lb)) < 0.6).astype(np.uint8)
+    mask[-1] = 0
+    active = (np.arange(B) % 3 != 1).astype(np.int32) * 7      # deliberately not derived from the mask
+    tok = rng.integers(0, 100, size=(B, Lb))
+    x = np.zeros((B, L), np.int32)
+    dk, dv = bf16_dev(c_k), bf16_dev(c_v)
+    got = run_commit(conf, tok, mask, x, P, rule="threshold", tau=0.9, group_len=group_len, writeback=dlm.WB_WHILE_ACTIVE,
+                     src=(bf16_dev(src_k), bf16_dev(src_v)), cache=(dk, dv), cache_pos0=P, active_in=active)
+    check_against_oracle(conf, tok, mask, x, P, got, rule="threshold", tau=0.9, group_len=group_len)
+    want_k, want_v = c_k.copy(), c_v.copy()
+    for b in range(B):
+        if active[b]:
+            want_k[b, :, P:P + Lb] = src_k[b]
+            want_v[b, :, P:P + Lb] = src_v[b]
+    assert np.array_equal(bf16_host(dk), want_k) and np.array_equal(bf16_host(dv), want_v)
+
+
+def test_writeback_while_active_rejects_aliased_or_missing_counts():
+    B, Hkv, Lb, d = 2, 1, 32, 64
+    z = torch.zeros((B, Lb), device=DEV)
+    conf, tok = z.float(), z.int()
+    x, mask = torch.zeros((B, 64), dtype=torch.int32, device=DEV), torch.ones((B, Lb), dtype=torch.uint8, device=DEV)
+    n_commit, remaining = torch.zeros(B, dtype=torch.int32, device=DEV), torch.zeros(B, dtype=torch.int32, device=DEV)
+    src = torch.zeros((B, Hkv, Lb, d), dtype=torch.bfloat16, device=DEV)
+    cache = torch.zeros((B, Hkv, 64, d), dtype=torch.bfloat16, device=DEV)
+    kw = dict(x_pos0=0, rule=dlm.RULE_THRESHOLD, threshold=2.0, writeback=dlm.WB_WHILE_ACTIVE, src_block=(src, src, 0),
+              cache_k=cache, cache_v=cache, cache_pos0=0)
+    for bad in (None, remaining, n_commit):
+        with pytest.raises(dlm.DlmError):
+            dlm.unmask_commit(conf, tok, x, mask, n_commit, remaining, active_in=bad, **kw)
+    torch.cuda.synchronize()
+    assert int(mask.sum()) == B * Lb and float(cache.float().abs().sum()) == 0    # nothing ran
 
 
 def test_kv_refresh_bitwise_and_strided():
