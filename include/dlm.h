@@ -104,6 +104,10 @@ typedef struct dlm_kv_seg {
  * Supported: d in {64, 128}; Hq % Hkv == 0; all base pointers 16-byte aligned and
  * all strides multiples of 8 elements.  Lq, Hq/Hkv and segment lengths are arbitrary.
  * workspace: dlm_block_attn_workspace_bytes(args) bytes (may be 0; then NULL is fine).
+ *   seq_active  optional device int32 [B]: sequence b is skipped (its rows of out and lse are left as they
+ *           are) when seq_active[b] == 0.  For denoising steps in which some sequences of the batch have no
+ *           masked position left: nothing reads their attention output (the LM head runs on masked rows
+ *           only), so the driver passes the previous step's per-sequence count of masked positions.
  *
  * Packed variable-length mode (cu_seqlens != NULL; Section 3.4, training-side optimization: the
  * padding-free bidirectional attention used for SFT, the actor update and log-prob
@@ -135,6 +139,7 @@ typedef struct dlm_attn_args {
     size_t workspace_bytes;
     const int32_t *cu_seqlens;
     int32_t total_tokens;
+    const int32_t *seq_active;
 } dlm_attn_args;
 
 int dlm_block_attn(const dlm_attn_args *args, void *stream);

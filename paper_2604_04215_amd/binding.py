@@ -40,7 +40,7 @@ class AttnArgs(C.Structure):
                 ("mask_mode", C.c_int32), ("block_size", C.c_int32), ("q_pos0", C.c_int32), ("scale", C.c_float),
                 ("out", C.c_void_p), ("o_stride_b", C.c_int64), ("o_stride_t", C.c_int64), ("o_stride_h", C.c_int64),
                 ("lse", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
-                ("cu_seqlens", C.c_void_p), ("total_tokens", C.c_int32)]
+                ("cu_seqlens", C.c_void_p), ("total_tokens", C.c_int32), ("seq_active", C.c_void_p)]
 
 
 class AttnBwdArgs(C.Structure):
@@ -192,8 +192,9 @@ def kv_seg(k=None, v=None, pos0: int = 0, rule: int = 0) -> KvSeg:
 def block_attn(q, out, prefix: Optional[Tuple] = None, block: Optional[Tuple] = None,
                suffix: Optional[Tuple] = None, *, n_kv_heads: Optional[int] = None,
                mask_mode: int = MASK_FULL, block_size: int = 0, q_pos0: int = 0, scale: float = 0.0,
-               prefix_len_b=None, lse=None, workspace=None, stream=None) -> None:
-    """q, out: bf16 [B, Lq, Hq, d]; each segment is (k, v, pos0[, rule]) with k, v bf16 [B, Hkv, len, d]."""
+               prefix_len_b=None, lse=None, workspace=None, seq_active=None, stream=None) -> None:
+    """q, out: bf16 [B, Lq, Hq, d]; each segment is (k, v, pos0[, rule]) with k, v bf16 [B, Hkv, len, d].
+    seq_active: optional int32 [B] on the device; sequences with a 0 are skipped (out / lse rows untouched)."""
     import torch
     a = AttnArgs()
     a.struct_size = C.sizeof(AttnArgs)
@@ -220,6 +221,10 @@ def block_attn(q, out, prefix: Optional[Tuple] = None, block: Optional[Tuple] = 
     a.lse = _dev(lse, torch.float32, "lse")
     a.workspace = _dev(workspace, None, "workspace")
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    if seq_active is not None:
+        if seq_active.numel() != B or not seq_active.is_contiguous():
+            raise ValueError("seq_active must be contiguous int32 [B]")
+        a.seq_active = _dev(seq_active, torch.int32, "seq_active")
     _check(lib().dlm_block_attn(C.byref(a), _stream(stream)))
 
 

@@ -43,6 +43,7 @@ struct AttnParams {
     const int32_t* cu;  // packed variable-length mode: sequence b owns tokens [cu[b], cu[b+1])
     int total;          // cu[B]
     GridRemap remap;
+    const int32_t* seq_active;   // optional [B]: 0 = skip the sequence
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
@@ -79,6 +80,7 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
         kvh = grp % p.Hkv;
         b = grp / p.Hkv;
     }
+    if (p.seq_active && p.seq_active[b] == 0) return;   // nobody reads this sequence's output in this step
     const int r0 = bx * (32 * NWR * RTW);
 
     // ---- visible extent of each segment for this workgroup -----------------
@@ -708,6 +710,7 @@ extern "C" int dlm_block_attn(const dlm_attn_args* a, void* stream) {
     p.out = (uint16_t*)a->out; p.o_sb = a->o_stride_b; p.o_st = a->o_stride_t; p.o_sh = a->o_stride_h;
     p.lse = a->lse;
     p.cu = a->cu_seqlens; p.total = a->total_tokens;
+    p.seq_active = a->seq_active;
     p.remap = no_remap();
     hipStream_t st = (hipStream_t)stream;
     const bool bc = a->mask_mode == DLM_MASK_BLOCK_CAUSAL;

@@ -117,9 +117,12 @@ class GpuRollout:
         self._ring_pos = (self._ring_pos + 1) % len(self._ring)
         st = torch.cuda.current_stream()     # looked up once per step: the query is a third of the enqueue time
         prefix, suffix = self._prefix, self._suffix
+        # from a block's second step on, sequences with nothing left masked after the previous step are skipped:
+        # the LM head reads only masked rows, so nothing would consume their attention output
         dlm.block_attn(q, self.O, prefix=prefix, block=(kblk, vblk, P), suffix=suffix,
                        mask_mode=_MASKS[cfg.mask_mode], block_size=cfg.bs, q_pos0=P,
-                       lse=self.lse_attn if self.diagnostics else None, stream=st)
+                       lse=self.lse_attn if self.diagnostics else None,
+                       seq_active=self.remaining if self.step_idx > 0 else None, stream=st)
         diag = self.diagnostics
         dlm.lmhead_confidence(hidden.view(cfg.B * Lb, cfg.Dh), self.w, self.conf, self.tok,
                               M=self.m_host, row_idx=self.row_idx, m_dev=self.m_dev,

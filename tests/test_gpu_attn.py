@@ -198,6 +198,29 @@ def test_xcd_grouped_grid_covers_every_tile_once(B, Hkv, g, Lq, variant):
         assert torch.equal(outs[0], outs[2]) and torch.equal(outs[1], outs[2])
 
 
+@pytest.mark.parametrize("Lq,Hq,Hkv,variant", [(32, 4, 4, 0), (8, 8, 2, 0), (130, 4, 2, 0), (130, 4, 2, 11), (300, 2, 1, 6)])
+def test_sequences_flagged_inactive_are_skipped(Lq, Hq, Hkv, variant):
+    """seq_active[b] == 0: the sequence's rows of out and lse keep what they held; the others match the oracle."""
+    B, d, P = 5, 64, 70
+    q, k, v = rnd(151, (B, Lq, Hq, d)), rnd(152, (B, Hkv, P + Lq, d)), rnd(153, (B, Hkv, P + Lq, d))
+    ref, ref_lse = oracle.attention(q, [KV(k[:, :, :P], v[:, :, :P], 0), KV(k[:, :, P:], v[:, :, P:], P)])
+    kd, vd = bf16_dev(k), bf16_dev(v)
+    active = np.array([3, 0, 1, 0, -2], np.int32)          # any non-zero value counts as active
+    out = torch.full((B, Lq, Hq, d), 7.0, dtype=torch.bfloat16, device=DEV)
+    lse = torch.full((B, Hq, Lq), -3.0, dtype=torch.float32, device=DEV)
+    dlm.set_option("attn_variant", variant)
+    try:
+        dlm.block_attn(bf16_dev(q), out, prefix=(kd[:, :, :P], vd[:, :, :P], 0), block=(kd[:, :, P:], vd[:, :, P:], P),
+                       lse=lse, seq_active=dev(active))
+        torch.cuda.synchronize()
+    finally:
+        dlm.set_option("attn_variant", 0)
+    on = active != 0
+    assert attn_rel_err(bf16_host(out)[on], ref[on]) <= TOL
+    assert np.abs(lse.cpu().numpy()[on] - ref_lse[on]).max() <= LSE_TOL
+    assert bool((out[~torch.from_numpy(on).to(DEV)] == 7.0).all()) and bool((lse[~torch.from_numpy(on).to(DEV)] == -3.0).all())
+
+
 @pytest.mark.parametrize("variant", [0, 1, 2])
 def test_planted_one_hot_values_expose_every_key(variant):
     """V[j] = e_(j mod d): output channel c is the total probability of keys j = c (mod d), so a
