@@ -64,6 +64,7 @@ class GpuRollout:
         self.step_idx = 0
         self.m_host = n          # host-side upper bound of the masked-row count
         self.diagnostics = True  # also write lse / zmax / z2nd (tests); the benchmark turns it off
+        self._exact_rows = False
         # ring of pinned host words + events: the commit kernel stores the total still-masked count straight
         # into pinned host memory, and an event recorded behind it tells the host when it may read it
         self._ring = [(torch.cuda.Event(), torch.zeros(1, dtype=torch.int32).pin_memory()) for _ in range(4)]
@@ -104,6 +105,9 @@ class GpuRollout:
             self.commit_step.fill_(-1)
         dlm.mask_compact(self.mask, self.row_idx, self.m_dev)
         self.m_host = cfg.B * Lb
+        # fixed schedule: from a fully masked block the top-k rule leaves exactly Lb - k (s + 1) positions per
+        # sequence after step s, so the LM-head launch can be sized exactly instead of from the late poll
+        self._exact_rows = cfg.rule == "topk" and init_mask is None
         # the cache views of this block's prefix / suffix are the same for all of its steps
         S = self.S
         self._prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
@@ -116,6 +120,8 @@ class GpuRollout:
         ev, host = self._ring[self._ring_pos]
         self._ring_pos = (self._ring_pos + 1) % len(self._ring)
         st = torch.cuda.current_stream()     # looked up once per step: the query is a third of the enqueue time
+        if self._exact_rows:
+            self.m_host = max(1, cfg.B * max(Lb - cfg.k * self.step_idx, 0))
         prefix, suffix = self._prefix, self._suffix
         # from a block's second step on, sequences with nothing left masked after the previous step are skipped:
         # the LM head reads only masked rows, so nothing would consume their attention output
@@ -154,7 +160,8 @@ class GpuRollout:
 
     def set_row_bound(self, m: int) -> None:
         """Tell the driver an upper bound of the masked-row count (sizes the LM-head launch)."""
-        self.m_host = max(1, min(int(m), self.cfg.B * self.cfg.Lb))
+        if not self._exact_rows:
+            self.m_host = max(1, min(int(m), self.cfg.B * self.cfg.Lb))
 
     def run_block(self, block: int, inputs: Callable[[int, int], tuple], init_mask=None,
                   refresh=None, lagged: bool = True, max_steps: Optional[int] = None) -> dict:

@@ -218,6 +218,33 @@ def test_lagged_loop_matches_synchronous(name):
     assert finals[0][2] == finals[1][2]
 
 
+def test_exact_row_schedule_of_the_topk_rule_changes_nothing():
+    """From a fully masked block the driver sizes the LM-head launch from the top-k schedule (Lb - k s positions per
+    sequence before step s) instead of the late poll.  Same final tokens and cache as when the mask is handed in
+    explicitly, which keeps the polled upper bound (the path the lock-step comparison with the oracle covers)."""
+    cfg = synth.CONFIGS["mini4"]
+    assert cfg.rule == "topk"
+    w = bf16_dev(synth.w_vocab(cfg))
+    x0 = dev(synth.initial_tokens(cfg, cfg.L))
+    k0, v0 = synth.cache_kv(cfg, 0)
+    finals = []
+    for explicit in (True, False):
+        g = GpuRollout(cfg, w, DEV)
+        g.x.copy_(x0)
+        g.cache_k.copy_(bf16_dev(k0))
+        g.cache_v.copy_(bf16_dev(v0))
+        steps = 0
+        for b in range(cfg.n_blocks):
+            ones = torch.ones((cfg.B, cfg.Lb), dtype=torch.uint8, device=DEV) if explicit else None
+            steps += g.run_block(b, lambda blk, s: step_inputs_dev(cfg, blk, s), init_mask=ones)["steps"]
+            assert g._exact_rows == (not explicit)
+        torch.cuda.synchronize()
+        finals.append((g.x.cpu().numpy(), bf16_host(g.cache_k), bf16_host(g.cache_v), steps))
+    assert finals[0][3] == finals[1][3] == cfg.n_blocks * -(-cfg.Lb // cfg.k)
+    for a, b in zip(finals[0][:3], finals[1][:3]):
+        assert np.array_equal(a, b)
+
+
 def test_full_pass_mini():
     """Block-causal full-sequence pass with Bernoulli masking, one threshold commit per block of 4."""
     cfg = synth.FULLPASS["mini5b"]
