@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip per-step LM-head event timing")
     ap.add_argument("--sync-loop", action="store_true", help="poll every step synchronously (no one-step-late poll)")
+    ap.add_argument("--expect-ratio", type=float, default=None,
+                    help="the driver's guess of (rows in a step) / (late row bound); 0 = no guess; default: the driver's")
     ap.add_argument("--dump-steps", default=None, metavar="FILE",
                     help="write one line per timed step: block, rows masked before / after, row bound, LM-head us")
     ap.add_argument("--kernel", default=None, choices=["lmhead", "attn_fullseq", "fullpass"],
@@ -195,6 +197,8 @@ def main():
     w = to_dev(w_host)
     g = GpuRollout(cfg, w, dev)
     g.diagnostics = False
+    if args.expect_ratio is not None:
+        g.expect_ratio = args.expect_ratio
     x0 = torch.from_numpy(synth.initial_tokens(cfg, cfg.L)).to(dev)
     images = {}
 

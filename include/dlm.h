@@ -210,6 +210,12 @@ size_t dlm_block_attn_bwd_workspace_bytes(const dlm_attn_bwd_args *args);
  *   m_dev   optional device int32 scalar: the call processes min(M, max(*m_dev,0))
  *           rows (lets the previous step's compaction set the row count without a
  *           host round trip); outputs beyond that count are left untouched
+ *   M_expected  0, or the row count the caller expects *m_dev to hold (a guess, not a bound; needs m_dev).
+ *           The kernel shape is chosen on the host from M, which a caller that polls the device late only
+ *           knows as an upper bound.  When M_expected falls in a smaller shape's range, the call queues that
+ *           shape guarded by "*m_dev fits it" and the shape for M guarded by the opposite, so a right
+ *           guess runs the better shape and a wrong one costs an empty launch.  Results depend on it only
+ *           through the summation order of the shape that ran (rounding).
  *   w       bf16 [V, Dh], row stride w_stride_row
  *   out_scatter  0: outputs are indexed by r; 1: by row(r) (dense per-position arrays)
  *   conf, tok    required; lse, zmax, z2nd, target+ztarget optional.  `target` is
@@ -253,6 +259,7 @@ typedef struct dlm_lmhead_args {
     uint32_t sample_step, sample_stream;
     uint64_t sample_seed;
     int32_t conf_mode;
+    int32_t M_expected;
 } dlm_lmhead_args;
 
 int dlm_lmhead_confidence(const dlm_lmhead_args *args, void *stream);

@@ -70,7 +70,7 @@ class LmheadArgs(C.Structure):
                 ("target", C.c_void_p), ("ztarget", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
                 ("sample", C.c_int32), ("sample_step", C.c_uint32), ("sample_stream", C.c_uint32),
-                ("sample_seed", C.c_uint64), ("conf_mode", C.c_int32)]
+                ("sample_seed", C.c_uint64), ("conf_mode", C.c_int32), ("M_expected", C.c_int32)]
 
 
 class CommitArgs(C.Structure):
@@ -337,9 +337,10 @@ def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=
                       inv_temperature: float = 1.0, forbid_token: int = -1, out_scatter: bool = False,
                       lse=None, zmax=None, z2nd=None, target=None, ztarget=None, workspace=None,
                       sample_seed: Optional[int] = None, sample_step: int = 0, sample_stream: int = 0,
-                      conf_mode: int = CONF_TOKEN_PROB, stream=None) -> None:
+                      conf_mode: int = CONF_TOKEN_PROB, M_expected: int = 0, stream=None) -> None:
     """hidden bf16 [rows, Dh]; w bf16 [V, Dh]; conf fp32 / tok int32 outputs; workspace: a uint8 tensor.
-    sample_seed: None = arg-max token; an integer = Gumbel-max sample with that seed."""
+    sample_seed: None = arg-max token; an integer = Gumbel-max sample with that seed.
+    M_expected: a guess of the row count m_dev holds (0 = none); only the choice of kernel shape depends on it."""
     import torch
     a = LmheadArgs()
     a.struct_size = C.sizeof(LmheadArgs)
@@ -362,6 +363,7 @@ def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=
     a.workspace = _dev(workspace, None, "workspace")
     a.workspace_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     a.conf_mode = int(conf_mode)
+    a.M_expected = int(M_expected)
     if sample_seed is not None:
         a.sample, a.sample_seed = 1, int(sample_seed) & 0xFFFFFFFFFFFFFFFF
         a.sample_step, a.sample_stream = int(sample_step) & 0xFFFFFFFF, int(sample_stream) & 0xFFFFFFFF

@@ -45,7 +45,22 @@ struct LmParams {
     // conf_mode: DLM_CONF_*.  For the negative entropy, slot 3 of the second partial carries
     // U = sum_v exp(z_v - max) * (z_v - max) of the tile (entropy = log(sumexp) - U / sumexp).
     int conf_mode;
+    // Two shapes queued for one call (the host expects fewer rows than its bound): a launch runs only when the
+    // device's row count lies in (m_lo, m_hi]; the reduction reads the layout of the launch that ran.
+    int m_lo, m_hi;
+    int alt_cap, alt_n_vt;   // reduction: row count <= alt_cap (> 0) -> alt_n_vt partials per row, second partials at alt_part2
+    f32x4* alt_part2;
 };
+
+// Row count of this launch; false when the device's count belongs to the other shape queued for the same call.
+__device__ __forceinline__ bool lm_rows(const LmParams& p, int& M) {
+    if (p.m_dev) {
+        const int md = max(*p.m_dev, 0);
+        if (md <= p.m_lo || md > p.m_hi) return false;
+        M = min(M, md);
+    }
+    return true;
+}
 
 struct Red {
     float m, s, m2;
@@ -354,7 +369,7 @@ __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
     const int v0 = vt * TV;
     const int m0 = mc * MB;
     int M = p.M;
-    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (!lm_rows(p, M)) return;
     if (m0 >= M) return;
 
     // ---- global -> register staging addresses --------------------------------
@@ -564,7 +579,7 @@ __global__ __launch_bounds__(64 * WV) void lmhead_wdirect_kernel(LmParams p) {
     const int v0 = vt * TV;
     const int m0 = mc * MB;
     int M = p.M;
-    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (!lm_rows(p, M)) return;
     if (m0 >= M) return;
 
     const uint16_t* wsrc[TVW];
@@ -709,7 +724,7 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
     if (vt >= p.n_vt) return;
     const int v0 = vt * TV, m0 = mc * MB;
     int M = p.M;
-    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (!lm_rows(p, M)) return;
     if (m0 >= M) return;
 
     // per-lane source of each of this wavefront's load instructions (row of the combined [W rows | H rows] panel)
@@ -897,7 +912,7 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_pair_kernel(LmParams p) {
     if (vt >= p.n_vt) return;
     const int v0 = vt * TV, m0 = mc * MB;
     int M = p.M;
-    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    if (!lm_rows(p, M)) return;
     if (m0 >= M) return;
 
     const uint16_t* src[IPW];
@@ -1051,23 +1066,32 @@ __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = blockIdx.x;
     int M = p.M;
-    if (p.m_dev) M = min(M, max(*p.m_dev, 0));
+    int n_vt = p.n_vt;
+    const f32x4* part2 = p.part2;
+    if (p.m_dev) {
+        const int md = max(*p.m_dev, 0);
+        M = min(M, md);
+        if (p.alt_cap > 0 && md <= p.alt_cap) {
+            n_vt = p.alt_n_vt;
+            part2 = p.alt_part2;
+        }
+    }
     if (r >= M) return;
     const bool ent = p.conf_mode == DLM_CONF_NEG_ENTROPY;
     const bool second = p.sample || ent;
-    const f32x4* row = p.part + (int64_t)r * p.n_vt;
-    const f32x4* row2 = p.part2 + (int64_t)r * p.n_vt;
+    const f32x4* row = p.part + (int64_t)r * n_vt;
+    const f32x4* row2 = part2 + (int64_t)r * n_vt;
     Red tot{-INFINITY, 0.f, -INFINITY, 0x7fffffff};
     Smp sm{-INFINITY, -INFINITY, 0x7fffffff};
     float uent = 0.f;
-    for (int t0 = 0; t0 < p.n_vt; t0 += 1024) {
+    for (int t0 = 0; t0 < n_vt; t0 += 1024) {
         f32x4 v[4], g[4];
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
             const int t = t0 + a * 256 + tid;
             v[a] = f32x4{-INFINITY, 0.f, -INFINITY, __int_as_float(0x7fffffff)};
             g[a] = f32x4{-INFINITY, -INFINITY, __int_as_float(0x7fffffff), 0.f};
-            if (t < p.n_vt) {
+            if (t < n_vt) {
                 v[a] = row[t];
                 if (second) g[a] = row2[t];
             }
@@ -1238,6 +1262,36 @@ static int validate_lm(const dlm_lmhead_args* a) {
 
 using namespace dlm;
 
+// largest row count served by the shape plan_lmhead picks for M rows
+static int plan_capacity(int M) {
+    static const int caps[] = {32, 64, 96, 128, 192, 256, 384};
+    for (int c : caps)
+        if (M <= c) return c;
+    return 0x7fffffff;
+}
+
+// Fills the layout fields of p for one kernel shape (p.M = the rows this launch may hold, m_bound = the caller's
+// bound, which places the second partials) and launches it.
+static int launch_lm_shape(const LmVariant& var, LmParams& p, int m_bound, hipStream_t st) {
+    p.n_vt = (p.V + var.tv - 1) / var.tv;
+    p.part2 = p.part + (size_t)p.n_vt * m_bound;
+    p.n_mc = (p.M + var.mb - 1) / var.mb;
+    // several row chunks: blocks of gm x gv workgroups for the 32 CUs of an XCD; gm is the largest divisor of the
+    // chunk count up to 8 (measured at V = 126464, Dh = 4096: +6 % at M >= 1024, +10..17 % at M = 512)
+    p.gm = 1; p.gv = 1;
+    if (p.n_mc >= 2) {
+        for (int c = 8; c >= 1; --c)
+            if (p.n_mc % c == 0) { p.gm = c; break; }
+        p.gv = 32 / p.gm > 8 ? 8 : 32 / p.gm;
+    }
+    if (g_lm_block_gv >= 0) { p.gv = g_lm_block_gv > 0 ? g_lm_block_gv : 1; if (g_lm_block_gv == 0) p.gm = 1; }
+    const int64_t n_vt8 = ((int64_t)(p.n_vt + 7) / 8 + p.gv - 1) / p.gv * p.gv;   // vocabulary tiles per XCD, padded to gv
+    const int64_t n_wg = n_vt8 * 8 * p.n_mc;
+    if (n_wg > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "lmhead: M * V too large for one launch");
+    ((p.n_mc == 1 && var.launch_nt && g_lm_nt) ? var.launch_nt : var.launch)(dim3((unsigned)n_wg), st, p);
+    return check_hip(hipGetLastError(), "lmhead_kernel launch");
+}
+
 extern "C" size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args* a) {
     if (!a || a->M <= 0 || a->V <= 0) return 0;
     const size_t n_vt = ((size_t)a->V + LM_MIN_TV - 1) / LM_MIN_TV;   // enough for every kernel shape
@@ -1252,7 +1306,6 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     if (!a->workspace || a->workspace_bytes < need)
         return fail(DLM_ERR_WORKSPACE, "lmhead: workspace of %zu bytes needed, %zu given", need, a->workspace ? a->workspace_bytes : (size_t)0);
     if (!aligned16(a->workspace)) return fail(DLM_ERR_WORKSPACE, "lmhead: workspace not 16-byte aligned");
-    const LmVariant& var = g_lm_variants[plan_lmhead(a->M)];
     LmParams p;
     p.M = a->M; p.Dh = a->Dh; p.V = a->V;
     p.hidden = (const uint16_t*)a->hidden; p.h_stride = a->hidden_stride_row;
@@ -1262,28 +1315,33 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     p.conf = a->conf; p.tok = a->tok; p.lse = a->lse; p.zmax = a->zmax; p.z2nd = a->z2nd;
     p.target = a->target; p.ztarget = a->ztarget;
     p.part = (f32x4*)a->workspace;
-    p.n_vt = (a->V + var.tv - 1) / var.tv;
     p.sample = a->sample;
     p.conf_mode = a->conf_mode;
     p.seed_lo = (uint32_t)a->sample_seed; p.seed_hi = (uint32_t)(a->sample_seed >> 32);
     p.step = a->sample_step; p.stream = a->sample_stream;
-    p.part2 = p.part + (size_t)p.n_vt * a->M;
-    p.n_mc = (a->M + var.mb - 1) / var.mb;
-    // several row chunks: blocks of gm x gv workgroups for the 32 CUs of an XCD; gm is the largest divisor of the
-    // chunk count up to 8 (measured at V = 126464, Dh = 4096: +6 % at M >= 1024, +10..17 % at M = 512)
-    p.gm = 1; p.gv = 1;
-    if (p.n_mc >= 2) {
-        for (int c = 8; c >= 1; --c)
-            if (p.n_mc % c == 0) { p.gm = c; break; }
-        p.gv = 32 / p.gm > 8 ? 8 : 32 / p.gm;
-    }
-    if (g_lm_block_gv >= 0) { p.gv = g_lm_block_gv > 0 ? g_lm_block_gv : 1; if (g_lm_block_gv == 0) p.gm = 1; }
-    const int64_t n_vt8 = ((int64_t)(p.n_vt + 7) / 8 + p.gv - 1) / p.gv * p.gv;   // vocabulary tiles per XCD, padded to gv
-    const int64_t n_wg = n_vt8 * 8 * p.n_mc;
-    if (n_wg > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "lmhead: M * V too large for one launch");
+    p.m_lo = -1; p.m_hi = 0x7fffffff;
+    p.alt_cap = 0; p.alt_n_vt = 0; p.alt_part2 = nullptr;
     hipStream_t st = (hipStream_t)stream;
-    ((p.n_mc == 1 && var.launch_nt && g_lm_nt) ? var.launch_nt : var.launch)(dim3((unsigned)n_wg), st, p);
-    rc = check_hip(hipGetLastError(), "lmhead_kernel launch");
+
+    // The caller's bound M sizes the launch, the device's count says how many rows there are.  When the caller
+    // expects the count to fall in a smaller shape's range, that shape is queued first, guarded by "count <= its
+    // capacity", and the bound's shape after it, guarded by the opposite: one of the two returns at once.
+    const int v_safe = plan_lmhead(a->M);
+    int v_try = v_safe, cap = 0;
+    if (a->m_dev && a->M_expected > 0 && a->M_expected < a->M && g_lm_variant < 0) {
+        cap = plan_capacity(a->M_expected);
+        if (cap < a->M) v_try = plan_lmhead(cap);
+    }
+    if (v_try != v_safe) {
+        LmParams q = p;
+        q.M = cap;
+        q.m_hi = cap;
+        rc = launch_lm_shape(g_lm_variants[v_try], q, a->M, st);
+        if (rc != DLM_OK) return rc;
+        p.m_lo = cap;
+        p.alt_cap = cap; p.alt_n_vt = q.n_vt; p.alt_part2 = q.part2;
+    }
+    rc = launch_lm_shape(g_lm_variants[v_safe], p, a->M, st);
     if (rc != DLM_OK) return rc;
     hipLaunchKernelGGL(lmhead_reduce_kernel, dim3(a->M), dim3(256), 0, st, p);
     return check_hip(hipGetLastError(), "lmhead_reduce_kernel launch");

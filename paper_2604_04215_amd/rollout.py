@@ -65,6 +65,10 @@ class GpuRollout:
         self.m_host = n          # host-side upper bound of the masked-row count
         self.diagnostics = True  # also write lse / zmax / z2nd (tests); the benchmark turns it off
         self._exact_rows = False
+        # The polled row bound is one step old; the count itself is expected to be this fraction of it (a guess
+        # that only selects which kernel shape is tried first; 0 turns the guess off).
+        self.expect_ratio = 0.85
+        self.late_bound = True    # False: the caller sets the row bound from the step just before (synchronous loop)
         # ring of pinned host words + events: the commit kernel stores the total still-masked count straight
         # into pinned host memory, and an event recorded behind it tells the host when it may read it
         self._ring = [(torch.cuda.Event(), torch.zeros(1, dtype=torch.int32).pin_memory()) for _ in range(4)]
@@ -138,6 +142,7 @@ class GpuRollout:
                               inv_temperature=self.inv_temperature, sample_seed=self.sample_seed,
                               sample_step=(self.block << 16) | self.step_idx, sample_stream=self.sample_stream,
                               conf_mode=self.conf_mode,
+                              M_expected=0 if (self._exact_rows or not self.late_bound) else int(self.m_host * self.expect_ratio),
                               stream=st)
         # Cache write-back of the block's K/V.  First step of a block: a sequence that finishes right away is copied
         # by a launch of its own.  Later steps: every sequence that was still masked after the previous step is
@@ -172,6 +177,7 @@ class GpuRollout:
         """
         cfg = self.cfg
         rk, rv = refresh if refresh is not None else (None, None)
+        self.late_bound = lagged
         self.begin_block(block, init_mask, rk, rv)
         max_steps = cfg.Lb + 1 if max_steps is None else max_steps
         pending = []   # (event, pinned host copy of remaining) of steps already queued
@@ -215,6 +221,7 @@ class StepRunner:
     def __init__(self, g: GpuRollout, inputs: Callable[[int, int], tuple], setup: Callable[[int], dict],
                  on_restart: Optional[Callable[[], None]] = None, lagged: bool = True, on_step=None):
         self.g, self.inputs, self.setup, self.on_restart, self.lagged = g, inputs, setup, on_restart, lagged
+        g.late_bound = lagged
         self.on_step = on_step          # optional hook(g, fn) wrapping the enqueue of one step (timing)
         self.block = -1
         self.in_block = False

@@ -15,7 +15,8 @@ MARGIN = 1e-3       # rows whose top-2 logit margin is below this may legitimate
 Z_TOL = 2e-3        # logits-scale outputs (lse, zmax, z2nd): fp32 accumulation over Dh terms
 
 
-def run_lm(hidden, w, *, row_idx=None, M=None, m_dev=None, forbid=-1, inv_t=1.0, scatter=False, target=None):
+def run_lm(hidden, w, *, row_idx=None, M=None, m_dev=None, forbid=-1, inv_t=1.0, scatter=False, target=None,
+           M_expected=0):
     R, Dh = hidden.shape
     V = w.shape[0]
     hd, wd = bf16_dev(hidden), bf16_dev(w)
@@ -32,7 +33,8 @@ def run_lm(hidden, w, *, row_idx=None, M=None, m_dev=None, forbid=-1, inv_t=1.0,
     dlm.lmhead_confidence(hd, wd, conf, tok, M=Mh, row_idx=ridx,
                           m_dev=None if m_dev is None else dev(np.asarray([m_dev], np.int32)),
                           forbid_token=forbid, inv_temperature=inv_t, out_scatter=scatter,
-                          lse=lse, zmax=zmax, z2nd=z2nd, target=tgt, ztarget=zt, workspace=ws)
+                          lse=lse, zmax=zmax, z2nd=z2nd, target=tgt, ztarget=zt, workspace=ws,
+                          M_expected=M_expected)
     torch.cuda.synchronize()
     out = dict(conf=conf.cpu().numpy(), tok=tok.cpu().numpy(), lse=lse.cpu().numpy(), zmax=zmax.cpu().numpy(),
                z2nd=z2nd.cpu().numpy())
@@ -324,3 +326,46 @@ def test_entropy_full_vocabulary_and_sampling_together():
     assert np.abs(conf.cpu().numpy()[pick] - ref["neg_entropy"]).max() <= Z_TOL
     clear = (smp["pmax"] - smp["p2nd"]) >= MARGIN
     assert np.array_equal(tok.cpu().numpy()[pick][clear], smp["tok"][clear])
+
+
+@pytest.mark.parametrize("M,m_dev,guess", [(256, 120, 125), (256, 130, 125), (256, 128, 128), (256, 129, 100), (200, 40, 60),
+                                           (200, 65, 60), (100, 20, 30), (100, 33, 30), (64, 10, 20), (500, 200, 250),
+                                           (500, 300, 250), (500, 500, 250), (300, 0, 100), (128, 128, 90), (70, 70, 1)])
+def test_expected_row_count_only_selects_the_shape(M, m_dev, guess):
+    """M_expected queues the shape for the guessed count, guarded by the device's count, in front of the shape for the
+    bound: whether the guess holds (count within that shape's capacity) or not, the outputs are the oracle's and,
+    up to the rounding of another summation order, those of a call without a guess."""
+    Dh, V = 256, 1500
+    h, w = rnd(7100 + M, (M, Dh)), rnd(7200 + M, (V, Dh), Dh ** -0.25)
+    idx = np.arange(M - 1, -1, -1).astype(np.int32)            # gathered rows, reversed
+    plain = run_lm(h, w, row_idx=idx, M=M, m_dev=m_dev, forbid=V - 1)
+    guessed = run_lm(h, w, row_idx=idx, M=M, m_dev=m_dev, forbid=V - 1, M_expected=guess)
+    assert np.array_equal(np.isnan(plain["conf"]), np.isnan(guessed["conf"]))
+    assert np.allclose(plain["conf"][:m_dev], guessed["conf"][:m_dev], rtol=0, atol=2e-6)
+    assert np.allclose(plain["lse"][:m_dev], guessed["lse"][:m_dev], rtol=0, atol=1e-4)
+    assert np.array_equal(plain["tok"], guessed["tok"])
+    ref = oracle.lmhead(h, w, row_idx=idx[:m_dev], forbid_token=V - 1)
+    compare_prefix(guessed, ref, m_dev)
+
+
+def test_expected_row_count_with_sampling_and_entropy_partials():
+    """The second partial array sits at another offset in the guessed shape's layout: sampled tokens and the
+    entropy confidence must not depend on the guess either (beyond rounding)."""
+    M, Dh, V = 200, 256, 3000
+    h, w = bf16_dev(rnd(7301, (M, Dh))), bf16_dev(rnd(7302, (V, Dh), Dh ** -0.25))
+    for kw in (dict(sample_seed=11, sample_step=3), dict(conf_mode=dlm.CONF_NEG_ENTROPY)):
+        outs = []
+        for guess, md in ((0, 50), (60, 50), (60, 70)):
+            conf = torch.full((M,), float("nan"), dtype=torch.float32, device=DEV)
+            tok = torch.full((M,), -7, dtype=torch.int32, device=DEV)
+            ws = torch.empty(dlm.lmhead_workspace_bytes(M, V, sample="sample_seed" in kw, conf_mode=kw.get("conf_mode", dlm.CONF_TOKEN_PROB)),
+                             dtype=torch.uint8, device=DEV)
+            dlm.lmhead_confidence(h, w, conf, tok, M=M, m_dev=dev(np.asarray([md], np.int32)), workspace=ws,
+                                  M_expected=guess, **kw)
+            torch.cuda.synchronize()
+            outs.append((conf.cpu().numpy(), tok.cpu().numpy()))
+        # the same tokens; confidences up to the rounding of another summation order
+        assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][1][:50], outs[2][1][:50])
+        assert np.allclose(outs[0][0], outs[1][0], rtol=0, atol=1e-5, equal_nan=True)
+        assert np.allclose(outs[0][0][:50], outs[2][0][:50], rtol=0, atol=1e-5)
+        assert not np.isnan(outs[2][0][:70]).any() and np.isnan(outs[2][0][70:]).all()
