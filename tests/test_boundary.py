@@ -41,6 +41,7 @@ int main(void) {
   printf("%zu %zu %zu %zu\n", offsetof(dlm_attn_args, suffix), offsetof(dlm_attn_args, scale), offsetof(dlm_attn_args, lse), offsetof(dlm_attn_args, total_tokens));
   printf("%zu %zu %zu %zu\n", offsetof(dlm_lmhead_args, w), offsetof(dlm_lmhead_args, forbid_token), offsetof(dlm_lmhead_args, conf), offsetof(dlm_lmhead_args, workspace));
   printf("%zu %zu %zu %zu\n", offsetof(dlm_commit_args, conf), offsetof(dlm_commit_args, x_pos0), offsetof(dlm_commit_args, src_block), offsetof(dlm_commit_args, d));
+  printf("%zu %zu %zu %zu\n", offsetof(dlm_attn_args, seq_active), offsetof(dlm_lmhead_args, M_expected), offsetof(dlm_commit_args, host_remaining_total), offsetof(dlm_commit_args, active_in));
   return 0;
 }''')
     exe = tmp_path / "layout"
@@ -50,7 +51,8 @@ int main(void) {
     want = [[C.sizeof(dlm.KvSeg), C.sizeof(A), C.sizeof(Lm), C.sizeof(Cm)],
             [A.suffix.offset, A.scale.offset, A.lse.offset, A.total_tokens.offset],
             [Lm.w.offset, Lm.forbid_token.offset, Lm.conf.offset, Lm.workspace.offset],
-            [Cm.conf.offset, Cm.x_pos0.offset, Cm.src_block.offset, Cm.d.offset]]
+            [Cm.conf.offset, Cm.x_pos0.offset, Cm.src_block.offset, Cm.d.offset],
+            [A.seq_active.offset, Lm.M_expected.offset, Cm.host_remaining_total.offset, Cm.active_in.offset]]
     assert got == want
 
 
@@ -177,6 +179,15 @@ def test_commit_validation():
     assert L.dlm_unmask_commit(C.byref(_cm(next_m=0x1000)), None) == dlm.DLM_ERR_INVALID_ARG     # without next_row_idx
     assert L.dlm_unmask_commit(C.byref(_cm(writeback=9)), None) == dlm.DLM_ERR_INVALID_ARG
     assert L.dlm_unmask_commit(C.byref(_cm(writeback=dlm.WB_BLOCK_WHEN_DONE, Hkv=2, d=128)), None) == dlm.DLM_ERR_INVALID_ARG  # null src
+    def wb_active(**kw):   # a complete write-back request of the "while active" kind, then one thing wrong with it
+        a = _cm(writeback=dlm.WB_WHILE_ACTIVE, Hkv=2, d=128, cache_k=0x2000, cache_v=0x3000, c_stride_b=65536,
+                c_stride_h=8192, c_stride_t=128, n_commit=0x4000, remaining=0x5000, **kw)
+        a.src_block.k, a.src_block.v, a.src_block.len = 0x6000, 0x7000, 32
+        a.src_block.stride_b, a.src_block.stride_h, a.src_block.stride_t = 8192, 4096, 128
+        return a
+    assert L.dlm_unmask_commit(C.byref(wb_active()), None) == dlm.DLM_ERR_INVALID_ARG                    # no active_in
+    assert L.dlm_unmask_commit(C.byref(wb_active(active_in=0x5000)), None) == dlm.DLM_ERR_INVALID_ARG   # aliases remaining
+    assert L.dlm_unmask_commit(C.byref(wb_active(active_in=0x4000)), None) == dlm.DLM_ERR_INVALID_ARG   # aliases n_commit
     assert L.dlm_unmask_commit(C.byref(_cm(B=0)), None) == dlm.DLM_OK
 
 
@@ -194,6 +205,8 @@ def test_refresh_compact_option_validation():
     assert L.dlm_set_option(b"nope", 1) == dlm.DLM_ERR_INVALID_ARG
     assert L.dlm_set_option(b"attn_variant", 99) == dlm.DLM_ERR_INVALID_ARG
     assert L.dlm_set_option(b"attn_variant", 0) == dlm.DLM_OK
+    assert L.dlm_set_option(b"attn_remap", 8) == dlm.DLM_ERR_INVALID_ARG
+    assert L.dlm_set_option(b"attn_remap", 7) == dlm.DLM_OK
 
 
 def test_binding_refuses_cpu_tensors():
