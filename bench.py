@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per LM-head launch on the default workload, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0, factors calibrated with a 1 GiB copy); summary and commands in
 # profiles/lmhead_c2_rollout_hbm_traffic.md.  Only valid for --config c2.
-LMHEAD_C2_TRAFFIC_BYTES = 1108.9e6
+LMHEAD_C2_TRAFFIC_BYTES = 1097.2e6
 
 
 def parse():
