@@ -224,7 +224,10 @@ def main():
     def setup(block):
         # block 0 installs the prompt cache image; later blocks refresh it when the workload says so
         refresh = image(block) if (block == 0 or cfg.refresh) else None
-        return dict(init_mask=init_masks[block], refresh=refresh, n_masked=n_masked0[block])
+        # a block that starts fully masked is announced as such (no mask tensor): the driver then knows the top-k
+        # rule's row schedule exactly
+        full = n_masked0[block] == cfg.B * cfg.Lb
+        return dict(init_mask=None if full else init_masks[block], refresh=refresh, n_masked=n_masked0[block])
 
     def restart():
         g.x.copy_(x0)
