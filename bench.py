@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--sync-loop", action="store_true", help="poll every step synchronously (no one-step-late poll)")
     ap.add_argument("--expect-ratio", type=float, default=None,
                     help="the driver's guess of (rows in a step) / (late row bound); 0 = no guess; default: the driver's")
+    ap.add_argument("--set-option", action="append", default=[], metavar="NAME=VALUE",
+                    help="library tuning knob (dlm_set_option) applied before the run; may be repeated")
     ap.add_argument("--dump-steps", default=None, metavar="FILE",
                     help="write one line per timed step: block, rows masked before / after, row bound, LM-head us")
     ap.add_argument("--kernel", default=None, choices=["lmhead", "attn_fullseq", "fullpass"],
@@ -183,6 +185,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dlm.lib()  # fail loudly if the HIP library is missing
+    for kv in args.set_option:
+        name, _, val = kv.partition("=")
+        dlm.set_option(name, int(val))
     if args.kernel:
         micro(args)
         return

@@ -151,6 +151,7 @@ struct CopyParams {
     int n_pos;
     const int32_t* active_in;  // DLM_WB_WHILE_ACTIVE: copy sequence b iff active_in[b] != 0
     int Hkv;
+    int split;                 // kv_copy_kernel: K and V by different workgroups
 };
 
 // Rollout-sized problems (one commit group per sequence, at most 16384 positions in all): ONE workgroup
@@ -405,12 +406,16 @@ __global__ __launch_bounds__(1024) void compact_kernel(const uint8_t* mask, int6
 
 template <int U>
 __global__ __launch_bounds__(256) void kv_copy_kernel(CopyParams p) {
-    const int b = blockIdx.z, h = blockIdx.y;
+    const int b = blockIdx.z;
+    // split != 0: grid.y = 2 * Hkv, the first Hkv rows of workgroups copy K, the others V (one read and one write
+    // stream per workgroup instead of two of each)
+    const int h = p.split ? (int)blockIdx.y % p.Hkv : (int)blockIdx.y;
+    const bool do_k = !p.split || (int)blockIdx.y < p.Hkv, do_v = !p.split || (int)blockIdx.y >= p.Hkv;
     if (p.mode == DLM_WB_BLOCK_WHEN_DONE) {
         if (!(p.remaining[b] == 0 && p.n_commit[b] > 0)) return;
     }
     if (p.mode == DLM_WB_WHILE_ACTIVE && p.active_in[b] == 0) return;
-    const int64_t total = (int64_t)p.len * p.d8;
+    const uint32_t total = (uint32_t)p.len * (uint32_t)p.d8;      // < 2^31 (checked by the host)
     const uint16_t* sk = p.sk + b * p.s_sb + h * p.s_sh;
     const uint16_t* sv = p.sv + b * p.s_sb + h * p.s_sh;
     uint16_t* ck = p.ck + b * p.c_sb + h * p.c_sh + (int64_t)p.cache_pos0 * p.c_st;
@@ -418,27 +423,30 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(CopyParams p) {
     u32x4 kreg[U], vreg[U];
     int64_t so[U], co[U];
     bool ok[U];
+    // 16-byte pieces per row: a power of two for the usual head sizes (a shift instead of a division per piece)
+    const int sh = ((p.d8 & (p.d8 - 1)) == 0) ? __builtin_ctz(p.d8) : -1;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t e = ((int64_t)blockIdx.x * U + u) * 256 + threadIdx.x;
+        const uint32_t e = (blockIdx.x * U + u) * 256u + threadIdx.x;
         ok[u] = e < total;
-        const int t = ok[u] ? (int)(e / p.d8) : 0;
-        const int c = ok[u] ? (int)(e - (int64_t)t * p.d8) : 0;
+        const uint32_t ec = ok[u] ? e : 0u;
+        const int t = (int)(sh >= 0 ? ec >> sh : ec / (uint32_t)p.d8);
+        const int c = (int)(ec - (uint32_t)t * (uint32_t)p.d8);
         if (p.mode == DLM_WB_COMMITTED_ROWS && ok[u]) ok[u] = p.commit_now[(int64_t)b * p.n_pos + t] != 0;
-        so[u] = t * p.s_st + c * 8;
-        co[u] = t * p.c_st + c * 8;
+        so[u] = (int64_t)t * p.s_st + c * 8;
+        co[u] = (int64_t)t * p.c_st + c * 8;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (ok[u]) {
-            kreg[u] = *reinterpret_cast<const u32x4*>(sk + so[u]);
-            vreg[u] = *reinterpret_cast<const u32x4*>(sv + so[u]);
+            if (do_k) kreg[u] = *reinterpret_cast<const u32x4*>(sk + so[u]);
+            if (do_v) vreg[u] = *reinterpret_cast<const u32x4*>(sv + so[u]);
         }
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (ok[u]) {
-            *reinterpret_cast<u32x4*>(ck + co[u]) = kreg[u];
-            *reinterpret_cast<u32x4*>(cv + co[u]) = vreg[u];
+            if (do_k) *reinterpret_cast<u32x4*>(ck + co[u]) = kreg[u];
+            if (do_v) *reinterpret_cast<u32x4*>(cv + co[u]) = vreg[u];
         }
 }
 
@@ -492,6 +500,9 @@ static int validate_seg_copy(const dlm_kv_seg* s, int B, int Hkv, int d, const v
     return DLM_OK;
 }
 
+static int g_copy_split = 1;    // 1: K and V copied by different workgroups (tuning)
+static int g_copy_unroll = 4;   // 16-byte pieces of K and of V per thread of kv_copy_kernel (tuning: 2, 4, 8)
+
 static CopyParams copy_params(const dlm_kv_seg* s, int Hkv, int d, void* ck, void* cv, int64_t c_sb, int64_t c_sh,
                               int64_t c_st, int cache_pos0, int mode, const int32_t* n_commit, const int32_t* remaining,
                               const uint8_t* commit_now, int n_pos, const int32_t* active_in) {
@@ -502,7 +513,7 @@ static CopyParams copy_params(const dlm_kv_seg* s, int Hkv, int d, void* ck, voi
     p.c_sb = c_sb; p.c_sh = c_sh; p.c_st = c_st;
     p.len = s->len; p.d8 = d / 8; p.cache_pos0 = cache_pos0;
     p.mode = mode; p.n_commit = n_commit; p.remaining = remaining; p.commit_now = commit_now; p.n_pos = n_pos;
-    p.active_in = active_in; p.Hkv = Hkv;
+    p.active_in = active_in; p.Hkv = Hkv; p.split = 0;
     return p;
 }
 
@@ -510,14 +521,19 @@ static int launch_kv_copy(const dlm_kv_seg* s, int B, int Hkv, int d, void* ck, 
                           int64_t c_st, int cache_pos0, int mode, const int32_t* n_commit, const int32_t* remaining,
                           const uint8_t* commit_now, int n_pos, hipStream_t st, const int32_t* active_in = nullptr) {
     if (s->len == 0 || B == 0) return DLM_OK;
-    const CopyParams p = copy_params(s, Hkv, d, ck, cv, c_sb, c_sh, c_st, cache_pos0, mode, n_commit, remaining, commit_now,
-                                     n_pos, active_in);
+    CopyParams p = copy_params(s, Hkv, d, ck, cv, c_sb, c_sh, c_st, cache_pos0, mode, n_commit, remaining, commit_now,
+                               n_pos, active_in);
+    p.split = (g_copy_split && 2 * Hkv <= 65535) ? 1 : 0;
     const int64_t total = (int64_t)s->len * p.d8;
+    if (total > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "kv copy: segment too long");
     if (Hkv > 65535 || B > 65535) return fail(DLM_ERR_UNSUPPORTED, "kv copy: B or Hkv above 65535");
-    constexpr int U = 4;
+    const int U = g_copy_unroll;
     const int64_t gx = (total + 256 * U - 1) / (256 * U);
     if (gx > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "kv copy: segment too long");
-    hipLaunchKernelGGL(kv_copy_kernel<U>, dim3((unsigned)gx, Hkv, B), dim3(256), 0, st, p);
+    const dim3 grid((unsigned)gx, p.split ? 2 * Hkv : Hkv, B);
+    if (U == 2) hipLaunchKernelGGL(kv_copy_kernel<2>, grid, dim3(256), 0, st, p);
+    else if (U == 8) hipLaunchKernelGGL(kv_copy_kernel<8>, grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(kv_copy_kernel<4>, grid, dim3(256), 0, st, p);
     return check_hip(hipGetLastError(), "kv_copy_kernel launch");
 }
 
@@ -665,3 +681,14 @@ extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
     }
     return DLM_OK;
 }
+
+namespace dlm {
+int copy_set_unroll(int v) {
+    // low digit: pieces per thread (2, 4, 8); +16: K and V by different workgroups
+    const int u = v & 15;
+    if ((u != 2 && u != 4 && u != 8) || (v & ~31)) return fail(DLM_ERR_INVALID_ARG, "set_option: kv_copy_unroll must be 2, 4 or 8 (+16)");
+    g_copy_unroll = u;
+    g_copy_split = (v >> 4) & 1;
+    return DLM_OK;
+}
+}  // namespace dlm
