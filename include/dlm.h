@@ -379,8 +379,8 @@ int dlm_kv_refresh(const dlm_kv_seg *src, int32_t B, int32_t Hkv, int32_t d,
  *                   loads (default); 0 = never.
  *   "attn_nt"       1 = non-temporal K/V loads when one workgroup is the only reader of its (sequence, KV head)
  *                   (g*Lq <= 32; default); 0 = never.
- *   "kv_copy_unroll" 16-byte pieces of K and of V per thread of the copy kernel (2, 4 or 8; default 4), plus 16 when K
- *                   and V are copied by different workgroups (default: 20).
+ *   "kv_copy_unroll" 16-byte pieces per thread of the copy kernel (1, 2, 4 or 8), plus 16 when K and V are copied by
+ *                   different workgroups, plus 32 / 64 for non-temporal loads / stores (default: 17).
  *   "attn_remap"    bit mask, default 7: 1 = 128-row workgroups of one (sequence, KV head) run on ONE XCD (1-D
  *                   grid; forward and the dQ pass), 2 = under a block-causal mask the row tile with the longest
  *                   key range is dispatched first, 4 = the same grouping for the dK / dV passes; 0 = plain

@@ -152,6 +152,7 @@ struct CopyParams {
     const int32_t* active_in;  // DLM_WB_WHILE_ACTIVE: copy sequence b iff active_in[b] != 0
     int Hkv;
     int split;                 // kv_copy_kernel: K and V by different workgroups
+    int nt;                    // bit 0: non-temporal loads, bit 1: non-temporal stores (split form only)
 };
 
 // Rollout-sized problems (one commit group per sequence, at most 16384 positions in all): ONE workgroup
@@ -436,6 +437,29 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(CopyParams p) {
         so[u] = (int64_t)t * p.s_st + c * 8;
         co[u] = (int64_t)t * p.c_st + c * 8;
     }
+    // a workgroup that lies wholly inside the segment (all but the last of a slab): no per-piece conditions
+    if ((blockIdx.x * U + U) * 256u <= total && p.mode != DLM_WB_COMMITTED_ROWS) {
+        const uint16_t* src = do_k ? sk : sv;
+        uint16_t* dst = do_k ? ck : cv;
+#pragma unroll
+        for (int u = 0; u < U; ++u) kreg[u] = p.nt ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + so[u])) : *reinterpret_cast<const u32x4*>(src + so[u]);
+        if (do_k && do_v) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) vreg[u] = *reinterpret_cast<const u32x4*>(sv + so[u]);
+        }
+        if (p.nt & 2) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) __builtin_nontemporal_store(kreg[u], reinterpret_cast<u32x4*>(dst + co[u]));
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) *reinterpret_cast<u32x4*>(dst + co[u]) = kreg[u];
+        }
+        if (do_k && do_v) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) *reinterpret_cast<u32x4*>(cv + co[u]) = vreg[u];
+        }
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u)
         if (ok[u]) {
@@ -500,8 +524,9 @@ static int validate_seg_copy(const dlm_kv_seg* s, int B, int Hkv, int d, const v
     return DLM_OK;
 }
 
+static int g_copy_nt = 0;       // tuning: non-temporal loads (1) / stores (2) in the copy kernel
 static int g_copy_split = 1;    // 1: K and V copied by different workgroups (tuning)
-static int g_copy_unroll = 4;   // 16-byte pieces of K and of V per thread of kv_copy_kernel (tuning: 2, 4, 8)
+static int g_copy_unroll = 1;   // 16-byte pieces per thread of kv_copy_kernel (tuning: 1, 2, 4, 8): small workgroups interleave reads and writes best
 
 static CopyParams copy_params(const dlm_kv_seg* s, int Hkv, int d, void* ck, void* cv, int64_t c_sb, int64_t c_sh,
                               int64_t c_st, int cache_pos0, int mode, const int32_t* n_commit, const int32_t* remaining,
@@ -513,7 +538,7 @@ static CopyParams copy_params(const dlm_kv_seg* s, int Hkv, int d, void* ck, voi
     p.c_sb = c_sb; p.c_sh = c_sh; p.c_st = c_st;
     p.len = s->len; p.d8 = d / 8; p.cache_pos0 = cache_pos0;
     p.mode = mode; p.n_commit = n_commit; p.remaining = remaining; p.commit_now = commit_now; p.n_pos = n_pos;
-    p.active_in = active_in; p.Hkv = Hkv; p.split = 0;
+    p.active_in = active_in; p.Hkv = Hkv; p.split = 0; p.nt = 0;
     return p;
 }
 
@@ -524,6 +549,7 @@ static int launch_kv_copy(const dlm_kv_seg* s, int B, int Hkv, int d, void* ck, 
     CopyParams p = copy_params(s, Hkv, d, ck, cv, c_sb, c_sh, c_st, cache_pos0, mode, n_commit, remaining, commit_now,
                                n_pos, active_in);
     p.split = (g_copy_split && 2 * Hkv <= 65535) ? 1 : 0;
+    p.nt = p.split ? g_copy_nt : 0;
     const int64_t total = (int64_t)s->len * p.d8;
     if (total > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "kv copy: segment too long");
     if (Hkv > 65535 || B > 65535) return fail(DLM_ERR_UNSUPPORTED, "kv copy: B or Hkv above 65535");
@@ -531,7 +557,8 @@ static int launch_kv_copy(const dlm_kv_seg* s, int B, int Hkv, int d, void* ck, 
     const int64_t gx = (total + 256 * U - 1) / (256 * U);
     if (gx > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "kv copy: segment too long");
     const dim3 grid((unsigned)gx, p.split ? 2 * Hkv : Hkv, B);
-    if (U == 2) hipLaunchKernelGGL(kv_copy_kernel<2>, grid, dim3(256), 0, st, p);
+    if (U == 1) hipLaunchKernelGGL(kv_copy_kernel<1>, grid, dim3(256), 0, st, p);
+    else if (U == 2) hipLaunchKernelGGL(kv_copy_kernel<2>, grid, dim3(256), 0, st, p);
     else if (U == 8) hipLaunchKernelGGL(kv_copy_kernel<8>, grid, dim3(256), 0, st, p);
     else hipLaunchKernelGGL(kv_copy_kernel<4>, grid, dim3(256), 0, st, p);
     return check_hip(hipGetLastError(), "kv_copy_kernel launch");
@@ -686,9 +713,10 @@ namespace dlm {
 int copy_set_unroll(int v) {
     // low digit: pieces per thread (2, 4, 8); +16: K and V by different workgroups
     const int u = v & 15;
-    if ((u != 2 && u != 4 && u != 8) || (v & ~31)) return fail(DLM_ERR_INVALID_ARG, "set_option: kv_copy_unroll must be 2, 4 or 8 (+16)");
+    if ((u != 1 && u != 2 && u != 4 && u != 8) || (v & ~127)) return fail(DLM_ERR_INVALID_ARG, "set_option: kv_copy_unroll must be 1, 2, 4 or 8 (+16, +32, +64)");
     g_copy_unroll = u;
     g_copy_split = (v >> 4) & 1;
+    g_copy_nt = (v >> 5) & 3;
     return DLM_OK;
 }
 }  // namespace dlm
