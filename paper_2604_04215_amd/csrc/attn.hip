@@ -461,27 +461,48 @@ _Pragma("unroll") \
     // ---- finish -----------------------------------------------------------------
     constexpr float LN2 = 0.6931471805599453f;
     if (NWK == 1) {
+        // The accumulators hold O^T (lane = row, registers = head-dim entries): stored straight from registers a
+        // wavefront's store touches 32 rows with 16 bytes each, 64 such stores per row tile.  Each wavefront instead
+        // transposes its 32 rows through a private LDS region (the K/V tiles are dead: the loop ended with a
+        // barrier) and writes whole rows, 16 bytes per lane: 4 (d = 64) or 8 stores that cover full cache lines.
+        constexpr int OPB = D * 2 + 16;                    // staging row pitch in bytes (16-byte aligned)
+        static_assert(NWR * 32 * OPB + NWR * 32 * 8 <= 2 * TILE_BYTES, "output staging must fit in the tile buffers");
+        unsigned char* ob = smem + wr * (32 * OPB);
+        int64_t* roff = reinterpret_cast<int64_t*>(smem + NWR * 32 * OPB) + wr * 32;
 #pragma unroll
         for (int rt = 0; rt < RTW; ++rt) {
             const float l = l_run[rt] + shfl_xor(l_run[rt], 32);
             const float inv = l > 0.f ? 1.f / l : 0.f;
             const int r = r0 + (wr * RTW + rt) * 32 + n;
+            int64_t off = -1;
             if (r < R) {
                 const int i = r / p.g, hg = r - i * p.g;
                 const int h = kvh * p.g + hg;
-                uint16_t* op = p.out + o_off + i * p.o_st + (int64_t)h * p.o_sh;
-#pragma unroll
-                for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        u32x2 v;
-                        v[0] = pack_bf16x2(O[rt][dt][4 * q4] * inv, O[rt][dt][4 * q4 + 1] * inv);
-                        v[1] = pack_bf16x2(O[rt][dt][4 * q4 + 2] * inv, O[rt][dt][4 * q4 + 3] * inv);
-                        *reinterpret_cast<u32x2*>(op + 32 * dt + 8 * q4 + 4 * hi) = v;
-                    }
+                off = i * p.o_st + (int64_t)h * p.o_sh;
                 if (p.lse && hi == 0)
                     p.lse[p.cu ? (int64_t)h * p.total + s0 + i : ((int64_t)b * p.Hq + h) * p.Lq + i] = l > 0.f ? (m_run[rt] + log2f(l)) * LN2 : -INFINITY;
             }
+            if (hi == 0) roff[n] = off;
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    u32x2 v;
+                    v[0] = pack_bf16x2(O[rt][dt][4 * q4] * inv, O[rt][dt][4 * q4 + 1] * inv);
+                    v[1] = pack_bf16x2(O[rt][dt][4 * q4 + 2] * inv, O[rt][dt][4 * q4 + 3] * inv);
+                    *reinterpret_cast<u32x2*>(ob + n * OPB + (32 * dt + 8 * q4 + 4 * hi) * 2) = v;
+                }
+            // one wavefront's LDS operations complete in order: only the compiler must not move the reads up
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int q = 0; q < (32 * C8) / 64; ++q) {
+                const int id = q * 64 + lane;
+                const int row = id / C8, c = id - row * C8;
+                const int64_t ro = roff[row];
+                const u32x4 v = *reinterpret_cast<const u32x4*>(ob + row * OPB + c * 16);
+                if (ro >= 0) *reinterpret_cast<u32x4*>(p.out + o_off + ro + 8 * c) = v;
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // before the next row tile overwrites the region
         }
     } else {
         float* mb = reinterpret_cast<float*>(smem);
