@@ -102,7 +102,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(BwdParams p, GridRe
     constexpr int TP = D * 2 + 64;         // transposing-read image pitch
     constexpr int C8 = D / 8;
     constexpr int NLD = (32 * C8) / 256;   // 16-byte chunks per thread per 32-row tile
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * 32 * KP + 32 * TP];
+    constexpr int OPB = D * 2 + 16;        // output staging row pitch (bytes)
+    constexpr int TILES_BYTES = 2 * 32 * KP + 32 * TP, STAGE_BYTES = 4 * 32 * OPB + 4 * 32 * 8;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[TILES_BYTES > STAGE_BYTES ? TILES_BYTES : STAGE_BYTES];
     unsigned char* Krow = smem;
     unsigned char* Vrow = smem + 32 * KP;
     unsigned char* Ktr = smem + 2 * 32 * KP;
@@ -320,8 +322,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(BwdParams p, GridRe
 #undef BW_FETCH
 #undef BW_STORE
 
-    if (valid) {
-        uint16_t* op = p.dq + dq_off + qi * p.dq_st + (int64_t)h * p.dq_sh;
+    // dQ^T sits in the accumulators with lane = row: each wavefront transposes its 32 rows through a private LDS
+    // region (the tiles are dead: the loop ended with a barrier, or never ran) and stores whole rows, 16 bytes per
+    // lane, instead of 64 stores that touch 32 rows with 16 bytes each.
+    {
+        unsigned char* ob = smem + w * (32 * OPB);
+        int64_t* roff = reinterpret_cast<int64_t*>(smem + 4 * 32 * OPB) + w * 32;
+        if (hi == 0) roff[n] = valid ? qi * p.dq_st + (int64_t)h * p.dq_sh : (int64_t)-1;
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
@@ -329,8 +336,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(BwdParams p, GridRe
                 u32x2 v;
                 v[0] = pack_bf16x2(dq[dt][4 * q4] * p.scale, dq[dt][4 * q4 + 1] * p.scale);
                 v[1] = pack_bf16x2(dq[dt][4 * q4 + 2] * p.scale, dq[dt][4 * q4 + 3] * p.scale);
-                *reinterpret_cast<u32x2*>(op + 32 * dt + 8 * q4 + 4 * hi) = v;
+                *reinterpret_cast<u32x2*>(ob + n * OPB + (32 * dt + 8 * q4 + 4 * hi) * 2) = v;
             }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // one wavefront's LDS operations complete in order
+#pragma unroll
+        for (int q = 0; q < (32 * C8) / 64; ++q) {
+            const int id = q * 64 + lane;
+            const int row = id / C8, c = id - row * C8;
+            const int64_t ro = roff[row];
+            const u32x4 v = *reinterpret_cast<const u32x4*>(ob + row * OPB + c * 16);
+            if (ro >= 0) *reinterpret_cast<u32x4*>(p.dq + dq_off + ro + 8 * c) = v;
+        }
     }
 }
 
