@@ -50,6 +50,8 @@ def lockstep(cfg, blocks=None, **sample):
         assert np.array_equal(bf16_host(g.cache_k), o.cache_k), "cache refresh is a bitwise copy"
         traj = np.full((cfg.B, cfg.Lb), -1, np.int16)      # step at which each position was committed
         O_prev = None
+        final_kv = {}                                      # sequence -> block K/V of the step in which it finished
+        cache_at_block_start = (bf16_host(g.cache_k), bf16_host(g.cache_v))
         while o.mask.any():
             mask_before = o.mask.copy()
             r = o.step()
@@ -116,13 +118,30 @@ def lockstep(cfg, blocks=None, **sample):
             assert np.array_equal(commit_g, mask_before - mask_g)
             stats["committed"] += int(n_commit_g.sum())
             traj[commit_g.astype(bool)] = r["step"]
-            # re-synchronise the oracle to the GPU state (a no-op unless an ambiguous step differed)
+            # cache write-back: a sequence that finished in THIS step (on the GPU) holds this step's block K/V in its
+            # slot, one that finished earlier still holds what it held then, the rows outside the slot never change
+            ck_g, cv_g = bf16_host(g.cache_k), bf16_host(g.cache_v)
+            kb_s, vb_s = synth.step_kv(cfg, b, r["step"])
+            for s in range(cfg.B):
+                if remaining_g[s] == 0 and n_commit_g[s] > 0:
+                    final_kv[s] = (kb_s[s].copy(), vb_s[s].copy())
+                if s in final_kv:
+                    assert np.array_equal(ck_g[s, :, o.P:o.P + cfg.Lb], final_kv[s][0]), f"K write-back, block {b} seq {s}"
+                    assert np.array_equal(cv_g[s, :, o.P:o.P + cfg.Lb], final_kv[s][1]), f"V write-back, block {b} seq {s}"
+            outside = np.ones(cfg.L, bool)
+            outside[o.P:o.P + cfg.Lb] = False
+            assert np.array_equal(ck_g[:, :, outside], cache_at_block_start[0][:, :, outside])
+            assert np.array_equal(cv_g[:, :, outside], cache_at_block_start[1][:, :, outside])
+            # re-synchronise the oracle to the GPU state (a no-op unless an ambiguous step differed; the slot of a
+            # sequence that has not finished may hold an earlier step's K/V on the GPU, which nothing reads)
             o.x[:] = x_g
             o.mask[:] = mask_g
-            o.cache_k[:] = bf16_host(g.cache_k)
-            o.cache_v[:] = bf16_host(g.cache_v)
-        # block done: nothing masked, the final step's block K/V sits in the cache
+            o.cache_k[:] = ck_g
+            o.cache_v[:] = cv_g
+        # block done: nothing masked, the final step's block K/V sits in the cache of every sequence that had
+        # masked positions
         assert not g.mask.any().item()
+        assert set(final_kv) == set(np.flatnonzero(synth.initial_block_mask(cfg, b).any(axis=1)))
         init = synth.initial_block_mask(cfg, b).astype(bool)
         assert np.array_equal(g.commit_step.cpu().numpy()[init], traj[init]), "trajectory record"
     assert stats["excluded"] <= 0.05 * max(1, stats["seq_steps"]), stats
