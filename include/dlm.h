@@ -265,6 +265,21 @@ typedef struct dlm_lmhead_args {
 int dlm_lmhead_confidence(const dlm_lmhead_args *args, void *stream);
 size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args *args);
 
+/* dlm_lmhead_confidence_static -- dlm_lmhead_confidence for callers that cannot allocate or pass a
+ * workspace: code running under HIP graph capture, tight serving loops that own no allocator, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same results; a->workspace / a->workspace_bytes are ignored
+ * and the per-tile partials go to a scratch array built into the library (DLM_LMHEAD_STATIC_SCRATCH_BYTES of
+ * device memory per GPU the library runs on, held until the process ends).  The call allocates and frees
+ * nothing; on its first use on a device it looks up that device's address of the array (no allocation).
+ * Limit: dlm_lmhead_workspace_bytes(a) <= DLM_LMHEAD_STATIC_SCRATCH_BYTES (e.g. 1024 rows at V = 152064,
+ * 512 rows when sampling), else DLM_ERR_WORKSPACE and nothing is enqueued.
+ * All calls on one GPU share the one array: calls that overlap in time on the same GPU (different streams or
+ * threads) race; calls on one stream are ordered and safe.  Nothing in the array needs clearing between calls:
+ * every partial a call reads was written by that call. */
+#define DLM_LMHEAD_STATIC_SCRATCH_BYTES (32u << 20)
+int dlm_lmhead_confidence_static(const dlm_lmhead_args *args, void *stream);
+size_t dlm_lmhead_static_scratch_bytes(void);
+
 /* ------------------------------------------------------------------------- *
  * dlm_unmask_commit -- per sequence and per commit group of group_len
  * consecutive positions, among positions with mask == 1:

@@ -22,7 +22,7 @@ CONF_TOKEN_PROB, CONF_MARGIN, CONF_NEG_ENTROPY = 0, 1, 2
 WB_NONE, WB_BLOCK_WHEN_DONE, WB_COMMITTED_ROWS, WB_WHILE_ACTIVE = 0, 1, 2, 3
 
 EXPORTS = ["dlm_block_attn", "dlm_block_attn_workspace_bytes", "dlm_lmhead_confidence",
-           "dlm_lmhead_workspace_bytes", "dlm_unmask_commit", "dlm_mask_compact", "dlm_kv_refresh",
+           "dlm_lmhead_workspace_bytes", "dlm_lmhead_confidence_static", "dlm_lmhead_static_scratch_bytes", "dlm_unmask_commit", "dlm_mask_compact", "dlm_kv_refresh",
            "dlm_block_attn_bwd", "dlm_block_attn_bwd_workspace_bytes", "dlm_seq_logprob", "dlm_set_option", "dlm_last_error", "dlm_version"]
 
 
@@ -116,6 +116,10 @@ def lib():
         L.dlm_lmhead_confidence.argtypes = [C.POINTER(LmheadArgs), C.c_void_p]
         L.dlm_lmhead_workspace_bytes.restype = C.c_size_t
         L.dlm_lmhead_workspace_bytes.argtypes = [C.POINTER(LmheadArgs)]
+        L.dlm_lmhead_confidence_static.restype = C.c_int
+        L.dlm_lmhead_confidence_static.argtypes = [C.POINTER(LmheadArgs), C.c_void_p]
+        L.dlm_lmhead_static_scratch_bytes.restype = C.c_size_t
+        L.dlm_lmhead_static_scratch_bytes.argtypes = []
         L.dlm_unmask_commit.restype = C.c_int
         L.dlm_unmask_commit.argtypes = [C.POINTER(CommitArgs), C.c_void_p]
         L.dlm_mask_compact.restype = C.c_int
@@ -337,10 +341,12 @@ def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=
                       inv_temperature: float = 1.0, forbid_token: int = -1, out_scatter: bool = False,
                       lse=None, zmax=None, z2nd=None, target=None, ztarget=None, workspace=None,
                       sample_seed: Optional[int] = None, sample_step: int = 0, sample_stream: int = 0,
-                      conf_mode: int = CONF_TOKEN_PROB, M_expected: int = 0, stream=None) -> None:
+                      conf_mode: int = CONF_TOKEN_PROB, M_expected: int = 0, stream=None,
+                      static_scratch: bool = False) -> None:
     """hidden bf16 [rows, Dh]; w bf16 [V, Dh]; conf fp32 / tok int32 outputs; workspace: a uint8 tensor.
     sample_seed: None = arg-max token; an integer = Gumbel-max sample with that seed.
-    M_expected: a guess of the row count m_dev holds (0 = none); only the choice of kernel shape depends on it."""
+    M_expected: a guess of the row count m_dev holds (0 = none); only the choice of kernel shape depends on it.
+    static_scratch: call dlm_lmhead_confidence_static (the library's built-in scratch; no workspace tensor)."""
     import torch
     a = LmheadArgs()
     a.struct_size = C.sizeof(LmheadArgs)
@@ -367,7 +373,8 @@ def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=
     if sample_seed is not None:
         a.sample, a.sample_seed = 1, int(sample_seed) & 0xFFFFFFFFFFFFFFFF
         a.sample_step, a.sample_stream = int(sample_step) & 0xFFFFFFFF, int(sample_stream) & 0xFFFFFFFF
-    _check(lib().dlm_lmhead_confidence(C.byref(a), _stream(stream)))
+    fn = lib().dlm_lmhead_confidence_static if static_scratch else lib().dlm_lmhead_confidence
+    _check(fn(C.byref(a), _stream(stream)))
 
 
 def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group_len: Optional[int] = None,

@@ -1298,14 +1298,9 @@ extern "C" size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args* a) {
     return n_vt * (size_t)a->M * sizeof(f32x4) * ((a->sample || a->conf_mode == DLM_CONF_NEG_ENTROPY) ? 2 : 1);
 }
 
-extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
-    int rc = validate_lm(a);
-    if (rc != DLM_OK) return rc;
-    if (a->M == 0) return DLM_OK;
-    const size_t need = dlm_lmhead_workspace_bytes(a);
-    if (!a->workspace || a->workspace_bytes < need)
-        return fail(DLM_ERR_WORKSPACE, "lmhead: workspace of %zu bytes needed, %zu given", need, a->workspace ? a->workspace_bytes : (size_t)0);
-    if (!aligned16(a->workspace)) return fail(DLM_ERR_WORKSPACE, "lmhead: workspace not 16-byte aligned");
+// Enqueues the main kernel(s) and the reduction of one call; `workspace` holds the per-tile partials.
+static int lmhead_enqueue(const dlm_lmhead_args* a, void* workspace, void* stream) {
+    int rc;
     LmParams p;
     p.M = a->M; p.Dh = a->Dh; p.V = a->V;
     p.hidden = (const uint16_t*)a->hidden; p.h_stride = a->hidden_stride_row;
@@ -1314,7 +1309,7 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     p.inv_t = a->inv_temperature; p.forbid = a->forbid_token; p.out_scatter = a->out_scatter;
     p.conf = a->conf; p.tok = a->tok; p.lse = a->lse; p.zmax = a->zmax; p.z2nd = a->z2nd;
     p.target = a->target; p.ztarget = a->ztarget;
-    p.part = (f32x4*)a->workspace;
+    p.part = (f32x4*)workspace;
     p.sample = a->sample;
     p.conf_mode = a->conf_mode;
     p.seed_lo = (uint32_t)a->sample_seed; p.seed_hi = (uint32_t)(a->sample_seed >> 32);
@@ -1345,6 +1340,47 @@ extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
     if (rc != DLM_OK) return rc;
     hipLaunchKernelGGL(lmhead_reduce_kernel, dim3(a->M), dim3(256), 0, st, p);
     return check_hip(hipGetLastError(), "lmhead_reduce_kernel launch");
+}
+
+extern "C" int dlm_lmhead_confidence(const dlm_lmhead_args* a, void* stream) {
+    int rc = validate_lm(a);
+    if (rc != DLM_OK) return rc;
+    if (a->M == 0) return DLM_OK;
+    const size_t need = dlm_lmhead_workspace_bytes(a);
+    if (!a->workspace || a->workspace_bytes < need)
+        return fail(DLM_ERR_WORKSPACE, "lmhead: workspace of %zu bytes needed, %zu given", need, a->workspace ? a->workspace_bytes : (size_t)0);
+    if (!aligned16(a->workspace)) return fail(DLM_ERR_WORKSPACE, "lmhead: workspace not 16-byte aligned");
+    return lmhead_enqueue(a, a->workspace, stream);
+}
+
+// ---- the variant that allocates nothing ------------------------------------------------------------------
+// The per-tile partials live in a file-scope device array instead of a caller-provided workspace.  Every GPU the
+// library runs on holds its own copy of the array (at its own address) until the process ends; the address is
+// looked up once per device, with that device current, and only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[DLM_LMHEAD_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES];   // per device: device address of `scratch` (null until looked up)
+
+extern "C" size_t dlm_lmhead_static_scratch_bytes(void) { return sizeof(scratch); }
+
+extern "C" int dlm_lmhead_confidence_static(const dlm_lmhead_args* a, void* stream) {
+    int rc = validate_lm(a);
+    if (rc != DLM_OK) return rc;
+    if (a->M == 0) return DLM_OK;
+    const size_t need = dlm_lmhead_workspace_bytes(a);
+    if (need > sizeof(scratch))
+        return fail(DLM_ERR_WORKSPACE, "lmhead (static scratch): M=%d rows x V=%d needs %zu bytes of partials, the built-in "
+                    "scratch holds %zu; use dlm_lmhead_confidence with a workspace", a->M, a->V, need, sizeof(scratch));
+    int dev = -1;
+    if ((rc = check_hip(hipGetDevice(&dev), "hipGetDevice")) != DLM_OK) return rc;
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(DLM_ERR_UNSUPPORTED, "lmhead (static scratch): device index %d", dev);
+    void* ptr = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!ptr) {
+        if ((rc = check_hip(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) != DLM_OK) return rc;
+        if (!ptr || !aligned16(ptr)) return fail(DLM_ERR_HIP, "lmhead (static scratch): bad symbol address");
+        __atomic_store_n(&g_scratch_ptr[dev], ptr, __ATOMIC_RELEASE);
+    }
+    return lmhead_enqueue(a, ptr, stream);
 }
 
 namespace dlm {
