@@ -6,15 +6,23 @@ hidden 4096, vocabulary 126464, prompt 512, 256 generated tokens in 8 blocks of 
 with the most confident position always committed, prefix cache refreshed at every block start):
 block attention against [prefix | block], LM head -> confidence on the still-masked rows,
 threshold commit with KV write-back, plus the block-boundary cache refresh when a block starts.
-Steps continue across blocks and rollouts; K productive steps are timed.
+Steps continue across blocks and rollouts; K productive steps are timed, with nothing but the step's
+own launches inside the timed region.
 
-Prints ONE JSON line: committed tokens/s, the roofline of the dominant kernel (the LM head, which
-streams the 1.04 GB W_vocab every step) measured with HIP events on the launch stream, and the CPU
-oracle timed on a bounded sample of the same workload.
+After the timed region a separate pass of a FIXED number of steps (--sample-steps, independent of
+--steps) brackets every library call with HIP events on the launch stream; from it come the per-call
+durations, the algorithmic bytes / FLOP of each call (from the row and sequence counts the device
+reported for that very step) and the fraction of the roof that binds each of them.
+
+Prints ONE JSON line: committed tokens/s; `roofline` for the call that takes most of the step; `kernels`
+with the same figures for dlm_block_attn, dlm_lmhead_confidence, dlm_unmask_commit and dlm_kv_refresh,
+against nominal and measured peaks; `cpu_baseline`: the CPU oracle timed on a bounded sample of the
+same workload, with its linear extrapolation to the whole batch.
 """
 from __future__ import annotations
 
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -23,11 +31,26 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, nominal
+MFMA_PEAK_TFLOPS = 2500.0      # dense bf16 MFMA, nominal
+RIDGE = MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)     # FLOP per byte at which the two roofs meet (312.5)
 # HBM bytes per LM-head launch on the default workload, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0, factors calibrated with a 1 GiB copy); summary and commands in
-# profiles/lmhead_c2_rollout_hbm_traffic.md.  Only valid for --config c2.
+# profiles/lmhead_c2_rollout_hbm_traffic.md.  Only valid for --config c2 with the default W distribution.
 LMHEAD_C2_TRAFFIC_BYTES = 1097.2e6
+
+WORKLOADS = {
+    "c1": "c1: tiny single block, B=1, 4 heads MHA, d=64, hidden 256, V=2048, prefix 256, block 32 with 16 masked, "
+          "threshold 0.9 + forced top-1",
+    "c2": "c2: LLaDA-8B-shaped rollout, B=8, 32 heads MHA, d=128, hidden 4096, V=126464, prompt 512, gen 256 in 8 blocks "
+          "of 32, threshold 0.9 + forced top-1, prefix cache refreshed per block",
+    "c3": "c3: dual-cache rollout, B=16, 32 heads MHA, d=128, hidden 4096, V=126464, prompt 1024, gen 512 in 16 blocks of "
+          "32, keys = prefix + block + suffix (1536), threshold 0.9 + forced top-1, caches refreshed per block",
+    "c4": "c4: Dream-7B-shaped GQA rollout, B=32, 28 query / 4 KV heads, d=128, hidden 3584, V=152064, prompt 768, gen 256 "
+          "in 8 blocks of 32, fixed top-k=4 commits per step",
+    "c5a": "c5a: block-diffusion rollout of the last block, B=64, 32 query / 8 KV heads, d=128, hidden 4096, V=157184, "
+           "block-causal with block size 4 against a 4092-token cache, threshold 0.95 + forced top-1",
+}
 
 
 def parse():
@@ -35,22 +58,36 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1500)
     ap.add_argument("--warmup", type=int, default=150)
-    ap.add_argument("--config", default="c2")
+    ap.add_argument("--config", default="c2", choices=sorted(WORKLOADS))
+    ap.add_argument("--w-dist", default="var", choices=["var", "std"],
+                    help="W_vocab ~ N(0, x) with x = Dh^-1/2 read as a variance (default: logit std Dh^1/4, both branches of the "
+                         "threshold rule fire) or as a standard deviation (logit std 1: the threshold never fires and every "
+                         "step commits exactly one position per sequence)")
+    ap.add_argument("--ramp-steps", type=int, default=300,
+                    help="untimed steps queued before the --warmup steps so that a short run is timed at the same clock "
+                         "as a long one (the discovery pass before them leaves the GPU mostly idle)")
+    ap.add_argument("--sample-steps", type=int, default=400,
+                    help="steps of the per-call event-timing pass that follows the timed region (0 = skip it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-events", action="store_true", help="skip per-step LM-head event timing")
+    ap.add_argument("--oracle-seqs", type=int, default=0,
+                    help="cpu_baseline: sequences the oracle runs (block 0 to completion); 0 = as many as fit in ~12 s")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the achievable-peak micro-benchmarks")
     ap.add_argument("--sync-loop", action="store_true", help="poll every step synchronously (no one-step-late poll)")
     ap.add_argument("--expect-ratio", type=float, default=None,
                     help="the driver's guess of (rows in a step) / (late row bound); 0 = no guess; default: the driver's")
     ap.add_argument("--set-option", action="append", default=[], metavar="NAME=VALUE",
                     help="library tuning knob (dlm_set_option) applied before the run; may be repeated")
     ap.add_argument("--dump-steps", default=None, metavar="FILE",
-                    help="write one line per timed step: block, rows masked before / after, row bound, LM-head us")
-    ap.add_argument("--kernel", default=None, choices=["lmhead", "attn_fullseq", "fullpass"],
-                    help="time ONE kernel on random inputs instead of the rollout (record only, for profiles): "
-                         "lmhead = dlm_lmhead_confidence at --rows rows on the config's W shape; attn_fullseq = "
-                         "dlm_block_attn (and, with --backward, dlm_block_attn_bwd) on 64 x 4096 tokens, 32/8 heads, d = 128; "
-                         "fullpass = one full-sequence block-diffusion pass of workload c5b (attention, row compaction, "
-                         "LM head on the masked rows, one commit per block of 4), each part timed")
+                    help="write one line per sampled step: block, rows masked before / after, active sequences, "
+                         "attention / LM-head / commit call in us")
+    ap.add_argument("--kernel", default=None, choices=["lmhead", "attn_fullseq", "fullpass", "kv_refresh", "peaks", "attn"],
+                    help="time ONE library call on random inputs instead of the rollout (record only, for profiles): "
+                         "lmhead = dlm_lmhead_confidence at --rows rows on the config's W shape; attn = dlm_block_attn at the "
+                         "config's rollout shape (last block); attn_fullseq = dlm_block_attn (and, with --backward, "
+                         "dlm_block_attn_bwd) on 64 x 4096 tokens, 32/8 heads, d = 128; fullpass = one full-sequence "
+                         "block-diffusion pass of workload c5b (attention, row compaction, LM head on the masked rows, one "
+                         "commit per block of 4), each part timed; kv_refresh = dlm_kv_refresh on the cache images of c2, "
+                         "c3, c4 and c5; peaks = device copy, one-pass read and register-only MFMA loop")
     ap.add_argument("--rows", type=int, default=8192, help="--kernel lmhead: number of hidden rows M")
     ap.add_argument("--lmhead-variant", default="-1", help="--kernel lmhead: comma-separated entries of the shape table (-1 = planner)")
     ap.add_argument("--zeros", action="store_true", help="--kernel lmhead: all-zero operands (no data-dependent power)")
@@ -59,6 +96,52 @@ def parse():
     ap.add_argument("--backward", action="store_true", help="--kernel attn_fullseq: also time the backward pass")
     ap.add_argument("--reps", type=int, default=3, help="--kernel: timed calls per measurement")
     return ap.parse_args()
+
+
+# ---------------------------------------------------------------------------------------------------------- #
+# achievable peaks (libdlm_peaks: plain copy, one-pass read, register-only MFMA loop)
+# ---------------------------------------------------------------------------------------------------------- #
+def measure_peaks(torch, reps: int = 20) -> dict:
+    from paper_2604_04215_amd.build import PEAKS_LIB
+    if not os.path.exists(PEAKS_LIB):
+        raise RuntimeError(f"{PEAKS_LIB} not found: build it with `python -m paper_2604_04215_amd.build`")
+    L = C.CDLL(PEAKS_LIB)
+    L.dlm_peak_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]
+    L.dlm_peak_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p]
+    L.dlm_peak_mfma.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    dev = "cuda:0"
+    nbytes = 1 << 30
+    src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(nbytes // 16384 + 16, dtype=torch.int32, device=dev)
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def timed(fn):
+        for _ in range(3):
+            assert fn() == 0
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    out = {}
+    t = timed(lambda: L.dlm_peak_copy(src.data_ptr(), dst.data_ptr(), nbytes, 0, st))
+    out["copy_gbs"] = round(2 * nbytes / t / 1e9, 1)               # read + write
+    t = timed(lambda: L.dlm_peak_read(src.data_ptr(), nbytes, 0, sink.data_ptr(), st))
+    out["read_gbs"] = round(nbytes / t / 1e9, 1)
+    t = timed(lambda: L.dlm_peak_read(src.data_ptr(), nbytes, 1, sink.data_ptr(), st))
+    out["read_nt_gbs"] = round(nbytes / t / 1e9, 1)
+    n_wg, iters = 256 * 8, 4096
+    fs = torch.zeros(n_wg * 4, dtype=torch.float32, device=dev)
+    t = timed(lambda: L.dlm_peak_mfma(n_wg, iters, fs.data_ptr(), st))
+    out["mfma_bf16_tflops"] = round(n_wg * 4 * iters * 8 * 32768 / t / 1e12, 1)
+    out["what"] = ("1 GiB device copy (read + write), 1 GiB one-pass read with ordinary / non-temporal loads, "
+                   "register-only 32x32x16 bf16 MFMA loop on 2048 workgroups of 4 wavefronts")
+    return out
 
 
 def micro(args):
@@ -81,6 +164,48 @@ def micro(args):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
 
+    if args.kernel == "peaks":
+        print(json.dumps({"kernel": "peaks", **measure_peaks(torch, max(args.reps, 10))}), flush=True)
+        return
+    if args.kernel == "kv_refresh":
+        # the block-boundary cache refresh of every rollout workload: the prefix (and, dual cache, suffix) image
+        for name, B, Hkv, L, rows in (("c2 prefix at the last block", 8, 32, 768, 736), ("c3 prefix + suffix", 16, 32, 1536, 1504),
+                                      ("c4-sized cache", 32, 4, 1024, 992), ("c5 cache", 64, 8, 4096, 4092)):
+            src_k = torch.randn((B, Hkv, L, 128), device=dev).bfloat16()
+            src_v = torch.randn((B, Hkv, L, 128), device=dev).bfloat16()
+            ck, cv = torch.empty_like(src_k), torch.empty_like(src_v)
+            ms = timed(lambda: dlm.kv_refresh(src_k[:, :, :rows], src_v[:, :, :rows], ck, cv, 0), max(args.reps, 10))
+            moved = 2 * 2 * B * Hkv * rows * 128 * 2          # K and V, read + write
+            print(json.dumps({"kernel": "dlm_kv_refresh", "workload": name, "B": B, "Hkv": Hkv, "rows": rows, "d": 128,
+                              "bytes_read_plus_written": moved, "us": round(ms * 1e3, 1),
+                              "gbs": round(moved / ms / 1e6, 1), "frac_hbm_peak": round(moved / ms / 1e6 / HBM_PEAK_GBS, 3)}),
+                  flush=True)
+            del src_k, src_v, ck, cv
+        return
+    if args.kernel == "attn":
+        cfg = synth.CONFIGS[args.config]
+        blk = cfg.n_blocks - 1
+        P = cfg.prompt + blk * cfg.Lb
+        S = cfg.L - P - cfg.Lb if cfg.dual_cache else 0
+        mk = lambda *shape: torch.randn(shape, device=dev).bfloat16()
+        ck, cv = mk(cfg.B, cfg.Hkv, cfg.L, cfg.d), mk(cfg.B, cfg.Hkv, cfg.L, cfg.d)
+        q, kb, vb = mk(cfg.B, cfg.Lb, cfg.Hq, cfg.d), mk(cfg.B, cfg.Hkv, cfg.Lb, cfg.d), mk(cfg.B, cfg.Hkv, cfg.Lb, cfg.d)
+        out = torch.empty_like(q)
+        mode = dlm.MASK_FULL if cfg.mask_mode == "full" else dlm.MASK_BLOCK_CAUSAL
+        suffix = (ck[:, :, P + cfg.Lb:], cv[:, :, P + cfg.Lb:], P + cfg.Lb) if S > 0 else None
+        ws_bytes = dlm.block_attn_workspace_bytes(q, prefix=(ck[:, :, :P], cv[:, :, :P], 0), block=(kb, vb, P), suffix=suffix,
+                                                  mask_mode=mode, block_size=cfg.bs, q_pos0=P)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+        ms = timed(lambda: dlm.block_attn(q, out, prefix=(ck[:, :, :P], cv[:, :, :P], 0), block=(kb, vb, P), suffix=suffix,
+                                          mask_mode=mode, block_size=cfg.bs, q_pos0=P, workspace=ws), max(args.reps, 20))
+        Lk = P + cfg.Lb + S
+        nbytes, flop = attn_cost(cfg, cfg.B, Lk)
+        print(json.dumps({"kernel": "dlm_block_attn", "workload": f"{cfg.name} rollout step, last block", "B": cfg.B,
+                          "heads": [cfg.Hq, cfg.Hkv], "Lq": cfg.Lb, "Lk": Lk, "workspace_bytes": ws_bytes,
+                          "us": round(ms * 1e3, 1), "gbs": round(nbytes / ms / 1e6, 1), "tflops": round(flop / ms / 1e9, 1),
+                          "frac_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 3),
+                          "frac_mfma_peak": round(flop / ms / 1e9 / MFMA_PEAK_TFLOPS, 3)}), flush=True)
+        return
     if args.kernel == "lmhead":
         cfg = synth.CONFIGS[args.config]
         M, V, Dh = args.rows, cfg.V, cfg.Dh
@@ -96,10 +221,12 @@ def micro(args):
         for variant in [int(x) for x in args.lmhead_variant.split(",")]:
             dlm.set_option("lmhead_variant", variant)
             ms = timed(lambda: dlm.lmhead_confidence(h, w, conf, tok, workspace=ws, forbid_token=V - 1), args.reps)
+            nbytes, flop = lmhead_cost(cfg, M)
             print(json.dumps({"kernel": "dlm_lmhead_confidence", "M": M, "V": V, "Dh": Dh, "variant": variant,
                               "data": "zeros" if args.zeros else "normal", "us": round(ms * 1e3, 1),
-                              "tflops": round(2.0 * M * V * Dh / ms / 1e9, 1),
-                              "w_stream_gbs": round(V * Dh * 2 / ms / 1e6, 1)}), flush=True)
+                              "tflops": round(flop / ms / 1e9, 1), "frac_mfma_peak": round(flop / ms / 1e9 / MFMA_PEAK_TFLOPS, 3),
+                              "gbs": round(nbytes / ms / 1e6, 1), "frac_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 3),
+                              "bound": "mfma" if flop / nbytes >= RIDGE else "hbm"}), flush=True)
         dlm.set_option("lmhead_variant", -1)
         return
     if args.kernel == "fullpass":
@@ -144,6 +271,7 @@ def micro(args):
             rec = {"kernel": name, "workload": "c5b full pass", "ms": round(ms, 3)}
             if flop:
                 rec["tflops"] = round(flop / ms / 1e9, 1)
+                rec["frac_mfma_peak"] = round(flop / ms / 1e9 / MFMA_PEAK_TFLOPS, 3)
             if name == "dlm_lmhead_confidence":
                 rec["M"] = M
             print(json.dumps(rec), flush=True)
@@ -159,7 +287,8 @@ def micro(args):
     pairs = L * L if args.mask == "full" else L * (L + bs) / 2
     ms = timed(lambda: dlm.block_attn(q, out, block=(k, v, 0), mask_mode=mode, block_size=bs, lse=lse), args.reps)
     print(json.dumps({"kernel": "dlm_block_attn", "mask": args.mask, "B": B, "L": L, "heads": [Hq, Hkv], "d": d,
-                      "ms": round(ms, 3), "tflops": round(4.0 * B * Hq * d * pairs / ms / 1e9, 1)}), flush=True)
+                      "ms": round(ms, 3), "tflops": round(4.0 * B * Hq * d * pairs / ms / 1e9, 1),
+                      "frac_mfma_peak": round(4.0 * B * Hq * d * pairs / ms / 1e9 / MFMA_PEAK_TFLOPS, 3)}), flush=True)
     if args.backward:
         dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
         ws = torch.empty(dlm.block_attn_bwd_workspace_bytes(B * L, Hq), dtype=torch.uint8, device=dev)
@@ -167,6 +296,54 @@ def micro(args):
                                               block_size=bs, workspace=ws), args.reps)
         print(json.dumps({"kernel": "dlm_block_attn_bwd", "mask": args.mask, "B": B, "L": L, "heads": [Hq, Hkv], "d": d,
                           "ms": round(ms, 3), "tflops": round(10.0 * B * Hq * d * pairs / ms / 1e9, 1)}), flush=True)
+
+
+# ---------------------------------------------------------------------------------------------------------- #
+# algorithmic bytes / FLOP of one call
+# ---------------------------------------------------------------------------------------------------------- #
+def attn_cost(cfg, active_seqs, Lk):
+    """K and V once per KV head, Q read, O written; 4 * d FLOP per visible (query, key) pair and query head.  Every
+    rollout workload's query block sees all Lk keys (the block-causal one denoises the last block)."""
+    nbytes = active_seqs * (2 * cfg.Hkv * Lk * cfg.d * 2 + 2 * cfg.Lb * cfg.Hq * cfg.d * 2)
+    flop = 4.0 * active_seqs * cfg.Hq * cfg.d * cfg.Lb * Lk
+    return nbytes, flop
+
+
+def lmhead_cost(cfg, rows):
+    """W_vocab once, the gathered hidden rows, 8 bytes of outputs per row; 2 * Dh * V FLOP per row."""
+    return cfg.V * cfg.Dh * 2 + rows * cfg.Dh * 2 + rows * 8, 2.0 * rows * cfg.Dh * cfg.V
+
+
+def commit_cost(cfg, copied_seqs):
+    """Per position: confidence, token, mask in and out, commit flag, next-row list (18 B); per copied sequence the
+    block's K and V read and written."""
+    return cfg.B * cfg.Lb * 18 + copied_seqs * 2 * 2 * cfg.Hkv * cfg.Lb * cfg.d * 2, 0.0
+
+
+def roof_record(name, us_list, bytes_list, flop_list, measured):
+    """Aggregate of one call over the sampled steps: total algorithmic work / total measured time, against the roof
+    that binds at the aggregate arithmetic intensity (nominal peaks), and against the measured peaks."""
+    n = len(us_list)
+    if n == 0:
+        return None
+    tot_s = sum(us_list) * 1e-6
+    tot_b, tot_f = float(sum(bytes_list)), float(sum(flop_list))
+    gbs = tot_b / tot_s / 1e9
+    tfl = tot_f / tot_s / 1e12
+    ai = tot_f / tot_b if tot_b else 0.0
+    bound = "mfma" if ai >= RIDGE else "hbm"
+    rec = {"call": name, "calls": n, "avg_us": round(sum(us_list) / n, 2), "median_us": round(sorted(us_list)[n // 2], 2),
+           "bytes_per_call": int(tot_b / n), "flop_per_call": int(tot_f / n), "intensity_flop_per_byte": round(ai, 1),
+           "bound": bound, "gbs": round(gbs, 1), "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+           "tflops": round(tfl, 1), "frac_mfma_peak": round(tfl / MFMA_PEAK_TFLOPS, 4),
+           # the most the other roof's fraction could be at this intensity
+           "ceiling_frac_mfma_peak": round(min(1.0, ai / RIDGE), 4), "ceiling_frac_hbm_peak": round(min(1.0, RIDGE / ai) if ai else 1.0, 4),
+           "frac": round((tfl / MFMA_PEAK_TFLOPS) if bound == "mfma" else (gbs / HBM_PEAK_GBS), 4)}
+    if measured:
+        ref_bw = measured["copy_gbs"] if name in ("dlm_unmask_commit", "dlm_kv_refresh") else measured["read_nt_gbs"]
+        rec["frac_of_measured_hbm"] = round(gbs / ref_bw, 4)
+        rec["frac_of_measured_mfma"] = round(tfl / measured["mfma_bf16_tflops"], 4)
+    return rec
 
 
 def main():
@@ -192,7 +369,7 @@ def main():
         micro(args)
         return
     dev = "cuda:0"
-    cfg = synth.CONFIGS[args.config]
+    cfg = synth.CONFIGS[args.config].replace(w_dist=args.w_dist)
     t_setup = time.time()
 
     def to_dev(u16):
@@ -251,65 +428,137 @@ def main():
     rollout_steps = sum(steps_per_block)
     setup_s = time.time() - t_setup
 
-    # ---- LM-head event timing hook ------------------------------------------------------------------
-    lm_events = []
-    orig_lmhead = dlm.lmhead_confidence
-
-    def timed_lmhead(*a, **kw):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(torch.cuda.current_stream())
-        orig_lmhead(*a, **kw)
-        e1.record(torch.cuda.current_stream())
-        lm_events.append((e0, e1, kw.get("M")))
-
-    import paper_2604_04215_amd.rollout as ro_mod
-
-    # ---- warm-up, then the timed region -------------------------------------------------------------
-    runner.run(args.warmup) if args.warmup > 0 else None
+    # ---- clock ramp + warm-up, then the timed region (nothing but the steps' own launches inside) ----
+    if args.ramp_steps > 0:
+        runner.run(args.ramp_steps)
+    if args.warmup > 0:
+        runner.run(args.warmup)
     torch.cuda.synchronize()
-    if not args.no_kernel_events:
-        ro_mod.dlm.lmhead_confidence = timed_lmhead
-    c0, e0, log0 = runner.committed, runner.empty, len(runner.log)
+    c0, e0 = runner.committed, runner.empty
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     res = runner.run(args.steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ro_mod.dlm.lmhead_confidence = orig_lmhead
     elapsed = t1 - t0
     committed = runner.committed - c0
     empty = runner.empty - e0
     assert res["steps"] == args.steps
 
-    # ---- roofline of the LM head (dominant kernel): algorithmic bytes / measured duration -----------
-    # One dlm_lmhead_confidence call streams W_vocab once (V*Dh*2 bytes), gathers M hidden rows
-    # (M*Dh*2 bytes) and writes a handful of bytes per row; M is the number of rows masked before the step.
-    roof = None
-    w_bytes = cfg.V * cfg.Dh * 2
-    if lm_events:
+    # ---- achievable peaks on this machine (own kernels, a few ms each) ------------------------------------
+    measured = None
+    if not args.no_peaks:
+        measured = measure_peaks(torch)
+
+    # ---- per-call sample pass: a fixed number of steps, every library call between two events --------
+    kernels, roof, sample_info = {}, None, None
+    if args.sample_steps > 0:
+        import paper_2604_04215_amd.rollout as ro_mod
+        orig = {n: getattr(dlm, n) for n in ("block_attn", "lmhead_confidence", "unmask_commit", "kv_refresh")}
+        ev = {n: [] for n in orig}
+        cap = args.sample_steps + 8 * cfg.n_blocks * (args.sample_steps // max(1, rollout_steps) + 2) + 64
+        rem_hist = torch.zeros((cap, cfg.B), dtype=torch.int32, device=dev)   # per-sequence still-masked counts after each step
+        n_commit_calls = [0]
+
+        def bracket(name, meta_fn):
+            fn = orig[name]
+
+            def wrapped(*a, **kw):
+                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                st = torch.cuda.current_stream()
+                a0.record(st)
+                fn(*a, **kw)
+                a1.record(st)
+                ev[name].append((a0, a1, meta_fn(a, kw)))
+            return wrapped
+
+        def attn_meta(a, kw):
+            Lk = sum(t[0].shape[2] for t in (kw.get("prefix"), kw.get("block"), kw.get("suffix")) if t is not None)
+            return dict(first=kw.get("seq_active") is None, Lk=Lk, prev=n_commit_calls[0] - 1)
+
+        def commit_meta(a, kw):
+            i = n_commit_calls[0]
+            n_commit_calls[0] += 1
+            return dict(idx=i, first=kw.get("active_in") is None)
+
+        def refresh_meta(a, kw):
+            src = a[0]
+            return dict(bytes=2 * 2 * src.shape[0] * src.shape[1] * src.shape[2] * src.shape[3] * 2)
+
+        def commit_wrapped(*a, **kw):
+            inner(*a, **kw)
+            rem_hist[n_commit_calls[0] - 1].copy_(a[5])        # after the bracketed call: the counts of this step
+
+        inner = bracket("unmask_commit", commit_meta)
+        dlm.block_attn = bracket("block_attn", attn_meta)
+        dlm.lmhead_confidence = bracket("lmhead_confidence", lambda a, kw: None)
+        dlm.unmask_commit = commit_wrapped
+        dlm.kv_refresh = bracket("kv_refresh", refresh_meta)
+        assert ro_mod.dlm is dlm
+        log0 = len(runner.log)
+        try:
+            runner.run(args.sample_steps)
+            torch.cuda.synchronize()
+        finally:
+            for n, f in orig.items():
+                setattr(dlm, n, f)
         log = runner.log[log0:]
-        assert len(log) == len(lm_events)
-        ms, rows = [], []
-        for (a, b, _bound), (_, before, _after) in zip(lm_events, log):
-            if before > 0:                      # launches that found nothing masked move no data
-                ms.append(a.elapsed_time(b))
-                rows.append(before)
-        if args.dump_steps:                     # per step: rows masked before, host-side row bound, LM-head call in us
+        # the runner polls every step it queued except possibly the last one or two of an unfinished block
+        n_steps = min(len(log), len(ev["lmhead_confidence"]))
+        hist = rem_hist[:n_commit_calls[0]].cpu().numpy()
+        us = lambda e: e[0].elapsed_time(e[1]) * 1e3
+        at = dict(us=[], b=[], f=[])
+        lm = dict(us=[], b=[], f=[], rows=[])
+        cm = dict(us=[], b=[], f=[])
+        lines = []
+        for i in range(n_steps):
+            blk, before, after = log[i]
+            ea, el, ec = ev["block_attn"][i], ev["lmhead_confidence"][i], ev["unmask_commit"][i]
+            am, cmeta = ea[2], ec[2]
+            active = cfg.B if (am["first"] or am["prev"] < 0) else int((hist[am["prev"]] > 0).sum())
+            if before <= 0:
+                continue                     # a queued step that found nothing masked moves no data
+            b_, f_ = attn_cost(cfg, active, am["Lk"])
+            at["us"].append(us(ea)); at["b"].append(b_); at["f"].append(f_)
+            b_, f_ = lmhead_cost(cfg, before)
+            lm["us"].append(us(el)); lm["b"].append(b_); lm["f"].append(f_); lm["rows"].append(before)
+            copied = int((hist[cmeta["idx"]] == 0).sum()) - (cfg.B - active) if cmeta["first"] else active
+            b_, f_ = commit_cost(cfg, max(copied, 0))
+            cm["us"].append(us(ec)); cm["b"].append(b_); cm["f"].append(f_)
+            lines.append(f"{blk} {before} {after} {active} {us(ea):.1f} {us(el):.1f} {us(ec):.1f}")
+        if args.dump_steps:
             with open(args.dump_steps, "w") as f:
-                for (a, b, bound), (blk, before, after) in zip(lm_events, log):
-                    f.write(f"{blk} {before} {after} {bound} {a.elapsed_time(b) * 1e3:.1f}\n")
-        avg_ms = sum(ms) / len(ms)
-        mean_rows = sum(rows) / len(rows)
-        bytes_per_launch = w_bytes + mean_rows * cfg.Dh * 2 + mean_rows * 8
-        achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
-        roof = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=int(LMHEAD_C2_TRAFFIC_BYTES) if args.config == "c2" else None,
-                    kernel="lmhead_kernel (M <= 192) or lmhead_pair_kernel (above) + lmhead_reduce_kernel (one dlm_lmhead_confidence call)",
-                    avg_us=round(avg_ms * 1e3, 2), median_us=round(sorted(ms)[len(ms) // 2] * 1e3, 2),
-                    launches=len(ms), bytes_per_launch=int(bytes_per_launch), mean_rows=round(mean_rows, 1),
-                    flops_per_launch=int(2 * mean_rows * cfg.Dh * cfg.V),
-                    mfma_tflops=round(2 * mean_rows * cfg.Dh * cfg.V / (avg_ms * 1e-3) / 1e12, 1))
+                f.write("\n".join(lines) + "\n")
+        rf = ev["kv_refresh"]
+        kernels = {"dlm_block_attn": roof_record("dlm_block_attn", at["us"], at["b"], at["f"], measured),
+                   "dlm_lmhead_confidence": roof_record("dlm_lmhead_confidence", lm["us"], lm["b"], lm["f"], measured),
+                   "dlm_unmask_commit": roof_record("dlm_unmask_commit", cm["us"], cm["b"], cm["f"], measured),
+                   "dlm_kv_refresh": roof_record("dlm_kv_refresh", [us(e) for e in rf], [e[2]["bytes"] for e in rf],
+                                                 [0.0] * len(rf), measured)}
+        if kernels["dlm_lmhead_confidence"]:
+            kernels["dlm_lmhead_confidence"]["mean_rows"] = round(sum(lm["rows"]) / len(lm["rows"]), 1)
+        if kernels["dlm_unmask_commit"]:
+            kernels["dlm_unmask_commit"]["note"] = "selection + commit + row compaction + block K/V write-back in one launch: launch-latency-bound, bytes are the ones it touches"
+        sample_info = {"steps": len(lm["us"]), "events": "torch.cuda.Event pairs on the launch stream around every library call, after the timed region"}
+        # the call that takes most of a step is the one the roofline object describes
+        dom = max((k for k in kernels.values() if k and k["call"] != "dlm_kv_refresh"), key=lambda k: k["avg_us"] * k["calls"])
+        peak, unit, ach = (MFMA_PEAK_TFLOPS, "TFLOP/s", dom["tflops"]) if dom["bound"] == "mfma" else (HBM_PEAK_GBS, "GB/s", dom["gbs"])
+        other = ({"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["frac_hbm_peak"],
+                  "ceiling_frac": dom["ceiling_frac_hbm_peak"]} if dom["bound"] == "mfma" else
+                 {"bound": "mfma", "achieved": dom["tflops"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dom["frac_mfma_peak"],
+                  "ceiling_frac": dom["ceiling_frac_mfma_peak"]})
+        kern_names = {"dlm_lmhead_confidence": "lmhead_kernel (M <= 192) or lmhead_pair_kernel (above) + lmhead_reduce_kernel (one dlm_lmhead_confidence call)",
+                      "dlm_block_attn": "attn_kernel (one dlm_block_attn call)",
+                      "dlm_unmask_commit": "commit_fused_kernel (one dlm_unmask_commit call)"}
+        roof = dict(bound=dom["bound"], achieved=ach, peak=peak, unit=unit, frac=round(ach / peak, 4),
+                    traffic=int(LMHEAD_C2_TRAFFIC_BYTES) if (args.config == "c2" and args.w_dist == "var" and dom["call"] == "dlm_lmhead_confidence") else None,
+                    kernel=kern_names[dom["call"]], call=dom["call"], avg_us=dom["avg_us"], median_us=dom["median_us"],
+                    launches=dom["calls"], bytes_per_launch=dom["bytes_per_call"], flops_per_launch=dom["flop_per_call"],
+                    intensity_flop_per_byte=dom["intensity_flop_per_byte"], other_roof=other)
+        if dom["call"] == "dlm_lmhead_confidence":
+            roof["mean_rows"] = kernels["dlm_lmhead_confidence"]["mean_rows"]
+        if measured:
+            roof["frac_of_measured_peak"] = dom["frac_of_measured_mfma"] if dom["bound"] == "mfma" else dom["frac_of_measured_hbm"]
 
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------------
     cpu = None
@@ -317,7 +566,8 @@ def main():
         import oracle
         tc0 = time.perf_counter()
         n_tok = n_steps_cpu = n_seq = 0
-        for b in range(cfg.B):                       # whole sequences of block 0 until ~12 s of CPU work
+        want = min(args.oracle_seqs, cfg.B) if args.oracle_seqs > 0 else cfg.B
+        for b in range(want):                        # whole sequences of block 0, one at a time
             o = oracle.OracleRollout(cfg, synth, seqs=[b], w=w_host)
             o.begin_block(0)
             while o.mask.any():
@@ -325,12 +575,17 @@ def main():
                 n_tok += int(r["n_commit"].sum())
                 n_steps_cpu += 1
             n_seq += 1
-            if time.perf_counter() - tc0 > 12.0:
+            if args.oracle_seqs <= 0 and time.perf_counter() - tc0 > 12.0:
                 break
         tc = time.perf_counter() - tc0
+        full_s = tc * cfg.B / n_seq * cfg.n_blocks
         cpu = dict(value=round(n_tok / tc, 3), unit="committed tokens/s", cores=oracle.num_threads(), kind="oracle",
                    sample=f"sequences 0..{n_seq - 1} of the batch, one at a time, block 0 (prefix {cfg.prompt} + block "
-                          f"{cfg.Lb}) to completion: {n_steps_cpu} denoising steps, {n_tok} tokens committed in {tc:.1f} s")
+                          f"{cfg.Lb}) to completion: {n_steps_cpu} denoising steps, {n_tok} tokens committed in {tc:.1f} s",
+                   measured_s=round(tc, 2),
+                   extrapolated_whole_rollout_s=round(full_s, 1),
+                   extrapolation=f"linear: measured time x (B={cfg.B} / {n_seq} sequences) x {cfg.n_blocks} blocks; later blocks "
+                                 "have longer prefixes, so this is a lower estimate")
 
     out = {
         "metric": "committed tokens/sec per denoise step",
@@ -345,14 +600,15 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "c2: LLaDA-8B-shaped rollout, B=8, 32 heads MHA, d=128, hidden 4096, V=126464, "
-                               "prompt 512, gen 256 in 8 blocks of 32, threshold 0.9 + forced top-1, "
-                               "prefix cache refreshed per block" if args.config == "c2" else args.config,
+        "config": {"workload": WORKLOADS[args.config] + ("" if args.w_dist == "var" else " [W_vocab std reading]"),
                    "committed_tokens": committed, "tokens_per_step": round(committed / args.steps, 3),
                    "steps_per_rollout": rollout_steps, "steps_per_block": steps_per_block,
-                   "empty_steps_in_timed_region": empty,
+                   "empty_steps_in_timed_region": empty, "ramp_steps": args.ramp_steps,
                    "loop": "sync" if args.sync_loop else "one-step-late poll", "setup_s": round(setup_s, 1)},
         "roofline": roof,
+        "kernels": kernels,
+        "kernel_sample": sample_info,
+        "peaks": {"nominal": {"hbm_gbs": HBM_PEAK_GBS, "mfma_bf16_tflops": MFMA_PEAK_TFLOPS}, "measured": measured},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

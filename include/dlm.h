@@ -289,8 +289,7 @@ size_t dlm_lmhead_static_scratch_bytes(void);
  * For committed position i: x[b, x_pos0 + i] = tok[b, i]; mask[b, i] = 0.
  * Positions with mask == 0 on entry are neither read for selection nor written.
  *
- * Defines: the reverse-process commit ("repeated denoising on partially fixed
- * states", Section 3.4) with the fixed schedule of Section 4.1 (top-k) or the
+ * Defines: the reverse-process commit of Section 3.4 (rollout paragraph) with the fixed schedule of Section 4.1 (top-k) or the
  * confidence-threshold parallel decoding the paper adopts for rollout.
  *
  *   conf, tok   dense fp32 / int32 [B, n_pos] contiguous (index b*n_pos + i)

@@ -1,0 +1,35 @@
+/*
+ * dlm_peaks.h -- C ABI of libdlm_peaks: three micro-benchmarks that measure what one MI355X (gfx950)
+ * can actually sustain, so that kernel timings can be quoted against measured as well as nominal peaks.
+ * A measuring instrument for the benchmark script; libdlm does not depend on it.
+ *
+ * All pointers are DEVICE pointers, 16-byte aligned; `bytes` must be a multiple of 16.  Calls enqueue on
+ * `stream` (a hipStream_t, NULL = default) and return without synchronising; the caller times them with
+ * events.  Return value: 0, or -1 for a bad argument, -4 when the launch failed.
+ */
+#ifndef DLM_PEAKS_H
+#define DLM_PEAKS_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* dst[0 .. bytes) = src[0 .. bytes): 16 bytes per lane, 4 KB per workgroup.  nt bit 0: non-temporal loads,
+ * bit 1: non-temporal stores.  Moves 2 * bytes through HBM. */
+int dlm_peak_copy(const void *src, void *dst, size_t bytes, int nt, void *stream);
+
+/* Reads src[0 .. bytes) once (16 bytes per lane, 16 KB per workgroup in 4 requests) and writes 4 bytes per
+ * workgroup to sink (at least bytes / 16384 + 1 words).  nt != 0: non-temporal loads.  The ceiling of a kernel
+ * that streams a large operand exactly once (W_vocab, a KV cache). */
+int dlm_peak_read(const void *src, size_t bytes, int nt, uint32_t *sink, void *stream);
+
+/* n_wg workgroups of 4 wavefronts, each wavefront issuing iters * 8 independent 32x32x16 bf16 MFMAs on
+ * register operands (no memory traffic in the loop); sink receives one float per wavefront (n_wg * 4 floats).
+ * FLOP = n_wg * 4 * iters * 8 * 32768.  The ceiling of any bf16 contraction on this clock and power budget. */
+int dlm_peak_mfma(int n_wg, int iters, float *sink, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -193,12 +193,28 @@ def kv_seg(k=None, v=None, pos0: int = 0, rule: int = 0) -> KvSeg:
     return s
 
 
+def block_attn_workspace_bytes(q, prefix: Optional[Tuple] = None, block: Optional[Tuple] = None,
+                               suffix: Optional[Tuple] = None, **kw) -> int:
+    """Bytes of workspace dlm_block_attn wants for this call (0 for most shapes)."""
+    kw.pop("workspace", None)
+    kw.pop("stream", None)
+    a = _attn_args(q, q, prefix, block, suffix, **kw)
+    return int(lib().dlm_block_attn_workspace_bytes(C.byref(a)))
+
+
 def block_attn(q, out, prefix: Optional[Tuple] = None, block: Optional[Tuple] = None,
-               suffix: Optional[Tuple] = None, *, n_kv_heads: Optional[int] = None,
-               mask_mode: int = MASK_FULL, block_size: int = 0, q_pos0: int = 0, scale: float = 0.0,
-               prefix_len_b=None, lse=None, workspace=None, seq_active=None, stream=None) -> None:
+               suffix: Optional[Tuple] = None, *, stream=None, **kw) -> None:
     """q, out: bf16 [B, Lq, Hq, d]; each segment is (k, v, pos0[, rule]) with k, v bf16 [B, Hkv, len, d].
-    seq_active: optional int32 [B] on the device; sequences with a 0 are skipped (out / lse rows untouched)."""
+    Keywords: n_kv_heads, mask_mode, block_size, q_pos0, scale, prefix_len_b, lse, workspace (a uint8 tensor of
+    block_attn_workspace_bytes(...) bytes when that is not 0), seq_active (optional int32 [B] on the device;
+    sequences with a 0 are skipped: out / lse rows untouched)."""
+    a = _attn_args(q, out, prefix, block, suffix, **kw)
+    _check(lib().dlm_block_attn(C.byref(a), _stream(stream)))
+
+
+def _attn_args(q, out, prefix, block, suffix, *, n_kv_heads: Optional[int] = None,
+               mask_mode: int = MASK_FULL, block_size: int = 0, q_pos0: int = 0, scale: float = 0.0,
+               prefix_len_b=None, lse=None, workspace=None, seq_active=None) -> AttnArgs:
     import torch
     a = AttnArgs()
     a.struct_size = C.sizeof(AttnArgs)
@@ -229,7 +245,7 @@ def block_attn(q, out, prefix: Optional[Tuple] = None, block: Optional[Tuple] = 
         if seq_active.numel() != B or not seq_active.is_contiguous():
             raise ValueError("seq_active must be contiguous int32 [B]")
         a.seq_active = _dev(seq_active, torch.int32, "seq_active")
-    _check(lib().dlm_block_attn(C.byref(a), _stream(stream)))
+    return a
 
 
 def varlen_attn(q, k, v, out, cu_seqlens, max_seqlen: int, *, mask_mode: int = MASK_FULL, block_size: int = 0,

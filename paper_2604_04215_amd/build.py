@@ -9,7 +9,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libdlm.so")
+PEAKS_LIB = os.path.join(HERE, "libdlm_peaks.so")     # achievable-peak micro-benchmarks (bench.py --kernel peaks)
 SOURCES = ["core.hip", "commit.hip", "attn.hip", "attn_bwd.hip", "lmhead.hip"]
+PEAKS_SOURCES = ["peaks.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE,
          # packed-fp32 code generation off (hipcc-only flag; the host pass warns that it ignores it)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -25,13 +27,13 @@ def build_lib(verbose: bool = False, save_temps: str | None = None) -> str:
     os.makedirs(objdir, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "hipcc")
     procs = []
-    for src in SOURCES:
+    for src in SOURCES + PEAKS_SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         if save_temps:
             cmd.append("-save-temps=obj")
         procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
-    objs = []
+    objs, peak_objs = [], []
     for src, obj, pr in procs:
         out, _ = pr.communicate()
         out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
@@ -39,10 +41,11 @@ def build_lib(verbose: bool = False, save_temps: str | None = None) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
         if verbose and out.strip():
             print(out)
-        objs.append(obj)
-    tmp = LIB + f".tmp{os.getpid()}"
-    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
+        (peak_objs if src in PEAKS_SOURCES else objs).append(obj)
+    for lib, lib_objs in ((LIB, objs), (PEAKS_LIB, peak_objs)):
+        tmp = lib + f".tmp{os.getpid()}"
+        subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *lib_objs])
+        os.replace(tmp, lib)
     return LIB
 
 

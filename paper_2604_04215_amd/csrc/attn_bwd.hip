@@ -686,8 +686,10 @@ static int launch_bwd(const BwdParams& p, hipStream_t st) {
             else rm = no_remap();
         }
         hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, false>), grid, dim3(256), 0, st, p, s, n_slabs, pair, rm);
+        rc = check_hip(hipGetLastError(), "attn_bwd_dkv_kernel (dV pass) launch");
+        if (rc != DLM_OK) return rc;
         hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, BC, true>), grid, dim3(256), 0, st, p, s, n_slabs, pair, rm);
-        rc = check_hip(hipGetLastError(), "attn_bwd_dkv_kernel launch");
+        rc = check_hip(hipGetLastError(), "attn_bwd_dkv_kernel (dK pass) launch");
         if (rc != DLM_OK) return rc;
     }
     return DLM_OK;

@@ -442,7 +442,7 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(CopyParams p) {
         const uint16_t* src = do_k ? sk : sv;
         uint16_t* dst = do_k ? ck : cv;
 #pragma unroll
-        for (int u = 0; u < U; ++u) kreg[u] = p.nt ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + so[u])) : *reinterpret_cast<const u32x4*>(src + so[u]);
+        for (int u = 0; u < U; ++u) kreg[u] = (p.nt & 1) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + so[u])) : *reinterpret_cast<const u32x4*>(src + so[u]);
         if (do_k && do_v) {
 #pragma unroll
             for (int u = 0; u < U; ++u) vreg[u] = *reinterpret_cast<const u32x4*>(sv + so[u]);

@@ -75,6 +75,33 @@ class GpuRollout:
         self._ring_pos = 0
         self._last_poll = None
 
+    def snapshot(self) -> dict:
+        """Everything needed to resume this rollout elsewhere (another GpuRollout on the same workload, possibly in
+        another process after a save): the token buffer, block mask, cache, the compacted row list with its count,
+        both per-sequence count buffers and the host-side counters.  Synchronises the current stream."""
+        torch.cuda.current_stream().synchronize()
+        t = lambda x: None if x is None else x.clone()
+        return dict(x=t(self.x), mask=t(self.mask), cache_k=t(self.cache_k), cache_v=t(self.cache_v),
+                    row_idx=t(self.row_idx), m_dev=t(self.m_dev), remaining2=[t(r) for r in self._remaining2],
+                    remaining_is=0 if self.remaining is self._remaining2[0] else 1, commit_step=t(self.commit_step),
+                    block=self.block, step_idx=self.step_idx, m_host=self.m_host, exact_rows=self._exact_rows)
+
+    def restore(self, snap: dict) -> None:
+        """Continue from a snapshot() (taken at any step boundary of a block)."""
+        for name in ("x", "mask", "cache_k", "cache_v", "row_idx", "m_dev"):
+            getattr(self, name).copy_(snap[name])
+        for dst, src in zip(self._remaining2, snap["remaining2"]):
+            dst.copy_(src)
+        self.remaining = self._remaining2[snap["remaining_is"]]
+        if self.commit_step is not None and snap["commit_step"] is not None:
+            self.commit_step.copy_(snap["commit_step"])
+        self.block, self.step_idx = snap["block"], snap["step_idx"]
+        self.m_host, self._exact_rows = snap["m_host"], snap["exact_rows"]
+        if self.block >= 0:
+            P, Lb, S = self.P, self.cfg.Lb, self.S
+            self._prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
+            self._suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
+
     def queue_poll(self):
         """(event, pinned host word) of the step queued last: after event.synchronize() the word holds the
         number of positions still masked after that step.  At most 3 polls may be outstanding."""

@@ -17,7 +17,7 @@ from oracle import KV
 from oracle import backward as obw
 from paper_2604_04215_amd import binding as dlm
 from paper_2604_04215_amd import synth
-from gpu_util import DEV, attn_rel_err, bf16_dev, bf16_host, dev, rnd
+from gpu_util import DEV, GuardedWorkspace, attn_rel_err, bf16_dev, bf16_host, dev, rnd
 
 pytestmark = pytest.mark.gpu
 
@@ -50,11 +50,11 @@ def run_bwd(q, segs, d_out, mode="full", bs=0, q_pos0=0, want=(True, True, True)
     mm = dlm.MASK_BLOCK_CAUSAL if mode == "block_causal" else dlm.MASK_FULL
     dlm.block_attn(qd, out, prefix=tup[0], block=tup[1], suffix=tup[2], mask_mode=mm, block_size=bs, q_pos0=q_pos0, lse=lse)
     dq = torch.full_like(qd, float("nan"))
-    ws = torch.empty(dlm.block_attn_bwd_workspace_bytes(B * Lq, Hq), dtype=torch.uint8, device=DEV)
+    gw = GuardedWorkspace(dlm.block_attn_bwd_workspace_bytes(B * Lq, Hq))   # exactly the size asked for, guarded
     dlm.block_attn_bwd(qd, out, dod, lse, dq, prefix=tup[0], block=tup[1], suffix=tup[2],
                        d_prefix=grads[0], d_block=grads[1], d_suffix=grads[2],
-                       mask_mode=mm, block_size=bs, q_pos0=q_pos0, workspace=ws)
-    torch.cuda.synchronize()
+                       mask_mode=mm, block_size=bs, q_pos0=q_pos0, workspace=gw.ws)
+    gw.check()
     return bf16_host(dq), [None if g is None else (bf16_host(g[0]), bf16_host(g[1])) for g in grads]
 
 

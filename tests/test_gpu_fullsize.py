@@ -10,7 +10,7 @@ from oracle.denoise import apply_commit, select_commit
 from paper_2604_04215_amd import binding as dlm
 from paper_2604_04215_amd import synth
 from paper_2604_04215_amd.rollout import GpuRollout
-from gpu_util import DEV, bf16_dev, bf16_host, dev
+from gpu_util import DEV, attn_err_report, bf16_dev, bf16_host, dev, fmt_err
 
 pytestmark = pytest.mark.gpu
 
@@ -169,3 +169,182 @@ def test_c5b_full_sequence_block_causal_pass():
     assert np.array_equal(x_g[commit_g == 0], x0[commit_g == 0])
     assert np.array_equal(x_g[commit_g == 1], tok_g[commit_g == 1])
     assert np.array_equal(mask.cpu().numpy(), mask0 - commit_g)
+
+
+# --------------------------------------------------------------------------------------------------------- #
+# Whole blocks at full size, driven the way the benchmark drives them, in lock-step with the oracle on a
+# subset of the batch (sequences are independent and keyed one by one, so the oracle's results for the
+# subset are what the GPU must produce for those sequences inside the full batch).
+# --------------------------------------------------------------------------------------------------------- #
+def lockstep_block_fullsize(name, block, seqs, max_excluded=0.05):
+    """The GPU runs ALL sequences of workload `name` through one whole block with GpuRollout.step exactly as
+    the benchmark's loop queues it: the LM-head row bound is the still-masked total of two steps ago (the
+    one-step-late poll), M_expected guesses the count from it, sequences that finished are skipped by the
+    attention call (seq_active) and written back inside the selection's launch (DLM_WB_WHILE_ACTIVE); for the
+    top-k workload the exact row schedule replaces the late bound.  OracleRollout runs `seqs` beside it; every
+    step both start from the same state, and after a step the oracle marks numerically ambiguous it is
+    re-synchronised to the GPU's state (same rules as tests/test_gpu_rollout.py::lockstep)."""
+    cfg = synth.CONFIGS[name]
+    seqs = list(seqs)
+    B, Lb = cfg.B, cfg.Lb
+    w = synth.w_vocab(cfg)
+    o = oracle.OracleRollout(cfg, synth, seqs=seqs, w=w)
+    g = GpuRollout(cfg, bf16_dev(w), DEV, record_steps=True)
+    g.late_bound = True
+    k0, v0 = synth.cache_kv(cfg, 0)
+    g.cache_k.copy_(bf16_dev(k0))
+    g.cache_v.copy_(bf16_dev(v0))
+    del k0, v0
+    x0 = synth.initial_tokens(cfg, cfg.L)
+    g.x.copy_(dev(x0))
+    o.begin_block(block)
+    rk = rv = None
+    if cfg.refresh and block > 0:
+        k, v = synth.cache_kv(cfg, block)
+        rk, rv = bf16_dev(k), bf16_dev(v)
+        del k, v
+    g.begin_block(block, refresh_k=rk, refresh_v=rv)      # every position masked, as in the benchmark
+    torch.cuda.synchronize()
+    P = o.P
+    assert np.array_equal(bf16_host(g.cache_k[seqs]), o.cache_k) and np.array_equal(bf16_host(g.cache_v[seqs]), o.cache_v)
+    cache_start = (bf16_host(g.cache_k), bf16_host(g.cache_v))
+    outside = np.ones(cfg.L, bool)
+    outside[P:P + Lb] = False
+    stats = dict(steps=0, seq_steps=0, excluded=0, oracle_rows=0, worst_attn=0.0, worst_conf=0.0, bounds=[])
+    rem_hist = []                    # still-masked total after every step (what the benchmark's poll reads)
+    mask_prev = np.ones((B, Lb), np.uint8)
+    x_prev = x0.copy()
+    final_kv = {}
+    step = 0
+    worst = None
+    while mask_prev.any():
+        assert step <= Lb, "block did not finish"
+        if step >= 2:
+            g.set_row_bound(rem_hist[step - 2] if rem_hist[step - 2] > 0 else 1)
+        stats["bounds"].append(g.m_host if not g._exact_rows else -1)
+        q = synth.step_q(cfg, block, step)
+        kb, vb = synth.step_kv(cfg, block, step)
+        hid = synth.step_hidden(cfg, block, step)
+        r = o.step() if o.mask.any() else None
+        g.step(bf16_dev(q), bf16_dev(kb), bf16_dev(vb), bf16_dev(hid))
+        torch.cuda.synchronize()
+        commit_g = g.commit_now.cpu().numpy()
+        x_g, mask_g = g.x.cpu().numpy(), g.mask.cpu().numpy()
+        conf_all, tok_all = g.conf.cpu().numpy(), g.tok.cpu().numpy()
+        n_commit_g, remaining_g = g.n_commit.cpu().numpy(), g.remaining.cpu().numpy()
+        # ---- properties of the whole batch --------------------------------------------------------------
+        had = mask_prev.sum(axis=1) > 0
+        assert np.all(n_commit_g[had] >= 1) and np.all(n_commit_g[~had] == 0)
+        assert np.array_equal(remaining_g, mask_g.sum(axis=1)) and np.all(mask_g <= mask_prev)
+        assert np.array_equal(commit_g, mask_prev - mask_g)
+        cm = commit_g.astype(bool)
+        blk = x_g[:, P:P + Lb]
+        assert np.array_equal(blk[cm], tok_all[cm]) and np.array_equal(blk[~cm], x_prev[:, P:P + Lb][~cm])
+        assert np.array_equal(x_g[:, outside], x0[:, outside])
+        assert np.all((tok_all[mask_prev.astype(bool)] >= 0) & (tok_all[mask_prev.astype(bool)] < cfg.V - 1))
+        if cfg.rule == "topk":
+            assert np.all(n_commit_g[had] == np.minimum(cfg.k, mask_prev.sum(axis=1)[had]))
+        # selection is exact given the confidences the GPU produced, for every sequence of the batch
+        commit_ref, nc_ref, rem_ref = select_commit(conf_all.astype(np.float64), mask_prev, rule=cfg.rule,
+                                                    tau=float(np.float32(cfg.tau)), k=cfg.k)
+        assert np.array_equal(commit_g, commit_ref) and np.array_equal(n_commit_g, nc_ref)
+        flat = np.flatnonzero(mask_g.ravel())
+        assert int(g.m_dev.item()) == len(flat) and np.array_equal(g.row_idx.cpu().numpy()[:len(flat)], flat)
+        # cache: a sequence that finished holds its final step's block K/V; everything outside the slot is untouched
+        ck_g, cv_g = bf16_host(g.cache_k), bf16_host(g.cache_v)
+        for s in range(B):
+            if remaining_g[s] == 0 and n_commit_g[s] > 0:
+                final_kv[s] = (kb[s].copy(), vb[s].copy())
+            if s in final_kv:
+                assert np.array_equal(ck_g[s, :, P:P + Lb], final_kv[s][0]), f"K write-back, seq {s}"
+                assert np.array_equal(cv_g[s, :, P:P + Lb], final_kv[s][1]), f"V write-back, seq {s}"
+        assert np.array_equal(ck_g[:, :, outside], cache_start[0][:, :, outside])
+        assert np.array_equal(cv_g[:, :, outside], cache_start[1][:, :, outside])
+        # ---- the oracle's sequences, element by element -------------------------------------------------
+        if r is not None:
+            mb = r["mask_before"]
+            assert np.array_equal(mb, mask_prev[seqs])
+            O_g = bf16_host(g.O)[seqs]
+            act = mb.any(axis=1) if step > 0 else np.ones(len(seqs), bool)
+            rep = attn_err_report(O_g[act], r["O"][act])
+            if worst is None or rep["rms_floor"] > worst["rms_floor"]:
+                worst = rep
+            assert rep["rms_floor"] <= ATTN_TOL, f"step {step}: attention {fmt_err(rep)}"
+            lse_g = g.lse_attn.cpu().numpy()[seqs]
+            assert np.abs(lse_g[act] - r["lse_attn"][act]).max() <= 2e-3
+            rows = r["row_idx"]
+            stats["oracle_rows"] += len(rows)
+            conf_g = conf_all[seqs].ravel()[rows].astype(np.float64)
+            tok_g = tok_all[seqs].ravel()[rows]
+            lm = r["lm"]
+            cerr = float(np.abs(conf_g - lm["conf"]).max())
+            stats["worst_conf"] = max(stats["worst_conf"], cerr)
+            assert cerr <= CONF_TOL, f"step {step}: confidence abs err {cerr}"
+            clear_tok = (lm["zmax"] - lm["z2nd"]) >= NEAR
+            assert np.array_equal(tok_g[clear_tok], lm["tok"][clear_tok])
+            assert np.abs(g.lse.cpu().numpy().reshape(B, Lb)[seqs].ravel()[rows] - lm["lse"]).max() <= 5e-3   # logits-scale, fp32 sums over Dh = 4096
+            conf_o = r["conf"]
+            for n, s in enumerate(seqs):
+                if not mb[n].any():
+                    assert not commit_g[s].any()
+                    continue
+                stats["seq_steps"] += 1
+                m = mb[n].astype(bool)
+                top = np.sort(conf_o[n][m])[::-1]
+                if cfg.rule == "threshold":
+                    amb = bool((np.abs(conf_o[n][m] - cfg.tau) < NEAR).any())
+                    amb |= bool(len(top) > 1 and top[0] - top[1] < NEAR and top[0] < cfg.tau + NEAR)
+                else:
+                    kk = min(cfg.k, len(top))
+                    amb = bool(len(top) > kk and top[kk - 1] - top[kk] < NEAR)
+                sel = r["commit"][n].astype(bool)
+                amb_tok = bool((~clear_tok[(rows // Lb) == n]).any())
+                if np.array_equal(commit_g[s], r["commit"][n]):
+                    same_tok = np.array_equal(x_g[s, P:P + Lb][sel], r["tok"][n][sel])
+                    assert same_tok or amb_tok, f"token mismatch, step {step} seq {s}"
+                    stats["excluded"] += 0 if same_tok else 1
+                else:
+                    assert amb, f"commit mask mismatch, step {step} seq {s}"
+                    stats["excluded"] += 1
+            # both sides start the next step from the same state (a no-op unless an ambiguous step differed)
+            o.x[:] = x_g[seqs]
+            o.mask[:] = mask_g[seqs]
+            o.cache_k[:] = ck_g[seqs]
+            o.cache_v[:] = cv_g[seqs]
+        rem_hist.append(int(remaining_g.sum()))
+        mask_prev, x_prev = mask_g, x_g
+        stats["steps"] += 1
+        step += 1
+    assert not o.mask.any() and set(final_kv) == set(range(B))
+    # the step the one-step-late poll queues after the block has finished finds nothing masked and changes nothing
+    g.set_row_bound(rem_hist[-2] if len(rem_hist) >= 2 and rem_hist[-2] > 0 else 1)
+    kb, vb = synth.step_kv(cfg, block, step)
+    g.step(bf16_dev(synth.step_q(cfg, block, step)), bf16_dev(kb), bf16_dev(vb), bf16_dev(synth.step_hidden(cfg, block, step)))
+    torch.cuda.synchronize()
+    assert np.array_equal(g.x.cpu().numpy(), x_prev) and not g.mask.any().item() and int(g.m_dev.item()) == 0
+    assert not g.commit_now.any().item() and not g.n_commit.any().item()
+    assert np.array_equal(bf16_host(g.cache_k), ck_g) and np.array_equal(bf16_host(g.cache_v), cv_g)
+    assert stats["excluded"] <= max_excluded * max(1, stats["seq_steps"]), stats
+    stats["worst_attn"] = worst
+    print(f"{name} block {block} seqs {seqs}: {stats['steps']} steps, {stats['seq_steps']} oracle sequence-steps "
+          f"({stats['excluded']} excluded as ambiguous), {stats['oracle_rows']} LM-head rows checked, worst confidence "
+          f"error {stats['worst_conf']:.2e}, worst attention step: {fmt_err(worst)}; row bounds {stats['bounds']}", flush=True)
+    return stats
+
+
+def test_c2_whole_block_lockstep_as_the_benchmark_drives_it():
+    st = lockstep_block_fullsize("c2", block=3, seqs=[0, 5])
+    assert st["steps"] >= 4
+
+
+def test_c3_whole_block_lockstep_as_the_benchmark_drives_it():
+    lockstep_block_fullsize("c3", block=9, seqs=[2, 15])
+
+
+def test_c4_whole_block_lockstep_as_the_benchmark_drives_it():
+    st = lockstep_block_fullsize("c4", block=2, seqs=[0, 31])
+    assert st["steps"] == 8
+
+
+def test_c5a_whole_block_lockstep_as_the_benchmark_drives_it():
+    lockstep_block_fullsize("c5a", block=0, seqs=[0, 1, 62, 63])

@@ -6,7 +6,7 @@ import torch
 import oracle
 from paper_2604_04215_amd import binding as dlm
 from paper_2604_04215_amd import synth
-from gpu_util import DEV, bf16_dev, dev, rnd
+from gpu_util import DEV, GuardedWorkspace, bf16_dev, dev, rnd
 
 pytestmark = pytest.mark.gpu
 
@@ -29,13 +29,13 @@ def run_lm(hidden, w, *, row_idx=None, M=None, m_dev=None, forbid=-1, inv_t=1.0,
     tgt = zt = None
     if target is not None:
         tgt, zt = dev(np.asarray(target, np.int32)), f()
-    ws = torch.empty(max(16, dlm.lmhead_workspace_bytes(Mh, V)), dtype=torch.uint8, device=DEV)
+    gw = GuardedWorkspace(dlm.lmhead_workspace_bytes(Mh, V))     # exactly the size the library asks for, guarded
     dlm.lmhead_confidence(hd, wd, conf, tok, M=Mh, row_idx=ridx,
                           m_dev=None if m_dev is None else dev(np.asarray([m_dev], np.int32)),
                           forbid_token=forbid, inv_temperature=inv_t, out_scatter=scatter,
-                          lse=lse, zmax=zmax, z2nd=z2nd, target=tgt, ztarget=zt, workspace=ws,
+                          lse=lse, zmax=zmax, z2nd=z2nd, target=tgt, ztarget=zt, workspace=gw.ws,
                           M_expected=M_expected)
-    torch.cuda.synchronize()
+    gw.check()
     out = dict(conf=conf.cpu().numpy(), tok=tok.cpu().numpy(), lse=lse.cpu().numpy(), zmax=zmax.cpu().numpy(),
                z2nd=z2nd.cpu().numpy())
     if zt is not None:

@@ -307,3 +307,61 @@ def test_full_pass_mini():
     assert np.array_equal(cg[~amb], cr[~amb]) and amb.mean() < 0.05
     xg, xr = x.cpu().numpy().reshape(conf_o.shape), ref["x"].reshape(conf_o.shape)
     assert np.array_equal(xg[~amb], xr[~amb])
+
+
+@pytest.mark.parametrize("name,stop_after", [("mini2", 2), ("mini3", 1), ("mini4", 3)])
+def test_stop_copy_resume_gives_same_trajectory(name, stop_after):
+    """A rollout stopped after a few steps of a block, its state copied into a fresh driver, and resumed there ends
+    with exactly the tokens, commit steps and cache of the rollout that was never stopped (the GPU-side twin of the
+    oracle's stop/copy/resume test: a rollout's state is just its buffers and two counters)."""
+    cfg = synth.CONFIGS[name]
+    w = bf16_dev(synth.w_vocab(cfg))
+
+    def fresh():
+        g = GpuRollout(cfg, w, DEV, record_steps=True)
+        k, v = synth.cache_kv(cfg, 0)
+        g.cache_k.copy_(bf16_dev(k))
+        g.cache_v.copy_(bf16_dev(v))
+        g.x.copy_(dev(synth.initial_tokens(cfg, cfg.L)))
+        return g
+
+    def finish(g, block, first_step):
+        """run `block` from step `first_step` to completion, then every later block; returns the commit steps per block"""
+        traj = []
+        for b in range(block, cfg.n_blocks):
+            if b > block or first_step == 0:
+                rk = rv = None
+                if cfg.refresh and b > 0:
+                    k, v = synth.cache_kv(cfg, b)
+                    rk, rv = bf16_dev(k), bf16_dev(v)
+                g.begin_block(b, init_mask=dev(synth.initial_block_mask(cfg, b)), refresh_k=rk, refresh_v=rv)
+            s = first_step if b == block else 0
+            while True:
+                torch.cuda.synchronize()
+                if not g.mask.any().item():
+                    break
+                g.set_row_bound(int(g.mask.sum().item()))
+                g.step(*step_inputs_dev(cfg, b, s))
+                s += 1
+                assert s <= cfg.Lb + 1
+            traj.append((s, g.commit_step.cpu().numpy().copy()))
+        return traj
+
+    a = fresh()
+    a.begin_block(0, init_mask=dev(synth.initial_block_mask(cfg, 0)))
+    for s in range(stop_after):
+        a.set_row_bound(int(a.mask.sum().item()))
+        a.step(*step_inputs_dev(cfg, 0, s))
+    snap = a.snapshot()
+    assert a.mask.any().item(), "stopped too late to test anything"
+    b = GpuRollout(cfg, w, DEV, record_steps=True)      # never saw the first steps
+    b.restore(snap)
+    ta, tb = finish(a, 0, stop_after), finish(b, 0, stop_after)
+    assert [s for s, _ in ta] == [s for s, _ in tb]
+    for (_, ca), (_, cb) in zip(ta, tb):
+        assert np.array_equal(ca, cb)
+    assert torch.equal(a.x, b.x) and torch.equal(a.cache_k, b.cache_k) and torch.equal(a.cache_v, b.cache_v)
+    # and the uninterrupted reference: a third driver that runs straight through
+    c = fresh()
+    tc = finish(c, 0, 0)
+    assert [s for s, _ in tc] == [s for s, _ in ta] and torch.equal(c.x, a.x) and torch.equal(c.cache_k, a.cache_k)
