@@ -44,6 +44,12 @@ struct AttnParams {
     int total;          // cu[B]
     GridRemap remap;
     const int32_t* seq_active;   // optional [B]: 0 = skip the sequence
+    // Key split across workgroups (nsplit > 1): workgroup `split` of a row tile walks the key tiles
+    // [T * split / nsplit, T * (split + 1) / nsplit) and stores its unnormalised accumulators and its (running
+    // maximum, sum) instead of the output; attn_merge_kernel combines the nsplit partials of every row.
+    int nsplit;
+    float* part_o;    // [nsplit][B * Hkv * R][d]
+    float* part_ml;   // [nsplit][B * Hkv * R][2]  (maximum in log2 units, sum of exponentials relative to it)
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
@@ -56,7 +62,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
 // (sequence, KV head): the rollout step streams 70 - 1000 MB of cache that nothing reads twice.
 template <int D, int NWR, int NWK, int RTW, bool BC, int PF = 1, int OCC = 1, bool NTKV = false>
 __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p) {
-    static_assert(NWR == 1 || NWK == 1, "waves split either rows or keys");
+    static_assert(NWR == 1 || NWK <= 2, "row-split workgroups have at most two key groups");
     constexpr int NT = 64 * NWR * NWK;
     constexpr int KP = D * 2 + 16;          // K tile row pitch (bytes): 16-byte reads of 16 rows hit distinct banks
     constexpr int VP = D * 2 + 64;          // V tile row pitch: 4 rows x 64 B of a transposing read tile the 64 banks
@@ -64,8 +70,10 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     constexpr int C8 = D / 8;               // 16-byte chunks per row
     constexpr int NLD = (32 * C8) / (64 * NWR);
     constexpr int MP = D + 4;               // merge buffer row pitch (floats)
-    constexpr int MERGE_BYTES = (NWK > 1) ? NWK * 32 * MP * 4 : 0;
-    constexpr bool DB = (NWK == 1);        // row-split shapes double-buffer the shared K/V tile: one barrier per tile
+    // merge buffer: key-split wavefronts (NWR == 1) leave all NWK partials there; a row-split workgroup with two key
+    // groups (NWR > 1, NWK == 2) passes the second group's partial through it
+    constexpr int MERGE_BYTES = (NWK > 1) ? (NWR > 1 ? NWR : NWK) * 32 * MP * 4 : 0;
+    constexpr bool DB = (NWR > 1) || (NWK == 1);   // row-split shapes double-buffer the K/V tile their NWR wavefronts share: one barrier per tile
     constexpr int NBUF = DB ? 2 : 1;
     constexpr int SMEM = (NBUF * NWK * TILE_BYTES > MERGE_BYTES) ? NBUF * NWK * TILE_BYTES : MERGE_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
@@ -81,6 +89,11 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
         b = grp / p.Hkv;
     }
     if (p.seq_active && p.seq_active[b] == 0) return;   // nobody reads this sequence's output in this step
+    int split = 0;
+    if (p.nsplit > 1) {
+        split = bx % p.nsplit;
+        bx /= p.nsplit;
+    }
     const int r0 = bx * (32 * NWR * RTW);
 
     // ---- visible extent of each segment for this workgroup -----------------
@@ -127,7 +140,13 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     // be ragged), so a tile's rows share one base pointer, stride and position origin (all wave-uniform).
     const int T0 = ((len0 + 31) >> 5) - F0, T1 = ((len1 + 31) >> 5) - F1, T2 = ((len2 + 31) >> 5) - F2;
     const int T = T0 + T1 + T2;
-    const int n_it = (T + NWK - 1) / NWK;
+    // this workgroup's share of the key tiles: tiles t_lo .. t_lo + Tn - 1 (all of them without a key split)
+    int t_lo = 0, Tn = T;
+    if (p.nsplit > 1) {
+        t_lo = (int)((int64_t)T * split / p.nsplit);
+        Tn = (int)((int64_t)T * (split + 1) / p.nsplit) - t_lo;
+    }
+    const int n_it = (Tn + NWK - 1) / NWK;
 
     const uint16_t* kb0 = p.seg[0].k + b * p.seg[0].sb + kvh * p.seg[0].sh;
     const uint16_t* vb0 = p.seg[0].v + b * p.seg[0].sb + kvh * p.seg[0].sh;
@@ -187,7 +206,7 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
             for (int i = 0; i < 16; ++i) O[rt][dt][i] = 0.f;
     }
 
-    unsigned char* Kl = smem + wk * TILE_BYTES;   // re-pointed per tile when double-buffering
+    unsigned char* Kl = smem + wk * NBUF * TILE_BYTES;   // re-pointed per tile when double-buffering
     unsigned char* Vl = Kl + 32 * KP;
     const int tl = wr * 64 + lane;  // thread index inside the wave group that shares a tile
 
@@ -207,15 +226,16 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
         const int row = cidx / C8, c = cidx - row * C8;
         toff[q] = (uint32_t)(row * (int)st_c + c * 8);
     }
-    // segment of tile t (t < T), its index inside the segment, and the segment's extent
+    // segment of this workgroup's tile t (t < Tn), its index inside the segment, and the segment's extent
 #define ATTN_TILE(t, sg, lt, slen)                                                                       \
-    const int sg = ((t) < T0) ? 0 : (((t) < T0 + T1) ? 1 : 2);                                           \
-    const int lt = ((t) < T0) ? (t) + F0 : (((t) < T0 + T1) ? (t) - T0 + F1 : (t) - T0 - T1 + F2);      \
+    const int gt_##sg = (t) + t_lo;                                                                      \
+    const int sg = (gt_##sg < T0) ? 0 : ((gt_##sg < T0 + T1) ? 1 : 2);                                   \
+    const int lt = (gt_##sg < T0) ? gt_##sg + F0 : ((gt_##sg < T0 + T1) ? gt_##sg - T0 + F1 : gt_##sg - T0 - T1 + F2); \
     const int slen = (sg == 0) ? len0 : ((sg == 1) ? len1 : len2);
 #define ATTN_LD(ptr) (NTKV ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ptr)) : *reinterpret_cast<const u32x4*>(ptr))
 #define ATTN_PREFETCH(slot, t)                                                                           \
     {                                                                                                    \
-        const int tc_ = min((t), T - 1);                                                                 \
+        const int tc_ = min((t), Tn - 1);                                                                 \
         ATTN_TILE(tc_, sg_, lt_, slen_)                                                                  \
         const uint16_t* kb = (sg_ == 0) ? kb0 : ((sg_ == 1) ? kb1 : kb2);                                \
         const uint16_t* vb = (sg_ == 0) ? vb0 : ((sg_ == 1) ? vb1 : vb2);                                \
@@ -248,13 +268,13 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     }
 #define ATTN_STAGE(slot, t)                                                                              \
     {                                                                                                    \
-        ATTN_TILE(min((t), T - 1), sg_, lt_, slen_)                                                      \
+        ATTN_TILE(min((t), Tn - 1), sg_, lt_, slen_)                                                      \
         (void)sg_;                                                                                       \
         ATTN_TILE_SYNC(); /* the previous tile has been read */                                          \
         _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                                \
             const int cidx = tl + q * (64 * NWR);                                                        \
             const int row = cidx / C8, c = cidx - row * C8;                                              \
-            const bool live = ((t) < T) && (lt_ * 32 + row < slen_);                                     \
+            const bool live = ((t) < Tn) && (lt_ * 32 + row < slen_);                                     \
             const u32x4 z = {0, 0, 0, 0};                                                                \
             *reinterpret_cast<u32x4*>(Kl + row * KP + c * 16) = live ? kreg[slot][q] : z;                \
             *reinterpret_cast<u32x4*>(Vl + row * VP + c * 16) = live ? vreg[slot][q] : z;                \
@@ -264,11 +284,11 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
 
 #define ATTN_STORE(slot, t, buf)                                                                         \
     {                                                                                                    \
-        ATTN_TILE(min((t), T - 1), sg_, lt_, slen_)                                                      \
+        ATTN_TILE(min((t), Tn - 1), sg_, lt_, slen_)                                                      \
         (void)sg_;                                                                                       \
-        unsigned char* Kd = smem + (buf) * TILE_BYTES;                                                   \
+        unsigned char* Kd = smem + (wk * NBUF + (buf)) * TILE_BYTES;                                     \
         unsigned char* Vd = Kd + 32 * KP;                                                                \
-        if ((t) < T && lt_ * 32 + 32 <= slen_) {   /* a full tile: every row is live */                  \
+        if ((t) < Tn && lt_ * 32 + 32 <= slen_) {   /* a full tile: every row is live */                  \
             _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                            \
                 const int cidx = tl + q * (64 * NWR);                                                    \
                 const int row = cidx / C8, c = cidx - row * C8;                                          \
@@ -279,7 +299,7 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
             _Pragma("unroll") for (int q = 0; q < NLD; ++q) {                                            \
                 const int cidx = tl + q * (64 * NWR);                                                    \
                 const int row = cidx / C8, c = cidx - row * C8;                                          \
-                const bool live = ((t) < T) && (lt_ * 32 + row < slen_);                                 \
+                const bool live = ((t) < Tn) && (lt_ * 32 + row < slen_);                                 \
                 const u32x4 z = {0, 0, 0, 0};                                                            \
                 *reinterpret_cast<u32x4*>(Kd + row * KP + c * 16) = live ? kreg[slot][q] : z;            \
                 *reinterpret_cast<u32x4*>(Vd + row * VP + c * 16) = live ? vreg[slot][q] : z;            \
@@ -290,7 +310,7 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     // One K/V tile: scores, (lazy) online softmax, P V.  A macro rather than a lambda: every array it
     // touches must stay in registers.
 #define ATTN_COMPUTE() /* uses the tile index `t` of the enclosing scope */                              \
-    if (t < T) {                                                                                         \
+    if (t < Tn) {                                                                                        \
         f32x16 S[RTW]; \
 _Pragma("unroll") \
         for (int rt = 0; rt < RTW; ++rt) \
@@ -386,11 +406,13 @@ _Pragma("unroll") \
             if (s < n_it) ATTN_PREFETCH(s, ((s + rot0 >= n_it) ? s + rot0 - n_it : s + rot0) * NWK + wk);
     }
     if (DB) {
-        // tile `it` is multiplied from LDS buffer it & 1 while tile it+1 is stored into the other buffer and
-        // tile it+1+PF is requested into the register slot that store frees
+        // iteration `i` multiplies this key group's tile i * NWK + wk from LDS buffer i & 1 while the tile of iteration
+        // i + 1 is stored into the other buffer and the one of iteration i + 1 + PF is requested into the register slot
+        // that store frees
+#define ATTN_DB_TILE(i) ((i) * NWK + wk)
         if (n_it > 0) {
-            ATTN_STORE(0, 0, 0);
-            if (PF < n_it) ATTN_PREFETCH(0, PF);
+            ATTN_STORE(0, ATTN_DB_TILE(0), 0);
+            if (PF < n_it) ATTN_PREFETCH(0, ATTN_DB_TILE(PF));
         }
         __syncthreads();
         int it = 0;
@@ -398,10 +420,11 @@ _Pragma("unroll") \
         for (; it < n_steady; it += PF) {
 #pragma unroll
             for (int u = 0; u < PF; ++u) {
-                const int t = it + u;
-                ATTN_STORE((u + 1) % PF, t + 1, (t + 1) & 1);
-                ATTN_PREFETCH((u + 1) % PF, t + 1 + PF);
-                Kl = smem + (t & 1) * TILE_BYTES;
+                const int i = it + u;
+                const int t = ATTN_DB_TILE(i);
+                ATTN_STORE((u + 1) % PF, ATTN_DB_TILE(i + 1), (i + 1) & 1);
+                ATTN_PREFETCH((u + 1) % PF, ATTN_DB_TILE(i + 1 + PF));
+                Kl = smem + (wk * NBUF + (i & 1)) * TILE_BYTES;
                 Vl = Kl + 32 * KP;
                 ATTN_COMPUTE();
                 __syncthreads();
@@ -409,18 +432,20 @@ _Pragma("unroll") \
         }
 #pragma unroll
         for (int u = 0; u < 2 * PF + 1; ++u) {
-            const int t = it + u;
-            if (t < n_it) {
-                if (t + 1 < n_it) {
-                    ATTN_STORE((u + 1) % PF, t + 1, (t + 1) & 1);
-                    if (t + 1 + PF < n_it) ATTN_PREFETCH((u + 1) % PF, t + 1 + PF);
+            const int i = it + u;
+            if (i < n_it) {
+                const int t = ATTN_DB_TILE(i);
+                if (i + 1 < n_it) {
+                    ATTN_STORE((u + 1) % PF, ATTN_DB_TILE(i + 1), (i + 1) & 1);
+                    if (i + 1 + PF < n_it) ATTN_PREFETCH((u + 1) % PF, ATTN_DB_TILE(i + 1 + PF));
                 }
-                Kl = smem + (t & 1) * TILE_BYTES;
+                Kl = smem + (wk * NBUF + (i & 1)) * TILE_BYTES;
                 Vl = Kl + 32 * KP;
                 ATTN_COMPUTE();
                 __syncthreads();
             }
         }
+#undef ATTN_DB_TILE
     } else {
         // Each (sequence, KV head) starts its walk over the key tiles at a different tile and wraps: the K/V
         // blocks of different heads are a large power-of-two-ish stride apart, so workgroups that all begin at
@@ -460,7 +485,48 @@ _Pragma("unroll") \
 
     // ---- finish -----------------------------------------------------------------
     constexpr float LN2 = 0.6931471805599453f;
-    if (NWK == 1) {
+    if (NWR > 1 && NWK > 1) {
+        // Two key groups of NWR wavefronts each: group 1 hands its accumulators, running maximum and (per half-wave)
+        // sum to group 0 through LDS (the tiles are dead: the loop ended with a barrier); group 0 folds them into its own
+        // registers, lane for lane, and finishes alone.
+        float* mb = reinterpret_cast<float*>(smem);
+#pragma unroll
+        for (int rt = 0; rt < RTW; ++rt) {
+            float* row = mb + (wr * 32 + n) * MP;
+            if (rt > 0) __syncthreads();
+            if (wk == 1) {
+#pragma unroll
+                for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const f32x4 v = {O[rt][dt][4 * q4], O[rt][dt][4 * q4 + 1], O[rt][dt][4 * q4 + 2], O[rt][dt][4 * q4 + 3]};
+                        *reinterpret_cast<f32x4*>(row + 32 * dt + 8 * q4 + 4 * hi) = v;
+                    }
+                if (hi == 0) row[D] = m_run[rt];
+                row[D + 1 + hi] = l_run[rt];
+            }
+            __syncthreads();
+            if (wk == 0) {
+                const float m1 = row[D], l1 = row[D + 1 + hi];
+                const float M = fmaxf(m_run[rt], m1);
+                const float a0 = (m_run[rt] == -INFINITY) ? 0.f : fast_exp2(m_run[rt] - M);
+                const float a1 = (m1 == -INFINITY) ? 0.f : fast_exp2(m1 - M);
+#pragma unroll
+                for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        const f32x4 v = *reinterpret_cast<const f32x4*>(row + 32 * dt + 8 * q4 + 4 * hi);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) O[rt][dt][4 * q4 + e] = a0 * O[rt][dt][4 * q4 + e] + a1 * v[e];
+                    }
+                l_run[rt] = a0 * l_run[rt] + a1 * l1;
+                m_run[rt] = M;
+            }
+        }
+        __syncthreads();     // group 0 re-uses the buffer for its output staging
+        if (wk != 0) return;
+    }
+    if (NWR > 1 || NWK == 1) {
         // The accumulators hold O^T (lane = row, registers = head-dim entries): stored straight from registers a
         // wavefront's store touches 32 rows with 16 bytes each, 64 such stores per row tile.  Each wavefront instead
         // transposes its 32 rows through a private LDS region (the K/V tiles are dead: the loop ended with a
@@ -469,6 +535,31 @@ _Pragma("unroll") \
         static_assert(NWR * 32 * OPB + NWR * 32 * 8 <= 2 * TILE_BYTES, "output staging must fit in the tile buffers");
         unsigned char* ob = smem + wr * (32 * OPB);
         int64_t* roff = reinterpret_cast<int64_t*>(smem + NWR * 32 * OPB) + wr * 32;
+        if (p.nsplit > 1) {
+            // a partial result: accumulators as they are (relative to the running maximum), 16 bytes per store
+            const int64_t rows_total = (int64_t)p.B * p.Hkv * p.R;
+#pragma unroll
+            for (int rt = 0; rt < RTW; ++rt) {
+                const float l = l_run[rt] + shfl_xor(l_run[rt], 32);
+                const int r = r0 + (wr * RTW + rt) * 32 + n;
+                if (r < R) {
+                    const int64_t row = (int64_t)split * rows_total + ((int64_t)b * p.Hkv + kvh) * p.R + r;
+                    float* po = p.part_o + row * D;
+#pragma unroll
+                    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            const f32x4 v = {O[rt][dt][4 * q4], O[rt][dt][4 * q4 + 1], O[rt][dt][4 * q4 + 2], O[rt][dt][4 * q4 + 3]};
+                            *reinterpret_cast<f32x4*>(po + 32 * dt + 8 * q4 + 4 * hi) = v;
+                        }
+                    if (hi == 0) {
+                        p.part_ml[row * 2] = m_run[rt];
+                        p.part_ml[row * 2 + 1] = l;
+                    }
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int rt = 0; rt < RTW; ++rt) {
             const float l = l_run[rt] + shfl_xor(l_run[rt], 32);
@@ -551,6 +642,17 @@ _Pragma("unroll") \
                         o[4 + e] += wgt[k] * c[e];
                     }
                 }
+                if (p.nsplit > 1) {   // a partial result: the merged accumulators of the four wavefronts, unnormalised
+                    const int64_t row = (int64_t)split * ((int64_t)p.B * p.Hkv * p.R) + ((int64_t)b * p.Hkv + kvh) * p.R + r;
+                    float* po = p.part_o + row * D + 8 * c8;
+                    *reinterpret_cast<f32x4*>(po) = f32x4{o[0], o[1], o[2], o[3]};
+                    *reinterpret_cast<f32x4*>(po + 4) = f32x4{o[4], o[5], o[6], o[7]};
+                    if (c8 == 0) {
+                        p.part_ml[row * 2] = M;
+                        p.part_ml[row * 2 + 1] = den;
+                    }
+                    continue;
+                }
                 const int i = r / p.g, hg = r - i * p.g;
                 const int h = kvh * p.g + hg;
                 u32x4 v;
@@ -564,26 +666,102 @@ _Pragma("unroll") \
     }
 }
 
+// Combines the nsplit partial results of every (sequence, head, query row) in a fixed order (split 0, 1, ...): with
+// M = max_s m_s and w_s = 2^(m_s - M), out = sum_s w_s o_s / sum_s w_s l_s and lse = (M + log2 sum_s w_s l_s) ln 2.
+// D / 4 threads per row (16 bytes of fp32 in, 8 bytes of bf16 out each), 256 / (D / 4) rows per workgroup.
+template <int D>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnParams p) {
+    constexpr int TPR = D / 4, RPW = 256 / TPR;
+    const int64_t rows_total = (int64_t)p.B * p.Hkv * p.R;
+    const int64_t row = (int64_t)blockIdx.x * RPW + threadIdx.x / TPR;
+    const int c4 = threadIdx.x % TPR;
+    if (row >= rows_total) return;
+    const int grp = (int)(row / p.R), r = (int)(row - (int64_t)grp * p.R);
+    const int b = grp / p.Hkv, kvh = grp - b * p.Hkv;
+    if (p.seq_active && p.seq_active[b] == 0) return;
+    float M = -INFINITY;
+    for (int s = 0; s < p.nsplit; ++s) M = fmaxf(M, p.part_ml[(s * rows_total + row) * 2]);
+    float den = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < p.nsplit; ++s) {
+        const float ms = p.part_ml[(s * rows_total + row) * 2];
+        const float ls = p.part_ml[(s * rows_total + row) * 2 + 1];
+        const float wgt = (ms == -INFINITY) ? 0.f : fast_exp2(ms - M);
+        const f32x4 o = *reinterpret_cast<const f32x4*>(p.part_o + (s * rows_total + row) * D + 4 * c4);
+        den += wgt * ls;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += wgt * o[e];
+    }
+    const float inv = den > 0.f ? 1.f / den : 0.f;
+    const int i = r / p.g, hg = r - i * p.g;
+    const int h = kvh * p.g + hg;
+    u32x2 v;
+    v[0] = pack_bf16x2(acc[0] * inv, acc[1] * inv);
+    v[1] = pack_bf16x2(acc[2] * inv, acc[3] * inv);
+    *reinterpret_cast<u32x2*>(p.out + b * p.o_sb + i * p.o_st + (int64_t)h * p.o_sh + 4 * c4) = v;
+    if (p.lse && c4 == 0)
+        p.lse[((int64_t)b * p.Hq + h) * p.Lq + i] = den > 0.f ? (M + log2f(den)) * 0.6931471805599453f : -INFINITY;
+}
+
+int g_attn_split = 0;    // 0 = choose the key split across workgroups from the shape; 1 = never; 2..16 = force (dlm_set_option "attn_split")
 int g_attn_nt = 1;       // 1 = non-temporal K/V loads in the one-workgroup-per-KV-head shape (default); 0 = never (tuning)
 int g_attn_variant = 0;  // 0 = choose by shape; 1..3 force a kernel shape (dlm_set_option "attn_variant")
 int g_attn_remap = 7;    // XCD-grouped grids: bit 0 forward and dQ, bit 1 longest key range first, bit 2 dK / dV (dlm_set_option "attn_remap")
 
-template <int D, bool BC>
-static int launch_attn(const AttnParams& p, hipStream_t st) {
+// The kernel shape the planner picks for a problem (0 = "automatic" resolved).  Measured on MI355X (us, GPU time):
+//   g * Lq <= 32 (every rollout step): one key-split workgroup per (sequence, KV head); sized for two per CU it is
+//     8 - 10 % faster than sized for one even when only one is resident (c2 22.4 -> 19.7, c3 72 -> 66, c5a 173 -> 162);
+//   more rows: 128-row workgroups; with at most one of them per CU, eight wavefronts in two key groups (two wavefronts
+//     per SIMD from one workgroup: c4 39.1 -> 32.2), otherwise two or three four-wavefront workgroups per CU.
+static int plan_variant(const AttnParams& p) {
     const int64_t BH = (int64_t)p.B * p.Hkv;
     int variant = g_attn_variant;
     if (variant == 0) {
-        const int64_t wgs128 = BH * ((p.R + 127) / 128);
-        if (p.R <= 32) variant = 1;           // waves split the keys, merge on chip
-        // far too few 128-row workgroups for 256 CUs: 32-row key-split tiles (K/V re-read per row tile, through one L2)
+        const int64_t wgs128 = BH * ((p.R + 127) / 128) * (p.nsplit > 1 ? p.nsplit : 1);
+        if (p.R <= 32) variant = 12;          // waves split the keys, merge on chip
+        // far too few 128-row workgroups for 256 CUs (and no workspace to split the keys across workgroups with):
+        // 32-row key-split tiles (K/V re-read per row tile, through one L2)
         else if (wgs128 <= 64 || (wgs128 <= 128 && p.R <= 64)) variant = 11;
+        else if (wgs128 <= 256) variant = 13; // one 128-row workgroup per CU at most: eight wavefronts, two key groups
         else if (wgs128 >= 768) variant = 6;  // 128-row workgroups, three resident per CU (softmax of one overlaps MFMA of another)
         else variant = 4;                     // 128-row workgroups, two resident per CU, deeper prefetch
     }
+    return variant;
+}
+
+// How many workgroups share the keys of one row tile.  A split costs a second launch (the merge) and (d + 2) * 4 bytes
+// written and read again per row and split, so it pays only where the unsplit launch leaves most of the chip idle: at
+// most 128 workgroups (half the CUs) and at least 32 key tiles.  Then the count brings the launch to about one
+// workgroup per CU with at least four key tiles each.  Measured (us): 1 x 32 heads x 8192 keys 114 -> 33 (8 splits);
+// 1 x 32/8 heads x 16384 keys 318 -> 43 (16); 8 x 28/4 heads x 4096 keys 88 -> 40 (4); 4 x 32 heads x 2048 keys 33 -> 30 (2).
+// With 256 or more workgroups every split measured slower (c2 19.7 -> 28.4, c3 66 -> 81, c4 32 -> 50, c5a 162 -> 180):
+// those launches already keep the memory system busy and the partials and the second launch are pure cost.
+// Never in packed mode (each sequence has its own key range) and only when the caller provides the workspace.
+static int plan_nsplit(const dlm_attn_args* a) {
+    if (a->cu_seqlens || g_attn_split == 1) return 1;
+    const int g = a->Hq / a->Hkv;
+    const int64_t R = (int64_t)g * a->Lq, BH = (int64_t)a->B * a->Hkv;
+    const int64_t tiles = ((int64_t)a->prefix.len + 31) / 32 + ((int64_t)a->block.len + 31) / 32 + ((int64_t)a->suffix.len + 31) / 32;
+    int64_t n = 1;
+    if (g_attn_split >= 2) n = g_attn_split;
+    else if (g_attn_variant == 0) {
+        const int64_t wgs = R <= 32 ? BH : BH * ((R + 127) / 128);
+        if (wgs <= 128 && tiles >= 32) n = 256 / wgs;
+    }
+    if (n > 16) n = 16;
+    if (n > tiles / 4) n = tiles / 4;         // at least four key tiles per workgroup
+    return n < 1 ? 1 : (int)n;
+}
+
+template <int D, bool BC>
+static int launch_attn(const AttnParams& p, hipStream_t st) {
+    const int64_t BH = (int64_t)p.B * p.Hkv;
+    const int ns = p.nsplit > 1 ? p.nsplit : 1;
+    int variant = plan_variant(p);
     if (variant == 0 + 11 || (variant == 1 && p.R > 32)) {
         // 32-row workgroups whose wavefronts split the keys, several row tiles per (sequence, KV head), XCD-grouped
         AttnParams q = p;
-        const int64_t n_wg = set_remap(q.remap, BH, (p.R + 31) / 32, BC && (g_attn_remap & 2));
+        const int64_t n_wg = set_remap(q.remap, BH, (p.R + 31) / 32 * ns, BC && (g_attn_remap & 2));
         if (n_wg > 0) {
             hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1>), dim3((unsigned)n_wg), dim3(256), 0, st, q);
             return check_hip(hipGetLastError(), "attn_kernel launch");
@@ -591,15 +769,30 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
         variant = 2;
     }
     if (variant >= 8 && p.R <= 32) {   // key-split alternatives (tuning)
-        const dim3 grid(1, p.Hkv, p.B);
-        if (variant == 8) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2, 1, true>), grid, dim3(256), 0, st, p);
+        const dim3 grid(ns, p.Hkv, p.B);
+        if (variant == 12) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1, 2, true>), grid, dim3(256), 0, st, p);
+        else if (variant == 8) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 2, 1, true>), grid, dim3(256), 0, st, p);
         else if (variant == 9) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 3, 1, true>), grid, dim3(256), 0, st, p);
         else hipLaunchKernelGGL((attn_kernel<D, 1, 8, 1, BC, 1, 1, true>), grid, dim3(512), 0, st, p);
         return check_hip(hipGetLastError(), "attn_kernel launch");
     }
+    if (variant == 13 || variant == 14) {
+        // 128-row workgroups of 8 wavefronts: two key groups of 4 (two wavefronts per SIMD from ONE workgroup per CU),
+        // combined through LDS at the end.  For row counts that give at most one 128-row workgroup per CU.
+        dim3 grid((p.R + 127) / 128 * ns, p.Hkv, p.B);
+        AttnParams q = p;
+        if ((g_attn_remap & 1) && grid.x >= 2) {
+            const int64_t n_wg = set_remap(q.remap, BH, (int)grid.x, BC && (g_attn_remap & 2));
+            if (n_wg > 0) grid = dim3((unsigned)n_wg);
+            else q = p;
+        }
+        if (variant == 13) hipLaunchKernelGGL((attn_kernel<D, 4, 2, 1, BC, 1, 1>), grid, dim3(512), 0, st, q);
+        else hipLaunchKernelGGL((attn_kernel<D, 4, 2, 1, BC, 2, 1>), grid, dim3(512), 0, st, q);
+        return check_hip(hipGetLastError(), "attn_kernel launch");
+    }
     if (variant >= 8) variant = 0 + 4;
     if (variant >= 4) {   // 128-row workgroups, several resident per CU
-        dim3 grid((p.R + 127) / 128, p.Hkv, p.B);
+        dim3 grid((p.R + 127) / 128 * ns, p.Hkv, p.B);
         AttnParams q = p;
         if ((g_attn_remap & 1) && grid.x >= 2) {
             const int64_t n_wg = set_remap(q.remap, BH, (int)grid.x, BC && (g_attn_remap & 2));
@@ -613,12 +806,12 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
         return check_hip(hipGetLastError(), "attn_kernel launch");
     }
     if (variant == 1) {
-        if (g_attn_nt) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1, 1, true>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
-        else hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1>), dim3(1, p.Hkv, p.B), dim3(256), 0, st, p);
+        if (g_attn_nt) hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1, 1, true>), dim3(ns, p.Hkv, p.B), dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((attn_kernel<D, 1, 4, 1, BC, 1>), dim3(ns, p.Hkv, p.B), dim3(256), 0, st, p);
     } else if (variant == 2) {
-        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 3>), dim3((p.R + 127) / 128, p.Hkv, p.B), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 3>), dim3((p.R + 127) / 128 * ns, p.Hkv, p.B), dim3(256), 0, st, p);
     } else {
-        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 2, BC, 3>), dim3((p.R + 255) / 256, p.Hkv, p.B), dim3(256), 0, st, p);
+        hipLaunchKernelGGL((attn_kernel<D, 4, 1, 2, BC, 3>), dim3((p.R + 255) / 256 * ns, p.Hkv, p.B), dim3(256), 0, st, p);
     }
     return check_hip(hipGetLastError(), "attn_kernel launch");
 }
@@ -685,7 +878,7 @@ using namespace dlm;
 extern "C" int dlm_set_option(const char* name, int value) {
     if (!name) return fail(DLM_ERR_INVALID_ARG, "set_option: null name");
     if (!strcmp(name, "attn_variant")) {
-        if (value < 0 || value > 11) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..11");
+        if (value < 0 || value > 14) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..14");
         g_attn_variant = value;
         return DLM_OK;
     }
@@ -698,6 +891,11 @@ extern "C" int dlm_set_option(const char* name, int value) {
         g_attn_remap = value;
         return DLM_OK;
     }
+    if (!strcmp(name, "attn_split")) {
+        if (value < 0 || value > 16) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_split must be 0..16");
+        g_attn_split = value;
+        return DLM_OK;
+    }
     if (!strcmp(name, "attn_nt")) {
         if (value < 0 || value > 1) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_nt must be 0 or 1");
         g_attn_nt = value;
@@ -706,9 +904,16 @@ extern "C" int dlm_set_option(const char* name, int value) {
     return fail(DLM_ERR_INVALID_ARG, "set_option: unknown option '%s'", name);
 }
 
+static size_t split_workspace_bytes(const dlm_attn_args* a, int nsplit) {
+    if (nsplit <= 1) return 0;
+    return (size_t)nsplit * (size_t)a->B * (size_t)a->Hq * (size_t)a->Lq * (size_t)(a->d + 2) * sizeof(float);
+}
+
 extern "C" size_t dlm_block_attn_workspace_bytes(const dlm_attn_args* a) {
-    (void)a;
-    return 0;  // key-split partials are merged on chip
+    if (!a || a->struct_size != sizeof(dlm_attn_args) || a->B <= 0 || a->Lq <= 0 || a->Hq <= 0 || a->Hkv <= 0 ||
+        a->Hq % a->Hkv || a->d <= 0)
+        return 0;
+    return split_workspace_bytes(a, plan_nsplit(a));
 }
 
 extern "C" int dlm_block_attn(const dlm_attn_args* a, void* stream) {
@@ -734,8 +939,23 @@ extern "C" int dlm_block_attn(const dlm_attn_args* a, void* stream) {
     p.cu = a->cu_seqlens; p.total = a->total_tokens;
     p.seq_active = a->seq_active;
     p.remap = no_remap();
+    // The key split across workgroups is taken only when the caller brought the workspace it needs.
+    p.nsplit = 1; p.part_o = nullptr; p.part_ml = nullptr;
+    const int ns = plan_nsplit(a);
+    const size_t need = split_workspace_bytes(a, ns);
+    if (ns > 1 && a->workspace && a->workspace_bytes >= need && aligned16(a->workspace)) {
+        const size_t rows_total = (size_t)a->B * a->Hq * a->Lq;
+        p.nsplit = ns;
+        p.part_o = (float*)a->workspace;
+        p.part_ml = p.part_o + (size_t)ns * rows_total * a->d;
+    }
     hipStream_t st = (hipStream_t)stream;
     const bool bc = a->mask_mode == DLM_MASK_BLOCK_CAUSAL;
-    if (a->d == 128) return bc ? launch_attn<128, true>(p, st) : launch_attn<128, false>(p, st);
-    return bc ? launch_attn<64, true>(p, st) : launch_attn<64, false>(p, st);
+    if (a->d == 128) rc = bc ? launch_attn<128, true>(p, st) : launch_attn<128, false>(p, st);
+    else rc = bc ? launch_attn<64, true>(p, st) : launch_attn<64, false>(p, st);
+    if (rc != DLM_OK || p.nsplit <= 1) return rc;
+    const int64_t rows_total = (int64_t)a->B * a->Hq * a->Lq;
+    if (a->d == 128) hipLaunchKernelGGL(attn_merge_kernel<128>, dim3((unsigned)((rows_total + 7) / 8)), dim3(256), 0, st, p);
+    else hipLaunchKernelGGL(attn_merge_kernel<64>, dim3((unsigned)((rows_total + 15) / 16)), dim3(256), 0, st, p);
+    return check_hip(hipGetLastError(), "attn_merge_kernel launch");
 }

@@ -59,6 +59,7 @@ class GpuRollout:
         self.m_dev = torch.zeros(1, dtype=torch.int32, device=dev)
         self.commit_step = torch.full((B, Lb), -1, dtype=torch.int16, device=dev) if record_steps else None
         self.workspace = torch.empty(max(16, dlm.lmhead_workspace_bytes(n, cfg.V, sample=sample_seed is not None, conf_mode=self.conf_mode)), dtype=torch.uint8, device=dev)
+        self.attn_workspace = None    # sized per block (key split across workgroups)
         self.total_committed = torch.zeros(1, dtype=torch.int64, device=dev)
         self.block = -1
         self.step_idx = 0
@@ -101,6 +102,7 @@ class GpuRollout:
             P, Lb, S = self.P, self.cfg.Lb, self.S
             self._prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
             self._suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
+            self._size_attn_workspace()
 
     def queue_poll(self):
         """(event, pinned host word) of the step queued last: after event.synchronize() the word holds the
@@ -143,6 +145,17 @@ class GpuRollout:
         S = self.S
         self._prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
         self._suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
+        self._size_attn_workspace()
+
+    def _size_attn_workspace(self) -> None:
+        """The attention call may split the keys across workgroups when it is given a workspace; its size depends on
+        the block's key count, so it is queried (and the buffer grown) once per block, never inside a step."""
+        cfg, Lb = self.cfg, self.cfg.Lb
+        blk = (self.cache_k[:, :, :Lb], self.cache_v[:, :, :Lb], self.P)      # stands in for the step's block K/V (same shape)
+        need = dlm.block_attn_workspace_bytes(self.O, prefix=self._prefix, block=blk, suffix=self._suffix,
+                                              mask_mode=_MASKS[cfg.mask_mode], block_size=cfg.bs, q_pos0=self.P)
+        if need > (0 if self.attn_workspace is None else self.attn_workspace.numel()):
+            self.attn_workspace = torch.empty(need, dtype=torch.uint8, device=self.dev)
 
     def step(self, q: torch.Tensor, kblk: torch.Tensor, vblk: torch.Tensor, hidden: torch.Tensor) -> None:
         """Enqueue one denoising step.  q [B, Lb, Hq, d]; kblk, vblk [B, Hkv, Lb, d]; hidden [B, Lb, Dh]."""
@@ -159,7 +172,8 @@ class GpuRollout:
         dlm.block_attn(q, self.O, prefix=prefix, block=(kblk, vblk, P), suffix=suffix,
                        mask_mode=_MASKS[cfg.mask_mode], block_size=cfg.bs, q_pos0=P,
                        lse=self.lse_attn if self.diagnostics else None,
-                       seq_active=self.remaining if self.step_idx > 0 else None, stream=st)
+                       seq_active=self.remaining if self.step_idx > 0 else None, workspace=self.attn_workspace,
+                       stream=st)
         diag = self.diagnostics
         dlm.lmhead_confidence(hidden.view(cfg.B * Lb, cfg.Dh), self.w, self.conf, self.tok,
                               M=self.m_host, row_idx=self.row_idx, m_dev=self.m_dev,
