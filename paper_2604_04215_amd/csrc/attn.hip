@@ -885,6 +885,7 @@ extern "C" int dlm_set_option(const char* name, int value) {
     if (!strcmp(name, "lmhead_variant")) return lm_set_variant(value);
     if (!strcmp(name, "lmhead_block")) return lm_set_block(value);
     if (!strcmp(name, "lmhead_nt")) return lm_set_nt(value);
+    if (!strcmp(name, "lmhead_cus")) return lm_set_cus(value);
     if (!strcmp(name, "kv_copy_unroll")) return copy_set_unroll(value);
     if (!strcmp(name, "attn_remap")) {
         if (value < 0 || value > 7) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_remap must be 0..7");

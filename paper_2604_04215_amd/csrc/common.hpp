@@ -25,6 +25,7 @@ int check_hip(hipError_t e, const char* what);
 int lm_set_variant(int v);   // lmhead.hip
 int lm_set_block(int v);     // lmhead.hip
 int lm_set_nt(int v);        // lmhead.hip
+int lm_set_cus(int v);       // lmhead.hip
 int copy_set_unroll(int v);  // commit.hip
 extern int g_attn_remap;     // attn.hip: bit 0 forward + dQ, bit 1 longest key range first, bit 2 dK / dV passes
 

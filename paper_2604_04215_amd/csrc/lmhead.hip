@@ -34,8 +34,11 @@ struct LmParams {
     float *lse, *zmax, *z2nd;
     const int32_t* target;
     float* ztarget;
-    f32x4* part;  // [M][n_vtiles] of (max, sumexp, runner-up, argmax bits)
-    int n_vt, n_mc;
+    f32x4* part;  // [M][n_vt] of (max, sumexp, runner-up, argmax bits)
+    int n_vt, n_mc;   // partials per row (all launches of the call together), row chunks
+    // One call may cover the vocabulary with two launches (full-height tiles, then half-height ones for the tail):
+    // a launch owns n_vt_l tiles that begin at vocabulary row v_first and fill the partials vt0 .. vt0 + n_vt_l - 1.
+    int n_vt_l, vt0, v_first;
     int gm, gv;   // workgroup blocking per XCD: gm row chunks x gv vocabulary tiles run side by side
     // Gumbel-max sampling (sample != 0): a second partial per (tile, row) of
     // (perturbed max, logit of that token, its index bits, unused)
@@ -365,8 +368,9 @@ __global__ __launch_bounds__(64 * WV * WH, OCC) void lmhead_kernel(LmParams p) {
     const int n = lane & 31, hi = lane >> 5;
     int vt, mc, kgroup;
     lm_tile_of_block(blockIdx.x, p.n_mc, p.gm, p.gv, vt, mc, kgroup);
-    if (vt >= p.n_vt) return;
-    const int v0 = vt * TV;
+    if (vt >= p.n_vt_l) return;
+    const int v0 = p.v_first + vt * TV;
+    vt += p.vt0;
     const int m0 = mc * MB;
     int M = p.M;
     if (!lm_rows(p, M)) return;
@@ -575,8 +579,9 @@ __global__ __launch_bounds__(64 * WV) void lmhead_wdirect_kernel(LmParams p) {
     const int n = lane & 31, hi = lane >> 5;
     int vt, mc, kgroup;
     lm_tile_of_block(blockIdx.x, p.n_mc, p.gm, p.gv, vt, mc, kgroup);
-    if (vt >= p.n_vt) return;
-    const int v0 = vt * TV;
+    if (vt >= p.n_vt_l) return;
+    const int v0 = p.v_first + vt * TV;
+    vt += p.vt0;
     const int m0 = mc * MB;
     int M = p.M;
     if (!lm_rows(p, M)) return;
@@ -721,8 +726,9 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_dma_kernel(LmParams p) {
     const int n = lane & 31, hi = lane >> 5;
     int vt, mc, kgroup;
     lm_tile_of_block(blockIdx.x, p.n_mc, p.gm, p.gv, vt, mc, kgroup);
-    if (vt >= p.n_vt) return;
-    const int v0 = vt * TV, m0 = mc * MB;
+    if (vt >= p.n_vt_l) return;
+    const int v0 = p.v_first + vt * TV, m0 = mc * MB;
+    vt += p.vt0;
     int M = p.M;
     if (!lm_rows(p, M)) return;
     if (m0 >= M) return;
@@ -909,8 +915,9 @@ __global__ __launch_bounds__(64 * WV * WH) void lmhead_pair_kernel(LmParams p) {
     const int n = lane & 31, hi = lane >> 5;
     int vt, mc, kgroup;
     lm_tile_of_block(blockIdx.x, p.n_mc, p.gm, p.gv, vt, mc, kgroup);
-    if (vt >= p.n_vt) return;
-    const int v0 = vt * TV, m0 = mc * MB;
+    if (vt >= p.n_vt_l) return;
+    const int v0 = p.v_first + vt * TV, m0 = mc * MB;
+    vt += p.vt0;
     int M = p.M;
     if (!lm_rows(p, M)) return;
     if (m0 >= M) return;
@@ -1154,6 +1161,7 @@ __global__ __launch_bounds__(256) void lmhead_reduce_kernel(LmParams p) {
 
 struct LmVariant {
     int tv, mb, threads;
+    int half;   // table entry with the same rows and half the vocabulary tile height (for the tail of a launch), -1: none
     void (*launch)(dim3, hipStream_t, const LmParams&);
     // The same shape with W fetched by non-temporal loads, for launches with ONE row chunk, where every element of
     // W is used exactly once: W then streams through L2 without being kept.  Measured on one box, V = 126464,
@@ -1166,24 +1174,24 @@ template <int WV, int WH, int TVW, int THW, int PD, int KCH = 64, int OCC = 1, b
 static void launch_lm(dim3 grid, hipStream_t st, const LmParams& p) {
     hipLaunchKernelGGL((lmhead_kernel<WV, WH, TVW, THW, PD, KCH, OCC, PIPE, NTW>), grid, dim3(64 * WV * WH), 0, st, p);
 }
-#define LMP(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD, 64, 1, true>, launch_lm<WV, WH, TVW, THW, PD, 64, 1, true, true>}
+#define LMP(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, -1, launch_lm<WV, WH, TVW, THW, PD, 64, 1, true>, launch_lm<WV, WH, TVW, THW, PD, 64, 1, true, true>}
 template <int WV, int TVW, int THW, int PDW>
 static void launch_lmd(dim3 grid, hipStream_t st, const LmParams& p) {
     hipLaunchKernelGGL((lmhead_wdirect_kernel<WV, TVW, THW, PDW>), grid, dim3(64 * WV), 0, st, p);
 }
-#define LMD(WV, TVW, THW, PDW) {32 * TVW * WV, 32 * THW, 64 * WV, launch_lmd<WV, TVW, THW, PDW>, nullptr}
+#define LMD(WV, TVW, THW, PDW) {32 * TVW * WV, 32 * THW, 64 * WV, -1, launch_lmd<WV, TVW, THW, PDW>, nullptr}
 template <int WV, int WH, int TVW, int THW, int NS, bool XB = false>
 static void launch_lma(dim3 grid, hipStream_t st, const LmParams& p) {
     hipLaunchKernelGGL((lmhead_dma_kernel<WV, WH, TVW, THW, NS, XB>), grid, dim3(64 * WV * WH), 0, st, p);
 }
-#define LMA(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lma<WV, WH, TVW, THW, NS>, nullptr}
-#define LMX(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lma<WV, WH, TVW, THW, NS, true>, nullptr}
+#define LMA(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, -1, launch_lma<WV, WH, TVW, THW, NS>, nullptr}
+#define LMX(WV, WH, TVW, THW, NS) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, -1, launch_lma<WV, WH, TVW, THW, NS, true>, nullptr}
 template <int WV, int WH, int TVW, int THW>
 static void launch_lmq(dim3 grid, hipStream_t st, const LmParams& p) {
     hipLaunchKernelGGL((lmhead_pair_kernel<WV, WH, TVW, THW>), grid, dim3(64 * WV * WH), 0, st, p);
 }
-#define LMQ(WV, WH, TVW, THW) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lmq<WV, WH, TVW, THW>, nullptr}
-#define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, launch_lm<WV, WH, TVW, THW, PD>, launch_lm<WV, WH, TVW, THW, PD, 64, 1, false, true>}
+#define LMQ(WV, WH, TVW, THW) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, -1, launch_lmq<WV, WH, TVW, THW>, nullptr}
+#define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, -1, launch_lm<WV, WH, TVW, THW, PD>, launch_lm<WV, WH, TVW, THW, PD, 64, 1, false, true>}
 static const LmVariant g_lm_variants[] = {
     // shapes the planner uses, by row count M (V = 126464, Dh = 4096 on MI355X, us per main-kernel launch in the
     // rollout, non-temporal W stream; entries 21, 22, 20 above 192 rows):
@@ -1212,7 +1220,15 @@ static const LmVariant g_lm_variants[] = {
     /*21*/ LMQ(4, 2, 2, 4),     // same, 8 waves x (64 x 128)                      M <= 256: ~245
     /*22*/ LMQ(4, 1, 2, 6),     // 256 x 192, 4 waves x (64 x 192)
     /*23*/ LMQ(4, 1, 2, 4),     // 256 x 128, 4 waves x (64 x 128)
+    // half-height forms of entries 2, 3, 4 and 21 (128 vocabulary rows): the tail of a launch whose tile count leaves
+    // at most half of the CUs busy in its last round (see launch_lm_shape)
+    /*24*/ LMP(4, 1, 1, 3, 3),  // 128 x 96,  4 waves
+    /*25*/ LMP(4, 2, 1, 2, 3),  // 128 x 128, 8 waves
+    /*26*/ LMP(4, 2, 1, 3, 2),  // 128 x 192, 8 waves
+    /*27*/ LMQ(4, 2, 1, 4),     // 128 x 256, paired ring, 8 waves x (32 x 128)
 };
+// entry -> its half-height form
+static int lm_half_of(int v) { return v == 2 ? 24 : v == 3 ? 25 : v == 4 ? 26 : v == 21 ? 27 : -1; }
 #undef LMV
 #undef LMA
 #undef LMX
@@ -1224,6 +1240,7 @@ constexpr int LM_MIN_TV = 128;   // smallest vocabulary tile of any variant: siz
 int g_lm_variant = -1;           // -1 = choose by M; otherwise force an entry of the table (dlm_set_option)
 int g_lm_nt = 1;                 // 1 = non-temporal W loads when there is one row chunk (default); 0 = never (tuning)
 int g_lm_block_gv = -1;          // -1 = automatic XCD blocking; 0 = none; n = n vocabulary tiles per block (tuning)
+int g_lm_cus = 0;                // CUs the tail rule assumes: 0 = the device's count; -1 = no half-height tail (tuning, tests)
 
 static int plan_lmhead(int M) {
     if (g_lm_variant >= 0) return g_lm_variant;
@@ -1270,12 +1287,9 @@ static int plan_capacity(int M) {
     return 0x7fffffff;
 }
 
-// Fills the layout fields of p for one kernel shape (p.M = the rows this launch may hold, m_bound = the caller's
-// bound, which places the second partials) and launches it.
-static int launch_lm_shape(const LmVariant& var, LmParams& p, int m_bound, hipStream_t st) {
-    p.n_vt = (p.V + var.tv - 1) / var.tv;
-    p.part2 = p.part + (size_t)p.n_vt * m_bound;
-    p.n_mc = (p.M + var.mb - 1) / var.mb;
+// Launches one kernel shape over n_vt_l vocabulary tiles that begin at row v_first (partials vt0 ...).
+static int launch_lm_tiles(const LmVariant& var, LmParams& p, int n_vt_l, int vt0, int v_first, hipStream_t st) {
+    p.n_vt_l = n_vt_l; p.vt0 = vt0; p.v_first = v_first;
     // several row chunks: blocks of gm x gv workgroups for the 32 CUs of an XCD; gm is the largest divisor of the
     // chunk count up to 8 (measured at V = 126464, Dh = 4096: +6 % at M >= 1024, +10..17 % at M = 512)
     p.gm = 1; p.gv = 1;
@@ -1285,11 +1299,49 @@ static int launch_lm_shape(const LmVariant& var, LmParams& p, int m_bound, hipSt
         p.gv = 32 / p.gm > 8 ? 8 : 32 / p.gm;
     }
     if (g_lm_block_gv >= 0) { p.gv = g_lm_block_gv > 0 ? g_lm_block_gv : 1; if (g_lm_block_gv == 0) p.gm = 1; }
-    const int64_t n_vt8 = ((int64_t)(p.n_vt + 7) / 8 + p.gv - 1) / p.gv * p.gv;   // vocabulary tiles per XCD, padded to gv
+    const int64_t n_vt8 = ((int64_t)(n_vt_l + 7) / 8 + p.gv - 1) / p.gv * p.gv;   // vocabulary tiles per XCD, padded to gv
     const int64_t n_wg = n_vt8 * 8 * p.n_mc;
     if (n_wg > 0x7fffffff) return fail(DLM_ERR_UNSUPPORTED, "lmhead: M * V too large for one launch");
     ((p.n_mc == 1 && var.launch_nt && g_lm_nt) ? var.launch_nt : var.launch)(dim3((unsigned)n_wg), st, p);
     return check_hip(hipGetLastError(), "lmhead_kernel launch");
+}
+
+static int device_cus() {
+    static int cus[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cus[dev] == 0) {
+        int n = 0;
+        cus[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+    }
+    return cus[dev];
+}
+
+// Fills the layout fields of p for one kernel shape (p.M = the rows this launch may hold, m_bound = the caller's
+// bound, which places the second partials) and launches it.
+// Tail rule: the shapes for 65 - 256 rows run one workgroup per CU, so a launch costs ceil(tiles / CUs) rounds of
+// equal length.  When the last round would occupy at most half of the CUs (V = 152064: 594 tiles = 2.32 rounds on 256
+// CUs, V = 157184: 614 = 2.40), the tiles of that round are launched at half height instead (a second launch of the
+// shape's 128-row form on twice as many tiles): 2.5 rounds' time instead of 3.
+static int launch_lm_shape(int v_idx, LmParams& p, int m_bound, hipStream_t st) {
+    const LmVariant& var = g_lm_variants[v_idx];
+    const int n_full = (p.V + var.tv - 1) / var.tv;
+    p.n_mc = (p.M + var.mb - 1) / var.mb;
+    const int half = lm_half_of(v_idx);
+    const int cus = g_lm_cus > 0 ? g_lm_cus : device_cus();
+    const int tail = n_full % cus;
+    if (g_lm_cus >= 0 && half >= 0 && p.n_mc == 1 && n_full > cus && tail > 0 && 2 * tail <= cus) {
+        const int n_main = n_full - tail, v_split = n_main * var.tv;
+        const int n_half = (p.V - v_split + var.tv / 2 - 1) / (var.tv / 2);
+        p.n_vt = n_main + n_half;
+        p.part2 = p.part + (size_t)p.n_vt * m_bound;
+        int rc = launch_lm_tiles(var, p, n_main, 0, 0, st);
+        if (rc != DLM_OK) return rc;
+        return launch_lm_tiles(g_lm_variants[half], p, n_half, n_main, v_split, st);
+    }
+    p.n_vt = n_full;
+    p.part2 = p.part + (size_t)p.n_vt * m_bound;
+    return launch_lm_tiles(var, p, n_full, 0, 0, st);
 }
 
 extern "C" size_t dlm_lmhead_workspace_bytes(const dlm_lmhead_args* a) {
@@ -1331,12 +1383,12 @@ static int lmhead_enqueue(const dlm_lmhead_args* a, void* workspace, void* strea
         LmParams q = p;
         q.M = cap;
         q.m_hi = cap;
-        rc = launch_lm_shape(g_lm_variants[v_try], q, a->M, st);
+        rc = launch_lm_shape(v_try, q, a->M, st);
         if (rc != DLM_OK) return rc;
         p.m_lo = cap;
         p.alt_cap = cap; p.alt_n_vt = q.n_vt; p.alt_part2 = q.part2;
     }
-    rc = launch_lm_shape(g_lm_variants[v_safe], p, a->M, st);
+    rc = launch_lm_shape(v_safe, p, a->M, st);
     if (rc != DLM_OK) return rc;
     hipLaunchKernelGGL(lmhead_reduce_kernel, dim3(a->M), dim3(256), 0, st, p);
     return check_hip(hipGetLastError(), "lmhead_reduce_kernel launch");
@@ -1387,6 +1439,11 @@ namespace dlm {
 int lm_set_block(int v) {
     if (v < -1 || v > 8) return fail(DLM_ERR_INVALID_ARG, "set_option: lmhead_block must be -1..8");
     g_lm_block_gv = v;
+    return DLM_OK;
+}
+int lm_set_cus(int v) {
+    if (v < -1 || v > 4096) return fail(DLM_ERR_INVALID_ARG, "set_option: lmhead_cus must be -1..4096");
+    g_lm_cus = v;
     return DLM_OK;
 }
 int lm_set_nt(int v) {

@@ -83,7 +83,7 @@ def test_shapes_vs_oracle(M, Dh, V):
     assert np.all(got["tok"] != V - 1)
 
 
-@pytest.mark.parametrize("variant", range(24))
+@pytest.mark.parametrize("variant", range(28))
 def test_every_kernel_shape(variant):
     # each entry of the library's shape table on a problem with several row chunks and ragged tails
     M, Dh, V = 300, 192, 1100
@@ -98,7 +98,7 @@ def test_every_kernel_shape(variant):
     compare(got, ref)
 
 
-@pytest.mark.parametrize("variant", range(10, 24))
+@pytest.mark.parametrize("variant", list(range(10, 24)) + [27])
 @pytest.mark.parametrize("Dh", [640, 704])
 def test_ring_shapes_reach_their_steady_state_loop(variant, Dh):
     # the direct-to-LDS shapes run prologue + drain only while Dh < 7 stages of 32: here 20 and 22 stages
@@ -369,3 +369,33 @@ def test_expected_row_count_with_sampling_and_entropy_partials():
         assert np.allclose(outs[0][0], outs[1][0], rtol=0, atol=1e-5, equal_nan=True)
         assert np.allclose(outs[0][0][:50], outs[2][0][:50], rtol=0, atol=1e-5)
         assert not np.isnan(outs[2][0][:70]).any() and np.isnan(outs[2][0][70:]).all()
+
+
+@pytest.mark.parametrize("M,cus,V", [(70, 8, 2600), (100, 8, 2400), (128, 4, 1500), (150, 8, 2561), (192, 8, 2300), (230, 8, 2500),
+                                     (256, 6, 2047), (96, 8, 2305)])
+def test_half_height_tail_launch(M, cus, V):
+    """A vocabulary whose tile count leaves the last round of workgroups at most half full is covered by two launches:
+    full-height tiles, then half-height ones for the tail.  The assumed CU count is lowered so that a small problem
+    takes that path (e.g. 2600 rows = 11 tiles of 256 on 8 'CUs': 8 full tiles + 5 half tiles, the last one ragged);
+    every output against the oracle, with a forbidden token in the tail and targets on both sides of the seam."""
+    Dh = 128
+    h, w = rnd(1300 + M, (M, Dh)), rnd(1301 + M, (V, Dh), Dh ** -0.25)
+    tgt = np.random.default_rng(M).integers(0, V, size=M).astype(np.int32)
+    tgt[:4] = [0, V - 2, (V // 256 // cus * cus) * 256 - 1, min(V - 2, (V // 256 // cus * cus) * 256)]   # around the seam
+    ref = oracle.lmhead(h, w, forbid_token=V - 1, target=tgt)
+    dlm.set_option("lmhead_cus", cus)
+    try:
+        got = run_lm(h, w, forbid=V - 1, target=tgt)
+        compare(got, ref)
+        # device-side row count below the bound, and the two-shape queue on top of the two-launch tail
+        m_dev = max(1, M - 37)
+        got = run_lm(h, w, forbid=V - 1, m_dev=m_dev, M_expected=max(1, int(0.8 * M)))
+        compare_prefix(got, ref, m_dev)
+    finally:
+        dlm.set_option("lmhead_cus", 0)
+    # and with the tail rule switched off the same values up to summation order
+    dlm.set_option("lmhead_cus", -1)
+    try:
+        compare(run_lm(h, w, forbid=V - 1, target=tgt), ref)
+    finally:
+        dlm.set_option("lmhead_cus", 0)
