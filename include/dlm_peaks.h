@@ -26,8 +26,13 @@ int dlm_peak_read(const void *src, size_t bytes, int nt, uint32_t *sink, void *s
 
 /* n_wg workgroups of 4 wavefronts, each wavefront issuing iters * 8 independent 32x32x16 bf16 MFMAs on
  * register operands (no memory traffic in the loop); sink receives one float per wavefront (n_wg * 4 floats).
- * FLOP = n_wg * 4 * iters * 8 * 32768.  The ceiling of any bf16 contraction on this clock and power budget. */
-int dlm_peak_mfma(int n_wg, int iters, float *sink, void *stream);
+ * FLOP = n_wg * 4 * iters * 8 * 32768; iters must be a multiple of 8.
+ * operands == NULL: small constant operands (few bits toggle: the clock stays high; the silicon's ceiling).
+ * operands != NULL: 16 * 64 * 16 bytes of bf16 values (e.g. N(0,1) draws), from which every lane takes eight
+ *   different A and eight different B fragments, so consecutive MFMAs see different random operands: what the
+ *   MFMA pipes sustain on realistic data, where the power limit lowers the clock.  This, not the nominal peak,
+ *   bounds any bf16 contraction on such data. */
+int dlm_peak_mfma(int n_wg, int iters, const void *operands, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -64,6 +64,8 @@ template <int D, int NWR, int NWK, int RTW, bool BC, int PF = 1, int OCC = 1, bo
 __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p) {
     static_assert(NWR == 1 || NWK <= 2, "row-split workgroups have at most two key groups");
     constexpr int NT = 64 * NWR * NWK;
+    constexpr int FD = (OCC >= 3 || (NWR == 1 && OCC == 2)) ? 2 : 4;  // operand fragments in flight from LDS ahead of the MFMA that uses them (registers permitting)
+    static_assert(D / 16 >= FD && 2 * (D / 32) >= FD, "fragment ring deeper than the step count");
     constexpr int KP = D * 2 + 16;          // K tile row pitch (bytes): 16-byte reads of 16 rows hit distinct banks
     constexpr int VP = D * 2 + 64;          // V tile row pitch: 4 rows x 64 B of a transposing read tile the 64 banks
     constexpr int TILE_BYTES = 32 * KP + 32 * VP;
@@ -78,8 +80,11 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     constexpr int SMEM = (NBUF * NWK * TILE_BYTES > MERGE_BYTES) ? NBUF * NWK * TILE_BYTES : MERGE_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int wr = w % NWR, wk = w / NWR;
+    const int tid = threadIdx.x, lane = tid & 63;
+    // wave-uniform by construction: kept in scalar registers so that the per-tile bookkeeping derived from the key
+    // group index stays scalar too
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = w % NWR, wk = (NWK == 1) ? 0 : w / NWR;
     const int n = lane & 31, hi = lane >> 5;
     int b = blockIdx.z, kvh = blockIdx.y, bx = blockIdx.x;
     if (p.remap.nx > 0) {
@@ -316,11 +321,19 @@ _Pragma("unroll") \
         for (int rt = 0; rt < RTW; ++rt) \
 _Pragma("unroll") \
             for (int i = 0; i < 16; ++i) S[rt][i] = 0.f; \
+        /* K fragments are requested FD MFMA steps ahead of their use, so that the LDS round trip of one fragment \
+           is covered by the MFMAs of the steps before it instead of sitting between two dependent MFMAs */ \
+        { \
+            bf16x8 kfr[FD]; \
 _Pragma("unroll") \
-        for (int c = 0; c < D / 16; ++c) { \
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Kl + n * KP + (16 * c + 8 * hi) * 2); \
+            for (int c = 0; c < FD; ++c) kfr[c] = *reinterpret_cast<const bf16x8*>(Kl + n * KP + (16 * c + 8 * hi) * 2); \
 _Pragma("unroll") \
-            for (int rt = 0; rt < RTW; ++rt) S[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rt][c], S[rt], 0, 0, 0); \
+            for (int c = 0; c < D / 16; ++c) { \
+_Pragma("unroll") \
+                for (int rt = 0; rt < RTW; ++rt) S[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[c % FD], qf[rt][c], S[rt], 0, 0, 0); \
+                if (c + FD < D / 16) kfr[c % FD] = *reinterpret_cast<const bf16x8*>(Kl + n * KP + (16 * (c + FD) + 8 * hi) * 2); \
+                __builtin_amdgcn_sched_barrier(0); \
+            } \
         } \
         ATTN_TILE(t, sg, lt, slen) \
         const int spos0 = ((sg == 0) ? sp0 : ((sg == 1) ? sp1 : sp2)) + lt * 32; \
@@ -380,20 +393,27 @@ _Pragma("unroll") \
             pf[rt][1] = as_bf16x8(hi4); \
         } \
         const int s16 = lane & 15, blk = (lane >> 4) & 1; \
+        /* step e = 2 * dt + j2 of the second product; its V^T fragment (two transposing reads) is requested FD steps ahead */ \
+        { \
+            union VFrag { s16x4 h[2]; bf16x8 v; }; \
+            VFrag vfr[FD]; \
+            const unsigned char* vbase = Vl + (4 * hi + (s16 >> 2)) * VP + (16 * blk + 4 * (s16 & 3)) * 2; \
 _Pragma("unroll") \
-        for (int dt = 0; dt < D / 32; ++dt) { \
+            for (int e = 0; e < FD; ++e) \
 _Pragma("unroll") \
-            for (int j2 = 0; j2 < 2; ++j2) { \
-                union { s16x4 h[2]; bf16x8 v; } vf; \
+                for (int q = 0; q < 2; ++q) \
+                    vfr[e].h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vbase + (16 * (e & 1) + 8 * q) * VP + 32 * (e >> 1) * 2)); \
 _Pragma("unroll") \
-                for (int q = 0; q < 2; ++q) { \
-                    const int krow = 16 * j2 + 8 * q + 4 * hi + (s16 >> 2); \
-                    const int dcol = 32 * dt + 16 * blk + 4 * (s16 & 3); \
-                    vf.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Vl + krow * VP + dcol * 2)); \
-                } \
+            for (int e = 0; e < 2 * (D / 32); ++e) { \
 _Pragma("unroll") \
                 for (int rt = 0; rt < RTW; ++rt) \
-                    O[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.v, pf[rt][j2], O[rt][dt], 0, 0, 0); \
+                    O[rt][e >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[e % FD].v, pf[rt][e & 1], O[rt][e >> 1], 0, 0, 0); \
+                if (e + FD < 2 * (D / 32)) { \
+_Pragma("unroll") \
+                    for (int q = 0; q < 2; ++q) \
+                        vfr[e % FD].h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vbase + (16 * ((e + FD) & 1) + 8 * q) * VP + 32 * ((e + FD) >> 1) * 2)); \
+                } \
+                __builtin_amdgcn_sched_barrier(0); \
             } \
         } \
     }

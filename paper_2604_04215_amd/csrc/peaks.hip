@@ -36,22 +36,37 @@ __global__ __launch_bounds__(256) void read_kernel(const u32x4* __restrict__ src
     if (threadIdx.x == (x & 255u)) sink[blockIdx.x] = x;
 }
 
-__global__ __launch_bounds__(256) void mfma_kernel(int iters, float* __restrict__ sink) {
+__global__ __launch_bounds__(256) void mfma_kernel(int iters, const u32x4* __restrict__ operands, float* __restrict__ sink) {
     const int lane = threadIdx.x & 63;
-    bf16x8 a, b;
+    bf16x8 a[8], b[8];
+    if (operands) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        a[i] = (__bf16)(0.001f * (float)((lane + i) & 7));
-        b[i] = (__bf16)(0.002f * (float)((lane * 3 + i) & 7));
+        for (int k = 0; k < 8; ++k) {
+            union { u32x4 u; bf16x8 v; } x, y;
+            x.u = operands[(2 * k) * 64 + lane];
+            y.u = operands[(2 * k + 1) * 64 + lane];
+            a[k] = x.v;
+            b[k] = y.v;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                a[k][i] = (__bf16)(0.001f * (float)((lane + i + k) & 7));
+                b[k][i] = (__bf16)(0.002f * (float)((lane * 3 + i + k) & 7));
+            }
     }
     f32x16 acc[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[k][i] = 0.f;
-    for (int it = 0; it < iters; ++it) {
+    for (int it = 0; it < iters; it += 8) {      // iters is a multiple of 8: every register index below is a constant
 #pragma unroll
-        for (int k = 0; k < 8; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[k], b[(k + u) & 7], acc[k], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
@@ -93,8 +108,8 @@ extern "C" int dlm_peak_read(const void* src, size_t bytes, int nt, uint32_t* si
     return launched();
 }
 
-extern "C" int dlm_peak_mfma(int n_wg, int iters, float* sink, void* stream) {
-    if (n_wg <= 0 || iters <= 0 || !sink) return -1;
-    hipLaunchKernelGGL(mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, (hipStream_t)stream, iters, sink);
+extern "C" int dlm_peak_mfma(int n_wg, int iters, const void* operands, float* sink, void* stream) {
+    if (n_wg <= 0 || iters <= 0 || iters % 8 || !sink || (operands && !ok16(operands))) return -1;
+    hipLaunchKernelGGL(mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, (hipStream_t)stream, iters, (const u32x4*)operands, sink);
     return launched();
 }
