@@ -60,11 +60,16 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
 
 // NTKV: K/V are fetched with non-temporal loads, for launches in which one workgroup is the only reader of its
 // (sequence, KV head): the rollout step streams 70 - 1000 MB of cache that nothing reads twice.
-template <int D, int NWR, int NWK, int RTW, bool BC, int PF = 1, int OCC = 1, bool NTKV = false>
+// SWP: software-pipelined form of the 128-row shapes.  MFMA and vector-ALU instructions of DIFFERENT wavefronts of a
+// SIMD do not run side by side on this chip (a wavefront of MFMAs beside a wavefront of exponentials takes the sum of
+// their times: measured), those of ONE wavefront do; so each wavefront weaves the softmax of tile t between the score
+// MFMAs of tile t + 1 and between the first P V MFMAs of tile t, instead of running the three phases one after another.
+template <int D, int NWR, int NWK, int RTW, bool BC, int PF = 1, int OCC = 1, bool NTKV = false, bool SWP = false>
 __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p) {
+    static_assert(!SWP || (RTW == 1 && NWK == 1 && NWR > 1 && D == 128 && PF == 1), "the pipelined form exists for 128-row workgroups, d = 128");
     static_assert(NWR == 1 || NWK <= 2, "row-split workgroups have at most two key groups");
     constexpr int NT = 64 * NWR * NWK;
-    constexpr int FD = (OCC >= 3 || (NWR == 1 && OCC == 2)) ? 2 : 4;  // operand fragments in flight from LDS ahead of the MFMA that uses them (registers permitting)
+    constexpr int FD = (SWP || OCC >= 3 || (NWR == 1 && OCC == 2)) ? 2 : 4;  // operand fragments in flight from LDS ahead of the MFMA that uses them (registers permitting)
     static_assert(D / 16 >= FD && 2 * (D / 32) >= FD, "fragment ring deeper than the step count");
     constexpr int KP = D * 2 + 16;          // K tile row pitch (bytes): 16-byte reads of 16 rows hit distinct banks
     constexpr int VP = D * 2 + 64;          // V tile row pitch: 4 rows x 64 B of a transposing read tile the 64 banks
@@ -76,7 +81,7 @@ __global__ __launch_bounds__(64 * NWR * NWK, OCC) void attn_kernel(AttnParams p)
     // groups (NWR > 1, NWK == 2) passes the second group's partial through it
     constexpr int MERGE_BYTES = (NWK > 1) ? (NWR > 1 ? NWR : NWK) * 32 * MP * 4 : 0;
     constexpr bool DB = (NWR > 1) || (NWK == 1);   // row-split shapes double-buffer the K/V tile their NWR wavefronts share: one barrier per tile
-    constexpr int NBUF = DB ? 2 : 1;
+    constexpr int NBUF = SWP ? 3 : (DB ? 2 : 1);   // the pipelined form reads K of tile t + 1 and V of tile t while tile t + 2 is stored
     constexpr int SMEM = (NBUF * NWK * TILE_BYTES > MERGE_BYTES) ? NBUF * NWK * TILE_BYTES : MERGE_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM];
 
@@ -425,6 +430,143 @@ _Pragma("unroll") \
         for (int s = 0; s < PF; ++s)
             if (s < n_it) ATTN_PREFETCH(s, ((s + rot0 >= n_it) ? s + rot0 - n_it : s + rot0) * NWK + wk);
     }
+    if constexpr (SWP) {
+        // Tile i lives in LDS buffer i % 3.  Iteration t first stores tile t + 2 (requested an iteration ago) into the third
+        // buffer and requests tile t + 3; it holds the raw scores of tile t in registers (SC), computes those of tile t + 1
+        // (SN) from buffer (t + 1) % 3 while turning SC into probabilities, and multiplies them with V of tile t from
+        // buffer t % 3.  One barrier per iteration.
+#define ATTN_SWP_MASK(SC, tt)                                                                            \
+    {                                                                                                    \
+        ATTN_TILE(tt, sg, lt, slen)                                                                      \
+        const int spos0 = ((sg == 0) ? sp0 : ((sg == 1) ? sp1 : sp2)) + lt * 32;                         \
+        const int hoff = (sg == 0) ? ho0 : ((sg == 1) ? ho1 : ho2);                                      \
+        const bool same = (sg == 0) ? same0 : ((sg == 1) ? same1 : same2);                               \
+        const bool ragged = (lt * 32 + 32 > slen) ||                                                     \
+                            (BC && (spos0 + 31 >= qlim_min - hoff || (same && spos0 < qlim_max - p.bs))); \
+        if (ragged) {                                                                                    \
+            const int pbase = spos0 + 4 * hi;                                                            \
+            int hi_r = spos0 - lt * 32 + slen;                                                           \
+            int lo_r = -(1 << 30);                                                                       \
+            if (BC) {                                                                                    \
+                hi_r = min(hi_r, qlim[0] - hoff);                                                        \
+                if (same) lo_r = qlim[0] - p.bs;                                                         \
+            }                                                                                            \
+            const unsigned span = (unsigned)max(hi_r - lo_r, 0);                                         \
+            const unsigned off0 = (unsigned)(pbase - lo_r);                                              \
+            _Pragma("unroll") for (int i = 0; i < 16; ++i)                                               \
+                if (off0 + (unsigned)(8 * (i >> 2) + (i & 3)) >= span) SC[i] = -INFINITY;                \
+        }                                                                                                \
+    }
+#define ATTN_SWP_PAIR(SC, j)                                                                             \
+    {                                                                                                    \
+        const float p0_ = fast_exp2(fmaf(SC[2 * (j)], p.scale_log2, -m_use));                            \
+        const float p1_ = fast_exp2(fmaf(SC[2 * (j) + 1], p.scale_log2, -m_use));                        \
+        rs += p0_ + p1_;                                                                                 \
+        pk[j] = pack_bf16x2(p0_, p1_);                                                                   \
+    }
+#define ATTN_SWP_ITER(SC, SN, tt)                                                                        \
+    {                                                                                                    \
+        const int t = (tt);                                                                              \
+        /* tile t + 2, requested an iteration ago, goes into the buffer that tile t - 1 has left; tile t + 3 is requested \
+           right away, so that it has this whole iteration to arrive */                                  \
+        ATTN_STORE(0, t + 2, (t + 2) % 3);                                                               \
+        ATTN_PREFETCH(0, t + 3);                                                                         \
+        ATTN_SWP_MASK(SC, t)                                                                             \
+        const unsigned char* Kn = smem + ((t + 1) % 3) * TILE_BYTES + n * KP + 16 * hi;                  \
+        const unsigned char* Vc = smem + (t % 3) * TILE_BYTES + 32 * KP + (4 * hi + ((lane & 15) >> 2)) * VP + \
+                                  (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;                         \
+        float mx = -INFINITY, m_new = 0.f, m_use = 0.f, alpha = 1.f, rs = 0.f;                           \
+        bool grow = false;                                                                               \
+        uint32_t pk[8];                                                                                  \
+        /* ---- scores of tile t + 1 between the softmax pieces of tile t ---- */                        \
+        /* The (rare) rescaling of the accumulators is a branch; it sits right behind the two steps that decide it, so  \
+           that everything after it, the exponentials and both MFMA chains, is one straight block the scheduler keeps   \
+           in the written order (code before a branch whose results are only used after it would be sunk past it). */   \
+        bf16x8 kfr[FD];                                                                                  \
+        _Pragma("unroll") for (int c = 0; c < FD; ++c) kfr[c] = *reinterpret_cast<const bf16x8*>(Kn + 32 * c); \
+        _Pragma("unroll") for (int c = 0; c < 2; ++c) {                                                  \
+            if (c == 0) { const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}; \
+                          SN = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[0], qf[0][0], z_, 0, 0, 0); } \
+            else SN = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[c % FD], qf[0][c], SN, 0, 0, 0);       \
+            kfr[c % FD] = *reinterpret_cast<const bf16x8*>(Kn + 32 * (c + FD));                          \
+            if (c == 0) {                                                                                \
+                _Pragma("unroll") for (int i = 0; i < 16; i += 2) mx = __builtin_fmaxf(__builtin_fmaxf(mx, SC[i]), SC[i + 1]); \
+            } else {                                                                                     \
+                const auto sw_ = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false); \
+                mx = __builtin_fmaxf(__uint_as_float(sw_[0]), __uint_as_float(sw_[1])) * p.scale_log2;   \
+                grow = mx > m_run[0] + 8.0f;                                                             \
+                m_new = grow ? mx : m_run[0];                                                            \
+                m_use = (m_new == -INFINITY) ? 0.f : m_new;                                              \
+                alpha = grow ? fast_exp2(m_run[0] - m_use) : 1.0f;                                       \
+            }                                                                                            \
+            __builtin_amdgcn_sched_barrier(0);                                                           \
+        }                                                                                                \
+        if (__any(grow && m_run[0] != -INFINITY)) {                                                      \
+            _Pragma("unroll") for (int dt = 0; dt < 4; ++dt)                                             \
+                _Pragma("unroll") for (int i = 0; i < 16; ++i) O[0][dt][i] *= alpha;                     \
+        }                                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                               \
+        _Pragma("unroll") for (int c = 2; c < 8; ++c) {                                                  \
+            SN = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[c % FD], qf[0][c], SN, 0, 0, 0);            \
+            if (c + FD < 8) kfr[c % FD] = *reinterpret_cast<const bf16x8*>(Kn + 32 * (c + FD));          \
+            ATTN_SWP_PAIR(SC, c - 2)                                                                     \
+            __builtin_amdgcn_sched_barrier(0);                                                           \
+        }                                                                                                \
+        /* ---- P V of tile t: the keys 0..15 half first, while the last probabilities of the other half are formed ---- */ \
+        {                                                                                                \
+            union VFrag { s16x4 h[2]; bf16x8 v; };                                                       \
+            VFrag vfr[FD];                                                                               \
+            _Pragma("unroll") for (int e = 0; e < FD; ++e)                                               \
+                _Pragma("unroll") for (int q = 0; q < 2; ++q)                                            \
+                    vfr[e].h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Vc + (16 * (e >> 2) + 8 * q) * VP + 32 * (e & 3) * 2)); \
+            bf16x8 pf0, pf1;                                                                             \
+            { const u32x4 lo_ = {pk[0], pk[1], pk[2], pk[3]}; pf0 = as_bf16x8(lo_); }                    \
+            _Pragma("unroll") for (int e = 0; e < 8; ++e) {                                              \
+                if (e == 4) { const u32x4 hi_ = {pk[4], pk[5], pk[6], pk[7]}; pf1 = as_bf16x8(hi_); }    \
+                O[0][e & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[e % FD].v, (e < 4) ? pf0 : pf1, O[0][e & 3], 0, 0, 0); \
+                if (e + FD < 8) {                                                                        \
+                    _Pragma("unroll") for (int q = 0; q < 2; ++q)                                        \
+                        vfr[e % FD].h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Vc + (16 * ((e + FD) >> 2) + 8 * q) * VP + 32 * ((e + FD) & 3) * 2)); \
+                }                                                                                        \
+                if (e == 0) { ATTN_SWP_PAIR(SC, 6) }                                                     \
+                else if (e == 1) { ATTN_SWP_PAIR(SC, 7) }                                                \
+                else if (e == 2) { l_run[0] = l_run[0] * alpha + rs; m_run[0] = m_new; }                 \
+                __builtin_amdgcn_sched_barrier(0);                                                       \
+            }                                                                                            \
+        }                                                                                                \
+        __syncthreads();                                                                                 \
+    }
+        f32x16 SA, SB;
+        if (n_it > 0) {
+            // Everything requested so far (Q, tile 0) is needed now; an explicit full wait leaves the compiler's
+            // load-counter bookkeeping with nothing pending from before the loop, so that its waits inside the loop
+            // count only the loop's own requests.
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            ATTN_STORE(0, 0, 0);
+            ATTN_PREFETCH(0, 1);
+            __syncthreads();
+            {   // scores of tile 0, not overlapped with anything
+                const unsigned char* K0 = smem + n * KP + 16 * hi;
+                const f32x16 z_ = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                SA = z_;
+#pragma unroll
+                for (int c = 0; c < 8; ++c)
+                    SA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(K0 + 32 * c), qf[0][c], SA, 0, 0, 0);
+            }
+            ATTN_STORE(0, 1, 1);
+            ATTN_PREFETCH(0, 2);
+            __syncthreads();
+        }
+        int it = 0;
+        for (; it + 1 < n_it; it += 2) {
+            ATTN_SWP_ITER(SA, SB, it);
+            ATTN_SWP_ITER(SB, SA, it + 1);
+        }
+        if (it < n_it) ATTN_SWP_ITER(SA, SB, it);
+#undef ATTN_SWP_ITER
+#undef ATTN_SWP_PAIR
+#undef ATTN_SWP_MASK
+    } else
     if (DB) {
         // iteration `i` multiplies this key group's tile i * NWK + wk from LDS buffer i & 1 while the tile of iteration
         // i + 1 is stored into the other buffer and the one of iteration i + 1 + PF is requested into the register slot
@@ -810,6 +952,22 @@ static int launch_attn(const AttnParams& p, hipStream_t st) {
         else hipLaunchKernelGGL((attn_kernel<D, 4, 2, 1, BC, 2, 1>), grid, dim3(512), 0, st, q);
         return check_hip(hipGetLastError(), "attn_kernel launch");
     }
+    if (variant == 15) {
+        // the software-pipelined 128-row shape (d = 128 only), two workgroups per CU
+        if constexpr (D == 128) {
+            dim3 grid((p.R + 127) / 128 * ns, p.Hkv, p.B);
+            AttnParams q = p;
+            if ((g_attn_remap & 1) && grid.x >= 2) {
+                const int64_t n_wg = set_remap(q.remap, BH, (int)grid.x, BC && (g_attn_remap & 2));
+                if (n_wg > 0) grid = dim3((unsigned)n_wg);
+                else q = p;
+            }
+            hipLaunchKernelGGL((attn_kernel<D, 4, 1, 1, BC, 1, 2, false, true>), grid, dim3(256), 0, st, q);
+            return check_hip(hipGetLastError(), "attn_kernel launch");
+        } else {
+            variant = 4;
+        }
+    }
     if (variant >= 8) variant = 0 + 4;
     if (variant >= 4) {   // 128-row workgroups, several resident per CU
         dim3 grid((p.R + 127) / 128 * ns, p.Hkv, p.B);
@@ -898,7 +1056,7 @@ using namespace dlm;
 extern "C" int dlm_set_option(const char* name, int value) {
     if (!name) return fail(DLM_ERR_INVALID_ARG, "set_option: null name");
     if (!strcmp(name, "attn_variant")) {
-        if (value < 0 || value > 14) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..14");
+        if (value < 0 || value > 15) return fail(DLM_ERR_INVALID_ARG, "set_option: attn_variant must be 0..15");
         g_attn_variant = value;
         return DLM_OK;
     }

@@ -70,7 +70,7 @@ def test_rollout_shape_mha(variant):
     run_case(B=2, Lq=32, Hq=4, Hkv=4, d=128, P=200, Lb=32, S=0, variant=variant, seed=1)
 
 
-@pytest.mark.parametrize("variant", [0, 2, 3, 4, 5, 6, 7, 11, 13, 14])
+@pytest.mark.parametrize("variant", [0, 2, 3, 4, 5, 6, 7, 11, 13, 14, 15])
 def test_dual_cache_and_gqa7(variant):
     # 7 query heads per KV head (224 packed rows), prefix | block | suffix, ragged suffix
     run_case(B=2, Lq=32, Hq=14, Hkv=2, d=128, P=96, Lb=32, S=45, variant=variant, seed=2)
@@ -82,14 +82,14 @@ def test_shapes(d, Lq, Hq, Hkv):
     run_case(B=2, Lq=Lq, Hq=Hq, Hkv=Hkv, d=d, P=77, Lb=Lq, S=9, seed=3 + Lq)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 6, 12, 13, 14])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 6, 12, 13, 14, 15])
 @pytest.mark.parametrize("bs", [1, 4, 32])
 def test_block_causal_rollout(variant, bs):
     # last block(s) of a block-diffusion sequence against the cache; positions are absolute
     run_case(B=2, Lq=8, Hq=8, Hkv=2, d=128, P=188, Lb=8, S=0, mode="block_causal", bs=bs, variant=variant, seed=5)
 
 
-@pytest.mark.parametrize("variant", [0, 2, 3, 4, 6, 13, 14])
+@pytest.mark.parametrize("variant", [0, 2, 3, 4, 6, 13, 14, 15])
 def test_block_causal_full_sequence(variant):
     # training-style pass: Lq = Lk, bidirectional inside blocks of 4, causal across blocks
     B, L, Hq, Hkv, d = 2, 204, 4, 2, 128
@@ -185,7 +185,7 @@ def test_non_temporal_kv_stream_changes_nothing():
 
 
 @pytest.mark.parametrize("B,Hkv,g,Lq", [(1, 1, 2, 300), (1, 3, 4, 130), (2, 2, 1, 700), (4, 2, 2, 129), (3, 4, 2, 257)])
-@pytest.mark.parametrize("variant", [4, 6, 11, 13])
+@pytest.mark.parametrize("variant", [4, 6, 11, 13, 15])
 def test_xcd_grouped_grid_covers_every_tile_once(B, Hkv, g, Lq, variant):
     """Group counts 1, 3, 4, 8, 12 (tiles of a group dealt to 8, 8, 2, 1, 2 XCDs) and ragged tile counts, both masks:
     the 1-D grid must produce what the plain (tile, KV head, sequence) grid does, bit for bit, and the oracle's result."""
@@ -232,7 +232,7 @@ def test_sequences_flagged_inactive_are_skipped(Lq, Hq, Hkv, variant):
     assert bool((out[~torch.from_numpy(on).to(DEV)] == 7.0).all()) and bool((lse[~torch.from_numpy(on).to(DEV)] == -3.0).all())
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 12, 13, 14])
+@pytest.mark.parametrize("variant", [0, 1, 2, 12, 13, 14, 15])
 def test_planted_one_hot_values_expose_every_key(variant):
     """V[j] = e_(j mod d): output channel c is the total probability of keys j = c (mod d), so a
     dropped, duplicated or misplaced key shifts some channel by a large relative amount; with Q = 0
@@ -296,7 +296,7 @@ def test_key_split_rollout_shape(variant, split):
     run_case(B=3, Lq=16, Hq=4, Hkv=2, d=64, P=1000, Lb=16, S=0, variant=variant, seed=42, split=split)
 
 
-@pytest.mark.parametrize("variant", [0, 2, 3, 4, 6, 11, 13, 14])
+@pytest.mark.parametrize("variant", [0, 2, 3, 4, 6, 11, 13, 14, 15])
 @pytest.mark.parametrize("split", [2, 3])
 def test_key_split_row_tile_shapes(variant, split):
     """128- / 256-row workgroups (7 heads per KV head x 32 rows = 224 rows, two ragged row tiles) with the keys split
@@ -372,7 +372,7 @@ def test_key_split_is_deterministic_and_skips_inactive_sequences():
         dlm.set_option("attn_split", 0)
 
 
-@pytest.mark.parametrize("variant", [13, 14])
+@pytest.mark.parametrize("variant", [13, 14, 15])
 def test_two_key_groups_per_workgroup_edge_cases(variant):
     """128-row workgroups whose eight wavefronts form two key groups: odd tile counts (the second group's last tile
     does not exist), a single tile, ragged per-sequence prefixes down to none, d = 64, rows that see nothing."""
