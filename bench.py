@@ -494,54 +494,48 @@ def main():
     kernels, roof, sample_info = {}, None, None
     if args.sample_steps > 0:
         import paper_2604_04215_amd.rollout as ro_mod
-        orig = {n: getattr(dlm, n) for n in ("block_attn", "lmhead_confidence", "unmask_commit", "kv_refresh")}
-        ev = {n: [] for n in orig}
+        orig_refresh = dlm.kv_refresh
+        ev = {n: [] for n in ("block_attn", "lmhead_confidence", "unmask_commit", "kv_refresh")}
         cap = args.sample_steps + 8 * cfg.n_blocks * (args.sample_steps // max(1, rollout_steps) + 2) + 64
         rem_hist = torch.zeros((cap, cfg.B), dtype=torch.int32, device=dev)   # per-sequence still-masked counts after each step
         n_commit_calls = [0]
 
-        def bracket(name, meta_fn):
-            fn = orig[name]
+        def on_call(name, fn, a, sp, meta):
+            """stands in for one library call of a step: the same call between two events on the launch stream"""
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            st = torch.cuda.current_stream()
+            a0.record(st)
+            rc = fn(C.byref(a), sp)
+            a1.record(st)
+            if name == "block_attn":
+                meta = dict(first=meta["first"], Lk=a.prefix.len + a.block.len + a.suffix.len, prev=n_commit_calls[0] - 1)
+            elif name == "unmask_commit":
+                i = n_commit_calls[0]
+                n_commit_calls[0] += 1
+                rem_hist[i].copy_(meta["remaining"])       # after the bracketed call: the counts of this step
+                meta = dict(idx=i, first=meta["first"])
+            ev[name].append((a0, a1, meta))
+            return rc
 
-            def wrapped(*a, **kw):
-                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                st = torch.cuda.current_stream()
-                a0.record(st)
-                fn(*a, **kw)
-                a1.record(st)
-                ev[name].append((a0, a1, meta_fn(a, kw)))
-            return wrapped
-
-        def attn_meta(a, kw):
-            Lk = sum(t[0].shape[2] for t in (kw.get("prefix"), kw.get("block"), kw.get("suffix")) if t is not None)
-            return dict(first=kw.get("seq_active") is None, Lk=Lk, prev=n_commit_calls[0] - 1)
-
-        def commit_meta(a, kw):
-            i = n_commit_calls[0]
-            n_commit_calls[0] += 1
-            return dict(idx=i, first=kw.get("active_in") is None)
-
-        def refresh_meta(a, kw):
+        def refresh_timed(*a, **kw):
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            st = torch.cuda.current_stream()
+            a0.record(st)
+            orig_refresh(*a, **kw)
+            a1.record(st)
             src = a[0]
-            return dict(bytes=2 * 2 * src.shape[0] * src.shape[1] * src.shape[2] * src.shape[3] * 2)
+            ev["kv_refresh"].append((a0, a1, dict(bytes=2 * 2 * src.shape[0] * src.shape[1] * src.shape[2] * src.shape[3] * 2)))
 
-        def commit_wrapped(*a, **kw):
-            inner(*a, **kw)
-            rem_hist[n_commit_calls[0] - 1].copy_(a[5])        # after the bracketed call: the counts of this step
-
-        inner = bracket("unmask_commit", commit_meta)
-        dlm.block_attn = bracket("block_attn", attn_meta)
-        dlm.lmhead_confidence = bracket("lmhead_confidence", lambda a, kw: None)
-        dlm.unmask_commit = commit_wrapped
-        dlm.kv_refresh = bracket("kv_refresh", refresh_meta)
+        g.on_call = on_call
+        dlm.kv_refresh = refresh_timed
         assert ro_mod.dlm is dlm
         log0 = len(runner.log)
         try:
             runner.run(args.sample_steps)
             torch.cuda.synchronize()
         finally:
-            for n, f in orig.items():
-                setattr(dlm, n, f)
+            g.on_call = None
+            dlm.kv_refresh = orig_refresh
         log = runner.log[log0:]
         # the runner polls every step it queued except possibly the last one or two of an unfinished block
         n_steps = min(len(log), len(ev["lmhead_confidence"]))

@@ -353,16 +353,22 @@ def lmhead_workspace_bytes(M: int, V: int, sample: bool = False, conf_mode: int 
     return int(lib().dlm_lmhead_workspace_bytes(C.byref(a)))
 
 
-def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=None, m_dev=None,
-                      inv_temperature: float = 1.0, forbid_token: int = -1, out_scatter: bool = False,
-                      lse=None, zmax=None, z2nd=None, target=None, ztarget=None, workspace=None,
-                      sample_seed: Optional[int] = None, sample_step: int = 0, sample_stream: int = 0,
-                      conf_mode: int = CONF_TOKEN_PROB, M_expected: int = 0, stream=None,
-                      static_scratch: bool = False) -> None:
-    """hidden bf16 [rows, Dh]; w bf16 [V, Dh]; conf fp32 / tok int32 outputs; workspace: a uint8 tensor.
-    sample_seed: None = arg-max token; an integer = Gumbel-max sample with that seed.
-    M_expected: a guess of the row count m_dev holds (0 = none); only the choice of kernel shape depends on it.
+def lmhead_confidence(hidden, w, conf, tok, *, stream=None, static_scratch: bool = False, **kw) -> None:
+    """hidden bf16 [rows, Dh]; w bf16 [V, Dh]; conf fp32 / tok int32 outputs.  Keywords: M, row_idx, m_dev,
+    inv_temperature, forbid_token, out_scatter, lse, zmax, z2nd, target, ztarget, workspace (a uint8 tensor),
+    sample_seed (None = arg-max token; an integer = Gumbel-max sample with that seed), sample_step, sample_stream,
+    conf_mode, M_expected (a guess of the row count m_dev holds, 0 = none; only the choice of kernel shape depends on it).
     static_scratch: call dlm_lmhead_confidence_static (the library's built-in scratch; no workspace tensor)."""
+    a = _lmhead_args(hidden, w, conf, tok, **kw)
+    fn = lib().dlm_lmhead_confidence_static if static_scratch else lib().dlm_lmhead_confidence
+    _check(fn(C.byref(a), _stream(stream)))
+
+
+def _lmhead_args(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=None, m_dev=None,
+                 inv_temperature: float = 1.0, forbid_token: int = -1, out_scatter: bool = False,
+                 lse=None, zmax=None, z2nd=None, target=None, ztarget=None, workspace=None,
+                 sample_seed: Optional[int] = None, sample_step: int = 0, sample_stream: int = 0,
+                 conf_mode: int = CONF_TOKEN_PROB, M_expected: int = 0) -> LmheadArgs:
     import torch
     a = LmheadArgs()
     a.struct_size = C.sizeof(LmheadArgs)
@@ -389,17 +395,23 @@ def lmhead_confidence(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=
     if sample_seed is not None:
         a.sample, a.sample_seed = 1, int(sample_seed) & 0xFFFFFFFFFFFFFFFF
         a.sample_step, a.sample_stream = int(sample_step) & 0xFFFFFFFF, int(sample_stream) & 0xFFFFFFFF
-    fn = lib().dlm_lmhead_confidence_static if static_scratch else lib().dlm_lmhead_confidence
-    _check(fn(C.byref(a), _stream(stream)))
+    return a
 
 
-def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group_len: Optional[int] = None,
-                  rule: int = RULE_THRESHOLD, threshold: float = 0.0, force_top1: bool = True, k: int = 0,
-                  commit_now=None, next_row_idx=None, next_m=None, commit_step=None, step: int = 0,
-                  writeback: int = WB_NONE, src_block: Optional[Tuple] = None, cache_k=None, cache_v=None,
-                  cache_pos0: int = 0, host_remaining_total=None, active_in=None, stream=None) -> None:
+def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, stream=None, **kw) -> None:
     """conf fp32 / tok int32 dense [B, n_pos]; x int32 [B, L]; mask uint8 [B, n_pos] (row-strided views are fine).
-    host_remaining_total: optional pinned CPU int32 tensor (1 element) the kernel writes through."""
+    Keywords: x_pos0 (required), group_len, rule, threshold, force_top1, k, commit_now, next_row_idx, next_m, commit_step,
+    step, writeback, src_block, cache_k, cache_v, cache_pos0, active_in, host_remaining_total (optional pinned CPU int32
+    tensor of 1 element the kernel writes through)."""
+    a = _commit_args(conf, tok, x, mask, n_commit, remaining, **kw)
+    _check(lib().dlm_unmask_commit(C.byref(a), _stream(stream)))
+
+
+def _commit_args(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group_len: Optional[int] = None,
+                 rule: int = RULE_THRESHOLD, threshold: float = 0.0, force_top1: bool = True, k: int = 0,
+                 commit_now=None, next_row_idx=None, next_m=None, commit_step=None, step: int = 0,
+                 writeback: int = WB_NONE, src_block: Optional[Tuple] = None, cache_k=None, cache_v=None,
+                 cache_pos0: int = 0, host_remaining_total=None, active_in=None) -> CommitArgs:
     import torch
     a = CommitArgs()
     a.struct_size = C.sizeof(CommitArgs)
@@ -434,7 +446,7 @@ def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group
         if host_remaining_total.is_cuda or not host_remaining_total.is_pinned() or host_remaining_total.dtype != torch.int32:
             raise ValueError("host_remaining_total must be a pinned CPU int32 tensor")
         a.host_remaining_total = host_remaining_total.data_ptr()
-    _check(lib().dlm_unmask_commit(C.byref(a), _stream(stream)))
+    return a
 
 
 def mask_compact(mask, row_idx, m_out, stream=None) -> None:

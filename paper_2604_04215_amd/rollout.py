@@ -14,6 +14,7 @@ step per block.
 """
 from __future__ import annotations
 
+import ctypes as C
 from typing import Callable, Optional
 
 import torch
@@ -32,6 +33,7 @@ class GpuRollout:
         inv_temperature; step s of block b draws with sample_step = (b << 16) | s, so no two steps of a
         rollout share noise, and rollouts of one prompt differ by sample_stream."""
         self.cfg, self.dev = cfg, torch.device(device)
+        self._dev_index = self.dev.index if self.dev.index is not None else torch.cuda.current_device()
         self.sample_seed, self.sample_stream, self.inv_temperature = sample_seed, sample_stream, inv_temperature
         # which score the commit rule ranks: token probability, top-2 margin or negative entropy
         self.conf_mode = {"prob": dlm.CONF_TOKEN_PROB, "margin": dlm.CONF_MARGIN, "neg_entropy": dlm.CONF_NEG_ENTROPY}[confidence]
@@ -60,6 +62,11 @@ class GpuRollout:
         self.commit_step = torch.full((B, Lb), -1, dtype=torch.int16, device=dev) if record_steps else None
         self.workspace = torch.empty(max(16, dlm.lmhead_workspace_bytes(n, cfg.V, sample=sample_seed is not None, conf_mode=self.conf_mode)), dtype=torch.uint8, device=dev)
         self.attn_workspace = None    # sized per block (key split across workgroups)
+        self._a_attn = self._a_lm = self._a_commit = None   # argument structs of a step, filled once per block
+        self._sig = None
+        # optional hook(name, c_function, args_struct, stream_ptr, meta) -> return code, called INSTEAD of the plain
+        # library call of a step (the benchmark's per-call event timing); None: the calls go straight to the library
+        self.on_call = None
         self.total_committed = torch.zeros(1, dtype=torch.int64, device=dev)
         self.block = -1
         self.step_idx = 0
@@ -103,6 +110,7 @@ class GpuRollout:
             self._prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
             self._suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
             self._size_attn_workspace()
+            self._a_attn = None
 
     def queue_poll(self):
         """(event, pinned host word) of the step queued last: after event.synchronize() the word holds the
@@ -146,6 +154,7 @@ class GpuRollout:
         self._prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
         self._suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
         self._size_attn_workspace()
+        self._a_attn = None           # the step's argument structs are rebuilt at the block's first step
 
     def _size_attn_workspace(self) -> None:
         """The attention call may split the keys across workgroups when it is given a workspace; its size depends on
@@ -157,50 +166,97 @@ class GpuRollout:
         if need > (0 if self.attn_workspace is None else self.attn_workspace.numel()):
             self.attn_workspace = torch.empty(need, dtype=torch.uint8, device=self.dev)
 
-    def step(self, q: torch.Tensor, kblk: torch.Tensor, vblk: torch.Tensor, hidden: torch.Tensor) -> None:
-        """Enqueue one denoising step.  q [B, Lb, Hq, d]; kblk, vblk [B, Hkv, Lb, d]; hidden [B, Lb, Dh]."""
+    def _prepare_step(self, q, kblk, vblk, hidden) -> None:
+        """Fill the three argument structs of a denoising step once per block (all validation happens here); the steps
+        of the block then only exchange the pointers and counters that change from step to step."""
         cfg = self.cfg
-        P, Lb, S = self.P, cfg.Lb, self.S
-        ev, host = self._ring[self._ring_pos]
-        self._ring_pos = (self._ring_pos + 1) % len(self._ring)
-        st = torch.cuda.current_stream()     # looked up once per step: the query is a third of the enqueue time
+        P, Lb = self.P, cfg.Lb
+        diag = self.diagnostics
+        self._sig = (q.shape, q.stride(), kblk.shape, kblk.stride(), vblk.stride(), hidden.shape, hidden.stride(), diag)
+        self._a_attn = dlm._attn_args(q, self.O, self._prefix, (kblk, vblk, P), self._suffix,
+                                      mask_mode=_MASKS[cfg.mask_mode], block_size=cfg.bs, q_pos0=P,
+                                      lse=self.lse_attn if diag else None, seq_active=self.remaining,
+                                      workspace=self.attn_workspace)
+        self._a_lm = dlm._lmhead_args(hidden.view(cfg.B * Lb, cfg.Dh), self.w, self.conf, self.tok,
+                                      M=self.m_host, row_idx=self.row_idx, m_dev=self.m_dev,
+                                      forbid_token=cfg.forbid_token, out_scatter=True,
+                                      lse=self.lse if diag else None, zmax=self.zmax if diag else None,
+                                      z2nd=self.z2nd if diag else None, workspace=self.workspace,
+                                      inv_temperature=self.inv_temperature, sample_seed=self.sample_seed,
+                                      sample_step=0, sample_stream=self.sample_stream, conf_mode=self.conf_mode)
+        self._a_commit = dlm._commit_args(self.conf, self.tok, self.x, self.mask, self.n_commit, self.remaining,
+                                          x_pos0=P, rule=_RULES[cfg.rule], threshold=cfg.tau, force_top1=True, k=cfg.k,
+                                          commit_now=self.commit_now, next_row_idx=self.row_idx, next_m=self.m_dev,
+                                          commit_step=self.commit_step, step=0, writeback=dlm.WB_WHILE_ACTIVE,
+                                          active_in=self.remaining, src_block=(kblk, vblk, 0),
+                                          cache_k=self.cache_k, cache_v=self.cache_v, cache_pos0=P,
+                                          host_remaining_total=self._ring[0][1])
+        self._rem_ptr = [r.data_ptr() for r in self._remaining2]
+        self._ring_ptr = [h.data_ptr() for _, h in self._ring]
+        self._lib = dlm.lib()
+
+    def step(self, q: torch.Tensor, kblk: torch.Tensor, vblk: torch.Tensor, hidden: torch.Tensor) -> None:
+        """Enqueue one denoising step.  q [B, Lb, Hq, d]; kblk, vblk [B, Hkv, Lb, d]; hidden [B, Lb, Dh].
+
+        Every step of a block passes tensors of one shape and layout (checked); what differs between steps is a handful
+        of pointers and counters, so the argument structs are filled once per block (_prepare_step) and only those
+        fields are rewritten here: the host side of a step is three foreign calls and an event record."""
+        cfg = self.cfg
+        Lb = cfg.Lb
+        if self._a_attn is None or self._sig != (q.shape, q.stride(), kblk.shape, kblk.stride(), vblk.stride(),
+                                                 hidden.shape, hidden.stride(), self.diagnostics):
+            self._prepare_step(q, kblk, vblk, hidden)
+        for t in (q, kblk, vblk, hidden):
+            if not t.is_cuda or t.dtype != torch.bfloat16:
+                raise ValueError("step inputs must be bf16 tensors on the GPU")
+        pos = self._ring_pos
+        ev, host = self._ring[pos]
+        self._ring_pos = (pos + 1) % len(self._ring)
+        # the raw handle of torch's current stream on this device, looked up once per step (the Stream object that
+        # torch.cuda.current_stream() builds costs several microseconds of Python)
+        sp = C.c_void_p(torch._C._cuda_getCurrentRawStream(self._dev_index))
         if self._exact_rows:
             self.m_host = max(1, cfg.B * max(Lb - cfg.k * self.step_idx, 0))
-        prefix, suffix = self._prefix, self._suffix
-        # from a block's second step on, sequences with nothing left masked after the previous step are skipped:
-        # the LM head reads only masked rows, so nothing would consume their attention output
-        dlm.block_attn(q, self.O, prefix=prefix, block=(kblk, vblk, P), suffix=suffix,
-                       mask_mode=_MASKS[cfg.mask_mode], block_size=cfg.bs, q_pos0=P,
-                       lse=self.lse_attn if self.diagnostics else None,
-                       seq_active=self.remaining if self.step_idx > 0 else None, workspace=self.attn_workspace,
-                       stream=st)
-        diag = self.diagnostics
-        dlm.lmhead_confidence(hidden.view(cfg.B * Lb, cfg.Dh), self.w, self.conf, self.tok,
-                              M=self.m_host, row_idx=self.row_idx, m_dev=self.m_dev,
-                              forbid_token=cfg.forbid_token, out_scatter=True,
-                              lse=self.lse if diag else None, zmax=self.zmax if diag else None,
-                              z2nd=self.z2nd if diag else None, workspace=self.workspace,
-                              inv_temperature=self.inv_temperature, sample_seed=self.sample_seed,
-                              sample_step=(self.block << 16) | self.step_idx, sample_stream=self.sample_stream,
-                              conf_mode=self.conf_mode,
-                              M_expected=0 if (self._exact_rows or not self.late_bound) else int(self.m_host * self.expect_ratio),
-                              stream=st)
-        # Cache write-back of the block's K/V.  First step of a block: a sequence that finishes right away is copied
-        # by a launch of its own.  Later steps: every sequence that was still masked after the previous step is
-        # copied inside the selection's launch (the last such copy is its final step's K/V: the same cache contents,
-        # one launch fewer per step).
-        prev, rem = self.remaining, self._remaining2[self.step_idx & 1]
         first = self.step_idx == 0
-        dlm.unmask_commit(self.conf, self.tok, self.x, self.mask, self.n_commit, rem,
-                          x_pos0=P, rule=_RULES[cfg.rule], threshold=cfg.tau, force_top1=True, k=cfg.k,
-                          commit_now=self.commit_now, next_row_idx=self.row_idx, next_m=self.m_dev,
-                          commit_step=self.commit_step, step=self.step_idx,
-                          writeback=dlm.WB_BLOCK_WHEN_DONE if first else dlm.WB_WHILE_ACTIVE,
-                          active_in=None if first else prev, src_block=(kblk, vblk, 0),
-                          cache_k=self.cache_k, cache_v=self.cache_v, cache_pos0=P,
-                          host_remaining_total=host, stream=st)
-        self.remaining = rem
-        ev.record(st)
+        L = self._lib
+        kp, vp = kblk.data_ptr(), vblk.data_ptr()
+        # 1. attention; from a block's second step on, sequences with nothing left masked after the previous step are
+        #    skipped: the LM head reads only masked rows, so nothing would consume their attention output
+        a = self._a_attn
+        a.q = q.data_ptr()
+        a.block.k, a.block.v = kp, vp
+        idx_prev = 0 if self.remaining is self._remaining2[0] else 1
+        a.seq_active = None if first else self._rem_ptr[idx_prev]
+        hook = self.on_call
+        rc = L.dlm_block_attn(C.byref(a), sp) if hook is None else hook("block_attn", L.dlm_block_attn, a, sp, dict(first=first))
+        if rc:
+            raise dlm.DlmError(rc, dlm.last_error())
+        # 2. LM head on the still-masked rows (count read on the device; the host's bound sizes the launch)
+        a = self._a_lm
+        a.hidden = hidden.data_ptr()
+        a.M = self.m_host
+        a.M_expected = 0 if (self._exact_rows or not self.late_bound) else int(self.m_host * self.expect_ratio)
+        a.sample_step = ((self.block << 16) | self.step_idx) & 0xFFFFFFFF
+        rc = L.dlm_lmhead_confidence(C.byref(a), sp) if hook is None else hook("lmhead_confidence", L.dlm_lmhead_confidence, a, sp, None)
+        if rc:
+            raise dlm.DlmError(rc, dlm.last_error())
+        # 3. selection, commit, compaction and the cache write-back of the block's K/V.  First step of a block: a
+        #    sequence that finishes right away is copied by a launch of its own.  Later steps: every sequence that was
+        #    still masked after the previous step is copied inside the selection's launch (the last such copy is its
+        #    final step's K/V: the same cache contents, one launch fewer per step).
+        idx_new = self.step_idx & 1
+        a = self._a_commit
+        a.remaining = self._rem_ptr[idx_new]
+        a.step = self.step_idx
+        a.writeback = dlm.WB_BLOCK_WHEN_DONE if first else dlm.WB_WHILE_ACTIVE
+        a.active_in = None if first else self._rem_ptr[idx_prev]
+        a.src_block.k, a.src_block.v = kp, vp
+        a.host_remaining_total = self._ring_ptr[pos]
+        rc = L.dlm_unmask_commit(C.byref(a), sp) if hook is None else hook("unmask_commit", L.dlm_unmask_commit, a, sp, dict(first=first, remaining=self._remaining2[idx_new]))
+        if rc:
+            raise dlm.DlmError(rc, dlm.last_error())
+        self.remaining = self._remaining2[idx_new]
+        ev.record()                          # on the current stream
         self._last_poll = (ev, host)
         self.step_idx += 1
 
