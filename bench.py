@@ -37,7 +37,7 @@ RIDGE = MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)     # FLOP per byte at wh
 # HBM bytes per LM-head launch on the default workload, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0, factors calibrated with a 1 GiB copy); summary and commands in
 # profiles/lmhead_c2_rollout_hbm_traffic.md.  Only valid for --config c2 with the default W distribution.
-LMHEAD_C2_TRAFFIC_BYTES = 1097.2e6
+LMHEAD_C2_TRAFFIC_BYTES = 1096.0e6
 
 WORKLOADS = {
     "c1": "c1: tiny single block, B=1, 4 heads MHA, d=64, hidden 256, V=2048, prefix 256, block 32 with 16 masked, "
@@ -144,6 +144,14 @@ def measure_peaks(torch, reps: int = 20) -> dict:
     ops = torch.randn(16 * 64 * 8, device=dev).bfloat16()          # N(0,1) operand fragments
     t = timed(lambda: L.dlm_peak_mfma(n_wg, iters, ops.data_ptr(), fs.data_ptr(), st))
     out["mfma_bf16_tflops_normal_data"] = round(n_wg * 4 * iters * 8 * 32768 / t / 1e12, 1)
+    # do MFMA and vector-ALU work overlap on a SIMD: across wavefronts (mode 2) / inside one wavefront's stream (mode 3)?
+    L.dlm_peak_overlap.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    ov = {}
+    for mode, key in ((0, "all_mfma"), (1, "all_valu"), (2, "mfma_waves_beside_valu_waves"), (3, "both_in_each_wave")):
+        ov[key] = round(timed(lambda: L.dlm_peak_overlap(mode, 256, 20000, fs.data_ptr(), st)) * 1e3, 3)
+    ov["note"] = ("ms for 20000 iterations, 8 wavefronts per CU; side by side across wavefronts would give max(all_mfma, all_valu) / 2 "
+                  "for the third figure, mutual exclusion their sum / 2")
+    out["mfma_valu_overlap_ms"] = ov
     out["what"] = ("1 GiB device copy (read + write), 1 GiB one-pass read with ordinary / non-temporal loads, "
                    "register-only 32x32x16 bf16 MFMA loop on 2048 workgroups of 4 wavefronts with small constant operands and "
                    "with N(0,1) operands (the power limit lowers the clock on realistic data)")

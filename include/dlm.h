@@ -103,7 +103,11 @@ typedef struct dlm_kv_seg {
  * gets out = 0 and lse = -inf.
  * Supported: d in {64, 128}; Hq % Hkv == 0; all base pointers 16-byte aligned and
  * all strides multiples of 8 elements.  Lq, Hq/Hkv and segment lengths are arbitrary.
- * workspace: dlm_block_attn_workspace_bytes(args) bytes (may be 0; then NULL is fine).
+ * workspace: optional.  dlm_block_attn_workspace_bytes(args) is non-zero for shapes that leave most of the chip idle with
+ *           one workgroup per row tile (few sequences x KV heads, long context): given that many bytes (16-byte aligned),
+ *           the call lets several workgroups share the keys of a row tile (fp32 partial results in the workspace, merged
+ *           in a fixed order by a second launch: deterministic).  Without it, or with a smaller buffer, the call runs
+ *           unsplit; results then differ by the rounding of another summation order only.
  *   seq_active  optional device int32 [B]: sequence b is skipped (its rows of out and lse are left as they
  *           are) when seq_active[b] == 0.  For denoising steps in which some sequences of the batch have no
  *           masked position left: nothing reads their attention output (the LM head runs on masked rows
@@ -377,20 +381,32 @@ int dlm_kv_refresh(const dlm_kv_seg *src, int32_t B, int32_t Hkv, int32_t d,
                    int64_t c_stride_b, int64_t c_stride_h, int64_t c_stride_t,
                    int32_t cache_pos0, void *stream);
 
-/* dlm_set_option -- process-wide tuning / test knobs (not thread-safe against running calls).
+/* dlm_set_option -- process-wide tuning / test knobs (not thread-safe against running calls).  These integers are the
+ * ONLY mutable state the library keeps between calls (besides the per-device address of the built-in scratch of
+ * dlm_lmhead_confidence_static); every default is the planner's choice, and every setting computes the same function.
  *   "attn_variant"  0 = pick the attention kernel shape from the problem shape (default);
- *                   1 = 32-row workgroups whose wavefronts split the keys (needs g*Lq <= 32,
- *                       otherwise falls back to 2); 2 = 128-row; 3 = 256-row workgroups (one per CU);
+ *                   1 = 32-row workgroups whose wavefronts split the keys (needs g*Lq <= 32, otherwise falls back to 2),
+ *                       sized for one workgroup per CU; 12 = the same sized for two (the planner's choice for g*Lq <= 32);
+ *                   2 = 128-row; 3 = 256-row workgroups (one per CU);
  *                   4..7 = 128-row workgroups sized for 2, 3, 3, 4 resident workgroups per CU;
  *                   8..10 = key-split alternatives (deeper prefetch, 8 wavefronts) for g*Lq <= 32;
- *                   11 = 32-row key-split workgroups for any row count, the row tiles of one (sequence,
- *                   KV head) grouped on one XCD (chosen when 128-row workgroups would leave most CUs idle).
- *   "lmhead_variant" -1 = pick the LM-head kernel shape (workgroup tile, wavefront layout, prefetch
- *                   depth) from M (default); >= 0 forces one entry of the library's shape table.
+ *                   11 = 32-row key-split workgroups for any row count, the row tiles of one (sequence, KV head) grouped
+ *                       on one XCD (chosen when 128-row workgroups would leave most CUs idle and no workspace is given);
+ *                   13, 14 = 128-row workgroups of 8 wavefronts in two key groups, combined through LDS (prefetch depth 1, 2;
+ *                       13 is chosen when there is at most one 128-row workgroup per CU);
+ *                   15 = software-pipelined 128-row workgroups (d = 128; softmax of one key tile woven between the MFMAs
+ *                       of the next).
+ *   "attn_split"    0 = the library decides whether several workgroups share the keys of a row tile (default: only with at
+ *                   most 128 workgroups and at least 32 key tiles, and only when the call brings the workspace);
+ *                   1 = never; 2..16 = that many (lowered to keep four key tiles per workgroup).
+ *   "lmhead_variant" -1 = pick the LM-head kernel shape (workgroup tile, wavefront layout, prefetch depth) from M
+ *                   (default); >= 0 forces one entry of the library's shape table.
  *   "lmhead_block"  -1 = automatic blocking of LM-head workgroups per XCD (default); 0 = none (row chunks of one
  *                   vocabulary tile side by side); 1..8 = that many vocabulary tiles per block.
  *   "lmhead_nt"     1 = when a launch has one row chunk (every element of W used once) fetch W with non-temporal
  *                   loads (default); 0 = never.
+ *   "lmhead_cus"    0 = the half-height tail rule of the LM head assumes the device's CU count (default); n > 0 = assume n
+ *                   (tests: makes a small vocabulary take the two-launch path); -1 = no half-height tail.
  *   "attn_nt"       1 = non-temporal K/V loads when one workgroup is the only reader of its (sequence, KV head)
  *                   (g*Lq <= 32; default); 0 = never.
  *   "kv_copy_unroll" 16-byte pieces per thread of the copy kernel (1, 2, 4 or 8), plus 16 when K and V are copied by
@@ -399,7 +415,7 @@ int dlm_kv_refresh(const dlm_kv_seg *src, int32_t B, int32_t Hkv, int32_t d,
  *                   grid; forward and the dQ pass), 2 = under a block-causal mask the row tile with the longest
  *                   key range is dispatched first, 4 = the same grouping for the dK / dV passes; 0 = plain
  *                   (tile, KV head, sequence) grids.
- * Every shape computes the same function; the knobs exist for tests and tuning sweeps. */
+ * The knobs exist for tests and tuning sweeps. */
 int dlm_set_option(const char *name, int value);
 
 const char *dlm_last_error(void);

@@ -34,6 +34,17 @@ int dlm_peak_read(const void *src, size_t bytes, int nt, uint32_t *sink, void *s
  *   bounds any bf16 contraction on such data. */
 int dlm_peak_mfma(int n_wg, int iters, const void *operands, float *sink, void *stream);
 
+/* Do matrix (MFMA) and vector-ALU instructions run side by side on a SIMD?  n_wg workgroups of 8 wavefronts (two per
+ * SIMD); per iteration a "matrix" wavefront issues 4 independent 32x32x16 bf16 MFMAs, a "vector" wavefront 16
+ * (fused multiply-add, exponential) pairs on 16 independent values.
+ *   mode 0: all eight wavefronts matrix work;   mode 1: all eight vector work;
+ *   mode 2: wavefronts 0-3 matrix, 4-7 vector (one of each kind per SIMD);
+ *   mode 3: every wavefront both, each MFMA followed by four of the pairs in its own instruction stream.
+ * If different wavefronts' MFMA and vector work overlapped, mode 2 would take the longer of half of mode 0 and half of
+ * mode 1; if they exclude each other, the sum.  Mode 3 against modes 0 + 1 says the same for one wavefront's own stream.
+ * sink: n_wg * 8 floats. */
+int dlm_peak_overlap(int mode, int n_wg, int iters, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

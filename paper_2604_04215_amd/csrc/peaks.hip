@@ -76,6 +76,54 @@ __global__ __launch_bounds__(256) void mfma_kernel(int iters, const u32x4* __res
     if (lane == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = s;
 }
 
+template <int MODE>
+__global__ __launch_bounds__(512) void overlap_kernel(int iters, float* __restrict__ sink) {
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(0.01f * (float)((lane + i) & 7));
+        b[i] = (__bf16)(0.02f * (float)((lane * 3 + i) & 7));
+    }
+    f32x16 acc[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[k][i] = 0.f;
+    float x[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = 0.001f * (float)(lane + i);
+    const bool do_m = MODE == 0 || (MODE == 2 && w < 4);
+    const bool do_v = MODE == 1 || (MODE == 2 && w >= 4);
+    for (int it = 0; it < iters; ++it) {
+        if (MODE == 3) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[4 * k + i] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[4 * k + i], 0.5f, -1.0f));
+            }
+        } else {
+            if (do_m) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
+            }
+            if (do_v) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) x[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(x[i], 0.5f, -1.0f));
+            }
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += acc[k][i];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += x[i];
+    if (lane == 0) sink[blockIdx.x * 8 + w] = s;
+}
+
 int launched() { return hipGetLastError() == hipSuccess ? 0 : -4; }
 bool ok16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -111,5 +159,18 @@ extern "C" int dlm_peak_read(const void* src, size_t bytes, int nt, uint32_t* si
 extern "C" int dlm_peak_mfma(int n_wg, int iters, const void* operands, float* sink, void* stream) {
     if (n_wg <= 0 || iters <= 0 || iters % 8 || !sink || (operands && !ok16(operands))) return -1;
     hipLaunchKernelGGL(mfma_kernel, dim3((unsigned)n_wg), dim3(256), 0, (hipStream_t)stream, iters, (const u32x4*)operands, sink);
+    return launched();
+}
+
+extern "C" int dlm_peak_overlap(int mode, int n_wg, int iters, float* sink, void* stream) {
+    if (mode < 0 || mode > 3 || n_wg <= 0 || iters <= 0 || !sink) return -1;
+    const dim3 grid((unsigned)n_wg), blk(512);
+    hipStream_t st = (hipStream_t)stream;
+    switch (mode) {
+        case 0: hipLaunchKernelGGL(overlap_kernel<0>, grid, blk, 0, st, iters, sink); break;
+        case 1: hipLaunchKernelGGL(overlap_kernel<1>, grid, blk, 0, st, iters, sink); break;
+        case 2: hipLaunchKernelGGL(overlap_kernel<2>, grid, blk, 0, st, iters, sink); break;
+        default: hipLaunchKernelGGL(overlap_kernel<3>, grid, blk, 0, st, iters, sink); break;
+    }
     return launched();
 }
