@@ -170,9 +170,17 @@ def micro(args):
     blocker = torch.randn(8192, 8192, device=dev).bfloat16() if args.kernel in ("attn", "kv_refresh") else None
 
     def timed(fn, reps):
-        fn()
-        torch.cuda.synchronize()
+        # untimed calls first, about 80 ms of them: the clock of an idle GPU takes tens of milliseconds of work to come up
+        # (the first shape measured in a process otherwise reads 10 - 20 % slow)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        for _ in range(min(400, int(80.0 / max(e0.elapsed_time(e1), 0.01)))):
+            fn()
+        torch.cuda.synchronize()
         if blocker is not None:
             # calls of a few tens of microseconds: a few milliseconds of unrelated work go first, so that the host has
             # queued every timed call before the first one starts and the events measure GPU time, not the Python loop
