@@ -317,9 +317,10 @@ size_t dlm_lmhead_static_scratch_bytes(void);
  *               selection (one launch fewer per denoising step; block-sized extra writes per step).
  *   active_in   int32 [B], WHILE_ACTIVE only (see above); ignored otherwise
  *   host_remaining_total  optional pointer to ONE int32 in pinned host memory that the device can
- *               address (hipHostMalloc): receives sum_b remaining[b] with a system-scope store, so a
- *               caller that records an event after the call can learn "block finished" without
- *               queueing a device-to-host copy.  Only the single-workgroup path (one commit group per
+ *               address (hipHostMalloc): receives sum_b remaining[b] (>= 0) with a system-scope release
+ *               store, so a caller can learn "block finished" without queueing a device-to-host copy:
+ *               either it records an event after the call, or it presets the word to a negative value
+ *               before the call and watches the word.  Only the single-workgroup path (one commit group per
  *               sequence and B * n_pos <= 16384) supports it; otherwise DLM_ERR_UNSUPPORTED.
  * Selection compares fp32 values; outputs are integers (bit-exact given conf).
  * Limits: 1 <= group_len <= 1024; d % 8 == 0 for write-back.

@@ -15,6 +15,7 @@ step per block.
 from __future__ import annotations
 
 import ctypes as C
+import time
 from typing import Callable, Optional
 
 import torch
@@ -23,6 +24,40 @@ from . import binding as dlm
 
 _RULES = {"threshold": dlm.RULE_THRESHOLD, "topk": dlm.RULE_TOPK}
 _MASKS = {"full": dlm.MASK_FULL, "block_causal": dlm.MASK_BLOCK_CAUSAL}
+
+
+class StepPoll:
+    """Where the host learns what one queued step left masked: one int32 of pinned host memory that the step's commit
+    kernel overwrites, with a system-scope store, with the number of positions still masked.  The host sets the word
+    to -1 before it queues the step and watches until the device's value (>= 0) shows.  Nothing sits in the queue
+    between one step's kernels and the next step's: an event recorded after every step put 5 - 6 us between the
+    commit kernel and the next attention kernel on MI355X (kernel trace), this costs the queue nothing."""
+
+    TIMEOUT_S = 60.0
+
+    def __init__(self):
+        self.word = torch.zeros(1, dtype=torch.int32).pin_memory()
+        self.view = self.word.numpy()          # shares the pinned memory; every read is a load from it
+        self.ptr = self.word.data_ptr()
+
+    def arm(self) -> None:
+        self.view[0] = -1
+
+    def wait(self) -> int:
+        """Blocks (spinning) until the step's commit kernel has stored its count; raises if none shows in TIMEOUT_S."""
+        view = self.view
+        t0 = None
+        while True:
+            for _ in range(4096):
+                v = int(view[0])
+                if v >= 0:
+                    return v
+            now = time.perf_counter()
+            if t0 is None:
+                t0 = now
+            elif now - t0 > self.TIMEOUT_S:
+                raise RuntimeError(f"no result of a queued denoising step within {self.TIMEOUT_S:.0f} s "
+                                   "(did its dlm_unmask_commit launch fail?)")
 
 
 class GpuRollout:
@@ -77,9 +112,9 @@ class GpuRollout:
         # that only selects which kernel shape is tried first; 0 turns the guess off).
         self.expect_ratio = 0.85
         self.late_bound = True    # False: the caller sets the row bound from the step just before (synchronous loop)
-        # ring of pinned host words + events: the commit kernel stores the total still-masked count straight
-        # into pinned host memory, and an event recorded behind it tells the host when it may read it
-        self._ring = [(torch.cuda.Event(), torch.zeros(1, dtype=torch.int32).pin_memory()) for _ in range(4)]
+        # ring of pinned host words: the commit kernel stores the total still-masked count straight into pinned
+        # host memory, where the host watches for it (StepPoll)
+        self._ring = [StepPoll() for _ in range(4)]
         self._ring_pos = 0
         self._last_poll = None
 
@@ -112,9 +147,9 @@ class GpuRollout:
             self._size_attn_workspace()
             self._a_attn = None
 
-    def queue_poll(self):
-        """(event, pinned host word) of the step queued last: after event.synchronize() the word holds the
-        number of positions still masked after that step.  At most 3 polls may be outstanding."""
+    def queue_poll(self) -> "StepPoll":
+        """The StepPoll of the step queued last: its wait() returns the number of positions still masked after that
+        step.  At most 3 polls may be outstanding (the slots are reused round-robin)."""
         return self._last_poll
 
     # geometry of the current block
@@ -190,9 +225,9 @@ class GpuRollout:
                                           commit_step=self.commit_step, step=0, writeback=dlm.WB_WHILE_ACTIVE,
                                           active_in=self.remaining, src_block=(kblk, vblk, 0),
                                           cache_k=self.cache_k, cache_v=self.cache_v, cache_pos0=P,
-                                          host_remaining_total=self._ring[0][1])
+                                          host_remaining_total=self._ring[0].word)
         self._rem_ptr = [r.data_ptr() for r in self._remaining2]
-        self._ring_ptr = [h.data_ptr() for _, h in self._ring]
+        self._ring_ptr = [sp.ptr for sp in self._ring]
         self._lib = dlm.lib()
 
     def step(self, q: torch.Tensor, kblk: torch.Tensor, vblk: torch.Tensor, hidden: torch.Tensor) -> None:
@@ -200,7 +235,7 @@ class GpuRollout:
 
         Every step of a block passes tensors of one shape and layout (checked); what differs between steps is a handful
         of pointers and counters, so the argument structs are filled once per block (_prepare_step) and only those
-        fields are rewritten here: the host side of a step is three foreign calls and an event record."""
+        fields are rewritten here: the host side of a step is three foreign calls."""
         cfg = self.cfg
         Lb = cfg.Lb
         if self._a_attn is None or self._sig != (q.shape, q.stride(), kblk.shape, kblk.stride(), vblk.stride(),
@@ -210,8 +245,9 @@ class GpuRollout:
             if not t.is_cuda or t.dtype != torch.bfloat16:
                 raise ValueError("step inputs must be bf16 tensors on the GPU")
         pos = self._ring_pos
-        ev, host = self._ring[pos]
+        poll = self._ring[pos]
         self._ring_pos = (pos + 1) % len(self._ring)
+        poll.arm()                           # before anything of this step is queued
         # the raw handle of torch's current stream on this device, looked up once per step (the Stream object that
         # torch.cuda.current_stream() builds costs several microseconds of Python)
         sp = C.c_void_p(torch._C._cuda_getCurrentRawStream(self._dev_index))
@@ -256,8 +292,7 @@ class GpuRollout:
         if rc:
             raise dlm.DlmError(rc, dlm.last_error())
         self.remaining = self._remaining2[idx_new]
-        ev.record()                          # on the current stream
-        self._last_poll = (ev, host)
+        self._last_poll = poll
         self.step_idx += 1
 
     def set_row_bound(self, m: int) -> None:
@@ -277,7 +312,7 @@ class GpuRollout:
         self.late_bound = lagged
         self.begin_block(block, init_mask, rk, rv)
         max_steps = cfg.Lb + 1 if max_steps is None else max_steps
-        pending = []   # (event, pinned host copy of remaining) of steps already queued
+        pending = []   # StepPoll of the steps already queued
         steps = empty = 0
         done = False
         while not done and steps < max_steps:
@@ -287,9 +322,7 @@ class GpuRollout:
             # look at the newest result that is allowed to be waited for
             lag = 1 if lagged else 0
             while len(pending) > lag:
-                ev0, h0 = pending.pop(0)
-                ev0.synchronize()
-                rem = int(h0[0])
+                rem = pending.pop(0).wait()
                 self.set_row_bound(rem if rem > 0 else 1)
                 if rem == 0:
                     done = True
@@ -297,9 +330,8 @@ class GpuRollout:
                     pending.clear()
                     break
         if not done:
-            for ev0, h0 in pending:
-                ev0.synchronize()
-                if int(h0[0]) == 0:
+            for p0 in pending:
+                if p0.wait() == 0:
                     done = True
             if not done:
                 raise RuntimeError(f"block {block} not finished after {steps} steps")
@@ -325,7 +357,7 @@ class StepRunner:
         self.queued = 0                 # steps queued in the current block
         self.known = 0                  # of those, how many are known to be productive
         self.rem_prev = 0               # masked count before the oldest not-yet-polled step
-        self.pending = []               # (event, pinned remaining copy)
+        self.pending = []               # StepPoll of the steps queued and not yet polled
         self.committed = 0
         self.empty = 0
         self.blocks_done = 0
@@ -346,9 +378,7 @@ class StepRunner:
 
     def _poll_one(self) -> bool:
         """Wait for the oldest queued step's result; returns True when it finished the block."""
-        ev, host = self.pending.pop(0)
-        ev.synchronize()
-        rem = int(host[0])
+        rem = self.pending.pop(0).wait()
         self.log.append((self.block, self.rem_prev, rem))
         if self.rem_prev > 0:
             self.known += 1
