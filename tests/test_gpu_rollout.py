@@ -365,3 +365,18 @@ def test_stop_copy_resume_gives_same_trajectory(name, stop_after):
     c = fresh()
     tc = finish(c, 0, 0)
     assert [s for s, _ in tc] == [s for s, _ in ta] and torch.equal(c.x, a.x) and torch.equal(c.cache_k, a.cache_k)
+
+
+def test_step_poll_reports_a_step_that_never_answers():
+    """The host's wait for a step's count is bounded: a word that no kernel ever writes (as after a failed launch of the
+    commit) raises instead of spinning for ever; a word the device has written returns at once.  No kernel runs here."""
+    from paper_2604_04215_amd.rollout import StepPoll
+    sp = StepPoll()
+    sp.arm()
+    assert int(sp.view[0]) == -1
+    sp.TIMEOUT_S = 0.05                      # instance attribute: the class default stays
+    with pytest.raises(RuntimeError, match="no result of a queued denoising step"):
+        sp.wait()
+    sp.view[0] = 7                           # what the commit kernel's system-scope store leaves there
+    assert sp.wait() == 7
+    assert StepPoll.TIMEOUT_S >= 10
