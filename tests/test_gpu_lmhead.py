@@ -113,6 +113,21 @@ def test_ring_shapes_reach_their_steady_state_loop(variant, Dh):
     compare(got, ref)
 
 
+@pytest.mark.parametrize("variant,M", [(0, 413), (1, 413), (20, 2806), (21, 2900), (3, 1400)])
+def test_row_chunk_counts_without_a_divisor(variant, M):
+    # 13 / 7 / 11 / 12 row chunks: counts that are prime or have only a small divisor, so the blocks of row chunks that an
+    # XCD runs side by side degenerate (one chunk per block, or blocks that do not fill the XCD)
+    Dh, V = 128, 600
+    h, w = rnd(940 + M, (M, Dh)), rnd(941 + M, (V, Dh), Dh ** -0.25)
+    ref = oracle.lmhead(h, w, forbid_token=V - 1)
+    dlm.set_option("lmhead_variant", variant)
+    try:
+        got = run_lm(h, w, forbid=V - 1)
+    finally:
+        dlm.set_option("lmhead_variant", -1)
+    compare(got, ref)
+
+
 def test_gather_scatter_mdev_temperature_target():
     R, Dh, V = 96, 128, 1000
     h, w = rnd(1, (R, Dh)), rnd(2, (V, Dh), Dh ** -0.25)
