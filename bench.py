@@ -37,7 +37,7 @@ RIDGE = MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)     # FLOP per byte at wh
 # HBM bytes per LM-head launch on the default workload, from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0, factors calibrated with a 1 GiB copy); summary and commands in
 # profiles/lmhead_c2_rollout_hbm_traffic.md.  Only valid for --config c2 with the default W distribution.
-LMHEAD_C2_TRAFFIC_BYTES = 1096.0e6
+LMHEAD_C2_TRAFFIC_BYTES = 1045.1e6
 
 WORKLOADS = {
     "c1": "c1: tiny single block, B=1, 4 heads MHA, d=64, hidden 256, V=2048, prefix 256, block 32 with 16 masked, "
@@ -597,7 +597,7 @@ def main():
                   "ceiling_frac": dom["ceiling_frac_hbm_peak"]} if dom["bound"] == "mfma" else
                  {"bound": "mfma", "achieved": dom["tflops"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dom["frac_mfma_peak"],
                   "ceiling_frac": dom["ceiling_frac_mfma_peak"]})
-        kern_names = {"dlm_lmhead_confidence": "lmhead_kernel (M <= 192) or lmhead_pair_kernel (above) + lmhead_reduce_kernel (one dlm_lmhead_confidence call)",
+        kern_names = {"dlm_lmhead_confidence": "lmhead_kernel (M <= 256) or lmhead_pair_kernel (above) + lmhead_reduce_kernel (one dlm_lmhead_confidence call)",
                       "dlm_block_attn": "attn_kernel (one dlm_block_attn call)",
                       "dlm_unmask_commit": "commit_fused_kernel (one dlm_unmask_commit call)"}
         roof = dict(bound=dom["bound"], achieved=ach, peak=peak, unit=unit, frac=round(ach / peak, 4),

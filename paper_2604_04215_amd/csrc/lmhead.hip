@@ -1194,13 +1194,13 @@ static void launch_lmq(dim3 grid, hipStream_t st, const LmParams& p) {
 #define LMV(WV, WH, TVW, THW, PD) {32 * TVW * WV, 32 * THW * WH, 64 * WV * WH, -1, launch_lm<WV, WH, TVW, THW, PD>, launch_lm<WV, WH, TVW, THW, PD, 64, 1, false, true>}
 static const LmVariant g_lm_variants[] = {
     // shapes the planner uses, by row count M (V = 126464, Dh = 4096 on MI355X, us per main-kernel launch in the
-    // rollout, non-temporal W stream; entries 21, 22, 20 above 192 rows):
+    // rollout, non-temporal W stream; entries 22, 20 above 256 rows):
     /*0*/ LMV(4, 1, 1, 1, 3),   // M <= 32   128 x 32 tile,  4 waves            ~161
     /*1*/ LMP(4, 1, 1, 2, 3),   // M <= 64   128 x 64,       4 waves            ~159
     /*2*/ LMP(8, 1, 1, 3, 3),   // M <= 96   256 x 96,       8 waves            ~166
     /*3*/ LMP(4, 2, 2, 2, 3),   // M <= 128  256 x 128,      8 waves            ~172
     /*4*/ LMP(4, 2, 2, 3, 2),   // M <= 192  256 x 192,      8 waves            ~203
-    /*5*/ LMP(4, 2, 2, 4, 2),   // 256 x 256, 8 waves, register-staged (the planner now takes entries 20..22 above 192 rows)
+    /*5*/ LMP(4, 2, 2, 4, 2),   // M <= 256  256 x 256,      8 waves            ~245
     // alternatives kept for tests and tuning sweeps
     /*6*/ LMV(2, 2, 2, 4, 3),   // 128 x 256, 4 waves, stores before the MFMA block
     /*7*/ LMD(4, 1, 1, 3),      // W fragments straight from global memory, 128 x 32
@@ -1217,18 +1217,19 @@ static const LmVariant g_lm_variants[] = {
     /*18*/ LMX(2, 2, 4, 4, 4),  // entry 10 with the operand fragments read one MFMA step ahead, across the barrier
     /*19*/ LMX(4, 2, 2, 4, 4),  // entry 13 likewise
     /*20*/ LMQ(2, 2, 4, 4),     // paired, evenly spread requests, 5 stages: 256 x 256, 4 waves x (128 x 128)
-    /*21*/ LMQ(4, 2, 2, 4),     // same, 8 waves x (64 x 128)                      M <= 256: ~245
+    /*21*/ LMQ(4, 2, 2, 4),     // same, 8 waves x (64 x 128): one 256-row chunk as fast as entry 5, with 1.47 x the HBM fetch
     /*22*/ LMQ(4, 1, 2, 6),     // 256 x 192, 4 waves x (64 x 192)
     /*23*/ LMQ(4, 1, 2, 4),     // 256 x 128, 4 waves x (64 x 128)
-    // half-height forms of entries 2, 3, 4 and 21 (128 vocabulary rows): the tail of a launch whose tile count leaves
+    // half-height forms of entries 2, 3, 4, 21 and 5 (128 vocabulary rows): the tail of a launch whose tile count leaves
     // at most half of the CUs busy in its last round (see launch_lm_shape)
     /*24*/ LMP(4, 1, 1, 3, 3),  // 128 x 96,  4 waves
     /*25*/ LMP(4, 2, 1, 2, 3),  // 128 x 128, 8 waves
     /*26*/ LMP(4, 2, 1, 3, 2),  // 128 x 192, 8 waves
     /*27*/ LMQ(4, 2, 1, 4),     // 128 x 256, paired ring, 8 waves x (32 x 128)
+    /*28*/ LMP(4, 2, 1, 4, 2),  // 128 x 256, register-staged, 8 waves
 };
 // entry -> its half-height form
-static int lm_half_of(int v) { return v == 2 ? 24 : v == 3 ? 25 : v == 4 ? 26 : v == 21 ? 27 : -1; }
+static int lm_half_of(int v) { return v == 2 ? 24 : v == 3 ? 25 : v == 4 ? 26 : v == 21 ? 27 : v == 5 ? 28 : -1; }
 #undef LMV
 #undef LMA
 #undef LMX
@@ -1249,7 +1250,7 @@ static int plan_lmhead(int M) {
     if (M <= 96) return 2;
     if (M <= 128) return 3;
     if (M <= 192) return 4;
-    if (M <= 256) return 21;        // one 256-row chunk: the paired ring with two wavefronts per SIMD
+    if (M <= 256) return 5;         // one 256-row chunk, register-staged: as fast as the ring (entry 21), which fetches 1.3 - 1.5 x W here
     if (M <= 384) return 22;        // two 192-row chunks
     return 20;                      // 256-row chunks, one wavefront per SIMD with a 128 x 128 tile
 }

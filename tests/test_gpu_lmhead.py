@@ -83,7 +83,7 @@ def test_shapes_vs_oracle(M, Dh, V):
     assert np.all(got["tok"] != V - 1)
 
 
-@pytest.mark.parametrize("variant", range(28))
+@pytest.mark.parametrize("variant", range(29))
 def test_every_kernel_shape(variant):
     # each entry of the library's shape table on a problem with several row chunks and ragged tails
     M, Dh, V = 300, 192, 1100
