@@ -99,6 +99,13 @@ class GpuRollout:
         self.attn_workspace = None    # sized per block (key split across workgroups)
         self._a_attn = self._a_lm = self._a_commit = None   # argument structs of a step, filled once per block
         self._sig = None
+        # What a block's steps need besides the per-step pointers depends on the block index alone (the cache views,
+        # the attention workspace size, the three argument structs): kept per block the first time the block is
+        # visited, so that a rollout that comes back to a block (the next prompt of a batch job) pays that host work
+        # once, not at every block boundary, where the GPU would sit idle meanwhile.
+        self._plans = {}              # block -> dict(prefix, suffix, sig, a_attn, a_lm, a_commit)
+        self._refresh_calls = {}      # (block, source pointers) -> prepared dlm_kv_refresh calls
+        self._compact_args = None
         # optional hook(name, c_function, args_struct, stream_ptr, meta) -> return code, called INSTEAD of the plain
         # library call of a step (the benchmark's per-call event timing); None: the calls go straight to the library
         self.on_call = None
@@ -169,27 +176,65 @@ class GpuRollout:
         self.block, self.step_idx = block, 0
         P, Lb = self.P, cfg.Lb
         if refresh_k is not None:
-            if P > 0:
-                dlm.kv_refresh(refresh_k[:, :, :P], refresh_v[:, :, :P], self.cache_k, self.cache_v, 0)
-            if cfg.dual_cache and P + Lb < cfg.L:
-                dlm.kv_refresh(refresh_k[:, :, P + Lb:], refresh_v[:, :, P + Lb:], self.cache_k, self.cache_v, P + Lb)
+            self._refresh(block, refresh_k, refresh_v)
         if init_mask is None:
             self.mask.fill_(1)
         else:
             self.mask.copy_(init_mask)
         if self.commit_step is not None:
             self.commit_step.fill_(-1)
-        dlm.mask_compact(self.mask, self.row_idx, self.m_dev)
+        self._compact()
         self.m_host = cfg.B * Lb
         # fixed schedule: from a fully masked block the top-k rule leaves exactly Lb - k (s + 1) positions per
         # sequence after step s, so the LM-head launch can be sized exactly instead of from the late poll
         self._exact_rows = cfg.rule == "topk" and init_mask is None
+        plan = self._plans.get(block)
+        if plan is not None:
+            self._prefix, self._suffix, self._sig = plan["prefix"], plan["suffix"], plan["sig"]
+            self._a_attn, self._a_lm, self._a_commit = plan["a_attn"], plan["a_lm"], plan["a_commit"]
+            return
         # the cache views of this block's prefix / suffix are the same for all of its steps
         S = self.S
         self._prefix = (self.cache_k[:, :, :P], self.cache_v[:, :, :P], 0) if P > 0 else None
         self._suffix = (self.cache_k[:, :, P + Lb:P + Lb + S], self.cache_v[:, :, P + Lb:P + Lb + S], P + Lb) if S > 0 else None
         self._size_attn_workspace()
-        self._a_attn = None           # the step's argument structs are rebuilt at the block's first step
+        self._a_attn = None           # the step's argument structs are built at the block's first step
+
+    def _refresh(self, block: int, refresh_k: torch.Tensor, refresh_v: torch.Tensor) -> None:
+        """The block-boundary cache refresh: prefix rows always, suffix rows too for the dual cache.  The argument
+        marshalling of the (at most two) dlm_kv_refresh calls is done once per (block, source image)."""
+        cfg = self.cfg
+        P, Lb = self.P, cfg.Lb
+        key = (block, refresh_k.data_ptr(), refresh_v.data_ptr(), tuple(refresh_k.shape), refresh_k.stride(), refresh_v.stride())
+        calls = self._refresh_calls.get(key)
+        if calls is None:
+            calls = []
+            spans = ([(0, P)] if P > 0 else []) + ([(P + Lb, cfg.L)] if cfg.dual_cache and P + Lb < cfg.L else [])
+            for lo, hi in spans:
+                sk, sv = refresh_k[:, :, lo:hi], refresh_v[:, :, lo:hi]
+                if hi > self.cache_k.shape[2] or self.cache_k.stride() != self.cache_v.stride():
+                    raise ValueError("refresh image does not fit the cache")
+                seg = dlm.kv_seg(sk, sv, 0)
+                calls.append((seg, (C.byref(seg), cfg.B, cfg.Hkv, cfg.d, self.cache_k.data_ptr(), self.cache_v.data_ptr(),
+                                    self.cache_k.stride(0), self.cache_k.stride(1), self.cache_k.stride(2), lo), (sk, sv)))
+            if len(self._refresh_calls) > 4 * max(1, cfg.n_blocks):      # a caller that brings a new image every time
+                self._refresh_calls.clear()
+            self._refresh_calls[key] = calls
+        sp = C.c_void_p(torch._C._cuda_getCurrentRawStream(self._dev_index))
+        fn = dlm.lib().dlm_kv_refresh
+        for _seg, args, _keep in calls:
+            rc = fn(*args, sp)
+            if rc:
+                raise dlm.DlmError(rc, dlm.last_error())
+
+    def _compact(self) -> None:
+        """dlm_mask_compact of the block mask into the row list (arguments marshalled once)."""
+        if self._compact_args is None:
+            self._compact_args = (self.mask.data_ptr(), self.mask.stride(0), self.cfg.B, self.cfg.Lb,
+                                  self.row_idx.data_ptr(), self.m_dev.data_ptr())
+        rc = dlm.lib().dlm_mask_compact(*self._compact_args, C.c_void_p(torch._C._cuda_getCurrentRawStream(self._dev_index)))
+        if rc:
+            raise dlm.DlmError(rc, dlm.last_error())
 
     def _size_attn_workspace(self) -> None:
         """The attention call may split the keys across workgroups when it is given a workspace; its size depends on
@@ -200,6 +245,7 @@ class GpuRollout:
                                               mask_mode=_MASKS[cfg.mask_mode], block_size=cfg.bs, q_pos0=self.P)
         if need > (0 if self.attn_workspace is None else self.attn_workspace.numel()):
             self.attn_workspace = torch.empty(need, dtype=torch.uint8, device=self.dev)
+            self._plans.clear()       # the structs kept for other blocks point at the old workspace
 
     def _prepare_step(self, q, kblk, vblk, hidden) -> None:
         """Fill the three argument structs of a denoising step once per block (all validation happens here); the steps
@@ -229,6 +275,8 @@ class GpuRollout:
         self._rem_ptr = [r.data_ptr() for r in self._remaining2]
         self._ring_ptr = [sp.ptr for sp in self._ring]
         self._lib = dlm.lib()
+        self._plans[self.block] = dict(prefix=self._prefix, suffix=self._suffix, sig=self._sig, a_attn=self._a_attn,
+                                       a_lm=self._a_lm, a_commit=self._a_commit)   # per-step pointers are rewritten by step()
 
     def step(self, q: torch.Tensor, kblk: torch.Tensor, vblk: torch.Tensor, hidden: torch.Tensor) -> None:
         """Enqueue one denoising step.  q [B, Lb, Hq, d]; kblk, vblk [B, Hkv, Lb, d]; hidden [B, Lb, Dh].
