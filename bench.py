@@ -77,6 +77,11 @@ def parse():
                     help="the driver's guess of (rows in a step) / (late row bound); 0 = no guess; default: the driver's")
     ap.add_argument("--set-option", action="append", default=[], metavar="NAME=VALUE",
                     help="library tuning knob (dlm_set_option) applied before the run; may be repeated")
+    ap.add_argument("--ab", default=None, metavar="NAME=V1,V2[,...]",
+                    help="A/B inside one process (boxes of the pool differ by a few percent, runs on one box repeat within "
+                         "0.2 %%): after the clock ramp, alternate the values of a dlm_set_option knob (or of 'expect_ratio', "
+                         "the rollout driver's row-count guess), --steps steps each, three rounds; prints one JSON line per "
+                         "measurement and returns")
     ap.add_argument("--dump-steps", default=None, metavar="FILE",
                     help="write one line per sampled step: block, rows masked before / after, active sequences, "
                          "attention / LM-head / commit call in us")
@@ -490,6 +495,23 @@ def main():
     if args.warmup > 0:
         runner.run(args.warmup)
     torch.cuda.synchronize()
+    if args.ab:
+        name, _, vals = args.ab.partition("=")
+        for rnd in range(3):
+            for v in vals.split(","):
+                if name == "expect_ratio":
+                    g.expect_ratio = float(v)
+                else:
+                    dlm.set_option(name, int(v))
+                runner.run(max(50, args.steps // 10))       # the new setting's own warm-up
+                torch.cuda.synchronize()
+                ta = time.perf_counter()
+                runner.run(args.steps)
+                torch.cuda.synchronize()
+                tb = time.perf_counter()
+                print(json.dumps({"ab": name, "value": v, "round": rnd, "workload": cfg.name, "steps": args.steps,
+                                  "us_per_step": round((tb - ta) / args.steps * 1e6, 2)}), flush=True)
+        return
     c0, e0 = runner.committed, runner.empty
     torch.cuda.synchronize()
     t0 = time.perf_counter()
