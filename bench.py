@@ -66,6 +66,10 @@ def parse():
     ap.add_argument("--ramp-steps", type=int, default=300,
                     help="untimed steps queued before the --warmup steps so that a short run is timed at the same clock "
                          "as a long one (the discovery pass before them leaves the GPU mostly idle)")
+    ap.add_argument("--ramp-seconds", type=float, default=0.4,
+                    help="the untimed ramp lasts at least this long (more --ramp-steps are queued until it has): a workload of "
+                         "small launches (c1: 20 us of kernels per step) brings the clock up far more slowly than one that "
+                         "streams a gigabyte per step, and runs at half its steady rate for the first ~0.1 s")
     ap.add_argument("--sample-steps", type=int, default=400,
                     help="steps of the per-call event-timing pass that follows the timed region (0 = skip it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -79,8 +83,8 @@ def parse():
                     help="library tuning knob (dlm_set_option) applied before the run; may be repeated")
     ap.add_argument("--ab", default=None, metavar="NAME=V1,V2[,...]",
                     help="A/B inside one process (boxes of the pool differ by a few percent, runs on one box repeat within "
-                         "0.2 %%): after the clock ramp, alternate the values of a dlm_set_option knob (or of 'expect_ratio', "
-                         "the rollout driver's row-count guess), --steps steps each, three rounds; prints one JSON line per "
+                         "0.2 %%): after the clock ramp, alternate the values of a dlm_set_option knob (or of the rollout driver's "
+                         "'expect_ratio', its row-count guess, or 'predict_finish'), --steps steps each, three rounds; prints one JSON line per "
                          "measurement and returns")
     ap.add_argument("--dump-steps", default=None, metavar="FILE",
                     help="write one line per sampled step: block, rows masked before / after, active sequences, "
@@ -490,8 +494,21 @@ def main():
     setup_s = time.time() - t_setup
 
     # ---- clock ramp + warm-up, then the timed region (nothing but the steps' own launches inside) ----
+    ramp_done = 0
     if args.ramp_steps > 0:
-        runner.run(args.ramp_steps)
+        t_ramp = time.perf_counter()
+        while True:
+            runner.run(args.ramp_steps)
+            ramp_done += args.ramp_steps
+            torch.cuda.synchronize()
+            if time.perf_counter() - t_ramp >= args.ramp_seconds or ramp_done >= 200 * args.ramp_steps:
+                break
+        # ... and ends where a rollout ends, so that the warm-up and the timed region always begin at the same place of the
+        # rollout whatever the length of the ramp was (a short timed region covers a fraction of a rollout, whose early
+        # steps commit many tokens and its late ones few)
+        while runner.in_block or runner.block != cfg.n_blocks - 1:
+            runner.run(1)
+            ramp_done += 1
     if args.warmup > 0:
         runner.run(args.warmup)
     torch.cuda.synchronize()
@@ -501,6 +518,8 @@ def main():
             for v in vals.split(","):
                 if name == "expect_ratio":
                     g.expect_ratio = float(v)
+                elif name == "predict_finish":
+                    g.predict_finish = bool(int(v))
                 else:
                     dlm.set_option(name, int(v))
                 runner.run(max(50, args.steps // 10))       # the new setting's own warm-up
@@ -675,7 +694,7 @@ def main():
         "config": {"workload": WORKLOADS[args.config] + ("" if args.w_dist == "var" else " [W_vocab std reading]"),
                    "committed_tokens": committed, "tokens_per_step": round(committed / args.steps, 3),
                    "steps_per_rollout": rollout_steps, "steps_per_block": steps_per_block,
-                   "empty_steps_in_timed_region": empty, "ramp_steps": args.ramp_steps,
+                   "empty_steps_in_timed_region": empty, "ramp_steps": ramp_done,
                    "loop": "sync" if args.sync_loop else "one-step-late poll", "setup_s": round(setup_s, 1)},
         "roofline": roof,
         "kernels": kernels,

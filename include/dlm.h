@@ -322,6 +322,11 @@ size_t dlm_lmhead_static_scratch_bytes(void);
  *               either it records an event after the call, or it presets the word to a negative value
  *               before the call and watches the word.  Only the single-workgroup path (one commit group per
  *               sequence and B * n_pos <= 16384) supports it; otherwise DLM_ERR_UNSUPPORTED.
+ *   host_remaining_max  optional, with host_remaining_total only: ONE more int32 of pinned host memory that
+ *               receives max_b remaining[b], stored before the total (a host that has seen the total
+ *               sees this value too).  With the forced top-1 of the threshold rule a maximum of 1 (with
+ *               the top-k rule a maximum <= k) means that the NEXT step commits everything that is left,
+ *               so a host that polls one step late knows a block's last step when it queues it.
  * Selection compares fp32 values; outputs are integers (bit-exact given conf).
  * Limits: 1 <= group_len <= 1024; d % 8 == 0 for write-back.
  * Calls on one stream are ordered; the kernels of one call race with nothing else.
@@ -352,6 +357,7 @@ typedef struct dlm_commit_args {
     int32_t cache_pos0, Hkv, d;
     int32_t *host_remaining_total;
     const int32_t *active_in;
+    int32_t *host_remaining_max;
 } dlm_commit_args;
 
 int dlm_unmask_commit(const dlm_commit_args *args, void *stream);

@@ -85,7 +85,7 @@ class CommitArgs(C.Structure):
                 ("src_block", KvSeg), ("cache_k", C.c_void_p), ("cache_v", C.c_void_p),
                 ("c_stride_b", C.c_int64), ("c_stride_h", C.c_int64), ("c_stride_t", C.c_int64),
                 ("cache_pos0", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32),
-                ("host_remaining_total", C.c_void_p), ("active_in", C.c_void_p)]
+                ("host_remaining_total", C.c_void_p), ("active_in", C.c_void_p), ("host_remaining_max", C.c_void_p)]
 
 
 class DlmError(RuntimeError):
@@ -401,8 +401,8 @@ def _lmhead_args(hidden, w, conf, tok, *, M: Optional[int] = None, row_idx=None,
 def unmask_commit(conf, tok, x, mask, n_commit, remaining, *, stream=None, **kw) -> None:
     """conf fp32 / tok int32 dense [B, n_pos]; x int32 [B, L]; mask uint8 [B, n_pos] (row-strided views are fine).
     Keywords: x_pos0 (required), group_len, rule, threshold, force_top1, k, commit_now, next_row_idx, next_m, commit_step,
-    step, writeback, src_block, cache_k, cache_v, cache_pos0, active_in, host_remaining_total (optional pinned CPU int32
-    tensor of 1 element the kernel writes through)."""
+    step, writeback, src_block, cache_k, cache_v, cache_pos0, active_in, host_remaining_total / host_remaining_max (optional
+    pinned CPU int32 tensors of 1 element each that the kernel writes through)."""
     a = _commit_args(conf, tok, x, mask, n_commit, remaining, **kw)
     _check(lib().dlm_unmask_commit(C.byref(a), _stream(stream)))
 
@@ -411,7 +411,7 @@ def _commit_args(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group_
                  rule: int = RULE_THRESHOLD, threshold: float = 0.0, force_top1: bool = True, k: int = 0,
                  commit_now=None, next_row_idx=None, next_m=None, commit_step=None, step: int = 0,
                  writeback: int = WB_NONE, src_block: Optional[Tuple] = None, cache_k=None, cache_v=None,
-                 cache_pos0: int = 0, host_remaining_total=None, active_in=None) -> CommitArgs:
+                 cache_pos0: int = 0, host_remaining_total=None, active_in=None, host_remaining_max=None) -> CommitArgs:
     import torch
     a = CommitArgs()
     a.struct_size = C.sizeof(CommitArgs)
@@ -446,6 +446,10 @@ def _commit_args(conf, tok, x, mask, n_commit, remaining, *, x_pos0: int, group_
         if host_remaining_total.is_cuda or not host_remaining_total.is_pinned() or host_remaining_total.dtype != torch.int32:
             raise ValueError("host_remaining_total must be a pinned CPU int32 tensor")
         a.host_remaining_total = host_remaining_total.data_ptr()
+    if host_remaining_max is not None:
+        if host_remaining_max.is_cuda or not host_remaining_max.is_pinned() or host_remaining_max.dtype != torch.int32:
+            raise ValueError("host_remaining_max must be a pinned CPU int32 tensor")
+        a.host_remaining_max = host_remaining_max.data_ptr()
     return a
 
 

@@ -161,9 +161,9 @@ struct CopyParams {
 constexpr int FUSED_MAX_POS = 16384;
 template <int CH>
 __global__ __launch_bounds__(1024) void commit_fused_kernel(CommitParams p, int32_t* row_idx, int32_t* next_m,
-                                                            int32_t* host_total, CopyParams cp) {
+                                                            int32_t* host_total, int32_t* host_max, CopyParams cp) {
     __shared__ uint8_t newmask[FUSED_MAX_POS];
-    __shared__ int wave_tot[16];
+    __shared__ int wave_tot[16], wave_max[16];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     if (blockIdx.x > 0) {
         // DLM_WB_WHILE_ACTIVE: workgroups 1.. copy the block's K/V of one (sequence, KV head) each.  They read
@@ -185,6 +185,7 @@ __global__ __launch_bounds__(1024) void commit_fused_kernel(CommitParams p, int3
         }
         return;
     }
+    int left_max = 0;                 // most positions any of this wavefront's sequences still has masked
     for (int b = w; b < p.B; b += 16) {
         const int64_t base = (int64_t)b * p.n_pos;
         uint8_t* mrow = p.mask + b * p.mask_stride_b;
@@ -250,11 +251,13 @@ __global__ __launch_bounds__(1024) void commit_fused_kernel(CommitParams p, int3
             }
         }
         ncom = wave_sum(ncom);
+        left_max = max(left_max, cnt - ncom);
         if (lane == 0) {
             p.n_commit[b] = ncom;
             p.remaining[b] = cnt - ncom;
         }
     }
+    if (lane == 0) wave_max[w] = left_max;
     __syncthreads();
     // ordered compaction of the still-masked positions (from LDS)
     const int N = p.B * p.n_pos;
@@ -280,7 +283,13 @@ __global__ __launch_bounds__(1024) void commit_fused_kernel(CommitParams p, int3
     if (tid == 0) {
         if (next_m) *next_m = running;
         if (host_total) {
-            __hip_atomic_store(host_total, running, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+            if (host_max) {
+                int mx = 0;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) mx = max(mx, wave_max[j]);
+                __hip_atomic_store(host_max, mx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
+            __hip_atomic_store(host_total, running, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);   // orders the maximum before it
         }
     }
 }
@@ -650,6 +659,8 @@ extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
     if (a->B == 0) return DLM_OK;
     const int n_groups = a->group_len > 0 ? a->n_pos / a->group_len : 0;
     const bool fused = N > 0 && n_groups == 1 && N <= FUSED_MAX_POS;
+    if (a->host_remaining_max && !a->host_remaining_total)
+        return fail(DLM_ERR_INVALID_ARG, "unmask_commit: host_remaining_max goes with host_remaining_total");
     if (a->host_remaining_total && !fused)
         return fail(DLM_ERR_UNSUPPORTED, "unmask_commit: host_remaining_total needs one group per sequence and B*n_pos <= %d", FUSED_MAX_POS);
     CommitParams p;
@@ -667,9 +678,9 @@ extern "C" int dlm_unmask_commit(const dlm_commit_args* a, void* stream) {
                              a->cache_pos0, a->writeback, a->n_commit, a->remaining, a->commit_now, a->n_pos, a->active_in);
             grid += (unsigned)(a->B * a->Hkv);
         }
-        if (a->group_len <= 64) hipLaunchKernelGGL(commit_fused_kernel<1>, dim3(grid), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total, cp);
-        else if (a->group_len <= 256) hipLaunchKernelGGL(commit_fused_kernel<4>, dim3(grid), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total, cp);
-        else hipLaunchKernelGGL(commit_fused_kernel<16>, dim3(grid), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total, cp);
+        if (a->group_len <= 64) hipLaunchKernelGGL(commit_fused_kernel<1>, dim3(grid), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total, a->host_remaining_max, cp);
+        else if (a->group_len <= 256) hipLaunchKernelGGL(commit_fused_kernel<4>, dim3(grid), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total, a->host_remaining_max, cp);
+        else hipLaunchKernelGGL(commit_fused_kernel<16>, dim3(grid), dim3(1024), 0, st, p, a->next_row_idx, a->next_m, a->host_remaining_total, a->host_remaining_max, cp);
         int rc = check_hip(hipGetLastError(), "commit_fused_kernel launch");
         if (rc != DLM_OK) return rc;
     } else {

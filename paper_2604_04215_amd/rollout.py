@@ -8,9 +8,11 @@ Loop control: the commit kernel leaves the compacted list of still-masked rows
 and its length on the device, and the next LM-head call reads that length from
 the device, so a step never needs a host round trip to size its work.  The
 host only has to learn when a block is finished; `run_block` polls `remaining`
-one step late (the copy of step s-1 is read after step s has been queued), so
-the GPU never idles waiting for the host, at the price of at most one empty
-step per block.
+one step late (the result of step s-1 is read after step s has been queued), so
+the GPU never idles waiting for the host.  With the total the commit kernel
+also reports the largest per-sequence count: when that is no more than the next
+step is certain to commit, the step already queued is the block's last, and
+the loop neither queues an empty step behind it nor waits for it.
 """
 from __future__ import annotations
 
@@ -36,12 +38,20 @@ class StepPoll:
     TIMEOUT_S = 60.0
 
     def __init__(self):
-        self.word = torch.zeros(1, dtype=torch.int32).pin_memory()
-        self.view = self.word.numpy()          # shares the pinned memory; every read is a load from it
-        self.ptr = self.word.data_ptr()
+        # [0]: positions still masked in all sequences together; [1]: the most any one sequence still has (stored by the
+        # kernel before [0], so it is there once [0] is)
+        self.words = torch.zeros(2, dtype=torch.int32).pin_memory()
+        self.word, self.word_max = self.words[0:1], self.words[1:2]
+        self.view = self.words.numpy()         # shares the pinned memory; every read is a load from it
+        self.ptr, self.ptr_max = self.word.data_ptr(), self.word_max.data_ptr()
 
     def arm(self) -> None:
         self.view[0] = -1
+
+    @property
+    def left_max(self) -> int:
+        """After wait(): the largest per-sequence count of still-masked positions that the step left."""
+        return int(self.view[1])
 
     def wait(self) -> int:
         """Blocks (spinning) until the step's commit kernel has stored its count; raises if none shows in TIMEOUT_S."""
@@ -119,6 +129,10 @@ class GpuRollout:
         # that only selects which kernel shape is tried first; 0 turns the guess off).
         self.expect_ratio = 0.85
         self.late_bound = True    # False: the caller sets the row bound from the step just before (synchronous loop)
+        # A step after which no sequence has more masked positions than the next step is certain to commit (1 with the
+        # forced top-1 of the threshold rule, k with the top-k rule) tells the host that the NEXT step ends the block: a
+        # loop that polls one step late then neither queues an empty step behind it nor waits for its result.
+        self.predict_finish = True
         # ring of pinned host words: the commit kernel stores the total still-masked count straight into pinned
         # host memory, where the host watches for it (StepPoll)
         self._ring = [StepPoll() for _ in range(4)]
@@ -271,9 +285,10 @@ class GpuRollout:
                                           commit_step=self.commit_step, step=0, writeback=dlm.WB_WHILE_ACTIVE,
                                           active_in=self.remaining, src_block=(kblk, vblk, 0),
                                           cache_k=self.cache_k, cache_v=self.cache_v, cache_pos0=P,
-                                          host_remaining_total=self._ring[0].word)
+                                          host_remaining_total=self._ring[0].word, host_remaining_max=self._ring[0].word_max)
         self._rem_ptr = [r.data_ptr() for r in self._remaining2]
         self._ring_ptr = [sp.ptr for sp in self._ring]
+        self._ring_ptr_max = [sp.ptr_max for sp in self._ring]
         self._lib = dlm.lib()
         self._plans[self.block] = dict(prefix=self._prefix, suffix=self._suffix, sig=self._sig, a_attn=self._a_attn,
                                        a_lm=self._a_lm, a_commit=self._a_commit)   # per-step pointers are rewritten by step()
@@ -336,12 +351,20 @@ class GpuRollout:
         a.active_in = None if first else self._rem_ptr[idx_prev]
         a.src_block.k, a.src_block.v = kp, vp
         a.host_remaining_total = self._ring_ptr[pos]
+        a.host_remaining_max = self._ring_ptr_max[pos]
         rc = L.dlm_unmask_commit(C.byref(a), sp) if hook is None else hook("unmask_commit", L.dlm_unmask_commit, a, sp, dict(first=first, remaining=self._remaining2[idx_new]))
         if rc:
             raise dlm.DlmError(rc, dlm.last_error())
         self.remaining = self._remaining2[idx_new]
         self._last_poll = poll
         self.step_idx += 1
+
+    def next_step_finishes(self, poll: "StepPoll") -> bool:
+        """poll: a waited-for StepPoll of this block.  True when the step AFTER the polled one is certain to leave nothing
+        masked: every sequence has at most as many masked positions left as the rule commits per step."""
+        if not self.predict_finish:
+            return False
+        return poll.left_max <= (self.cfg.k if self.cfg.rule == "topk" else 1)
 
     def set_row_bound(self, m: int) -> None:
         """Tell the driver an upper bound of the masked-row count (sizes the LM-head launch)."""
@@ -370,11 +393,16 @@ class GpuRollout:
             # look at the newest result that is allowed to be waited for
             lag = 1 if lagged else 0
             while len(pending) > lag:
-                rem = pending.pop(0).wait()
+                p0 = pending.pop(0)
+                rem = p0.wait()
                 self.set_row_bound(rem if rem > 0 else 1)
                 if rem == 0:
                     done = True
                     empty = len(pending)   # steps queued after the finishing one found nothing to do
+                    pending.clear()
+                    break
+                if len(pending) == 1 and self.next_step_finishes(p0):
+                    done = True            # the step already queued behind the polled one ends the block: no need to wait
                     pending.clear()
                     break
         if not done:
@@ -426,7 +454,8 @@ class StepRunner:
 
     def _poll_one(self) -> bool:
         """Wait for the oldest queued step's result; returns True when it finished the block."""
-        rem = self.pending.pop(0).wait()
+        self._polled = self.pending.pop(0)
+        rem = self._polled.wait()
         self.log.append((self.block, self.rem_prev, rem))
         if self.rem_prev > 0:
             self.known += 1
@@ -460,6 +489,16 @@ class StepRunner:
                 finished = self._poll_one()
                 if was_productive:
                     done_steps += 1
+                if not finished and len(self.pending) == 1 and g.next_step_finishes(self._polled):
+                    # the one step queued behind the polled one commits everything that is left: it is accounted for
+                    # without being waited for, and the next block's work is queued right behind it
+                    self.pending.pop(0)
+                    self.log.append((self.block, self.rem_prev, 0))
+                    self.known += 1
+                    self.committed += self.rem_prev
+                    self.rem_prev = 0
+                    done_steps += 1
+                    finished = True
                 if finished:
                     # whatever is still queued in this block found nothing masked
                     while self.pending:

@@ -96,6 +96,33 @@ def test_host_visible_total():
                           rule=dlm.RULE_TOPK, k=1, host_remaining_total=host)
 
 
+def test_host_visible_maximum():
+    """Beside the total, the most positions any one sequence still has masked (what tells a late-polling host that the next
+    step ends the block): after every step of a small rollout-like sequence of commits."""
+    rng = np.random.default_rng(13)
+    B, n = 20, 32
+    mask = (rng.random((B, n)) < 0.8).astype(np.uint8)
+    mask[3] = 0
+    d_mask, d_x = dev(mask), torch.zeros((B, n), dtype=torch.int32, device=DEV)
+    n_commit = torch.zeros(B, dtype=torch.int32, device=DEV)
+    remaining = torch.zeros(B, dtype=torch.int32, device=DEV)
+    host = torch.full((1,), -5, dtype=torch.int32).pin_memory()
+    host_max = torch.full((1,), -5, dtype=torch.int32).pin_memory()
+    for step in range(40):
+        conf, tok = rng.random((B, n)).astype(np.float32), rng.integers(0, 100, size=(B, n)).astype(np.int32)
+        dlm.unmask_commit(dev(conf), dev(tok), d_x, d_mask, n_commit, remaining, x_pos0=0, rule=dlm.RULE_THRESHOLD,
+                          threshold=0.8, force_top1=True, host_remaining_total=host, host_remaining_max=host_max)
+        torch.cuda.synchronize()
+        per_seq = d_mask.sum(1).cpu().numpy()
+        assert int(host[0]) == int(per_seq.sum()) and int(host_max[0]) == int(per_seq.max())
+        if per_seq.max() == 0:
+            break
+    assert per_seq.max() == 0
+    with pytest.raises(dlm.DlmError):       # the maximum goes with the total
+        dlm.unmask_commit(dev(conf), dev(tok), d_x, d_mask, n_commit, remaining, x_pos0=0, rule=dlm.RULE_TOPK, k=1,
+                          host_remaining_max=host_max)
+
+
 def test_no_forced_pick():
     rng = np.random.default_rng(3)
     conf, tok = rng.random((4, 32)) * 0.5, rng.integers(0, 100, size=(4, 32))

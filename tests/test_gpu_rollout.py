@@ -216,8 +216,9 @@ def test_lagged_loop_matches_synchronous(name):
     x0 = dev(synth.initial_tokens(cfg, cfg.L))
     k0, v0 = synth.cache_kv(cfg, 0)
     finals = []
-    for lagged in (False, True):
+    for lagged, predict in ((False, False), (True, False), (True, True)):
         g = GpuRollout(cfg, w, DEV)
+        g.predict_finish = predict
         g.x.copy_(x0)
         g.cache_k.copy_(bf16_dev(k0))
         g.cache_v.copy_(bf16_dev(v0))
@@ -232,9 +233,15 @@ def test_lagged_loop_matches_synchronous(name):
             tot_empty += res["empty"]
         torch.cuda.synchronize()
         assert tot_empty <= cfg.n_blocks
-        finals.append((g.x.cpu().numpy(), bf16_host(g.cache_k), tot_steps))
-    assert np.array_equal(finals[0][0], finals[1][0]) and np.array_equal(finals[0][1], finals[1][1])
-    assert finals[0][2] == finals[1][2]
+        finals.append((g.x.cpu().numpy(), bf16_host(g.cache_k), tot_steps, tot_empty))
+    for other in finals[1:]:
+        assert np.array_equal(finals[0][0], other[0]) and np.array_equal(finals[0][1], other[1])
+        assert finals[0][2] == other[2]
+    # a host that is told when no sequence has more left than the next step commits queues fewer empty steps (none when
+    # every block ends with such a step: always under the top-k rule, nearly always under the threshold rule)
+    assert finals[2][3] <= finals[1][3]
+    if cfg.rule == "topk":
+        assert finals[2][3] == 0
 
 
 def test_exact_row_schedule_of_the_topk_rule_changes_nothing():
