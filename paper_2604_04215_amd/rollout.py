@@ -117,7 +117,8 @@ class GpuRollout:
         self._refresh_calls = {}      # (block, source pointers) -> prepared dlm_kv_refresh calls
         self._compact_args = None
         # optional hook(name, c_function, args_struct, stream_ptr, meta) -> return code, called INSTEAD of the plain
-        # library call of a step (the benchmark's per-call event timing); None: the calls go straight to the library
+        # library call of a step or of a block's cache refresh (the benchmark's per-call event timing); None: the calls
+        # go straight to the library
         self.on_call = None
         self.total_committed = torch.zeros(1, dtype=torch.int64, device=dev)
         self.block = -1
@@ -229,15 +230,18 @@ class GpuRollout:
                 if hi > self.cache_k.shape[2] or self.cache_k.stride() != self.cache_v.stride():
                     raise ValueError("refresh image does not fit the cache")
                 seg = dlm.kv_seg(sk, sv, 0)
+                moved = 2 * 2 * cfg.B * cfg.Hkv * (hi - lo) * cfg.d * 2          # K and V, read + written
                 calls.append((seg, (C.byref(seg), cfg.B, cfg.Hkv, cfg.d, self.cache_k.data_ptr(), self.cache_v.data_ptr(),
-                                    self.cache_k.stride(0), self.cache_k.stride(1), self.cache_k.stride(2), lo), (sk, sv)))
+                                    self.cache_k.stride(0), self.cache_k.stride(1), self.cache_k.stride(2), lo), moved))
             if len(self._refresh_calls) > 4 * max(1, cfg.n_blocks):      # a caller that brings a new image every time
                 self._refresh_calls.clear()
             self._refresh_calls[key] = calls
         sp = C.c_void_p(torch._C._cuda_getCurrentRawStream(self._dev_index))
         fn = dlm.lib().dlm_kv_refresh
-        for _seg, args, _keep in calls:
-            rc = fn(*args, sp)
+        hook = self.on_call
+        for _seg, args, moved in calls:
+            # (the hook gets the positional arguments of dlm_kv_refresh without the stream, and calls fn(*args, stream))
+            rc = fn(*args, sp) if hook is None else hook("kv_refresh", fn, args, sp, dict(bytes=moved))
             if rc:
                 raise dlm.DlmError(rc, dlm.last_error())
 
